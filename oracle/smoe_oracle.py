@@ -1,0 +1,437 @@
+"""CPU oracle for the SMoE offloaded-MoE decode step.  TEST INFRASTRUCTURE ONLY.
+
+A plain, slow, fp64 numpy statement of what one decode step of one MoE layer
+computes under the SMoE scheduler (arxiv 2508.18983): router scores, the
+expert-cache router of Algorithm 1 (low-score substitution), the score-based
+eviction of Eq. 3 with its protection shield, hit/miss accounting in the sense
+of Eq. 1, and the SwiGLU expert FFN with the weighted combine.  It is written
+from the paper's text in the paper's order and notation; there is no tiling,
+fusion or reordering.  It shares no code with the HIP library and must never
+be imported by it: only tests, the smoke check and the benchmark's
+``cpu_baseline`` leg use this module.
+
+Where the paper fixes the behaviour the docstring cites the passage.  Where it
+is silent the convention taken is stated and marked *convention*; the outputs
+that depend on a convention alone are "parity unpinned" by the paper:
+
+* combine weight of a substituted slot (``cache_router`` / ``decode_layer``):
+  the slot keeps the replaced expert's gate score            -- parity unpinned
+* ranking of eligible substitutes by the similarity table (``subst_key=0``);
+  the paper ranks by gate score (``subst_key=1``, pinned)     -- parity unpinned
+* eviction window n (default 3), initial residency, tie rules, staging when
+  every resident expert is shielded, two-pass set C at batch>1 -- parity unpinned
+
+Inputs are the stored fp32 / bf16 values (bf16 arrives as raw uint16); all
+arithmetic is fp64 with no intermediate rounding.
+"""
+from __future__ import annotations
+
+from collections import deque
+from dataclasses import dataclass, field
+from typing import Callable, Dict, List, Optional, Sequence, Set
+
+import numpy as np
+
+
+# --------------------------------------------------------------------------
+# storage formats
+# --------------------------------------------------------------------------
+def widen(a: np.ndarray) -> np.ndarray:
+    """Stored values -> float64.  uint16 is bfloat16 bits (sign, 8 exponent,
+    7 mantissa bits = the upper half of an IEEE binary32)."""
+    a = np.asarray(a)
+    if a.dtype == np.uint16:
+        return (a.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    return a.astype(np.float64)
+
+
+# --------------------------------------------------------------------------
+# router (Section II-A: a router scores all experts and the top-k are active)
+# --------------------------------------------------------------------------
+def gate_logits(gate_w: np.ndarray, x: np.ndarray) -> np.ndarray:
+    """l_e = sum_h Wg[e][h] * x[h] for the E routed experts."""
+    return widen(gate_w) @ widen(x)
+
+
+def softmax_scores(logits: np.ndarray) -> np.ndarray:
+    """Gate score = softmax over all E routed experts (Section III: importance
+    is the router's gate score; shared experts are not scored)."""
+    z = np.exp(logits - np.max(logits))
+    return z / np.sum(z)
+
+
+def rank_experts(scores: np.ndarray) -> np.ndarray:
+    """Expert ids ordered by score descending, lower id first on equal scores
+    (Algorithm 1 "Sort S_t desc"; the tie rule is a convention)."""
+    e = len(scores)
+    return np.lexsort((np.arange(e), -np.asarray(scores, dtype=np.float64)))
+
+
+@dataclass
+class RouteInfo:
+    scores: np.ndarray          # [E] fp64
+    order: np.ndarray           # [E] ids by rank
+    topk: List[int]             # E_a in rank order (slot order)
+    s_k1: Optional[float]       # S_{k+1}; None when E == k
+    T: Optional[float]          # (1+alpha) S_{k+1}
+    R: Optional[float]          # (1-alpha) S_{k+1}
+    top_score: List[int]        # E_a \ E_l
+    low_score: List[int]        # E_l
+
+
+def route(scores: np.ndarray, k: int, alpha: float) -> RouteInfo:
+    """Top-k selection and the alpha classification of the active experts.
+
+    Algorithm 1: T = (1+alpha) S_{k+1}, L = S_{k+1}, R = (1-alpha) S_{k+1}.
+    Membership in E_a is by rank; an active expert is top-score when its score
+    reaches T and low-score otherwise (Section IV-B; the printed strict /
+    non-strict inequalities disagree between Section IV-A and Algorithm 1, the
+    workloads keep every comparison away from equality)."""
+    order = rank_experts(scores)
+    topk = [int(e) for e in order[:k]]
+    if len(scores) <= k:
+        return RouteInfo(scores, order, topk, None, None, None, list(topk), [])
+    s_k1 = float(scores[order[k]])
+    T = (1.0 + alpha) * s_k1
+    R = (1.0 - alpha) * s_k1
+    top_score = [e for e in topk if scores[e] >= T]
+    low_score = [e for e in topk if scores[e] < T]
+    return RouteInfo(scores, order, topk, s_k1, T, R, top_score, low_score)
+
+
+# --------------------------------------------------------------------------
+# expert-cache router (Algorithm 1 + its prose in Section IV-B)
+# --------------------------------------------------------------------------
+@dataclass
+class RouterResult:
+    final: List[int]            # expert per slot after substitution
+    substituted: List[bool]     # per slot
+    need: List[int]             # E_l \ (G u C) in processing order
+    cand: List[int]             # E_s before any assignment (ascending id)
+    margin: float               # smallest |log| distance of a threshold test
+
+
+def cache_router(info: RouteInfo, resident: Set[int], batch_top: Set[int],
+                 sim_rows: Optional[np.ndarray], subst_key: int) -> RouterResult:
+    """Replace low-score active experts that are not on the GPU.
+
+    Section IV-B: top-score experts are kept.  A low-score expert is kept when
+    it is resident or belongs to the batch's top-score set C.  Otherwise it may
+    be replaced by an inactive expert that is resident (or in C) and whose
+    score lies in [R, S_{k+1}].  When substitutes run short, the lowest-scoring
+    low-score experts are replaced first, so the ones left for loading are the
+    highest-scoring ("top |B_t|-|A_t| experts from B_t").  With no eligible
+    substitute the original expert stays and becomes a load (Section III).
+
+    Ranking of the eligible substitutes: ``subst_key == 1`` takes the highest
+    gate score first (the paper's rule); ``subst_key == 0`` takes the largest
+    entry of the similarity-table row of the expert being replaced
+    (*convention* of this build).  Ties go to the lower expert id.
+    """
+    s = info.scores
+    final = list(info.topk)
+    substituted = [False] * len(final)
+    margin = np.inf
+    if info.s_k1 is None:
+        return RouterResult(final, substituted, [], [], margin)
+    active = set(info.topk)
+    for e in info.topk:
+        margin = min(margin, abs(np.log(s[e] / info.T)))
+    available = set(resident) | set(batch_top)
+    # low-score actives that would have to be loaded, lowest score first
+    # (= walking the rank order of E_a backwards)
+    need = [e for e in reversed(info.topk)
+            if e in info.low_score and e not in available]
+    cand = []
+    for c in range(len(s)):
+        if c in active or c not in available:
+            continue
+        if info.R > 0:
+            margin = min(margin, abs(np.log(s[c] / info.R)))
+        if s[c] >= info.R:
+            cand.append(c)
+    cand0 = list(cand)
+    for b in need:
+        if not cand:
+            break
+        if subst_key == 1:
+            key = [s[c] for c in cand]
+        else:
+            key = [float(sim_rows[b][c]) for c in cand]
+        best = max(key)
+        pick = min(c for c, kv in zip(cand, key) if kv == best)
+        slot = info.topk.index(b)
+        final[slot] = pick
+        substituted[slot] = True
+        cand.remove(pick)
+    return RouterResult(final, substituted, need, cand0, float(margin))
+
+
+def hit_count_eq1(resident: Set[int], info: RouteInfo, n_candidates: int) -> int:
+    """Eq. 1: |G n E_a| + min(|E_l \\ G|, |E_s|)."""
+    g_and_a = len(set(info.topk) & set(resident))
+    l_not_g = len([e for e in info.low_score if e not in resident])
+    return g_and_a + min(l_not_g, n_candidates)
+
+
+# --------------------------------------------------------------------------
+# cache eviction (Section IV-B "Cache eviction", Eq. 3) + protection shield
+# --------------------------------------------------------------------------
+def mean_window_scores(history: Sequence[np.ndarray]) -> np.ndarray:
+    """Mean score of every expert over the retained window.  The caller keeps
+    the last n+1 iterations, i.e. k = max(1, j-n) .. j of Eq. 3."""
+    return np.sum(np.stack(list(history)), axis=0) / float(len(history))
+
+
+def pick_victim(mean_scores: np.ndarray, evictable: Sequence[int]):
+    """arg-min of the window mean among the evictable experts (Eq. 3), lower
+    id on ties.  Also returns the relative gap to the runner-up."""
+    ev = sorted(evictable)
+    vals = [mean_scores[e] for e in ev]
+    best = min(vals)
+    victim = min(e for e, v in zip(ev, vals) if v == best)
+    rest = [v for e, v in zip(ev, vals) if e != victim]
+    gap = np.inf if not rest else (min(rest) - best) / max(abs(best), 1e-300)
+    return victim, float(gap)
+
+
+# --------------------------------------------------------------------------
+# expert FFN
+# --------------------------------------------------------------------------
+def silu(z: np.ndarray) -> np.ndarray:
+    return z / (1.0 + np.exp(-z))
+
+
+def swiglu_expert(w1: np.ndarray, w3: np.ndarray, w2: np.ndarray, x: np.ndarray) -> np.ndarray:
+    """W2 ( silu(W1 x) * (W3 x) ): W1 gate-projection [F][H], W3 up-projection
+    [F][H], W2 down-projection [H][F] (the FFN form is fixed by the build's
+    problem statement; the paper only says experts are FFNs)."""
+    a = silu(w1 @ x) * (w3 @ x)
+    return w2 @ a
+
+
+# --------------------------------------------------------------------------
+# the stateful per-layer machine
+# --------------------------------------------------------------------------
+@dataclass
+class LayerCache:
+    cap: int
+    window: int
+    slot_expert: List[int]                       # slot -> expert id
+    history: deque = field(default_factory=deque)
+
+    @property
+    def resident(self) -> Set[int]:
+        return set(self.slot_expert)
+
+
+@dataclass
+class Stats:
+    tokens: int = 0
+    slots: int = 0
+    raw_hits: int = 0
+    hits: int = 0
+    misses: int = 0
+    substitutions: int = 0
+    evictions: int = 0
+    staged: int = 0
+    fetches: int = 0
+    bytes_fetched: int = 0
+
+    def add(self, o: "Stats") -> "Stats":
+        return Stats(*[getattr(self, f) + getattr(o, f) for f in self.__dataclass_fields__])
+
+    def as_dict(self) -> Dict[str, int]:
+        return {f: int(getattr(self, f)) for f in self.__dataclass_fields__}
+
+
+@dataclass
+class StepResult:
+    scores: np.ndarray            # [B, E] fp64
+    topk: np.ndarray              # [B, k] int
+    final: np.ndarray             # [B, k] int
+    substituted: np.ndarray       # [B, k] bool
+    hit: np.ndarray               # [B, k] bool  (slot served without a fetch)
+    weights: np.ndarray           # [B, k] fp64 combine weights
+    fetched: List[int]            # distinct missing experts in fetch order
+    victims: List[int]            # evicted expert per fetch, -1 when staged
+    y: Optional[np.ndarray]       # [B, H] fp64 or None
+    route_margin: float
+    evict_margin: float
+
+
+class SMoEOracle:
+    """One decode step of one layer at a time, in layer order per token."""
+
+    def __init__(self, *, n_layers: int, hidden: int, n_experts: int, ffn: int, top_k: int,
+                 cache_cap: int, alpha: float, gate_w: np.ndarray, experts: np.ndarray,
+                 sim: np.ndarray, shared: Optional[np.ndarray] = None, n_shared: int = 0,
+                 shared_ffn: int = 0, subst_key: int = 0, renorm_topk: int = 1,
+                 evict_window: int = 3, init_resident: Optional[np.ndarray] = None,
+                 elem_bytes: int = 2):
+        if not (top_k <= cache_cap <= n_experts):
+            raise ValueError("need top_k <= cache_cap <= n_experts")
+        self.L, self.H, self.E, self.F, self.k = n_layers, hidden, n_experts, ffn, top_k
+        self.cap, self.alpha = cache_cap, float(alpha)
+        self.gate_w, self.experts, self.sim, self.shared = gate_w, experts, sim, shared
+        self.n_shared, self.Fs = n_shared, shared_ffn
+        self.subst_key, self.renorm, self.window = subst_key, renorm_topk, evict_window
+        self.expert_bytes = 3 * hidden * ffn * elem_bytes
+        self._init_resident = init_resident
+        self._wcache: Dict = {}
+        self.reset()
+
+    # -- state ------------------------------------------------------------
+    def reset(self) -> None:
+        """Initial residency: the caller's list, else experts 0..cap-1
+        (*convention*); empty history, zero counters."""
+        self.layers: List[LayerCache] = []
+        for l in range(self.L):
+            if self._init_resident is None:
+                ids = list(range(self.cap))
+            else:
+                ids = [int(v) for v in self._init_resident[l]]
+            self.layers.append(LayerCache(self.cap, self.window, ids))
+        self.stats_per_layer = [Stats() for _ in range(self.L)]
+
+    def stats(self, layer: int = -1) -> Stats:
+        if layer >= 0:
+            return self.stats_per_layer[layer]
+        tot = Stats()
+        for s in self.stats_per_layer:
+            tot = tot.add(s)
+        return tot
+
+    # -- weights ----------------------------------------------------------
+    def _mats(self, layer: int, e: int, shared: bool = False):
+        key = (layer, e, shared)
+        if key in self._wcache:
+            return self._wcache[key]
+        H = self.H
+        if shared:
+            F, flat = self.Fs, self.shared[layer][e]
+        else:
+            F, flat = self.F, self.experts[layer][e]
+        hf = H * F
+        w1 = widen(flat[:hf]).reshape(F, H)
+        w3 = widen(flat[hf:2 * hf]).reshape(F, H)
+        w2 = widen(flat[2 * hf:3 * hf]).reshape(H, F)
+        if len(self._wcache) >= 24 or hf > (1 << 24):
+            self._wcache.clear()
+        self._wcache[key] = (w1, w3, w2)
+        return w1, w3, w2
+
+    # -- the step ---------------------------------------------------------
+    def decode_layer(self, layer: int, x: np.ndarray, compute_y: bool = True) -> StepResult:
+        """x: [B, H] stored values.  Order of operations (Section V-B,
+        dependency 1: cache update and shield strictly after gating):
+        gate -> scores -> top-k -> Algorithm 1 -> history push -> shield ->
+        evictions for the loads -> expert computation -> combine."""
+        x = np.atleast_2d(x)
+        B = x.shape[0]
+        k, E = self.k, self.E
+        cache = self.layers[layer]
+        st = self.stats_per_layer[layer]
+        G_before = cache.resident
+
+        infos = [route(softmax_scores(gate_logits(self.gate_w[layer], x[t])), k, self.alpha)
+                 for t in range(B)]
+        route_margin = np.inf
+        for info in infos:
+            ls = np.log(info.scores[info.order[:min(E, k + 2)]])
+            if len(ls) > 1:
+                route_margin = min(route_margin, float(np.min(ls[:-1] - ls[1:])))
+        # set C: the top-score experts of every token of the step (two-pass, *convention*)
+        C: Set[int] = set()
+        for info in infos:
+            C |= set(info.top_score)
+        results = []
+        for t, info in enumerate(infos):
+            extra = C if B > 1 else set()
+            r = cache_router(info, G_before, extra, self.sim[layer], self.subst_key)
+            route_margin = min(route_margin, r.margin)
+            results.append(r)
+            if B == 1:
+                # Eq. 1 holds per token-layer at batch 1
+                served = sum(1 for e in r.final if e in G_before)
+                assert served == hit_count_eq1(G_before, info, len(r.cand))
+
+        topk = np.array([info.topk for info in infos], dtype=np.int64)
+        final = np.array([r.final for r in results], dtype=np.int64)
+        substituted = np.array([r.substituted for r in results], dtype=bool)
+        scores = np.stack([info.scores for info in infos])
+        weights = np.array([[info.scores[e] for e in info.topk] for info in infos])
+        if self.renorm:
+            weights = weights / weights.sum(axis=1, keepdims=True)
+        hit = np.array([[e in G_before for e in r.final] for r in results], dtype=bool)
+
+        # history: one entry per decode step, the batch mean of the score vectors
+        cache.history.append(scores.mean(axis=0))
+        while len(cache.history) > self.window + 1:
+            cache.history.popleft()
+        means = mean_window_scores(cache.history)
+
+        shield = set(int(e) for e in final.reshape(-1))
+        fetched: List[int] = []
+        for e in final.reshape(-1):
+            e = int(e)
+            if e not in G_before and e not in fetched:
+                fetched.append(e)
+        victims: List[int] = []
+        evict_margin = np.inf
+        for m in fetched:
+            evictable = [e for e in cache.slot_expert if e not in shield]
+            if evictable:
+                v, gap = pick_victim(means, evictable)
+                evict_margin = min(evict_margin, gap)
+                cache.slot_expert[cache.slot_expert.index(v)] = m
+                victims.append(v)
+                st.evictions += 1
+            else:
+                victims.append(-1)          # computed from a transient slot, not inserted
+                st.staged += 1
+        st.tokens += B
+        st.slots += B * k
+        st.raw_hits += sum(len(set(info.topk) & G_before) for info in infos)
+        st.hits += int(hit.sum())
+        st.misses += int((~hit).sum())
+        st.substitutions += int(substituted.sum())
+        st.fetches += len(fetched)
+        st.bytes_fetched += len(fetched) * self.expert_bytes
+
+        y = None
+        if compute_y:
+            y = np.zeros((B, self.H))
+            for t in range(B):
+                xt = widen(x[t])
+                for j in range(k):
+                    w1, w3, w2 = self._mats(layer, int(final[t, j]))
+                    y[t] += weights[t, j] * swiglu_expert(w1, w3, w2, xt)
+                for sidx in range(self.n_shared):
+                    w1, w3, w2 = self._mats(layer, sidx, shared=True)
+                    y[t] += swiglu_expert(w1, w3, w2, xt)
+        return StepResult(scores, topk, final, substituted, hit, weights, fetched, victims, y,
+                          float(route_margin), float(evict_margin))
+
+
+def oracle_from_workload(wl, **override) -> SMoEOracle:
+    """Build the oracle on a generated workload (duck-typed: needs .shape and
+    the host tensors; arrays are taken as numpy views, bf16 as raw uint16)."""
+    import torch
+
+    def view(t):
+        if t is None:
+            return None
+        if t.dtype == torch.bfloat16:
+            return t.view(torch.int16).numpy().view(np.uint16)
+        return t.numpy()
+
+    s = wl.shape
+    kw = dict(n_layers=s.n_layers, hidden=s.hidden, n_experts=s.n_experts, ffn=s.ffn,
+              top_k=s.top_k, cache_cap=s.cache_cap, alpha=float(np.float32(s.alpha)),
+              gate_w=view(wl.gate_w), experts=view(wl.experts), sim=view(wl.sim),
+              shared=view(wl.shared), n_shared=s.n_shared, shared_ffn=s.shared_ffn,
+              subst_key=s.subst_key, renorm_topk=s.renorm_topk, evict_window=s.evict_window,
+              elem_bytes=s.elem_bytes)
+    kw.update(override)
+    return SMoEOracle(**kw)

@@ -1,0 +1,393 @@
+"""Pins for the CPU oracle: each checks it against something other than itself
+(values the paper states, closed forms, library routines, brute force)."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+import torch
+
+from oracle import smoe_oracle as O
+from smoe_inputs import SHAPES, make_workload, as_numpy
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ---------------------------------------------------------------- formats
+def test_widen_bf16_matches_library_conversion():
+    t = (torch.randn(4096, generator=torch.Generator().manual_seed(1)) * 3).to(torch.bfloat16)
+    t[0], t[1], t[2] = 0.0, -0.0, 1.0
+    got = O.widen(as_numpy(t))
+    assert got.dtype == np.float64
+    np.testing.assert_array_equal(got, t.to(torch.float64).numpy())
+
+
+# ---------------------------------------------------------------- router
+def test_scores_are_library_softmax():
+    rng = np.random.default_rng(0)
+    for e in (2, 8, 64):
+        l = rng.normal(size=e) * 5
+        np.testing.assert_allclose(O.softmax_scores(l), scipy.special.softmax(l), rtol=1e-14)
+        assert abs(O.softmax_scores(l).sum() - 1) < 1e-14
+    # shift invariance and overflow safety
+    np.testing.assert_allclose(O.softmax_scores(np.array([1000.0, 999.0])),
+                               scipy.special.softmax([1.0, 0.0]), rtol=1e-14)
+
+
+def test_gate_logits_is_matvec_with_rows_as_experts():
+    rng = np.random.default_rng(1)
+    wg = rng.normal(size=(5, 7)).astype(np.float32)
+    x = rng.normal(size=7).astype(np.float32)
+    want = [sum(float(wg[e, h]) * float(x[h]) for h in range(7)) for e in range(5)]
+    np.testing.assert_allclose(O.gate_logits(wg, x), want, rtol=1e-14)
+
+
+def test_topk_matches_full_sort_and_library_topk():
+    rng = np.random.default_rng(2)
+    for trial in range(200):
+        e = int(rng.integers(2, 65))
+        k = int(rng.integers(1, e + 1))
+        s = scipy.special.softmax(rng.normal(size=e) * 2)
+        info = O.route(s, k, 0.25)
+        brute = sorted(range(e), key=lambda i: (-s[i], i))[:k]
+        assert info.topk == brute
+        lib = torch.topk(torch.from_numpy(s), k).indices.tolist()
+        assert info.topk == lib
+        if e > k:
+            assert info.s_k1 == sorted(s, reverse=True)[k]
+
+
+def test_topk_tie_rule_lower_id_first():
+    s = np.array([0.1, 0.3, 0.3, 0.1, 0.2])
+    assert O.route(s, 3, 0.0).topk == [1, 2, 4]
+    assert O.route(np.array([0.25, 0.25, 0.25, 0.25]), 2, 0.0).topk == [0, 1]
+
+
+def test_alpha_classification_thresholds():
+    # S_{k+1} = 0.10; T = 0.13; R = 0.07  (Algorithm 1, threshold line)
+    s = np.array([0.40, 0.14, 0.12, 0.10, 0.08, 0.06, 0.10 - 1e-9])
+    s = s / 1.0
+    info = O.route(s, 3, 0.3)
+    assert info.topk == [0, 1, 2]
+    assert info.s_k1 == 0.10
+    assert info.T == pytest.approx(0.13) and info.R == pytest.approx(0.07)
+    assert info.top_score == [0, 1] and info.low_score == [2]
+
+
+# ---------------------------------------------------------------- Algorithm 1
+def _read_golden(name):
+    d = {}
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            key, *vals = line.split()
+            d[key] = vals
+    return d
+
+
+def test_intro_worked_example_hit_rate_2_of_5_to_4_of_5():
+    g = _read_golden("intro_example.txt")
+    names = g["experts"]
+    idx = {n: i for i, n in enumerate(names)}
+    active = [idx[n] for n in g["active"]]
+    resident = {idx[n] for n in g["resident"]}
+    # scores realising the example's structure: a,b,c clearly high; d,e just above
+    # the (k+1)-th score; f,g just below it; h far below
+    score = dict(a=0.30, b=0.25, c=0.20, d=0.062, e=0.060, f=0.055, g=0.054, h=0.019)
+    s = np.array([score[n] for n in names])
+    k = len(active)
+    alpha = 0.3
+    info = O.route(s, k, alpha)
+    assert sorted(info.topk) == sorted(active)
+    assert sorted(info.low_score) == sorted(idx[n] for n in g["low_score"])
+    hits_before = len(set(info.topk) & resident)
+    assert hits_before == int(g["hits_before"][0])
+    assert k - hits_before == int(g["loads_before"][0])
+    for key in (0, 1):
+        sim = np.eye(len(names))
+        r = O.cache_router(info, resident, set(), sim, key)
+        served = [e for e in r.final if e in resident]
+        assert len(served) == int(g["hits_after"][0])
+        assert k - len(served) == int(g["loads_after"][0])
+        subs = sorted(e for e, f in zip(r.final, r.substituted) if f)
+        assert subs == sorted(idx[n] for n in g["substitutes"])
+        assert O.hit_count_eq1(resident, info, len(r.cand)) == int(g["hits_after"][0])
+
+
+def _random_case(rng, e_max=8):
+    e = int(rng.integers(3, e_max + 1))
+    k = int(rng.integers(1, e))
+    s = scipy.special.softmax(rng.normal(size=e) * rng.choice([0.3, 1.0, 3.0]))
+    alpha = float(rng.choice([0.0, 0.1, 0.3, 0.6, 0.9]))
+    resident = {int(i) for i in np.nonzero(rng.random(e) < rng.choice([0.2, 0.5, 0.8]))[0]}
+    sim = rng.uniform(-1, 1, size=(e, e))
+    return e, k, s, alpha, resident, sim
+
+
+def test_hit_count_equals_eq1_closed_form_bruteforce_sets():
+    """Eq. 1 evaluated on sets built here from the definitions (Table
+    "Definitions" + the two score-band constraints) equals the number of slots
+    the router serves from the GPU."""
+    rng = np.random.default_rng(3)
+    for _ in range(3000):
+        e, k, s, alpha, G, sim = _random_case(rng)
+        rank = sorted(range(e), key=lambda i: (-s[i], i))
+        Ea = set(rank[:k])
+        sk1 = s[rank[k]]
+        El = {i for i in Ea if s[i] < (1 + alpha) * sk1}
+        Es = {i for i in range(e) if i not in Ea and i in G and s[i] >= (1 - alpha) * sk1}
+        want = len(G & Ea) + min(len(El - G), len(Es))
+        for key in (0, 1):
+            r = O.cache_router(O.route(s, k, alpha), G, set(), sim, key)
+            assert sum(1 for x in r.final if x in G) == want
+            assert sum(r.substituted) == min(len(El - G), len(Es))
+            assert len(set(r.final)) == k                      # no expert used twice
+            # top-score experts and resident lows are never touched
+            for slot, orig in enumerate(rank[:k]):
+                if orig not in El or orig in G:
+                    assert r.final[slot] == orig and not r.substituted[slot]
+                if r.substituted[slot]:
+                    assert r.final[slot] in Es
+
+
+def test_score_key_takes_highest_scoring_substitutes_and_keeps_highest_lows():
+    """Section IV-B: the |E_l \\ G| highest-scoring members of E_s are used; when
+    E_s is short, the lows that remain for loading are the highest-scoring."""
+    rng = np.random.default_rng(4)
+    seen_short = 0
+    for _ in range(3000):
+        e, k, s, alpha, G, sim = _random_case(rng)
+        info = O.route(s, k, alpha)
+        r = O.cache_router(info, G, set(), sim, 1)
+        rank = sorted(range(e), key=lambda i: (-s[i], i))
+        sk1 = s[rank[k]]
+        Es = sorted((i for i in rank[k:] if i in G and s[i] >= (1 - alpha) * sk1),
+                    key=lambda i: (-s[i], i))
+        need = [i for i in rank[:k] if s[i] < (1 + alpha) * sk1 and i not in G]
+        m = min(len(need), len(Es))
+        used = [r.final[j] for j in range(k) if r.substituted[j]]
+        assert sorted(used) == sorted(Es[:m])
+        replaced = [rank[j] for j in range(k) if r.substituted[j]]
+        assert sorted(replaced) == sorted(need[len(need) - m:])   # the m lowest-scoring
+        if m < len(need):
+            seen_short += 1
+            kept = [rank[j] for j in range(k) if rank[j] in need and not r.substituted[j]]
+            assert sorted(kept) == sorted(need[:len(need) - m])
+        # the lowest low gets the best substitute ("closest ranked first")
+        if m:
+            assert r.final[rank.index(need[-1])] == Es[0]
+    assert seen_short > 20
+
+
+def test_sim_key_is_greedy_argmax_over_all_assignments():
+    """With the similarity key the first expert processed gets its most similar
+    eligible candidate, the next one the best of what is left, ... : check
+    against enumeration of every injective assignment in that lexicographic
+    order."""
+    rng = np.random.default_rng(5)
+    checked = 0
+    for _ in range(1500):
+        e, k, s, alpha, G, sim = _random_case(rng)
+        info = O.route(s, k, alpha)
+        r = O.cache_router(info, G, set(), sim, 0)
+        if not r.need or not r.cand:
+            continue
+        m = min(len(r.need), len(r.cand))
+        best = max(itertools.permutations(r.cand, m),
+                   key=lambda p: tuple(sim[b][c] for b, c in zip(r.need, p)))
+        got = tuple(r.final[info.topk.index(b)] for b in r.need[:m])
+        assert got == best
+        checked += 1
+    assert checked > 100
+
+
+def test_no_candidate_keeps_original_expert():
+    s = scipy.special.softmax(np.array([3.0, 1.0, 0.9, 0.8, -4.0, -5.0]))
+    info = O.route(s, 3, 0.3)
+    # residents are all far below the band
+    r = O.cache_router(info, {4, 5}, set(), np.eye(6), 0)
+    assert r.final == info.topk and not any(r.substituted)
+    # alpha = 0: nothing is low-score, nothing is replaced even with residents in reach
+    info0 = O.route(s, 3, 0.0)
+    r0 = O.cache_router(info0, {3, 4, 5}, set(), np.eye(6), 0)
+    assert info0.low_score == [] and r0.final == info0.topk
+
+
+def test_batch_top_score_set_keeps_and_offers_experts():
+    """Section IV-B / VI-B: a low-score expert that another token of the batch
+    uses as a top-score expert is kept, and such experts can serve as
+    substitutes although they are not resident."""
+    s = scipy.special.softmax(np.array([3.0, 1.0, 0.95, 0.9, 0.85, -3.0]))
+    info = O.route(s, 3, 0.3)            # actives 0,1,2 ; lows 1,2 ; pivot 3
+    assert info.low_score == [1, 2]
+    r = O.cache_router(info, set(), {2, 4}, np.eye(6), 1)
+    assert r.need == [1]                 # 2 is in C: retained
+    assert r.final == [0, 4, 2] and r.substituted == [False, True, False]
+
+
+# ---------------------------------------------------------------- eviction
+def test_eviction_is_eq3_on_the_full_score_log():
+    """Replay a trace and recompute Eq. 3 from the complete log with the
+    printed 1-based window max(1, j-n) .. j."""
+    wl = make_workload(SHAPES["c1"].with_(tokens=48, seed=3))
+    for n in (0, 1, 3, 7):
+        orc = O.oracle_from_workload(wl, evict_window=n)
+        log = {l: [] for l in range(wl.shape.n_layers)}
+        fetches = 0
+        for t in range(wl.shape.tokens):
+            for l in range(wl.shape.n_layers):
+                before = list(orc.layers[l].slot_expert)
+                res = orc.decode_layer(l, as_numpy(wl.x[t, l]), compute_y=False)
+                log[l].append(res.scores[0])
+                j = len(log[l])                                    # 1-based iteration index
+                lo = max(1, j - n)
+                avg = sum(log[l][i - 1] for i in range(lo, j + 1)) / (j - lo + 1)
+                resident = list(before)
+                shield = set(res.final[0].tolist())
+                for m, v in zip(res.fetched, res.victims):
+                    cand = [e for e in resident if e not in shield]
+                    want = min(cand, key=lambda e: (avg[e], e))
+                    assert v == want
+                    resident[resident.index(v)] = m
+                    fetches += 1
+                assert resident == orc.layers[l].slot_expert
+        assert fetches > 10
+
+
+def test_residency_invariants_and_counters_follow_the_trace(c1_workload):
+    wl = c1_workload
+    orc = O.oracle_from_workload(wl)
+    s = wl.shape
+    hits = misses = subs = raw = 0
+    for t in range(s.tokens):
+        for l in range(s.n_layers):
+            before = set(orc.layers[l].slot_expert)
+            res = orc.decode_layer(l, as_numpy(wl.x[t, l]), compute_y=False)
+            after = set(orc.layers[l].slot_expert)
+            assert len(orc.layers[l].slot_expert) == s.cache_cap == len(after)
+            final = set(res.final[0].tolist())
+            assert final <= after                       # everything used is resident after the loads
+            assert not (set(res.victims) & final)       # shield: nothing in use was evicted
+            assert set(res.victims) <= before
+            assert res.fetched == [e for e in res.final[0] if e not in before]
+            hits += len(final & before)
+            misses += len(final - before)
+            raw += len(set(res.topk[0].tolist()) & before)
+            subs += int(res.substituted.sum())
+            for j in range(s.top_k):
+                if res.substituted[0, j]:
+                    assert res.final[0, j] in before and res.topk[0, j] not in before
+    st = orc.stats()
+    assert (st.hits, st.misses, st.raw_hits, st.substitutions) == (hits, misses, raw, subs)
+    assert st.hits + st.misses == st.slots == s.tokens * s.n_layers * s.top_k
+    assert st.evictions == st.fetches == misses and st.staged == 0
+    assert st.bytes_fetched == misses * s.expert_bytes
+    assert subs > 0 and misses > 0
+
+
+def test_staging_when_every_resident_expert_is_shielded():
+    wl = make_workload(SHAPES["c1"].with_(cache_cap=2, tokens=4), batch=4)
+    orc = O.oracle_from_workload(wl, alpha=0.0)
+    staged = 0
+    for t in range(4):
+        res = orc.decode_layer(0, as_numpy(wl.x[t, 0]), compute_y=False)
+        assert len(orc.layers[0].slot_expert) == 2
+        assert res.victims.count(-1) == max(0, len(res.fetched) - len(
+            [v for v in res.victims if v >= 0]))
+        staged += res.victims.count(-1)
+    assert staged == orc.stats().staged and staged > 0
+
+
+# ---------------------------------------------------------------- FFN + output
+def test_swiglu_expert_matches_library_ops():
+    g = torch.Generator().manual_seed(7)
+    H, F = 24, 40
+    w1 = torch.randn(F, H, generator=g, dtype=torch.float64)
+    w3 = torch.randn(F, H, generator=g, dtype=torch.float64)
+    w2 = torch.randn(H, F, generator=g, dtype=torch.float64)
+    x = torch.randn(H, generator=g, dtype=torch.float64)
+    want = torch.nn.functional.linear(
+        torch.nn.functional.silu(torch.nn.functional.linear(x, w1)) * torch.nn.functional.linear(x, w3), w2)
+    got = O.swiglu_expert(w1.numpy(), w3.numpy(), w2.numpy(), x.numpy())
+    np.testing.assert_allclose(got, want.numpy(), rtol=1e-12, atol=1e-14)
+    # silu at known points
+    np.testing.assert_allclose(O.silu(np.array([0.0, 1.0, -1.0])),
+                               [0.0, 1 / (1 + np.exp(-1)), -1 / (1 + np.exp(1))], rtol=1e-15)
+
+
+def _dense_plain_moe(wl, layer, x_row, renorm):
+    """Plain MoE layer with library ops: run every expert, mask by top-k."""
+    s = wl.shape
+    x = x_row.to(torch.float64)
+    logits = wl.gate_w[layer].to(torch.float64) @ x
+    p = torch.softmax(logits, dim=0)
+    top = torch.topk(p, s.top_k)
+    mask = torch.zeros(s.n_experts, dtype=torch.float64)
+    mask[top.indices] = top.values / (top.values.sum() if renorm else 1.0)
+    y = torch.zeros(s.hidden, dtype=torch.float64)
+    for e in range(s.n_experts):
+        w1, w3, w2 = (m.to(torch.float64) for m in wl.expert_mats(layer, e))
+        y += mask[e] * (w2 @ (torch.nn.functional.silu(w1 @ x) * (w3 @ x)))
+    for j in range(s.n_shared):
+        w1, w3, w2 = (m.to(torch.float64) for m in wl.shared_mats(layer, j))
+        y += w2 @ (torch.nn.functional.silu(w1 @ x) * (w3 @ x))
+    return y.numpy()
+
+
+@pytest.mark.parametrize("renorm", [0, 1])
+def test_alpha_zero_and_full_capacity_reduce_to_plain_moe(c1_workload, renorm):
+    wl = c1_workload
+    s = wl.shape
+    for kw in (dict(alpha=0.0), dict(cache_cap=s.n_experts)):
+        orc = O.oracle_from_workload(wl, renorm_topk=renorm, **kw)
+        for t in range(6):
+            for l in range(s.n_layers):
+                res = orc.decode_layer(l, as_numpy(wl.x[t, l]))
+                assert not res.substituted.any()
+                np.testing.assert_array_equal(res.final, res.topk)
+                want = _dense_plain_moe(wl, l, wl.x[t, l, 0], renorm)
+                np.testing.assert_allclose(res.y[0], want, rtol=1e-11, atol=1e-15)
+        st = orc.stats()
+        assert st.substitutions == 0
+        if "cache_cap" in kw:
+            assert st.misses == 0 and st.hits == st.slots
+
+
+def test_substituted_slot_keeps_weight_and_uses_substitute_expert(c1_workload):
+    """Output with substitutions = plain combine with the final experts and the
+    original gate weights (stated convention for the slot weight)."""
+    wl = c1_workload
+    s = wl.shape
+    orc = O.oracle_from_workload(wl)
+    n_sub = 0
+    for t in range(s.tokens):
+        for l in range(s.n_layers):
+            res = orc.decode_layer(l, as_numpy(wl.x[t, l]))
+            if not res.substituted.any():
+                continue
+            n_sub += 1
+            x = wl.x[t, l, 0].to(torch.float64)
+            p = torch.softmax(wl.gate_w[l].to(torch.float64) @ x, dim=0)
+            w = p[torch.from_numpy(res.topk[0])]
+            w = w / w.sum()
+            y = torch.zeros(s.hidden, dtype=torch.float64)
+            for j in range(s.top_k):
+                w1, w3, w2 = (m.to(torch.float64) for m in wl.expert_mats(l, int(res.final[0, j])))
+                y += w[j] * (w2 @ (torch.nn.functional.silu(w1 @ x) * (w3 @ x)))
+            np.testing.assert_allclose(res.y[0], y.numpy(), rtol=1e-11, atol=1e-15)
+    assert n_sub >= 3
+
+
+def test_shared_experts_and_bf16_path_against_dense_library_moe():
+    shp = SHAPES["c4"].with_(hidden=128, ffn=96, shared_ffn=64, n_experts=16, cache_cap=16,
+                             top_k=4, sim="uniform")
+    wl = make_workload(shp, n_layers=2, tokens=3)
+    orc = O.oracle_from_workload(wl)
+    for t in range(3):
+        for l in range(2):
+            res = orc.decode_layer(l, as_numpy(wl.x[t, l]))
+            want = _dense_plain_moe(wl, l, wl.x[t, l, 0], shp.renorm_topk)
+            np.testing.assert_allclose(res.y[0], want, rtol=1e-11, atol=1e-15)
