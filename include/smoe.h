@@ -1,0 +1,194 @@
+/*
+ * smoe.h -- C ABI of the MI355X (gfx950) SMoE offloaded-MoE decode library.
+ *
+ * One decode step of one MoE layer under the SMoE expert scheduler
+ * (arxiv 2508.18983):
+ *   router            gate GEMV, softmax over the routed experts, top-k
+ *                     (Section II-A; Algorithm 1, "Sort S_t desc")
+ *   expert-cache      low-score active experts that are not in the HBM expert
+ *   router            cache are replaced by eligible resident experts
+ *                     (Section IV-B, Algorithm 1; thresholds T, L, R around the
+ *                     (k+1)-th score S_{k+1}, Table "Definitions")
+ *   cache update      score-history eviction (Eq. 3) with the protection shield
+ *                     (Section IV-B "Cache eviction"; Section V-B dependency 1)
+ *   on-demand load    remaining misses are copied host -> HBM on a side stream
+ *                     (Section V-B, "Loading Experts from Layer i", dependency 2)
+ *   expert FFN        SwiGLU FFN of the chosen experts + shared experts and the
+ *                     weighted combine (Section V-B GPU operations 2 and 4,
+ *                     Section II-A for shared experts)
+ *
+ * All entry points return 0 on success or a negative SMOE_E* code; nothing
+ * throws across this boundary.  "device" pointers are HIP device pointers on
+ * the current device, "host" pointers are ordinary process memory, "pinned
+ * host" pointers come from hipHostMalloc (or an equivalent allocator).  The
+ * library never allocates or frees expert weights: the caller owns the host
+ * copy of every expert, the HBM cache slab, the gate and shared-expert weights
+ * and the two streams, and must keep them alive until moe_cache_destroy.  The
+ * library owns only its bookkeeping, a device copy of the similarity tables,
+ * a few hundred KB of device scratch and its events.
+ *
+ * A handle is not thread-safe.  Work is enqueued on the caller's compute
+ * stream; moe_decode_layer returns once the routing decision of this call has
+ * reached the host (it waits for the router kernel only, the FFN kernels are
+ * still in flight).  Calls on one handle that overlap race on its scratch.
+ */
+#ifndef SMOE_H_
+#define SMOE_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SMOE_MAX_EXPERTS 64   /* routed experts per layer: residency is one 64-bit mask */
+#define SMOE_MAX_TOPK     8
+#define SMOE_MAX_BATCH    8
+#define SMOE_MAX_SHARED   4
+#define SMOE_MAX_HIDDEN   8192
+
+#define SMOE_OK         0
+#define SMOE_EINVAL    -1   /* bad argument, shape or layout */
+#define SMOE_EHIP      -2   /* a HIP runtime call failed: see moe_last_hip_error() */
+#define SMOE_ENOTPINNED -3  /* experts_host is not pinned host memory */
+#define SMOE_ESTATE    -4   /* call not valid in the handle's state */
+
+#define SMOE_DTYPE_FP32 0
+#define SMOE_DTYPE_BF16 1
+
+typedef struct moe_handle moe_handle_t;   /* opaque, library-owned */
+
+typedef struct {
+  int32_t n_layers;      /* L                                                        */
+  int32_t hidden;        /* H, multiple of 8, <= SMOE_MAX_HIDDEN                     */
+  int32_t n_experts;     /* E routed experts per layer, <= SMOE_MAX_EXPERTS          */
+  int32_t ffn;           /* F of a routed expert, multiple of 8                      */
+  int32_t top_k;         /* k, 1 <= k <= min(E, SMOE_MAX_TOPK)                       */
+  int32_t cache_cap;     /* experts resident in HBM per layer, k <= cap <= E         */
+  int32_t n_shared;      /* always-resident shared experts per layer (weight 1)      */
+  int32_t shared_ffn;    /* F of one shared expert, multiple of 8 (0 if none)        */
+  int32_t dtype;         /* SMOE_DTYPE_*: type of weights, x and y                   */
+  int32_t max_batch;     /* 1..SMOE_MAX_BATCH tokens per call                        */
+  float   alpha;         /* substitution threshold of Algorithm 1; 0 disables it     */
+  int32_t subst_key;     /* ranking of eligible substitutes: 0 = similarity-table
+                            row of the replaced expert, 1 = gate score (Section IV-B) */
+  int32_t renorm_topk;   /* 1: combine weights divided by the sum of the k selected
+                            scores; 0: raw softmax scores                            */
+  int32_t evict_window;  /* n of Eq. 3: the mean runs over the last n+1 steps        */
+  int32_t n_stage;       /* transient slots after the L*cap cache slots, used when a
+                            missing expert finds no evictable resident (batch > 1)   */
+} moe_cfg_t;
+
+typedef struct {
+  const void*    gate_w_dev;      /* device  [L][E][H] dtype, row e = expert e                */
+  const void*    experts_host;    /* pinned host [L][E]{W1[F][H], W3[F][H], W2[H][F]} dtype:
+                                     W1 gate-projection, W3 up-projection, W2 down-projection,
+                                     each row-major, the three back to back                   */
+  const void*    shared_dev;      /* device  [L][n_shared]{W1[Fs][H], W3[Fs][H], W2[H][Fs]}
+                                     or NULL when n_shared == 0                               */
+  const float*   sim_host;        /* host    [L][E][E] fp32 similarity table, copied at init  */
+  void*          cache_slab_dev;  /* device  (L*cache_cap + n_stage) slots of
+                                     3*H*F*sizeof(dtype) bytes; slot l*cap+s belongs to
+                                     layer l; 256-byte aligned; contents overwritten          */
+  const int32_t* init_resident;   /* host    [L][cache_cap] distinct expert ids, or NULL for
+                                     experts 0..cap-1 in every layer                          */
+  void*          stream_compute;  /* hipStream_t all kernels run on                           */
+  void*          stream_copy;     /* hipStream_t the expert loads run on (must differ)        */
+} moe_buffers_t;
+
+/* Optional per-call trace, host memory owned by the caller, every pointer may be NULL. */
+typedef struct {
+  int32_t* topk_idx;     /* [B][k]  experts selected by the router, by descending score   */
+  int32_t* final_idx;    /* [B][k]  expert each slot computes after substitution          */
+  uint8_t* substituted;  /* [B][k]  1 where final_idx differs from topk_idx                */
+  uint8_t* hit;          /* [B][k]  1 where the slot was served without a load            */
+  float*   scores;       /* [B][E]  gate scores                                           */
+  float*   weights;      /* [B][k]  combine weight of each slot                           */
+  int32_t* fetched;      /* [B*k]   distinct experts loaded by this call, in load order,
+                                    -1 padded                                             */
+  int32_t* victims;      /* [B*k]   expert evicted for each load, -1 = staged / padding   */
+  int32_t  n_fetched;    /* out: number of loads issued by this call                      */
+} moe_trace_t;
+
+typedef struct {
+  int64_t tokens;         /* tokens decoded (per layer: calls * batch)                     */
+  int64_t slots;          /* tokens * k                                                    */
+  int64_t raw_hits;       /* sum |G n E_a|: router choices already resident               */
+  int64_t hits;           /* slots served without a load, after substitution (Eq. 1)      */
+  int64_t misses;         /* slots - hits                                                  */
+  int64_t substitutions;  /* slots whose expert was replaced                               */
+  int64_t evictions;      /* residents replaced by a loaded expert                         */
+  int64_t staged;         /* loads computed from a transient slot, not inserted            */
+  int64_t fetches;        /* expert loads issued                                           */
+  int64_t bytes_fetched;  /* fetches * expert bytes                                        */
+} moe_stats_t;
+
+/* In-stream duration of the launches, measured with HIP events recorded on the
+ * launching stream around every launch while profiling is enabled.  Kinds:
+ * the router kernel; the up / down FFN kernels of the resident pass; the host
+ * to HBM expert copies; the up / down kernels of the pass over loaded experts.
+ * bytes = algorithmic bytes those launches had to move (gate matrix; expert
+ * weights streamed once; expert bytes copied). */
+#define SMOE_PROF_ROUTE       0
+#define SMOE_PROF_UP          1
+#define SMOE_PROF_DOWN        2
+#define SMOE_PROF_COPY        3
+#define SMOE_PROF_UP_LOADED   4
+#define SMOE_PROF_DOWN_LOADED 5
+#define SMOE_PROF_KINDS       6
+typedef struct {
+  int64_t launches[SMOE_PROF_KINDS];
+  double  ms[SMOE_PROF_KINDS];      /* summed over the recorded launches */
+  int64_t bytes[SMOE_PROF_KINDS];
+} moe_profile_t;
+
+/* Create a handle: validates cfg, uploads the similarity tables, copies the
+ * initial residents into the slab (on stream_copy, waited for) and zeroes
+ * history and statistics.  SMOE_EINVAL for shapes outside the limits above,
+ * cap < k, duplicate ids in init_resident, NULL buffers or equal streams;
+ * SMOE_ENOTPINNED when experts_host is not pinned; SMOE_EHIP on HIP errors. */
+int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t** out);
+
+/* Decode `batch` tokens through MoE layer `layer`.
+ *   x_dev  device [batch][H] dtype (read by kernels until the stream drains)
+ *   y_dev  device [batch][H] dtype, overwritten with
+ *          sum_j w_j FFN_{final_j}(x) + sum_shared FFN_s(x)
+ * Enqueues router + substitution, the FFN over resident experts, and -- when
+ * the step has misses -- victim selection, the loads on stream_copy and a
+ * second FFN pass over the loaded experts.  y is complete when the compute
+ * stream has drained.  With a trace the call also fills it (host data only).
+ * SMOE_EINVAL for a bad layer / batch or NULL x, y. */
+int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch,
+                     const void* x_dev, void* y_dev, moe_trace_t* trace_or_null);
+
+/* Counters of one layer, or of all layers summed when layer == -1. */
+int moe_cache_stats(const moe_handle_t* h, int32_t layer, moe_stats_t* out);
+
+/* Expert id held by each cache slot of `layer`: out_slots[cache_cap]. */
+int moe_cache_residency(const moe_handle_t* h, int32_t layer, int32_t* out_slots);
+
+/* Drain both streams, reload the initial residents, zero history and counters. */
+int moe_cache_reset(moe_handle_t* h);
+
+/* Drain both streams and release everything the library owns. */
+int moe_cache_destroy(moe_handle_t* h);
+
+/* Per-kernel timing.  enable = 1 starts recording event pairs (at most
+ * max_launches launches per kernel are recorded), enable = 0 stops.
+ * moe_profile_read drains the compute and copy streams and returns the totals
+ * recorded since the last enable. */
+int moe_profile_enable(moe_handle_t* h, int32_t enable, int32_t max_launches);
+int moe_profile_read(moe_handle_t* h, moe_profile_t* out);
+
+/* hipError_t of the most recent failing HIP call in this thread (0 if none). */
+int moe_last_hip_error(void);
+
+/* Plain device-to-device copy kernel (n_bytes multiple of 16, both pointers
+ * 16-byte aligned) on `stream`: the known-size kernel hardware counters are
+ * calibrated against.  Returns SMOE_EINVAL on misaligned arguments. */
+int moe_calib_copy(void* dst_dev, const void* src_dev, int64_t n_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SMOE_H_ */

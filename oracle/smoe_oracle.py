@@ -146,7 +146,8 @@ def cache_router(info: RouteInfo, resident: Set[int], batch_top: Set[int],
     for c in range(len(s)):
         if c in active or c not in available:
             continue
-        if info.R > 0:
+        if info.R > 0 and c != int(info.order[len(info.topk)]):
+            # (the (k+1)-th expert itself always passes: s >= (1-alpha) s)
             margin = min(margin, abs(np.log(s[c] / info.R)))
         if s[c] >= info.R:
             cand.append(c)
@@ -268,7 +269,7 @@ class SMoEOracle:
                  sim: np.ndarray, shared: Optional[np.ndarray] = None, n_shared: int = 0,
                  shared_ffn: int = 0, subst_key: int = 0, renorm_topk: int = 1,
                  evict_window: int = 3, init_resident: Optional[np.ndarray] = None,
-                 elem_bytes: int = 2):
+                 elem_bytes: int = 2, widen_cache_bytes: int = 6 << 30):
         if not (top_k <= cache_cap <= n_experts):
             raise ValueError("need top_k <= cache_cap <= n_experts")
         self.L, self.H, self.E, self.F, self.k = n_layers, hidden, n_experts, ffn, top_k
@@ -278,7 +279,9 @@ class SMoEOracle:
         self.subst_key, self.renorm, self.window = subst_key, renorm_topk, evict_window
         self.expert_bytes = 3 * hidden * ffn * elem_bytes
         self._init_resident = init_resident
-        self._wcache: Dict = {}
+        self._wcache: Dict = {}          # fp64 copies of recently used experts (memo only)
+        self._wcache_bytes = 0
+        self._wcache_limit = widen_cache_bytes
         self.reset()
 
     # -- state ------------------------------------------------------------
@@ -316,9 +319,11 @@ class SMoEOracle:
         w1 = widen(flat[:hf]).reshape(F, H)
         w3 = widen(flat[hf:2 * hf]).reshape(F, H)
         w2 = widen(flat[2 * hf:3 * hf]).reshape(H, F)
-        if len(self._wcache) >= 24 or hf > (1 << 24):
+        if self._wcache_bytes + 24 * hf > self._wcache_limit:
             self._wcache.clear()
+            self._wcache_bytes = 0
         self._wcache[key] = (w1, w3, w2)
+        self._wcache_bytes += 24 * hf
         return w1, w3, w2
 
     # -- the step ---------------------------------------------------------

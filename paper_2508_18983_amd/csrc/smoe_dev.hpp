@@ -1,0 +1,72 @@
+// Device-side records and launch arguments shared by the kernels and the host
+// scheduler of libsmoe.  Not part of the public ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "smoe.h"
+
+namespace smoe {
+
+constexpr int kWave = 64;
+constexpr int kMaxTasks = SMOE_MAX_BATCH * (SMOE_MAX_TOPK + SMOE_MAX_SHARED);
+constexpr int kMaxChunks = 8;          // F-chunks of the down projection
+constexpr int kChunkElems = 4096;      // fp32 activations one down-projection block keeps in LDS
+
+// Routing decision of one token, written by the router kernel to device memory
+// (read by the FFN kernels) and to a pinned host mirror (read by the scheduler).
+struct TokRec {
+  int32_t topk[SMOE_MAX_TOPK];     // E_a by descending score
+  int32_t final_[SMOE_MAX_TOPK];   // expert computed in each slot after substitution
+  int32_t slot[SMOE_MAX_TOPK];     // cache slot (layer-local) of final_, -1 when not resident
+  int32_t subst[SMOE_MAX_TOPK];    // 1 where final_ != topk
+  float   w[SMOE_MAX_TOPK];        // combine weight
+  float   scores[SMOE_MAX_EXPERTS];
+};
+struct StepRec {
+  TokRec tok[SMOE_MAX_BATCH];
+};
+
+struct RouteArgs {
+  const void* gate_w;   // [E][H] of this layer
+  const void* x;        // [B][H]
+  const float* sim;     // [E][E] of this layer (device)
+  StepRec* rec_dev;
+  StepRec* rec_host;    // device-visible address of the pinned mirror
+  int32_t B, H, E, k;
+  int32_t renorm, subst_key;
+  float alpha;
+  uint64_t resident;                  // bit e = expert e is in the HBM cache
+  int8_t slot_of[SMOE_MAX_EXPERTS];   // layer-local slot of each resident expert
+};
+
+// One launch of the up (gate/up projection + SwiGLU) or down (down projection
+// + combine) kernel.  Task index = token * (k + ns) + j, j < k routed slot j,
+// j >= k shared expert j - k.
+struct FfnArgs {
+  const StepRec* rec;
+  const void* x;            // [B][H]
+  void* y;                  // [B][H]
+  const char* slab;         // cache slab base
+  const char* shared;       // this layer's shared experts, or null
+  float* act;               // [task][Fmax] weighted SwiGLU activations
+  float* partial;           // [task][kMaxChunks][H]
+  uint32_t* counters;       // [B][htiles]
+  int64_t expert_bytes;     // bytes of one routed expert
+  int64_t shared_bytes;     // bytes of one shared expert
+  int32_t B, H, F, Fs, k, ns;
+  int32_t Fmax;
+  int32_t slot_base;        // layer * cache_cap
+  int32_t pass;             // 0: routed tasks whose expert is resident + shared; 1: slot_override >= 0 only
+  int32_t TF, tilesR, tilesS;              // up: f-rows per block, blocks per routed / shared task
+  int32_t RB, htiles;                      // down: output rows per block
+  int32_t chunksR, chunksS, fcR, fcS;      // down: F-chunks per task and their length
+  int32_t slot_override[kMaxTasks];        // pass 1: global slot per task, -1 = not in this pass
+};
+
+void launch_route(const RouteArgs& a, int dtype, hipStream_t s);
+void launch_ffn_up(const FfnArgs& a, int dtype, hipStream_t s);
+void launch_ffn_down(const FfnArgs& a, int dtype, hipStream_t s);
+void launch_copy(void* dst, const void* src, int64_t n_bytes, hipStream_t s);
+void launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t s);
+
+}  // namespace smoe

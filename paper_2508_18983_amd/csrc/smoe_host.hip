@@ -1,0 +1,523 @@
+// Host side of libsmoe: the C ABI, the expert-cache bookkeeping (score history,
+// Eq. 3 eviction, protection shield; Section IV-B "Cache eviction") and the
+// two-stream schedule of one layer call (Section V-B: resident experts are
+// computed while the misses are loaded; loaded experts are computed after
+// their copy completes).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "smoe.h"
+#include "smoe_dev.hpp"
+
+using namespace smoe;
+
+namespace {
+
+thread_local int g_last_hip = 0;
+
+#define HIP_TRY(expr)                         \
+  do {                                        \
+    hipError_t e_ = (expr);                   \
+    if (e_ != hipSuccess) {                   \
+      g_last_hip = (int)e_;                   \
+      return SMOE_EHIP;                       \
+    }                                         \
+  } while (0)
+
+struct LayerState {
+  uint64_t resident = 0;
+  int8_t slot_of[SMOE_MAX_EXPERTS];
+  std::vector<int32_t> expert_of_slot;   // [cap]
+  std::vector<double> hist;              // ring [(n+1)][E] of batch-mean score vectors
+  int hist_count = 0, hist_head = 0;
+  moe_stats_t st{};
+};
+
+struct EventPair { hipEvent_t a, b; };
+struct ProfKind {
+  std::vector<EventPair> ev;
+  size_t used = 0;
+  int64_t bytes = 0;
+};
+
+}  // namespace
+
+struct moe_handle {
+  moe_cfg_t cfg{};
+  moe_buffers_t buf{};
+  hipStream_t s_compute = nullptr, s_copy = nullptr;
+  hipEvent_t ev_route = nullptr, ev_copy = nullptr;
+  int64_t esize = 0, expert_bytes = 0, shared_bytes = 0;
+  int Fmax = 0;
+  std::vector<LayerState> layers;
+  std::vector<int32_t> init_resident;    // [L][cap]
+  // device scratch
+  float* sim_dev = nullptr;
+  StepRec* rec_dev = nullptr;
+  StepRec* rec_host = nullptr;           // pinned
+  StepRec* rec_host_dev = nullptr;       // its device-visible address
+  float* act = nullptr;
+  float* partial = nullptr;
+  uint32_t* counters = nullptr;
+  int counters_n = 0;
+  // launch geometry
+  int TF = 0, tilesR = 0, tilesS = 0, RB = 0, htiles = 0, chunksR = 0, chunksS = 0, fcR = 0, fcS = 0;
+  // profiling
+  bool prof_on = false;
+  ProfKind prof[SMOE_PROF_KINDS];
+};
+
+namespace {
+
+int env_int(const char* name, int dflt) {
+  const char* v = std::getenv(name);
+  if (!v || !*v) return dflt;
+  return std::atoi(v);
+}
+
+void chunking(int F, int elem_units, int& chunks, int& fc) {
+  if (F <= 0) { chunks = 0; fc = 0; return; }
+  chunks = (F + kChunkElems - 1) / kChunkElems;
+  const int q = 64 * elem_units;                      // one wave pass
+  fc = ((F + chunks - 1) / chunks + q - 1) / q * q;
+  if (fc > kChunkElems) fc = kChunkElems;
+  chunks = (F + fc - 1) / fc;
+}
+
+void plan_geometry(moe_handle* h) {
+  const moe_cfg_t& c = h->cfg;
+  const int n = c.dtype == SMOE_DTYPE_FP32 ? 4 : 8;
+  const long total_f = (long)c.top_k * c.ffn + (long)c.n_shared * c.shared_ffn;
+  int tf = total_f >= 32 * 1024 ? 32 : (total_f >= 16 * 1024 ? 16 : 8);
+  tf = env_int("SMOE_TF", tf);
+  if (tf < 8) tf = 8;
+  tf = tf / 8 * 8;
+  h->TF = tf;
+  h->tilesR = (c.ffn + tf - 1) / tf;
+  h->tilesS = c.n_shared ? (c.shared_ffn + tf - 1) / tf : 0;
+  chunking(c.ffn, n, h->chunksR, h->fcR);
+  chunking(c.n_shared ? c.shared_ffn : 0, n, h->chunksS, h->fcS);
+  const long pairs = (long)c.top_k * h->chunksR + (long)c.n_shared * h->chunksS;
+  int rb = (pairs * ((c.hidden + 31) / 32) >= 1024) ? 32 : 16;
+  rb = env_int("SMOE_RB", rb);
+  if (rb < 16) rb = 16;
+  rb = rb / 16 * 16;
+  h->RB = rb;
+  h->htiles = (c.hidden + rb - 1) / rb;
+}
+
+int upload_initial(moe_handle* h) {
+  const moe_cfg_t& c = h->cfg;
+  for (int l = 0; l < c.n_layers; ++l) {
+    LayerState& ls = h->layers[l];
+    ls.resident = 0;
+    std::memset(ls.slot_of, -1, sizeof(ls.slot_of));
+    ls.expert_of_slot.assign(c.cache_cap, -1);
+    ls.hist.assign((size_t)(c.evict_window + 1) * c.n_experts, 0.0);
+    ls.hist_count = 0;
+    ls.hist_head = 0;
+    ls.st = moe_stats_t{};
+    for (int s = 0; s < c.cache_cap; ++s) {
+      const int e = h->init_resident[(size_t)l * c.cache_cap + s];
+      ls.resident |= 1ull << e;
+      ls.slot_of[e] = (int8_t)s;
+      ls.expert_of_slot[s] = e;
+      const char* src = static_cast<const char*>(h->buf.experts_host) +
+                        ((int64_t)l * c.n_experts + e) * h->expert_bytes;
+      char* dst = static_cast<char*>(h->buf.cache_slab_dev) +
+                  ((int64_t)l * c.cache_cap + s) * h->expert_bytes;
+      HIP_TRY(hipMemcpyAsync(dst, src, h->expert_bytes, hipMemcpyHostToDevice, h->s_copy));
+    }
+  }
+  HIP_TRY(hipStreamSynchronize(h->s_copy));
+  launch_fill_u32(h->counters, h->counters_n, 0u, h->s_compute);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipStreamSynchronize(h->s_compute));
+  return SMOE_OK;
+}
+
+void free_all(moe_handle* h) {
+  if (!h) return;
+  for (auto& k : h->prof)
+    for (auto& p : k.ev) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
+  if (h->ev_route) (void)hipEventDestroy(h->ev_route);
+  if (h->ev_copy) (void)hipEventDestroy(h->ev_copy);
+  if (h->sim_dev) (void)hipFree(h->sim_dev);
+  if (h->rec_dev) (void)hipFree(h->rec_dev);
+  if (h->rec_host) (void)hipHostFree(h->rec_host);
+  if (h->act) (void)hipFree(h->act);
+  if (h->partial) (void)hipFree(h->partial);
+  if (h->counters) (void)hipFree(h->counters);
+  delete h;
+}
+
+// Event pair around one launch while profiling; nullptr when not recording.
+EventPair* prof_begin(moe_handle* h, int kind, hipStream_t s) {
+  if (!h->prof_on) return nullptr;
+  ProfKind& k = h->prof[kind];
+  if (k.used >= k.ev.size()) return nullptr;
+  EventPair* p = &k.ev[k.used++];
+  (void)hipEventRecord(p->a, s);
+  return p;
+}
+void prof_end(EventPair* p, hipStream_t s) {
+  if (p) (void)hipEventRecord(p->b, s);
+}
+
+}  // namespace
+
+extern "C" {
+
+int moe_last_hip_error(void) { return g_last_hip; }
+
+int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t** out) {
+  if (!cfg || !buf || !out) return SMOE_EINVAL;
+  *out = nullptr;
+  const moe_cfg_t& c = *cfg;
+  if (c.dtype != SMOE_DTYPE_FP32 && c.dtype != SMOE_DTYPE_BF16) return SMOE_EINVAL;
+  if (c.n_layers < 1 || c.hidden < 8 || c.hidden > SMOE_MAX_HIDDEN || c.hidden % 8) return SMOE_EINVAL;
+  if (c.n_experts < 1 || c.n_experts > SMOE_MAX_EXPERTS) return SMOE_EINVAL;
+  if (c.ffn < 8 || c.ffn % 8) return SMOE_EINVAL;
+  if (c.top_k < 1 || c.top_k > SMOE_MAX_TOPK || c.top_k > c.n_experts) return SMOE_EINVAL;
+  if (c.cache_cap < c.top_k || c.cache_cap > c.n_experts) return SMOE_EINVAL;
+  if (c.n_shared < 0 || c.n_shared > SMOE_MAX_SHARED) return SMOE_EINVAL;
+  if (c.n_shared > 0 && (c.shared_ffn < 8 || c.shared_ffn % 8)) return SMOE_EINVAL;
+  if (c.max_batch < 1 || c.max_batch > SMOE_MAX_BATCH) return SMOE_EINVAL;
+  if (!(c.alpha >= 0.0f) || c.alpha >= 1.0f) return SMOE_EINVAL;
+  if (c.subst_key != 0 && c.subst_key != 1) return SMOE_EINVAL;
+  if (c.evict_window < 0 || c.evict_window > 1024 || c.n_stage < 0) return SMOE_EINVAL;
+  if (!buf->gate_w_dev || !buf->experts_host || !buf->sim_host || !buf->cache_slab_dev) return SMOE_EINVAL;
+  if (c.n_shared > 0 && !buf->shared_dev) return SMOE_EINVAL;
+  if (buf->stream_compute == buf->stream_copy) return SMOE_EINVAL;
+  if (reinterpret_cast<uintptr_t>(buf->cache_slab_dev) % 256) return SMOE_EINVAL;
+
+  hipPointerAttribute_t attr;
+  hipError_t pe = hipPointerGetAttributes(&attr, buf->experts_host);
+  if (pe != hipSuccess) { (void)hipGetLastError(); return SMOE_ENOTPINNED; }
+  if (attr.type != hipMemoryTypeHost) return SMOE_ENOTPINNED;
+
+  moe_handle* h = new (std::nothrow) moe_handle();
+  if (!h) return SMOE_EINVAL;
+  h->cfg = c;
+  h->buf = *buf;
+  h->s_compute = static_cast<hipStream_t>(buf->stream_compute);
+  h->s_copy = static_cast<hipStream_t>(buf->stream_copy);
+  h->esize = c.dtype == SMOE_DTYPE_FP32 ? 4 : 2;
+  h->expert_bytes = 3ll * c.hidden * c.ffn * h->esize;
+  h->shared_bytes = 3ll * c.hidden * c.shared_ffn * h->esize;
+  h->Fmax = std::max(c.ffn, c.n_shared ? c.shared_ffn : 0);
+  h->layers.resize(c.n_layers);
+  h->init_resident.resize((size_t)c.n_layers * c.cache_cap);
+  for (int l = 0; l < c.n_layers; ++l) {
+    uint64_t seen = 0;
+    for (int s = 0; s < c.cache_cap; ++s) {
+      const int e = buf->init_resident ? buf->init_resident[(size_t)l * c.cache_cap + s] : s;
+      if (e < 0 || e >= c.n_experts || ((seen >> e) & 1ull)) { delete h; return SMOE_EINVAL; }
+      seen |= 1ull << e;
+      h->init_resident[(size_t)l * c.cache_cap + s] = e;
+    }
+  }
+  h->buf.init_resident = nullptr;
+  plan_geometry(h);
+
+  const int nj = c.top_k + c.n_shared;
+  const size_t sim_bytes = (size_t)c.n_layers * c.n_experts * c.n_experts * sizeof(float);
+  h->counters_n = c.max_batch * h->htiles;
+  int rc = [&]() -> int {
+    HIP_TRY(hipEventCreateWithFlags(&h->ev_route, hipEventDisableTiming));
+    HIP_TRY(hipEventCreateWithFlags(&h->ev_copy, hipEventDisableTiming));
+    HIP_TRY(hipMalloc(&h->sim_dev, sim_bytes));
+    HIP_TRY(hipMemcpy(h->sim_dev, buf->sim_host, sim_bytes, hipMemcpyHostToDevice));
+    HIP_TRY(hipMalloc(&h->rec_dev, sizeof(StepRec)));
+    HIP_TRY(hipHostMalloc(&h->rec_host, sizeof(StepRec), hipHostMallocDefault));
+    std::memset(h->rec_host, 0, sizeof(StepRec));
+    void* dp = nullptr;
+    HIP_TRY(hipHostGetDevicePointer(&dp, h->rec_host, 0));
+    h->rec_host_dev = static_cast<StepRec*>(dp);
+    HIP_TRY(hipMalloc(&h->act, (size_t)c.max_batch * nj * h->Fmax * sizeof(float)));
+    HIP_TRY(hipMalloc(&h->partial, (size_t)c.max_batch * nj * kMaxChunks * c.hidden * sizeof(float)));
+    HIP_TRY(hipMalloc(&h->counters, (size_t)h->counters_n * sizeof(uint32_t)));
+    return upload_initial(h);
+  }();
+  if (rc != SMOE_OK) { free_all(h); return rc; }
+  if (h->chunksR > kMaxChunks || h->chunksS > kMaxChunks) { free_all(h); return SMOE_EINVAL; }
+  *out = h;
+  return SMOE_OK;
+}
+
+int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* x_dev, void* y_dev,
+                     moe_trace_t* trace) {
+  if (!h || !x_dev || !y_dev) return SMOE_EINVAL;
+  const moe_cfg_t& c = h->cfg;
+  if (layer < 0 || layer >= c.n_layers || batch < 1 || batch > c.max_batch) return SMOE_EINVAL;
+  LayerState& ls = h->layers[layer];
+  const int k = c.top_k, E = c.n_experts, B = batch, nj = k + c.n_shared;
+
+  // ---- router + expert-cache router ------------------------------------------
+  RouteArgs ra{};
+  ra.gate_w = static_cast<const char*>(h->buf.gate_w_dev) + (int64_t)layer * E * c.hidden * h->esize;
+  ra.x = x_dev;
+  ra.sim = h->sim_dev + (size_t)layer * E * E;
+  ra.rec_dev = h->rec_dev;
+  ra.rec_host = h->rec_host_dev;
+  ra.B = B; ra.H = c.hidden; ra.E = E; ra.k = k;
+  ra.renorm = c.renorm_topk; ra.subst_key = c.subst_key; ra.alpha = c.alpha;
+  ra.resident = ls.resident;
+  std::memcpy(ra.slot_of, ls.slot_of, sizeof(ra.slot_of));
+  EventPair* pr = prof_begin(h, SMOE_PROF_ROUTE, h->s_compute);
+  launch_route(ra, c.dtype, h->s_compute);
+  prof_end(pr, h->s_compute);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipEventRecord(h->ev_route, h->s_compute));
+
+  // ---- FFN over what is already resident (+ shared experts), enqueued before
+  //      the host knows the routing result ------------------------------------
+  FfnArgs fa{};
+  fa.rec = h->rec_dev;
+  fa.x = x_dev; fa.y = y_dev;
+  fa.slab = static_cast<const char*>(h->buf.cache_slab_dev);
+  fa.shared = c.n_shared ? static_cast<const char*>(h->buf.shared_dev) +
+                               (int64_t)layer * c.n_shared * h->shared_bytes
+                         : nullptr;
+  fa.act = h->act; fa.partial = h->partial; fa.counters = h->counters;
+  fa.expert_bytes = h->expert_bytes; fa.shared_bytes = h->shared_bytes;
+  fa.B = B; fa.H = c.hidden; fa.F = c.ffn; fa.Fs = c.n_shared ? c.shared_ffn : 0;
+  fa.k = k; fa.ns = c.n_shared; fa.Fmax = h->Fmax;
+  fa.slot_base = layer * c.cache_cap;
+  fa.pass = 0;
+  fa.TF = h->TF; fa.tilesR = h->tilesR; fa.tilesS = h->tilesS;
+  fa.RB = h->RB; fa.htiles = h->htiles;
+  fa.chunksR = h->chunksR; fa.chunksS = h->chunksS; fa.fcR = h->fcR; fa.fcS = h->fcS;
+  for (int i = 0; i < kMaxTasks; ++i) fa.slot_override[i] = -1;
+  EventPair* pu = prof_begin(h, SMOE_PROF_UP, h->s_compute);
+  launch_ffn_up(fa, c.dtype, h->s_compute);
+  prof_end(pu, h->s_compute);
+  EventPair* pd = prof_begin(h, SMOE_PROF_DOWN, h->s_compute);
+  launch_ffn_down(fa, c.dtype, h->s_compute);
+  prof_end(pd, h->s_compute);
+  HIP_TRY(hipGetLastError());
+
+  // ---- the decision reaches the host -----------------------------------------
+  HIP_TRY(hipEventSynchronize(h->ev_route));
+  const StepRec& rec = *h->rec_host;
+
+  // history: one entry per step, the batch mean of the score vectors (Eq. 3 window)
+  {
+    double* row = &ls.hist[(size_t)ls.hist_head * E];
+    for (int e = 0; e < E; ++e) {
+      double s = 0.0;
+      for (int t = 0; t < B; ++t) s += (double)rec.tok[t].scores[e];
+      row[e] = s / B;
+    }
+    ls.hist_head = (ls.hist_head + 1) % (c.evict_window + 1);
+    if (ls.hist_count < c.evict_window + 1) ++ls.hist_count;
+  }
+
+  // shield = every expert this step computes; misses in (token, slot) order
+  const uint64_t before = ls.resident;
+  uint64_t shield = 0;
+  int fetched[SMOE_MAX_BATCH * SMOE_MAX_TOPK], victims[SMOE_MAX_BATCH * SMOE_MAX_TOPK];
+  int gslot[SMOE_MAX_BATCH * SMOE_MAX_TOPK];
+  int n_fetch = 0;
+  int64_t raw_hits = 0, hits = 0, subs = 0;
+  for (int t = 0; t < B; ++t)
+    for (int j = 0; j < k; ++j) {
+      const int e = rec.tok[t].final_[j];
+      if (e < 0 || e >= E) return SMOE_ESTATE;
+      shield |= 1ull << e;
+      raw_hits += (before >> rec.tok[t].topk[j]) & 1ull;
+      subs += rec.tok[t].subst[j] != 0;
+      if ((before >> e) & 1ull) { ++hits; continue; }
+      bool dup = false;
+      for (int i = 0; i < n_fetch; ++i) dup |= fetched[i] == e;
+      if (!dup) fetched[n_fetch++] = e;
+    }
+
+  int n_staged = 0, n_evict = 0;
+  if (n_fetch > 0) {
+    double mean[SMOE_MAX_EXPERTS];
+    for (int e = 0; e < E; ++e) {
+      double s = 0.0;
+      for (int i = 0; i < ls.hist_count; ++i) s += ls.hist[(size_t)i * E + e];
+      mean[e] = s / ls.hist_count;
+    }
+    for (int i = 0; i < n_fetch; ++i) {
+      int victim = -1;
+      for (int e = 0; e < E; ++e) {
+        if (!((ls.resident >> e) & 1ull) || ((shield >> e) & 1ull)) continue;
+        if (victim < 0 || mean[e] < mean[victim]) victim = e;
+      }
+      victims[i] = victim;
+      const int m = fetched[i];
+      if (victim >= 0) {
+        const int s = ls.slot_of[victim];
+        ls.resident = (ls.resident & ~(1ull << victim)) | (1ull << m);
+        ls.slot_of[victim] = -1;
+        ls.slot_of[m] = (int8_t)s;
+        ls.expert_of_slot[s] = m;
+        gslot[i] = layer * c.cache_cap + s;
+        ++n_evict;
+      } else {
+        if (n_staged >= c.n_stage) return SMOE_ESTATE;   // out of transient slots
+        gslot[i] = c.n_layers * c.cache_cap + n_staged++;
+      }
+      const char* src = static_cast<const char*>(h->buf.experts_host) +
+                        ((int64_t)layer * E + m) * h->expert_bytes;
+      char* dst = static_cast<char*>(h->buf.cache_slab_dev) + (int64_t)gslot[i] * h->expert_bytes;
+      EventPair* pc = prof_begin(h, SMOE_PROF_COPY, h->s_copy);
+      HIP_TRY(hipMemcpyAsync(dst, src, h->expert_bytes, hipMemcpyHostToDevice, h->s_copy));
+      prof_end(pc, h->s_copy);
+    }
+    HIP_TRY(hipEventRecord(h->ev_copy, h->s_copy));
+    HIP_TRY(hipStreamWaitEvent(h->s_compute, h->ev_copy, 0));
+    // second FFN pass: only the slots whose expert has just been loaded
+    fa.pass = 1;
+    for (int t = 0; t < B; ++t)
+      for (int j = 0; j < k; ++j) {
+        const int e = rec.tok[t].final_[j];
+        if ((before >> e) & 1ull) continue;
+        for (int i = 0; i < n_fetch; ++i)
+          if (fetched[i] == e) fa.slot_override[t * nj + j] = gslot[i];
+      }
+    EventPair* pu2 = prof_begin(h, SMOE_PROF_UP_LOADED, h->s_compute);
+    launch_ffn_up(fa, c.dtype, h->s_compute);
+    prof_end(pu2, h->s_compute);
+    EventPair* pd2 = prof_begin(h, SMOE_PROF_DOWN_LOADED, h->s_compute);
+    launch_ffn_down(fa, c.dtype, h->s_compute);
+    prof_end(pd2, h->s_compute);
+    HIP_TRY(hipGetLastError());
+  }
+  if (h->prof_on) {
+    // algorithmic bytes each timed launch was asked to stream
+    const int64_t miss_slots = (int64_t)B * k - hits;
+    const int64_t up_r = 2ll * c.hidden * c.ffn * h->esize, up_s = 2ll * c.hidden * c.shared_ffn * h->esize;
+    h->prof[SMOE_PROF_ROUTE].bytes += (int64_t)E * c.hidden * h->esize;
+    h->prof[SMOE_PROF_UP].bytes += hits * up_r + (int64_t)B * c.n_shared * up_s;
+    h->prof[SMOE_PROF_DOWN].bytes += (hits * up_r + (int64_t)B * c.n_shared * up_s) / 2;
+    h->prof[SMOE_PROF_COPY].bytes += (int64_t)n_fetch * h->expert_bytes;
+    h->prof[SMOE_PROF_UP_LOADED].bytes += miss_slots * up_r;
+    h->prof[SMOE_PROF_DOWN_LOADED].bytes += miss_slots * up_r / 2;
+  }
+
+  ls.st.tokens += B;
+  ls.st.slots += (int64_t)B * k;
+  ls.st.raw_hits += raw_hits;
+  ls.st.hits += hits;
+  ls.st.misses += (int64_t)B * k - hits;
+  ls.st.substitutions += subs;
+  ls.st.evictions += n_evict;
+  ls.st.staged += n_staged;
+  ls.st.fetches += n_fetch;
+  ls.st.bytes_fetched += (int64_t)n_fetch * h->expert_bytes;
+
+  if (trace) {
+    for (int t = 0; t < B; ++t)
+      for (int j = 0; j < k; ++j) {
+        const int o = t * k + j;
+        if (trace->topk_idx) trace->topk_idx[o] = rec.tok[t].topk[j];
+        if (trace->final_idx) trace->final_idx[o] = rec.tok[t].final_[j];
+        if (trace->substituted) trace->substituted[o] = (uint8_t)(rec.tok[t].subst[j] != 0);
+        if (trace->hit) trace->hit[o] = (uint8_t)((before >> rec.tok[t].final_[j]) & 1ull);
+        if (trace->weights) trace->weights[o] = rec.tok[t].w[j];
+      }
+    if (trace->scores)
+      for (int t = 0; t < B; ++t)
+        std::memcpy(trace->scores + (size_t)t * E, rec.tok[t].scores, sizeof(float) * E);
+    for (int i = 0; i < B * k; ++i) {
+      if (trace->fetched) trace->fetched[i] = i < n_fetch ? fetched[i] : -1;
+      if (trace->victims) trace->victims[i] = i < n_fetch ? victims[i] : -1;
+    }
+    trace->n_fetched = n_fetch;
+  }
+  return SMOE_OK;
+}
+
+int moe_cache_stats(const moe_handle_t* h, int32_t layer, moe_stats_t* out) {
+  if (!h || !out || layer < -1 || layer >= h->cfg.n_layers) return SMOE_EINVAL;
+  moe_stats_t s{};
+  for (int l = 0; l < h->cfg.n_layers; ++l) {
+    if (layer >= 0 && l != layer) continue;
+    const moe_stats_t& a = h->layers[l].st;
+    s.tokens += a.tokens; s.slots += a.slots; s.raw_hits += a.raw_hits; s.hits += a.hits;
+    s.misses += a.misses; s.substitutions += a.substitutions; s.evictions += a.evictions;
+    s.staged += a.staged; s.fetches += a.fetches; s.bytes_fetched += a.bytes_fetched;
+  }
+  *out = s;
+  return SMOE_OK;
+}
+
+int moe_cache_residency(const moe_handle_t* h, int32_t layer, int32_t* out_slots) {
+  if (!h || !out_slots || layer < 0 || layer >= h->cfg.n_layers) return SMOE_EINVAL;
+  const LayerState& ls = h->layers[layer];
+  for (int s = 0; s < h->cfg.cache_cap; ++s) out_slots[s] = ls.expert_of_slot[s];
+  return SMOE_OK;
+}
+
+int moe_cache_reset(moe_handle_t* h) {
+  if (!h) return SMOE_EINVAL;
+  HIP_TRY(hipStreamSynchronize(h->s_compute));
+  HIP_TRY(hipStreamSynchronize(h->s_copy));
+  return upload_initial(h);
+}
+
+int moe_cache_destroy(moe_handle_t* h) {
+  if (!h) return SMOE_EINVAL;
+  (void)hipStreamSynchronize(h->s_compute);
+  (void)hipStreamSynchronize(h->s_copy);
+  free_all(h);
+  return SMOE_OK;
+}
+
+int moe_profile_enable(moe_handle_t* h, int32_t enable, int32_t max_launches) {
+  if (!h || (enable && max_launches < 1)) return SMOE_EINVAL;
+  HIP_TRY(hipStreamSynchronize(h->s_compute));
+  HIP_TRY(hipStreamSynchronize(h->s_copy));
+  if (enable) {
+    for (auto& k : h->prof) {
+      while ((int)k.ev.size() < max_launches) {
+        EventPair p{};
+        HIP_TRY(hipEventCreate(&p.a));
+        HIP_TRY(hipEventCreate(&p.b));
+        k.ev.push_back(p);
+      }
+      k.used = 0;
+      k.bytes = 0;
+    }
+  }
+  h->prof_on = enable != 0;
+  return SMOE_OK;
+}
+
+int moe_profile_read(moe_handle_t* h, moe_profile_t* out) {
+  if (!h || !out) return SMOE_EINVAL;
+  HIP_TRY(hipStreamSynchronize(h->s_compute));
+  HIP_TRY(hipStreamSynchronize(h->s_copy));
+  for (int kind = 0; kind < SMOE_PROF_KINDS; ++kind) {
+    double ms = 0.0;
+    for (size_t i = 0; i < h->prof[kind].used; ++i) {
+      float t = 0.f;
+      HIP_TRY(hipEventElapsedTime(&t, h->prof[kind].ev[i].a, h->prof[kind].ev[i].b));
+      ms += t;
+    }
+    out->launches[kind] = (int64_t)h->prof[kind].used;
+    out->ms[kind] = ms;
+    out->bytes[kind] = h->prof[kind].bytes;
+  }
+  return SMOE_OK;
+}
+
+int moe_calib_copy(void* dst_dev, const void* src_dev, int64_t n_bytes, void* stream) {
+  if (!dst_dev || !src_dev || n_bytes <= 0 || n_bytes % 16) return SMOE_EINVAL;
+  if (reinterpret_cast<uintptr_t>(dst_dev) % 16 || reinterpret_cast<uintptr_t>(src_dev) % 16)
+    return SMOE_EINVAL;
+  launch_copy(dst_dev, src_dev, n_bytes, static_cast<hipStream_t>(stream));
+  HIP_TRY(hipGetLastError());
+  return SMOE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,110 @@
+"""Device-memory plumbing around the C ABI: allocates the HBM cache slab and
+the I/O tensors with PyTorch, owns the two streams and forwards every call to
+libsmoe.  No arithmetic of the method happens here."""
+from __future__ import annotations
+
+from typing import Optional
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+class DecodeSession:
+    """One moe_handle_t plus the buffers it borrows.
+
+    ``shape`` needs the attributes n_layers, hidden, n_experts, ffn, top_k,
+    cache_cap, n_shared, shared_ffn, dtype ("fp32" | "bf16"), alpha, subst_key,
+    renorm_topk, evict_window.  ``experts`` is the host copy of all experts
+    [L, E, 3*H*F]; it is pinned here if it is not already."""
+
+    def __init__(self, shape, gate_w: torch.Tensor, experts: torch.Tensor,
+                 shared: Optional[torch.Tensor], sim: torch.Tensor, *, max_batch: int = 1,
+                 n_stage: int = 0, init_resident: Optional[np.ndarray] = None,
+                 device: str = "cuda:0", **cfg_override):
+        B.load_library()
+        if not torch.cuda.is_available():
+            raise RuntimeError("libsmoe needs a GPU: there is no CPU path")
+        self.shape = shape
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        self.tdtype = torch.float32 if shape.dtype == "fp32" else torch.bfloat16
+        esize = 4 if shape.dtype == "fp32" else 2
+        self.experts_host = experts if experts.is_pinned() else experts.pin_memory()
+        self.gate_w = gate_w.to(self.device).contiguous()
+        self.shared = shared.to(self.device).contiguous() if shared is not None else None
+        self.sim = sim.contiguous()
+        self.stream_compute = torch.cuda.Stream(self.device)
+        self.stream_copy = torch.cuda.Stream(self.device)
+        cfg = dict(n_layers=shape.n_layers, hidden=shape.hidden, n_experts=shape.n_experts,
+                   ffn=shape.ffn, top_k=shape.top_k, cache_cap=shape.cache_cap,
+                   n_shared=shape.n_shared, shared_ffn=shape.shared_ffn,
+                   dtype=0 if shape.dtype == "fp32" else 1, max_batch=max_batch,
+                   alpha=float(shape.alpha), subst_key=shape.subst_key,
+                   renorm_topk=shape.renorm_topk, evict_window=shape.evict_window, n_stage=n_stage)
+        cfg.update(cfg_override)
+        self.cfg = B.MoeCfg(**cfg)
+        self.expert_bytes = 3 * cfg["hidden"] * cfg["ffn"] * esize
+        n_slots = cfg["n_layers"] * cfg["cache_cap"] + n_stage
+        self.slab = torch.empty(n_slots * self.expert_bytes, dtype=torch.uint8, device=self.device)
+        self._init_res = None
+        if init_resident is not None:
+            self._init_res = np.ascontiguousarray(init_resident, dtype=np.int32)
+        buf = B.MoeBuffers(
+            self.gate_w.data_ptr(), self.experts_host.data_ptr(),
+            self.shared.data_ptr() if self.shared is not None else None,
+            self.sim.data_ptr(), self.slab.data_ptr(),
+            self._init_res.ctypes.data if self._init_res is not None else None,
+            self.stream_compute.cuda_stream, self.stream_copy.cuda_stream)
+        torch.cuda.synchronize(self.device)
+        self.handle = B.moe_cache_init(self.cfg, buf)
+        self.max_batch = max_batch
+
+    # ------------------------------------------------------------------
+    def new_trace(self, batch: int = 1) -> B.Trace:
+        return B.Trace(batch, self.cfg.top_k, self.cfg.n_experts)
+
+    def decode(self, layer: int, x_dev: torch.Tensor, y_dev: Optional[torch.Tensor] = None,
+               trace: Optional[B.Trace] = None) -> torch.Tensor:
+        """x_dev [B, H] on the device (produced on any stream that has been
+        synchronised).  Returns y_dev; valid after ``sync()``."""
+        batch = x_dev.shape[0]
+        if y_dev is None:
+            y_dev = torch.empty_like(x_dev)
+        B.moe_decode_layer(self.handle, layer, batch, x_dev.data_ptr(), y_dev.data_ptr(), trace)
+        return y_dev
+
+    def sync(self) -> None:
+        self.stream_compute.synchronize()
+        self.stream_copy.synchronize()
+
+    def stats(self, layer: int = -1) -> dict:
+        return B.moe_cache_stats(self.handle, layer).as_dict()
+
+    def residency(self, layer: int) -> np.ndarray:
+        return B.moe_cache_residency(self.handle, layer, self.cfg.cache_cap)
+
+    def reset(self) -> None:
+        B.moe_cache_reset(self.handle)
+
+    def close(self) -> None:
+        if self.handle:
+            B.moe_cache_destroy(self.handle)
+            self.handle = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def session_from_workload(wl, **kw) -> DecodeSession:
+    return DecodeSession(wl.shape, wl.gate_w, wl.experts, wl.shared, wl.sim, **kw)

@@ -1,0 +1,86 @@
+"""Shared driver of the GPU parity tests: runs the HIP library and the CPU
+oracle over the same seeded workload and compares them call by call."""
+import numpy as np
+import torch
+
+from oracle import smoe_oracle as O
+from smoe_inputs import as_numpy
+from paper_2508_18983_amd.session import session_from_workload
+
+TOL = {"fp32": 1e-5, "bf16": 2e-2}      # relative, on ||.||_2 and on max|.|
+ROUTE_MARGIN = 5e-4                     # log-space slack every routing comparison must have
+EVICT_MARGIN = 2e-5                     # relative slack of every eviction arg-min
+
+
+def rel_errors(y, ref):
+    y = np.asarray(y, np.float64)
+    ref = np.asarray(ref, np.float64)
+    l2 = np.linalg.norm(y - ref) / max(np.linalg.norm(ref), 1e-300)
+    mx = np.max(np.abs(y - ref)) / max(np.max(np.abs(ref)), 1e-300)
+    return l2, mx
+
+
+def run_parity(wl, *, y_every=1, tokens=None, session_kw=None, oracle_kw=None, batch=None,
+               check_margins=True, label=""):
+    """Decisions, counters and residency must match exactly on every call; y is
+    compared on every ``y_every``-th (token, layer).  Returns summary dict."""
+    s = wl.shape
+    T = s.tokens if tokens is None else tokens
+    B = s.batch if batch is None else batch
+    session_kw = dict(session_kw or {})
+    oracle_kw = dict(oracle_kw or {})
+    orc = O.oracle_from_workload(wl, **oracle_kw)
+    tol = TOL[s.dtype]
+    worst = dict(l2=0.0, mx=0.0, route_margin=np.inf, evict_margin=np.inf)
+    n_y = 0
+    with session_from_workload(wl, max_batch=B, **session_kw) as ses:
+        x_dev = wl.x[:T].to(ses.device)
+        y_dev = torch.zeros(T, s.n_layers, B, s.hidden, dtype=ses.tdtype, device=ses.device)
+        pending = []
+        call = 0
+        for t in range(T):
+            for l in range(s.n_layers):
+                print(f"[parity {label}] t={t} l={l}", flush=True) if (t < 1 and l < 2) else None
+                tr = ses.new_trace(B)
+                ses.decode(l, x_dev[t, l], y_dev[t, l], tr)
+                want_y = (call % y_every) == 0
+                res = orc.decode_layer(l, as_numpy(wl.x[t, l]), compute_y=want_y)
+                call += 1
+                ctx = f"{label} token {t} layer {l}"
+                np.testing.assert_array_equal(tr.topk_idx, res.topk, err_msg=f"topk {ctx}")
+                np.testing.assert_array_equal(tr.final_idx, res.final, err_msg=f"final {ctx}")
+                np.testing.assert_array_equal(tr.substituted.astype(bool), res.substituted,
+                                              err_msg=f"substituted {ctx}")
+                np.testing.assert_array_equal(tr.hit.astype(bool), res.hit, err_msg=f"hit {ctx}")
+                assert tr.n_fetched == len(res.fetched), ctx
+                assert tr.fetched[:tr.n_fetched].tolist() == res.fetched, ctx
+                assert tr.victims[:tr.n_fetched].tolist() == res.victims, ctx
+                np.testing.assert_allclose(tr.scores, res.scores, rtol=2e-5, atol=1e-9,
+                                           err_msg=f"scores {ctx}")
+                np.testing.assert_allclose(tr.weights, res.weights, rtol=2e-5, atol=1e-9,
+                                           err_msg=f"weights {ctx}")
+                assert ses.residency(l).tolist() == orc.layers[l].slot_expert, ctx
+                worst["route_margin"] = min(worst["route_margin"], res.route_margin)
+                worst["evict_margin"] = min(worst["evict_margin"], res.evict_margin)
+                if want_y:
+                    pending.append((t, l, res.y))
+        ses.sync()
+        y_host = y_dev.to(torch.float64).cpu().numpy()
+        for t, l, ref in pending:
+            l2, mx = rel_errors(y_host[t, l], ref)
+            assert l2 <= tol and mx <= tol, f"{label} y token {t} layer {l}: l2 {l2:.3e} max {mx:.3e}"
+            worst["l2"] = max(worst["l2"], l2)
+            worst["mx"] = max(worst["mx"], mx)
+            n_y += 1
+        got = ses.stats()
+        want = orc.stats().as_dict()
+        assert got == want, f"{label} stats {got} != {want}"
+        for l in range(s.n_layers):
+            assert ses.stats(l) == orc.stats(l).as_dict()
+    if check_margins:
+        # the exact comparison above is meaningful only if no decision sat on a knife edge
+        assert worst["route_margin"] >= ROUTE_MARGIN, worst
+        assert worst["evict_margin"] >= EVICT_MARGIN, worst
+    worst.update(n_y=n_y, stats=want)
+    print(f"[parity {label}] ok: {worst}", flush=True)
+    return worst

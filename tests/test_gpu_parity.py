@@ -1,0 +1,118 @@
+"""GPU parity: libsmoe (through the C ABI) against the CPU oracle on the same
+seeded workloads.  Integer outputs bit-exact, y within the stated tolerance."""
+import numpy as np
+import pytest
+import torch
+
+from smoe_inputs import SHAPES, make_workload
+from tests.parity import run_parity
+
+pytestmark = pytest.mark.gpu
+
+
+def test_c1_tiny_fp32_all_tokens():
+    wl = make_workload(SHAPES["c1"])
+    r = run_parity(wl, label="c1")
+    assert r["stats"]["substitutions"] > 0 and r["stats"]["misses"] > 0
+
+
+def test_c2_small_bf16_all_tokens():
+    wl = make_workload(SHAPES["c2"])
+    r = run_parity(wl, label="c2")
+    assert r["stats"]["substitutions"] > 0 and r["stats"]["misses"] > 0
+
+
+@pytest.mark.parametrize("subst_key", [0, 1])
+def test_c4_shaped_shared_experts_top6(subst_key):
+    shp = SHAPES["c4"].with_(subst_key=subst_key, seed=subst_key)
+    wl = make_workload(shp, n_layers=3, tokens=48)
+    r = run_parity(wl, y_every=3, label=f"c4-key{subst_key}")
+    assert r["stats"]["substitutions"] > 0 and r["stats"]["misses"] > 0
+
+
+def test_c5_shaped_wide_shared_ffn_top8():
+    wl = make_workload(SHAPES["c5"], n_layers=2, tokens=40)
+    r = run_parity(wl, y_every=2, label="c5")
+    assert r["stats"]["substitutions"] > 0 and r["stats"]["misses"] > 0
+
+
+def test_c3_shaped_long_rows_two_layers():
+    # real per-layer shape (H 4096, F 14336, 8 experts), two layers, few tokens
+    wl = make_workload(SHAPES["c3"], n_layers=2, tokens=12, device="cuda")
+    run_parity(wl, y_every=4, label="c3x2")
+
+
+@pytest.mark.parametrize("kw", [dict(alpha=0.0), dict(cache_cap=8)])
+def test_invariants_alpha_zero_and_full_capacity(kw):
+    wl = make_workload(SHAPES["c1"].with_(**kw, seed=5))
+    r = run_parity(wl, label=f"c1-{kw}")
+    assert r["stats"]["substitutions"] == 0
+    if "cache_cap" in kw:
+        assert r["stats"]["misses"] == 0
+
+
+@pytest.mark.parametrize("shape_kw", [
+    dict(hidden=264, ffn=520, n_experts=5, top_k=5, cache_cap=5),      # E == k: no (k+1)-th score
+    dict(hidden=200, ffn=72, n_experts=3, top_k=1, cache_cap=1),       # single slot cache
+    dict(hidden=1032, ffn=4104, n_experts=9, top_k=3, cache_cap=4),    # F just over one chunk
+    dict(hidden=8, ffn=8, n_experts=2, top_k=1, cache_cap=1),          # smallest legal shapes
+])
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_ragged_and_degenerate_shapes(shape_kw, dtype):
+    shp = SHAPES["c1"].with_(dtype=dtype, tokens=10, seed=11, **shape_kw)
+    wl = make_workload(shp)
+    run_parity(wl, label=f"ragged-{dtype}-{shape_kw['hidden']}")
+
+
+def test_max_sizes_hidden_8192_64_experts_top8():
+    shp = SHAPES["c1"].with_(dtype="bf16", hidden=8192, ffn=256, n_experts=64, top_k=8,
+                             cache_cap=20, n_shared=4, shared_ffn=136, tokens=8, seed=2,
+                             sim="uniform", alpha=0.4)
+    wl = make_workload(shp, n_layers=1)
+    run_parity(wl, label="max")
+
+
+def test_error_paths_and_reset():
+    import paper_2508_18983_amd as M
+    from paper_2508_18983_amd.session import session_from_workload
+    wl = make_workload(SHAPES["c1"].with_(tokens=4))
+    with pytest.raises(M.SmoeError) as ei:
+        session_from_workload(wl, cache_cap=1)                    # cap < k
+    assert ei.value.code == -1
+    with pytest.raises(M.SmoeError) as ei:
+        session_from_workload(wl, n_experts=65)
+    assert ei.value.code == -1
+    with pytest.raises(M.SmoeError) as ei:
+        session_from_workload(wl, init_resident=np.array([[0, 0, 1, 2], [0, 1, 2, 3]]))   # duplicate id
+    assert ei.value.code == -1
+    with session_from_workload(wl) as ses:
+        # unpinned expert storage is refused
+        cfg = ses.cfg
+        dev = ses.device
+        s1, s2 = torch.cuda.Stream(dev), torch.cuda.Stream(dev)
+        buf = M.MoeBuffers(ses.gate_w.data_ptr(), wl.experts.clone().data_ptr(), None, wl.sim.data_ptr(),
+                           ses.slab.data_ptr(), None, s1.cuda_stream, s2.cuda_stream)
+        with pytest.raises(M.SmoeError) as ei:
+            M.moe_cache_init(cfg, buf)
+        assert ei.value.code == -3
+        x = wl.x[0, 0].to(dev)
+        y = torch.empty_like(x)
+        for bad in (dict(layer=-1), dict(layer=2), dict(batch=0), dict(batch=2)):
+            with pytest.raises(M.SmoeError) as ei:
+                M.moe_decode_layer(ses.handle, bad.get("layer", 0), bad.get("batch", 1),
+                                   x.data_ptr(), y.data_ptr())
+            assert ei.value.code == -1
+        # a run, a reset, and the same run again give identical results and counters
+        outs = []
+        for rep in range(2):
+            ys = []
+            for t in range(4):
+                for l in range(2):
+                    ys.append(ses.decode(l, wl.x[t, l].to(dev)).clone())
+            ses.sync()
+            outs.append((torch.stack([y.cpu() for y in ys]), ses.stats(),
+                         [ses.residency(l).tolist() for l in range(2)]))
+            ses.reset()
+            assert ses.stats()["tokens"] == 0
+        assert torch.equal(outs[0][0], outs[1][0])
+        assert outs[0][1] == outs[1][1] and outs[0][2] == outs[1][2]
