@@ -1,0 +1,192 @@
+#!/usr/bin/env python3
+"""Benchmark of the SMoE offloaded-MoE decode hot path on one MI355X.
+
+A step = one decode token through every MoE layer of the workload: router,
+substitution, cache bookkeeping, on-demand loads of the misses, expert FFNs.
+Inputs (weights in pinned host memory, gate / shared weights and hidden states
+in HBM, initial residents in the HBM cache) are in place before the timed
+region starts.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+def log(msg: str) -> None:
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def run_tokens(ses, x_dev, y_dev, t0: int, t1: int, n_layers: int) -> None:
+    for t in range(t0, t1):
+        for l in range(n_layers):
+            ses.decode(l, x_dev[t, l], y_dev[l])
+
+
+def timed_run(ses, x_dev, y_dev, warmup: int, steps: int, n_layers: int, prof_launches: int):
+    import paper_2508_18983_amd as M
+    run_tokens(ses, x_dev, y_dev, 0, warmup, n_layers)
+    ses.sync()
+    st0 = ses.stats()
+    M.moe_profile_enable(ses.handle, 1, prof_launches)
+    ses.sync()
+    t_begin = time.perf_counter()
+    run_tokens(ses, x_dev, y_dev, warmup, warmup + steps, n_layers)
+    ses.sync()
+    elapsed = time.perf_counter() - t_begin
+    prof = M.moe_profile_read(ses.handle).as_dict()
+    M.moe_profile_enable(ses.handle, 0, 1)
+    st1 = ses.stats()
+    delta = {k: st1[k] - st0[k] for k in st1}
+    return elapsed, prof, delta
+
+
+def cpu_baseline(wl, budget_s: float):
+    """Time the CPU oracle, as it stands, on the first token's layers until
+    about ``budget_s`` seconds are spent; scale to tokens/s."""
+    from oracle import smoe_oracle as O
+    from smoe_inputs import as_numpy
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    s = wl.shape
+    orc = O.oracle_from_workload(wl, widen_cache_bytes=0)
+    done = 0
+    t0 = time.perf_counter()
+    for l in range(s.n_layers):
+        orc.decode_layer(l, as_numpy(wl.x[0, l]), compute_y=True)
+        done += 1
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    per_token = dt / done * s.n_layers
+    return {"value": 1.0 / per_token, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"token 0, layers 0..{done - 1} of {s.n_layers} ({dt:.1f} s of fp64 numpy), "
+                      f"scaled to a whole token"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=96)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--workload", default="c3", help="c1..c5 (default c3: Mixtral-8x7B-shaped)")
+    ap.add_argument("--layers", type=int, default=None, help="override layer count (diagnostic only)")
+    ap.add_argument("--cpu-budget", type=float, default=20.0, help="seconds of oracle timing; 0 = skip")
+    ap.add_argument("--no-miss-free", action="store_true", help="skip the all-resident reference run")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is a one-GPU path (no sharding, no collectives); run with --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 2
+    import paper_2508_18983_amd as M
+    from paper_2508_18983_amd.session import session_from_workload
+    from smoe_inputs import shape_by_name, make_workload
+
+    M.load_library()
+    shape = shape_by_name(args.workload)
+    n_tok = args.warmup + args.steps
+    if n_tok > shape.tokens:
+        print(f"bench.py: warmup+steps must be <= {shape.tokens} tokens of {shape.name}", file=sys.stderr)
+        return 2
+    t0 = time.perf_counter()
+    log(f"drawing {shape.name}: {shape.n_layers if args.layers is None else args.layers} layers, "
+        f"{n_tok} tokens ...")
+    wl = make_workload(shape, device="cuda", n_layers=args.layers, tokens=n_tok, batch=1, pin=True)
+    s = wl.shape
+    L = s.n_layers
+    log(f"inputs ready in {time.perf_counter() - t0:.1f} s (margin audit redrew {wl.redraws} token-layers)")
+
+    prof_launches = args.steps * L + 8
+    with session_from_workload(wl, max_batch=1) as ses:
+        x_dev = wl.x.to(ses.device)[:, :, :, :].contiguous()
+        y_dev = torch.empty(L, 1, s.hidden, dtype=ses.tdtype, device=ses.device)
+        log("timed run ...")
+        elapsed, prof, st = timed_run(ses, x_dev, y_dev, args.warmup, args.steps, L, prof_launches)
+    tok_s = args.steps / elapsed
+    up = prof["up"]
+    down = prof["down"]
+    up_avg_s = up["ms"] / max(up["launches"], 1) * 1e-3
+    up_bytes_per_launch = up["bytes"] / max(up["launches"], 1)
+    achieved = up_bytes_per_launch / up_avg_s / 1e9 if up_avg_s > 0 else 0.0
+    down_gbs = (down["bytes"] / (down["ms"] * 1e-3) / 1e9) if down["ms"] > 0 else 0.0
+    copy = prof["copy"]
+    host_link = (copy["bytes"] / (copy["ms"] * 1e-3) / 1e9) if copy["ms"] > 0 else None
+
+    extra = {
+        "hit_rate_raw": st["raw_hits"] / max(st["slots"], 1),
+        "hit_rate": st["hits"] / max(st["slots"], 1),
+        "substitutions_per_token": st["substitutions"] / args.steps,
+        "fetches_per_token": st["fetches"] / args.steps,
+        "host_link_GBs": host_link,
+        "kernel_avg_us": {k: (v["ms"] * 1e3 / v["launches"] if v["launches"] else None)
+                          for k, v in prof.items()},
+        "down_kernel_GBs": down_gbs,
+        "down_kernel_frac": down_gbs / HBM_PEAK_GBS,
+        "layer_bytes": s.layer_bytes(),
+        "hbm_roofline_tokens_per_s": HBM_PEAK_GBS * 1e9 / (s.layer_bytes() * L),
+    }
+
+    if not args.no_miss_free:
+        # same tokens with every expert resident: the pure HBM path, no loads
+        log("all-resident reference run ...")
+        full = wl.shape.with_(cache_cap=s.n_experts)
+        wl_full = type(wl)(full, wl.gate_w, wl.experts, wl.shared, wl.sim, wl.x, wl.redraws)
+        try:
+            with session_from_workload(wl_full, max_batch=1) as ses2:
+                x_dev = wl.x.to(ses2.device).contiguous()
+                y_dev = torch.empty(L, 1, s.hidden, dtype=ses2.tdtype, device=ses2.device)
+                e2, p2, _ = timed_run(ses2, x_dev, y_dev, min(args.warmup, 4), args.steps, L, prof_launches)
+            extra["miss_free_tokens_per_s"] = args.steps / e2
+            extra["miss_free_frac_of_hbm_roofline"] = (args.steps / e2) / extra["hbm_roofline_tokens_per_s"]
+            u2, d2 = p2["up"], p2["down"]
+            extra["miss_free_up_GBs"] = u2["bytes"] / (u2["ms"] * 1e-3) / 1e9
+            extra["miss_free_down_GBs"] = d2["bytes"] / (d2["ms"] * 1e-3) / 1e9
+        except Exception as exc:            # e.g. not enough HBM for every expert
+            extra["miss_free_error"] = repr(exc)
+
+    cpu = None
+    if args.cpu_budget > 0:
+        log("timing the CPU oracle ...")
+        cpu = cpu_baseline(wl, args.cpu_budget)
+
+    out = {
+        "metric": "decode tokens/s at batch 1 (full MoE stack)",
+        "value": tok_s, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if s.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": s.name, "layers": L, "hidden": s.hidden, "experts": s.n_experts,
+                   "ffn": s.ffn, "top_k": s.top_k, "cache_cap": s.cache_cap, "alpha": s.alpha,
+                   "n_shared": s.n_shared, "shared_ffn": s.shared_ffn, "batch": 1,
+                   "zipf_s": s.zipf_s, "seed": s.seed},
+        "roofline": {"bound": "hbm", "kernel": "ffn_up_kernel (resident pass)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": up_bytes_per_launch, "avg_launch_us": up_avg_s * 1e6,
+                     "launches": up["launches"]},
+        "cpu_baseline": cpu,
+        "extra": extra,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

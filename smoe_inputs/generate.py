@@ -64,11 +64,14 @@ def logit_margin_ok(logits: np.ndarray, k: int, alpha: float,
         return (gaps >= delta).all(axis=1)
     ok = (gaps[:, :min(e - 1, k + 1)] >= delta).all(axis=1)
     pivot = srt[:, k:k + 1]
-    d = logits - pivot
-    ok &= (np.abs(d - np.log1p(alpha)) >= delta).all(axis=1)
-    if 0.0 < alpha < 1.0:
+    # active experts against T = (1+alpha) S_{k+1}
+    ok &= (np.abs(srt[:, :k] - pivot - np.log1p(alpha)) >= delta).all(axis=1)
+    if 0.0 < alpha < 1.0 and e > k + 1:
+        # inactive experts below the (k+1)-th against R = (1-alpha) S_{k+1}, and the
+        # order of those that fall inside the band
         lo = np.log1p(-alpha)
-        ok &= (np.abs(d - lo) >= delta).all(axis=1)
+        below = srt[:, k + 1:] - pivot
+        ok &= (np.abs(below - lo) >= delta).all(axis=1)
         lower_in_band = (srt[:, 1:] - pivot) >= (lo - delta)
         ok &= ((gaps >= delta) | ~lower_in_band).all(axis=1)
     return ok
