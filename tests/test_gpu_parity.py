@@ -104,11 +104,12 @@ def test_error_paths_and_reset():
             assert ei.value.code == -1
         # a run, a reset, and the same run again give identical results and counters
         outs = []
+        x_all = wl.x.to(dev)                 # x must stay alive until the stream drains
         for rep in range(2):
             ys = []
             for t in range(4):
                 for l in range(2):
-                    ys.append(ses.decode(l, wl.x[t, l].to(dev)).clone())
+                    ys.append(ses.decode(l, x_all[t, l]))
             ses.sync()
             outs.append((torch.stack([y.cpu() for y in ys]), ses.stats(),
                          [ses.residency(l).tolist() for l in range(2)]))
