@@ -50,7 +50,7 @@ extern "C" {
 #define SMOE_OK         0
 #define SMOE_EINVAL    -1   /* bad argument, shape or layout */
 #define SMOE_EHIP      -2   /* a HIP runtime call failed: see moe_last_hip_error() */
-#define SMOE_ENOTPINNED -3  /* experts_host is not pinned host memory */
+#define SMOE_ENOTPINNED -3  /* an experts_host block is not pinned host memory */
 #define SMOE_ESTATE    -4   /* call not valid in the handle's state */
 
 #define SMOE_DTYPE_FP32 0
@@ -81,9 +81,11 @@ typedef struct {
 
 typedef struct {
   const void*    gate_w_dev;      /* device  [L][E][H] dtype, row e = expert e                */
-  const void*    experts_host;    /* pinned host [L][E]{W1[F][H], W3[F][H], W2[H][F]} dtype:
+  const void* const* experts_host; /* host array of L pointers; entry l -> pinned host
+                                     [E]{W1[F][H], W3[F][H], W2[H][F]} dtype of layer l:
                                      W1 gate-projection, W3 up-projection, W2 down-projection,
-                                     each row-major, the three back to back                   */
+                                     each row-major, the three back to back.  The array itself
+                                     is copied at init; the blocks it points to are borrowed  */
   const void*    shared_dev;      /* device  [L][n_shared]{W1[Fs][H], W3[Fs][H], W2[H][Fs]}
                                      or NULL when n_shared == 0                               */
   const float*   sim_host;        /* host    [L][E][E] fp32 similarity table, copied at init  */
@@ -146,7 +148,7 @@ typedef struct {
  * initial residents into the slab (on stream_copy, waited for) and zeroes
  * history and statistics.  SMOE_EINVAL for shapes outside the limits above,
  * cap < k, duplicate ids in init_resident, NULL buffers or equal streams;
- * SMOE_ENOTPINNED when experts_host is not pinned; SMOE_EHIP on HIP errors. */
+ * SMOE_ENOTPINNED when a block of experts_host is not pinned; SMOE_EHIP on HIP errors. */
 int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t** out);
 
 /* Decode `batch` tokens through MoE layer `layer`.
@@ -182,6 +184,13 @@ int moe_profile_read(moe_handle_t* h, moe_profile_t* out);
 
 /* hipError_t of the most recent failing HIP call in this thread (0 if none). */
 int moe_last_hip_error(void);
+
+/* Page-locked host memory for expert storage (hipHostMalloc of exactly n_bytes;
+ * PyTorch's pinned allocator rounds large requests up to a power of two).
+ * moe_host_alloc stores the pointer in *out; SMOE_EHIP when the system cannot
+ * pin that much.  Free with moe_host_free after the handles using it are gone. */
+int moe_host_alloc(int64_t n_bytes, void** out);
+int moe_host_free(void* p);
 
 /* Plain device-to-device copy kernel (n_bytes multiple of 16, both pointers
  * 16-byte aligned) on `stream`: the known-size kernel hardware counters are

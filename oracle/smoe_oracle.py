@@ -434,7 +434,7 @@ def oracle_from_workload(wl, **override) -> SMoEOracle:
     s = wl.shape
     kw = dict(n_layers=s.n_layers, hidden=s.hidden, n_experts=s.n_experts, ffn=s.ffn,
               top_k=s.top_k, cache_cap=s.cache_cap, alpha=float(np.float32(s.alpha)),
-              gate_w=view(wl.gate_w), experts=view(wl.experts), sim=view(wl.sim),
+              gate_w=view(wl.gate_w), experts=[view(b) for b in wl.experts], sim=view(wl.sim),
               shared=view(wl.shared), n_shared=s.n_shared, shared_ffn=s.shared_ffn,
               subst_key=s.subst_key, renorm_topk=s.renorm_topk, evict_window=s.evict_window,
               elem_bytes=s.elem_bytes)

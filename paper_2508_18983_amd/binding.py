@@ -86,9 +86,11 @@ def load_library():
     lib.moe_profile_read.argtypes = [P, C.POINTER(MoeProfile)]
     lib.moe_last_hip_error.argtypes = []
     lib.moe_calib_copy.argtypes = [P, P, C.c_int64, P]
+    lib.moe_host_alloc.argtypes = [C.c_int64, C.POINTER(P)]
+    lib.moe_host_free.argtypes = [P]
     for fn in ("moe_cache_init", "moe_decode_layer", "moe_cache_stats", "moe_cache_residency",
                "moe_cache_reset", "moe_cache_destroy", "moe_profile_enable", "moe_profile_read",
-               "moe_last_hip_error", "moe_calib_copy"):
+               "moe_last_hip_error", "moe_calib_copy", "moe_host_alloc", "moe_host_free"):
         getattr(lib, fn).restype = C.c_int
     _lib = lib
     return lib
@@ -168,3 +170,13 @@ def moe_profile_read(handle: int) -> MoeProfile:
 
 def moe_calib_copy(dst_dev: int, src_dev: int, n_bytes: int, stream: int) -> None:
     _check("moe_calib_copy", load_library().moe_calib_copy(dst_dev, src_dev, n_bytes, stream))
+
+
+def moe_host_alloc(n_bytes: int) -> int:
+    p = C.c_void_p()
+    _check("moe_host_alloc", load_library().moe_host_alloc(n_bytes, C.byref(p)))
+    return p.value
+
+
+def moe_host_free(ptr: int) -> None:
+    _check("moe_host_free", load_library().moe_host_free(ptr))

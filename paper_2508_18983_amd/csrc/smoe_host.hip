@@ -56,6 +56,7 @@ struct moe_handle {
   int Fmax = 0;
   std::vector<LayerState> layers;
   std::vector<int32_t> init_resident;    // [L][cap]
+  std::vector<const char*> experts_host; // [L] pinned blocks of E experts
   // device scratch
   float* sim_dev = nullptr;
   StepRec* rec_dev = nullptr;
@@ -127,8 +128,7 @@ int upload_initial(moe_handle* h) {
       ls.resident |= 1ull << e;
       ls.slot_of[e] = (int8_t)s;
       ls.expert_of_slot[s] = e;
-      const char* src = static_cast<const char*>(h->buf.experts_host) +
-                        ((int64_t)l * c.n_experts + e) * h->expert_bytes;
+      const char* src = h->experts_host[l] + (int64_t)e * h->expert_bytes;
       char* dst = static_cast<char*>(h->buf.cache_slab_dev) +
                   ((int64_t)l * c.cache_cap + s) * h->expert_bytes;
       HIP_TRY(hipMemcpyAsync(dst, src, h->expert_bytes, hipMemcpyHostToDevice, h->s_copy));
@@ -196,10 +196,13 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
   if (buf->stream_compute == buf->stream_copy) return SMOE_EINVAL;
   if (reinterpret_cast<uintptr_t>(buf->cache_slab_dev) % 256) return SMOE_EINVAL;
 
-  hipPointerAttribute_t attr;
-  hipError_t pe = hipPointerGetAttributes(&attr, buf->experts_host);
-  if (pe != hipSuccess) { (void)hipGetLastError(); return SMOE_ENOTPINNED; }
-  if (attr.type != hipMemoryTypeHost) return SMOE_ENOTPINNED;
+  for (int l = 0; l < c.n_layers; ++l) {
+    if (!buf->experts_host[l]) return SMOE_EINVAL;
+    hipPointerAttribute_t attr;
+    hipError_t pe = hipPointerGetAttributes(&attr, buf->experts_host[l]);
+    if (pe != hipSuccess) { (void)hipGetLastError(); return SMOE_ENOTPINNED; }
+    if (attr.type != hipMemoryTypeHost) return SMOE_ENOTPINNED;
+  }
 
   moe_handle* h = new (std::nothrow) moe_handle();
   if (!h) return SMOE_EINVAL;
@@ -212,6 +215,9 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
   h->shared_bytes = 3ll * c.hidden * c.shared_ffn * h->esize;
   h->Fmax = std::max(c.ffn, c.n_shared ? c.shared_ffn : 0);
   h->layers.resize(c.n_layers);
+  for (int l = 0; l < c.n_layers; ++l)
+    h->experts_host.push_back(static_cast<const char*>(buf->experts_host[l]));
+  h->buf.experts_host = nullptr;
   h->init_resident.resize((size_t)c.n_layers * c.cache_cap);
   for (int l = 0; l < c.n_layers; ++l) {
     uint64_t seen = 0;
@@ -366,8 +372,7 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
         if (n_staged >= c.n_stage) return SMOE_ESTATE;   // out of transient slots
         gslot[i] = c.n_layers * c.cache_cap + n_staged++;
       }
-      const char* src = static_cast<const char*>(h->buf.experts_host) +
-                        ((int64_t)layer * E + m) * h->expert_bytes;
+      const char* src = h->experts_host[layer] + (int64_t)m * h->expert_bytes;
       char* dst = static_cast<char*>(h->buf.cache_slab_dev) + (int64_t)gslot[i] * h->expert_bytes;
       EventPair* pc = prof_begin(h, SMOE_PROF_COPY, h->s_copy);
       HIP_TRY(hipMemcpyAsync(dst, src, h->expert_bytes, hipMemcpyHostToDevice, h->s_copy));
@@ -508,6 +513,19 @@ int moe_profile_read(moe_handle_t* h, moe_profile_t* out) {
     out->ms[kind] = ms;
     out->bytes[kind] = h->prof[kind].bytes;
   }
+  return SMOE_OK;
+}
+
+int moe_host_alloc(int64_t n_bytes, void** out) {
+  if (!out || n_bytes <= 0) return SMOE_EINVAL;
+  *out = nullptr;
+  HIP_TRY(hipHostMalloc(out, (size_t)n_bytes, hipHostMallocDefault));
+  return SMOE_OK;
+}
+
+int moe_host_free(void* p) {
+  if (!p) return SMOE_EINVAL;
+  HIP_TRY(hipHostFree(p));
   return SMOE_OK;
 }
 

@@ -5,10 +5,30 @@ from __future__ import annotations
 
 from typing import Optional
 
+import ctypes as C
+
 import numpy as np
 import torch
 
 from . import binding as B
+
+_PINNED_BLOCKS = {}     # data_ptr -> owner: blocks handed out by pinned_empty()
+
+
+def pinned_empty(n_elems: int, dtype: torch.dtype) -> torch.Tensor:
+    """Host tensor of exactly n_elems elements in page-locked memory obtained
+    from moe_host_alloc (freed at process exit)."""
+    nbytes = n_elems * torch.empty(0, dtype=dtype).element_size()
+    ptr = B.moe_host_alloc(nbytes)
+    raw = (C.c_uint8 * nbytes).from_address(ptr)
+    t = torch.frombuffer(raw, dtype=torch.uint8).view(dtype)
+    _PINNED_BLOCKS[t.data_ptr()] = raw
+    return t
+
+
+def _is_pinned(t: torch.Tensor) -> bool:
+    return t.data_ptr() in _PINNED_BLOCKS or any(
+        base <= t.data_ptr() < base + len(raw) for base, raw in _PINNED_BLOCKS.items()) or t.is_pinned()
 
 
 class DecodeSession:
@@ -16,10 +36,11 @@ class DecodeSession:
 
     ``shape`` needs the attributes n_layers, hidden, n_experts, ffn, top_k,
     cache_cap, n_shared, shared_ffn, dtype ("fp32" | "bf16"), alpha, subst_key,
-    renorm_topk, evict_window.  ``experts`` is the host copy of all experts
-    [L, E, 3*H*F]; it is pinned here if it is not already."""
+    renorm_topk, evict_window.  ``experts`` holds one host tensor [E, 3*H*F]
+    per layer (entries may alias); blocks that are not pinned are copied into
+    pinned memory here."""
 
-    def __init__(self, shape, gate_w: torch.Tensor, experts: torch.Tensor,
+    def __init__(self, shape, gate_w: torch.Tensor, experts,
                  shared: Optional[torch.Tensor], sim: torch.Tensor, *, max_batch: int = 1,
                  n_stage: int = 0, init_resident: Optional[np.ndarray] = None,
                  device: str = "cuda:0", **cfg_override):
@@ -31,7 +52,13 @@ class DecodeSession:
         torch.cuda.set_device(self.device)
         self.tdtype = torch.float32 if shape.dtype == "fp32" else torch.bfloat16
         esize = 4 if shape.dtype == "fp32" else 2
-        self.experts_host = experts if experts.is_pinned() else experts.pin_memory()
+        pinned = {}
+        for blk in experts:
+            if id(blk) not in pinned:
+                pinned[id(blk)] = blk if _is_pinned(blk) else blk.pin_memory()
+        self.experts_host = [pinned[id(blk)] for blk in experts]
+        self._expert_ptrs = (C.c_void_p * len(self.experts_host))(
+            *[blk.data_ptr() for blk in self.experts_host])
         self.gate_w = gate_w.to(self.device).contiguous()
         self.shared = shared.to(self.device).contiguous() if shared is not None else None
         self.sim = sim.contiguous()
@@ -52,7 +79,7 @@ class DecodeSession:
         if init_resident is not None:
             self._init_res = np.ascontiguousarray(init_resident, dtype=np.int32)
         buf = B.MoeBuffers(
-            self.gate_w.data_ptr(), self.experts_host.data_ptr(),
+            self.gate_w.data_ptr(), C.cast(self._expert_ptrs, C.c_void_p),
             self.shared.data_ptr() if self.shared is not None else None,
             self.sim.data_ptr(), self.slab.data_ptr(),
             self._init_res.ctypes.data if self._init_res is not None else None,

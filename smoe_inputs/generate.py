@@ -81,7 +81,8 @@ def logit_margin_ok(logits: np.ndarray, k: int, alpha: float,
 class Workload:
     shape: MoEShape
     gate_w: torch.Tensor              # [L, E, H] storage dtype, host
-    experts: torch.Tensor             # [L, E, 3*H*F]: W1[F][H] | W3[F][H] | W2[H][F], host
+    experts: list                     # L host tensors [E, 3*H*F]: W1[F][H] | W3[F][H] | W2[H][F];
+                                      # entries may alias when fewer distinct layers were drawn
     shared: Optional[torch.Tensor]    # [L, n_shared, 3*H*Fs] or None, host
     sim: torch.Tensor                 # [L, E, E] fp32, host
     x: torch.Tensor                   # [T, L, B, H] storage dtype, host
@@ -90,7 +91,7 @@ class Workload:
     def expert_mats(self, layer: int, e: int):
         s = self.shape
         hf = s.hidden * s.ffn
-        flat = self.experts[layer, e]
+        flat = self.experts[layer][e]
         return (flat[:hf].view(s.ffn, s.hidden),
                 flat[hf:2 * hf].view(s.ffn, s.hidden),
                 flat[2 * hf:].view(s.hidden, s.ffn))
@@ -141,10 +142,15 @@ def _uniform_table(e: int, rng: np.random.Generator) -> torch.Tensor:
 
 def make_workload(shape: MoEShape, device: str = "cpu", n_layers: int | None = None,
                   tokens: int | None = None, batch: int | None = None,
-                  pin: bool = False, delta: float = LOGIT_DELTA) -> Workload:
+                  host_alloc=None, distinct_layers: int | None = None,
+                  delta: float = LOGIT_DELTA) -> Workload:
     """Draw one workload.  ``device`` is where the normal deviates for the
     weights are drawn ("cuda" makes the 100 GB shapes practical); everything
-    is returned in host memory (pinned when ``pin``)."""
+    is returned in host memory.  ``host_alloc(n_elems, dtype)`` may supply the
+    (pinned) storage of each layer's experts.  With ``distinct_layers = D < L``
+    only D layers of expert weights are drawn and layer l uses the block of
+    layer l mod D (for hosts that cannot pin the whole model); gate weights,
+    similarity tables and hidden states stay distinct per layer."""
     L = shape.n_layers if n_layers is None else n_layers
     T = shape.tokens if tokens is None else tokens
     B = shape.batch if batch is None else batch
@@ -154,7 +160,11 @@ def make_workload(shape: MoEShape, device: str = "cpu", n_layers: int | None = N
     rng = np.random.default_rng([shape.seed, 0x5E0E])
 
     gate_w = torch.empty(L, E, H, dtype=dt)
-    experts = torch.empty(L, E, shape.expert_elems, dtype=dt, pin_memory=pin)
+    D = L if distinct_layers is None else max(1, min(L, distinct_layers))
+    if host_alloc is None:
+        host_alloc = lambda n, dtype: torch.empty(n, dtype=dtype)
+    blocks = [host_alloc(E * shape.expert_elems, dt).view(E, shape.expert_elems) for _ in range(D)]
+    experts = [blocks[l % D] for l in range(L)]
     shared = None
     if shape.n_shared:
         shared = torch.empty(L, shape.n_shared, shape.shared_elems, dtype=dt)
@@ -162,7 +172,8 @@ def make_workload(shape: MoEShape, device: str = "cpu", n_layers: int | None = N
     for l in range(L):
         gen.manual_seed(shape.seed * 1_000_003 + 7919 * l + 1)
         _draw_weights(E * H, dt, gen, device, gate_w[l])
-        _draw_weights(E * shape.expert_elems, dt, gen, device, experts[l])
+        if l < D:
+            _draw_weights(E * shape.expert_elems, dt, gen, device, experts[l])
         if shared is not None:
             _draw_weights(shape.n_shared * shape.shared_elems, dt, gen, device, shared[l])
         if shape.sim == "cosine":

@@ -90,8 +90,11 @@ def test_error_paths_and_reset():
         cfg = ses.cfg
         dev = ses.device
         s1, s2 = torch.cuda.Stream(dev), torch.cuda.Stream(dev)
-        buf = M.MoeBuffers(ses.gate_w.data_ptr(), wl.experts.clone().data_ptr(), None, wl.sim.data_ptr(),
-                           ses.slab.data_ptr(), None, s1.cuda_stream, s2.cuda_stream)
+        import ctypes
+        pageable = [blk.clone() for blk in wl.experts]
+        ptrs = (ctypes.c_void_p * len(pageable))(*[b.data_ptr() for b in pageable])
+        buf = M.MoeBuffers(ses.gate_w.data_ptr(), ctypes.cast(ptrs, ctypes.c_void_p), None,
+                           wl.sim.data_ptr(), ses.slab.data_ptr(), None, s1.cuda_stream, s2.cuda_stream)
         with pytest.raises(M.SmoeError) as ei:
             M.moe_cache_init(cfg, buf)
         assert ei.value.code == -3

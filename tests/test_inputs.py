@@ -9,12 +9,16 @@ def test_shapes_and_determinism():
     s = SHAPES["c1"]
     a, b = make_workload(s), make_workload(s)
     assert a.x.shape == (16, 2, 1, 256) and a.x.dtype == torch.float32
-    assert a.experts.shape == (2, 8, 3 * 256 * 512)
-    for f in ("gate_w", "experts", "sim", "x"):
+    assert len(a.experts) == 2 and a.experts[0].shape == (8, 3 * 256 * 512)
+    for f in ("gate_w", "sim", "x"):
         assert torch.equal(getattr(a, f), getattr(b, f))
+    assert all(torch.equal(p, q) for p, q in zip(a.experts, b.experts))
     c = make_workload(s.with_(seed=1))
     assert not torch.equal(a.x, c.x)
-    assert abs(float(a.experts.std()) - 0.02) < 1e-4
+    assert abs(float(a.experts[0].std()) - 0.02) < 1e-4
+    al = make_workload(s.with_(n_layers=4), distinct_layers=2)
+    assert al.experts[2] is al.experts[0] and al.experts[3] is al.experts[1]
+    assert not torch.equal(al.gate_w[0], al.gate_w[2])
 
 
 def test_byte_counts_match_the_workload_table():
@@ -32,8 +36,8 @@ def test_cosine_table_properties():
     sim = wl.sim.numpy()
     assert np.array_equal(sim, np.transpose(sim, (0, 2, 1)))
     assert (np.diagonal(sim, axis1=1, axis2=2) == 1).all()
-    e0 = wl.experts[0, 0].double()
-    e3 = wl.experts[0, 3].double()
+    e0 = wl.experts[0][0].double()
+    e3 = wl.experts[0][3].double()
     want = float(e0 @ e3 / (e0.norm() * e3.norm()))
     assert abs(sim[0, 0, 3] - want) < 1e-7
 
