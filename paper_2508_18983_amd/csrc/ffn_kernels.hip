@@ -1,42 +1,49 @@
 // Batch-1-style SwiGLU expert FFN for the chosen experts and the shared experts
 // (Section V-B, GPU operations "Direct expert computation" and "New Expert
 // Computation"; shared experts per Section II-A).  Pure weight streaming: every
-// weight element is read once from HBM with 128-bit loads, the activation
-// vector sits in LDS, one wavefront owns whole rows and reduces with
-// cross-lane shuffles, accumulation is fp32.
+// weight element is read once from HBM with non-temporal 128-bit loads, the
+// activation vector sits in LDS, one wavefront owns whole rows and reduces
+// with cross-lane shuffles, accumulation is fp32.
 //
 //   up   : act[task][f] = w_task * silu(W1[f].x) * (W3[f].x)
 //   down : y[h] = sum_task sum_f W2[h][f] * act[task][f]
-//          split over F-chunks; partial sums are combined in a fixed order by
-//          the last block to finish each row tile, so the result does not
-//          depend on scheduling.
+//          one wave produces y[h] for its rows over all tasks in a fixed
+//          order: no partial buffers, atomics or fences.
 #include "smoe_dev.hpp"
 
 namespace smoe {
 namespace {
 
 struct bf16_t { uint16_t v; };
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 template <typename T> struct Unit;
 template <> struct Unit<float> {
-  static constexpr int N = 4;
-  __device__ static __forceinline__ void load(const float* p, float (&v)[4]) {
-    const float4 q = *reinterpret_cast<const float4*>(p);
+  static constexpr int N = 4;          // elements per 128-bit load
+  using raw = f32x4;
+  __device__ static __forceinline__ raw load(const float* p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const raw*>(p));
+  }
+  __device__ static __forceinline__ void widen(const raw& q, float (&v)[4]) {
     v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
   }
-  __device__ static __forceinline__ float widen(float s) { return s; }
+  __device__ static __forceinline__ float widen1(float s) { return s; }
   __device__ static __forceinline__ float narrow(float s) { return s; }
 };
 template <> struct Unit<bf16_t> {
   static constexpr int N = 8;
-  __device__ static __forceinline__ void load(const bf16_t* p, float (&v)[8]) {
-    const uint4 q = *reinterpret_cast<const uint4*>(p);
+  using raw = u32x4;
+  __device__ static __forceinline__ raw load(const bf16_t* p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const raw*>(p));
+  }
+  __device__ static __forceinline__ void widen(const raw& q, float (&v)[8]) {
     v[0] = __uint_as_float(q.x << 16); v[1] = __uint_as_float(q.x & 0xffff0000u);
     v[2] = __uint_as_float(q.y << 16); v[3] = __uint_as_float(q.y & 0xffff0000u);
     v[4] = __uint_as_float(q.z << 16); v[5] = __uint_as_float(q.z & 0xffff0000u);
     v[6] = __uint_as_float(q.w << 16); v[7] = __uint_as_float(q.w & 0xffff0000u);
   }
-  __device__ static __forceinline__ float widen(bf16_t s) {
+  __device__ static __forceinline__ float widen1(bf16_t s) {
     return __uint_as_float(uint32_t(s.v) << 16);
   }
   __device__ static __forceinline__ bf16_t narrow(float s) {   // round to nearest even
@@ -75,9 +82,56 @@ __device__ __forceinline__ const char* task_weights(const FfnArgs& a, int t, int
   return a.shared + (int64_t)(j - a.k) * a.shared_bytes;
 }
 
+// acc[r] += sum_u row_r[u] . vec[u] over `units` 128-bit units, ROWS rows at a
+// time, UNR independent steps in flight per row.
+template <typename T, int ROWS, int UNR>
+__device__ __forceinline__ void dot_rows(const T* const (&row)[ROWS], const float* __restrict__ vec,
+                                         int units, int lane, float (&acc)[ROWS]) {
+  constexpr int N = Unit<T>::N;
+  using raw = typename Unit<T>::raw;
+  int u = lane;
+  for (; u + (UNR - 1) * kWave < units; u += UNR * kWave) {
+    raw q[UNR][ROWS];
+#pragma unroll
+    for (int s = 0; s < UNR; ++s)
+#pragma unroll
+      for (int r = 0; r < ROWS; ++r) q[s][r] = Unit<T>::load(row[r] + (size_t)(u + s * kWave) * N);
+#pragma unroll
+    for (int s = 0; s < UNR; ++s) {
+      const float* xv = vec + (size_t)(u + s * kWave) * N;
+      float xq[N];
+#pragma unroll
+      for (int e = 0; e < N; ++e) xq[e] = xv[e];
+#pragma unroll
+      for (int r = 0; r < ROWS; ++r) {
+        float w[N];
+        Unit<T>::widen(q[s][r], w);
+#pragma unroll
+        for (int e = 0; e < N; ++e) acc[r] = fmaf(w[e], xq[e], acc[r]);
+      }
+    }
+  }
+  for (; u < units; u += kWave) {
+    raw q[ROWS];
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) q[r] = Unit<T>::load(row[r] + (size_t)u * N);
+    const float* xv = vec + (size_t)u * N;
+    float xq[N];
+#pragma unroll
+    for (int e = 0; e < N; ++e) xq[e] = xv[e];
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+      float w[N];
+      Unit<T>::widen(q[r], w);
+#pragma unroll
+      for (int e = 0; e < N; ++e) acc[r] = fmaf(w[e], xq[e], acc[r]);
+    }
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void ffn_up_kernel(const FfnArgs a) {
-  extern __shared__ float xs[];                       // H floats
+  extern __shared__ __align__(16) float xs[];       // H floats
   constexpr int N = Unit<T>::N;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
   const int nj = a.k + a.ns;
@@ -95,7 +149,7 @@ __global__ __launch_bounds__(256) void ffn_up_kernel(const FfnArgs a) {
   const T* W3 = W1 + (size_t)F * H;
 
   const T* x = static_cast<const T*>(a.x) + (size_t)t * H;
-  for (int h = tid; h < H; h += 256) xs[h] = Unit<T>::widen(x[h]);
+  for (int h = tid; h < H; h += 256) xs[h] = Unit<T>::widen1(x[h]);
   __syncthreads();
 
   const int units = H / N;
@@ -105,129 +159,108 @@ __global__ __launch_bounds__(256) void ffn_up_kernel(const FfnArgs a) {
   for (int i = 0; i < per_wave; i += 2) {
     const int f = f_begin + i;
     if (f >= F) break;
-    const T* g0 = W1 + (size_t)f * H;
-    const T* u0 = W3 + (size_t)f * H;
-    const T* g1 = g0 + H;
-    const T* u1 = u0 + H;
-    float ag0 = 0.f, au0 = 0.f, ag1 = 0.f, au1 = 0.f;
-#pragma unroll 2
-    for (int u = lane; u < units; u += kWave) {
-      float a0[N], b0[N], a1[N], b1[N];
-      Unit<T>::load(g0 + u * N, a0);
-      Unit<T>::load(u0 + u * N, b0);
-      Unit<T>::load(g1 + u * N, a1);
-      Unit<T>::load(u1 + u * N, b1);
-      const float* xv = xs + u * N;
+    const T* const rows[4] = {W1 + (size_t)f * H, W3 + (size_t)f * H,
+                              W1 + (size_t)(f + 1) * H, W3 + (size_t)(f + 1) * H};
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    dot_rows<T, 4, 2>(rows, xs, units, lane, acc);
 #pragma unroll
-      for (int q = 0; q < N; ++q) {
-        const float xq = xv[q];
-        ag0 = fmaf(a0[q], xq, ag0);
-        au0 = fmaf(b0[q], xq, au0);
-        ag1 = fmaf(a1[q], xq, ag1);
-        au1 = fmaf(b1[q], xq, au1);
-      }
-    }
-    ag0 = wave_sum(ag0); au0 = wave_sum(au0);
-    ag1 = wave_sum(ag1); au1 = wave_sum(au1);
+    for (int q = 0; q < 4; ++q) acc[q] = wave_sum(acc[q]);
     if (lane == 0) {
-      act[f] = wgt * (ag0 / (1.0f + expf(-ag0))) * au0;
-      act[f + 1] = wgt * (ag1 / (1.0f + expf(-ag1))) * au1;
+      act[f] = wgt * (acc[0] / (1.0f + expf(-acc[0]))) * acc[1];
+      act[f + 1] = wgt * (acc[2] / (1.0f + expf(-acc[2]))) * acc[3];
     }
   }
 }
 
-template <typename T>
+// Down projection + combine.  A block owns 4*R consecutive output rows of one
+// token (one wave = R rows) and keeps their running sums in registers while it
+// walks this pass's tasks.  `stage_all` != 0: the activations of all tasks fit
+// in LDS together and are loaded once; otherwise each task is processed in
+// chunks of `chunk` floats.  Pass 0 writes y when the token has no missing
+// expert, else fp32 sums to `ysum`; pass 1 adds the loaded experts to `ysum`
+// and writes y.
+template <typename T, int R>
 __global__ __launch_bounds__(256) void ffn_down_kernel(const FfnArgs a) {
-  extern __shared__ float as[];                       // one F-chunk of act
-  __shared__ int is_last;
+  extern __shared__ __align__(16) float as[];
   constexpr int N = Unit<T>::N;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
   const int nj = a.k + a.ns;
-  const int per_tok = a.k * a.chunksR + a.ns * a.chunksS;   // (task, chunk) pairs per token
-  const int bpt = a.htiles * per_tok;
-  const int t = blockIdx.x / bpt;
-  int r = blockIdx.x - t * bpt;
-  int tc = r / a.htiles;
-  const int ht = r - tc * a.htiles;
-  int j, ch, fc;
-  if (tc < a.k * a.chunksR) { j = tc / a.chunksR; ch = tc - j * a.chunksR; fc = a.fcR; }
-  else { tc -= a.k * a.chunksR; j = a.k + tc / a.chunksS; ch = tc - (j - a.k) * a.chunksS; fc = a.fcS; }
-  const int task = t * nj + j;
-  int F; float wgt;
-  const char* base = task_weights(a, t, j, task, F, wgt);
-  if (base == nullptr) return;                        // not in this pass: does not count
+  const int t = blockIdx.x / a.htiles;
+  const int ht = blockIdx.x - t * a.htiles;
   const int H = a.H;
-  const T* W2 = reinterpret_cast<const T*>(base) + 2 * (size_t)F * H;
-  const int c0 = ch * fc;
-  const int clen = min(fc, F - c0);
+  const int h0 = ht * (4 * R) + wave * R;
 
-  const float* act = a.act + (size_t)task * a.Fmax + c0;
-  for (int i = tid; i < clen; i += 256) as[i] = act[i];
-  __syncthreads();
+  bool any_miss = false;
+  for (int q = 0; q < a.k; ++q) any_miss |= (a.rec->tok[t].slot[q] < 0);
+  if (a.pass == 1 && !any_miss) return;               // y of this token is already final
 
-  const int units = clen / N;
-  const int per_wave = a.RB >> 2;
-  const int h_begin = ht * a.RB + wave * per_wave;
-  float* part = a.partial + ((size_t)task * kMaxChunks + ch) * H;
-  for (int i = 0; i < per_wave; i += 4) {
-    const int h = h_begin + i;
-    if (h >= H) break;
-    const T* r0 = W2 + (size_t)h * F + c0;
-    const T* r1 = W2 + (size_t)min(h + 1, H - 1) * F + c0;
-    const T* r2 = W2 + (size_t)min(h + 2, H - 1) * F + c0;
-    const T* r3 = W2 + (size_t)min(h + 3, H - 1) * F + c0;
-    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-#pragma unroll 2
-    for (int u = lane; u < units; u += kWave) {
-      float w0[N], w1[N], w2[N], w3[N];
-      Unit<T>::load(r0 + u * N, w0);
-      Unit<T>::load(r1 + u * N, w1);
-      Unit<T>::load(r2 + u * N, w2);
-      Unit<T>::load(r3 + u * N, w3);
-      const float* av = as + u * N;
+  float acc[R];
 #pragma unroll
-      for (int q = 0; q < N; ++q) {
-        const float aq = av[q];
-        s0 = fmaf(w0[q], aq, s0);
-        s1 = fmaf(w1[q], aq, s1);
-        s2 = fmaf(w2[q], aq, s2);
-        s3 = fmaf(w3[q], aq, s3);
+  for (int r = 0; r < R; ++r) acc[r] = 0.f;
+
+  if (a.stage_all) {
+    int off = 0;
+    for (int j = 0; j < nj; ++j) {
+      int F; float wgt;
+      if (task_weights(a, t, j, t * nj + j, F, wgt) == nullptr) continue;
+      const float* act = a.act + (size_t)(t * nj + j) * a.Fmax;
+      for (int i = tid; i < F; i += 256) as[off + i] = act[i];
+      off += F;
+    }
+    __syncthreads();
+    off = 0;
+    for (int j = 0; j < nj; ++j) {
+      int F; float wgt;
+      const char* base = task_weights(a, t, j, t * nj + j, F, wgt);
+      if (base == nullptr) continue;
+      if (h0 < H) {
+        const T* W2 = reinterpret_cast<const T*>(base) + 2 * (size_t)F * H;
+        const T* rows[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) rows[r] = W2 + (size_t)min(h0 + r, H - 1) * F;
+        dot_rows<T, R, (R >= 4 ? 2 : 4)>(rows, as + off, F / N, lane, acc);
+      }
+      off += F;
+    }
+  } else {
+    for (int j = 0; j < nj; ++j) {
+      int F; float wgt;
+      const char* base = task_weights(a, t, j, t * nj + j, F, wgt);
+      if (base == nullptr) continue;
+      const T* W2 = reinterpret_cast<const T*>(base) + 2 * (size_t)F * H;
+      const float* act = a.act + (size_t)(t * nj + j) * a.Fmax;
+      for (int c0 = 0; c0 < F; c0 += a.chunk) {
+        const int clen = min(a.chunk, F - c0);
+        __syncthreads();                              // previous chunk consumed by every wave
+        for (int i = tid; i < clen; i += 256) as[i] = act[c0 + i];
+        __syncthreads();
+        if (h0 < H) {
+          const T* rows[R];
+#pragma unroll
+          for (int r = 0; r < R; ++r) rows[r] = W2 + (size_t)min(h0 + r, H - 1) * F + c0;
+          dot_rows<T, R, (R >= 4 ? 2 : 4)>(rows, as, clen / N, lane, acc);
+        }
       }
     }
-    s0 = wave_sum(s0); s1 = wave_sum(s1); s2 = wave_sum(s2); s3 = wave_sum(s3);
-    if (lane == 0) {
-      part[h] = s0;
-      if (h + 1 < H) part[h + 1] = s1;
-      if (h + 2 < H) part[h + 2] = s2;
-      if (h + 3 < H) part[h + 3] = s3;
-    }
   }
 
-  // ---- last block of this (token, row tile) combines all partial sums -------
-  __syncthreads();
-  uint32_t* counter = a.counters + (size_t)t * a.htiles + ht;
-  if (tid == 0) {
-    __threadfence();
-    const uint32_t old = atomicAdd(counter, 1u);
-    is_last = (old + 1u == (uint32_t)per_tok);
-  }
-  __syncthreads();
-  if (!is_last) return;
-  __threadfence();
-  T* y = static_cast<T*>(a.y) + (size_t)t * H;
-  for (int row = tid; row < a.RB; row += 256) {
-    const int h = ht * a.RB + row;
-    if (h >= H) break;
-    float sum = 0.f;
-    for (int jj = 0; jj < nj; ++jj) {
-      const int nch = jj < a.k ? a.chunksR : a.chunksS;
-      const float* p = a.partial + ((size_t)(t * nj + jj) * kMaxChunks) * H + h;
-      for (int c = 0; c < nch; ++c)
-        sum += __hip_atomic_load(p + (size_t)c * H, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+  for (int r = 0; r < R; ++r) acc[r] = wave_sum(acc[r]);
+  if (lane == 0) {
+    T* y = static_cast<T*>(a.y) + (size_t)t * H;
+    float* ysum = a.ysum + (size_t)t * H;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int h = h0 + r;
+      if (h >= H) break;
+      if (a.pass == 0) {
+        if (any_miss) ysum[h] = acc[r];
+        else y[h] = Unit<T>::narrow(acc[r]);
+      } else {
+        y[h] = Unit<T>::narrow(ysum[h] + acc[r]);
+      }
     }
-    y[h] = Unit<T>::narrow(sum);
   }
-  if (tid == 0) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 __global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst,
@@ -235,11 +268,6 @@ __global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst,
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
     dst[i] = src[i];
-}
-
-__global__ void fill_u32_kernel(uint32_t* p, int64_t n, uint32_t v) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = v;
 }
 
 }  // namespace
@@ -253,13 +281,18 @@ void launch_ffn_up(const FfnArgs& a, int dtype, hipStream_t s) {
     hipLaunchKernelGGL(ffn_up_kernel<bf16_t>, dim3(grid), dim3(256), lds, s, a);
 }
 
+template <typename T>
+static void launch_down_t(const FfnArgs& a, hipStream_t s) {
+  const int grid = a.B * a.htiles;
+  const size_t lds = (size_t)a.down_lds_floats * sizeof(float);
+  if (a.R == 1) hipLaunchKernelGGL((ffn_down_kernel<T, 1>), dim3(grid), dim3(256), lds, s, a);
+  else if (a.R == 2) hipLaunchKernelGGL((ffn_down_kernel<T, 2>), dim3(grid), dim3(256), lds, s, a);
+  else hipLaunchKernelGGL((ffn_down_kernel<T, 4>), dim3(grid), dim3(256), lds, s, a);
+}
+
 void launch_ffn_down(const FfnArgs& a, int dtype, hipStream_t s) {
-  const int grid = a.B * a.htiles * (a.k * a.chunksR + a.ns * a.chunksS);
-  const size_t lds = (size_t)(a.fcR > a.fcS ? a.fcR : a.fcS) * sizeof(float);
-  if (dtype == SMOE_DTYPE_FP32)
-    hipLaunchKernelGGL(ffn_down_kernel<float>, dim3(grid), dim3(256), lds, s, a);
-  else
-    hipLaunchKernelGGL(ffn_down_kernel<bf16_t>, dim3(grid), dim3(256), lds, s, a);
+  if (dtype == SMOE_DTYPE_FP32) launch_down_t<float>(a, s);
+  else launch_down_t<bf16_t>(a, s);
 }
 
 void launch_copy(void* dst, const void* src, int64_t n_bytes, hipStream_t s) {
@@ -269,11 +302,6 @@ void launch_copy(void* dst, const void* src, int64_t n_bytes, hipStream_t s) {
   if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
                      static_cast<uint4*>(dst), static_cast<const uint4*>(src), n);
-}
-
-void launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t s) {
-  if (n <= 0) return;
-  hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, n, v);
 }
 
 }  // namespace smoe

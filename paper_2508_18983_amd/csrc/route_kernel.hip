@@ -43,12 +43,34 @@ __device__ __forceinline__ int wave_argmax(float v, bool valid, int lane) {
   return idx == kWave ? -1 : idx;
 }
 
-__device__ __forceinline__ float to_f32(float v) { return v; }
-__device__ __forceinline__ float to_f32(bf16_t v) { return __uint_as_float(uint32_t(v.v) << 16); }
+template <typename T> struct GateUnit;
+template <> struct GateUnit<float> {
+  static constexpr int N = 4;
+  __device__ static __forceinline__ void load(const float* p, float (&v)[4]) {
+    const float4 q = *reinterpret_cast<const float4*>(p);
+    v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+  }
+  __device__ static __forceinline__ float widen1(float s) { return s; }
+};
+template <> struct GateUnit<bf16_t> {
+  static constexpr int N = 8;
+  __device__ static __forceinline__ void load(const bf16_t* p, float (&v)[8]) {
+    const uint4 q = *reinterpret_cast<const uint4*>(p);
+    v[0] = __uint_as_float(q.x << 16); v[1] = __uint_as_float(q.x & 0xffff0000u);
+    v[2] = __uint_as_float(q.y << 16); v[3] = __uint_as_float(q.y & 0xffff0000u);
+    v[4] = __uint_as_float(q.z << 16); v[5] = __uint_as_float(q.z & 0xffff0000u);
+    v[6] = __uint_as_float(q.w << 16); v[7] = __uint_as_float(q.w & 0xffff0000u);
+  }
+  __device__ static __forceinline__ float widen1(bf16_t s) { return __uint_as_float(uint32_t(s.v) << 16); }
+};
 
-template <typename T>
+constexpr int kMaxSeg = 8;   // a gate row is split into at most this many segments
+
+// NTOK = tokens whose hidden states sit in LDS together (dynamic LDS: NTOK*H floats).
+template <typename T, int NTOK>
 __global__ __launch_bounds__(1024) void route_kernel(const RouteArgs a) {
-  __shared__ float xs[SMOE_MAX_HIDDEN];
+  extern __shared__ __align__(16) float xs[];                 // [NTOK][H]
+  __shared__ float part[SMOE_MAX_BATCH][kWave][kMaxSeg];
   __shared__ float lg[SMOE_MAX_BATCH][kWave];
   __shared__ float sc[SMOE_MAX_BATCH][kWave];
   __shared__ int rk[SMOE_MAX_BATCH][kWave];
@@ -57,28 +79,59 @@ __global__ __launch_bounds__(1024) void route_kernel(const RouteArgs a) {
   __shared__ unsigned long long top_m_sh[SMOE_MAX_BATCH];
   __shared__ int slot_of[kWave];
 
+  constexpr int N = GateUnit<T>::N;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
   const int nw = blockDim.x >> 6;
   const int H = a.H, E = a.E, k = a.k, B = a.B;
   if (tid < kWave) slot_of[tid] = a.slot_of[tid];
 
   // ---- gate GEMV: logits[t][e] = Wg[e] . x[t] --------------------------------
+  // work item = (expert row, segment of the row); segments are summed in a fixed order
   const T* wg = static_cast<const T*>(a.gate_w);
   const T* x = static_cast<const T*>(a.x);
-  for (int t = 0; t < B; ++t) {
+  const int units = H / N;
+  const int nseg = a.nseg;
+  const int items = E * nseg;
+  for (int t0 = 0; t0 < B; t0 += NTOK) {
+    const int nt = min(NTOK, B - t0);
     __syncthreads();
-    for (int h = tid; h < H; h += blockDim.x) xs[h] = to_f32(x[(size_t)t * H + h]);
+    for (int i = tid; i < nt * H; i += blockDim.x) xs[i] = GateUnit<T>::widen1(x[(size_t)t0 * H + i]);
     __syncthreads();
-    for (int e = wave; e < E; e += nw) {
+    for (int it = wave; it < items; it += nw) {
+      const int e = it / nseg, sg = it - e * nseg;
+      const int u0 = (int)((long)units * sg / nseg), u1 = (int)((long)units * (sg + 1) / nseg);
       const T* row = wg + (size_t)e * H;
-      float acc = 0.f;
-      for (int h = lane; h < H; h += kWave) acc = fmaf(to_f32(row[h]), xs[h], acc);
-      acc = wave_sum(acc);
-      if (lane == 0) lg[t][e] = acc;
+      float acc[NTOK];
+#pragma unroll
+      for (int q = 0; q < NTOK; ++q) acc[q] = 0.f;
+#pragma unroll 4
+      for (int u = u0 + lane; u < u1; u += kWave) {
+        float w[N];
+        GateUnit<T>::load(row + (size_t)u * N, w);
+#pragma unroll
+        for (int q = 0; q < NTOK; ++q) {
+          if (q < nt) {
+            const float* xv = xs + (size_t)q * H + (size_t)u * N;
+#pragma unroll
+            for (int i = 0; i < N; ++i) acc[q] = fmaf(w[i], xv[i], acc[q]);
+          }
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < NTOK; ++q) {
+        const float v = wave_sum(acc[q]);
+        if (lane == 0 && q < nt) part[t0 + q][e][sg] = v;
+      }
     }
   }
   __syncthreads();
   if (wave != 0) return;
+  for (int t = 0; t < B; ++t) {
+    float v = 0.f;
+    if (lane < E)
+      for (int sg = 0; sg < nseg; ++sg) v += part[t][lane][sg];
+    lg[t][lane] = v;
+  }
 
   // ---- pass 1: scores, top-(k+1), alpha classes, batch top-score set C ------
   const bool has_pivot = E > k;
@@ -156,11 +209,24 @@ __global__ __launch_bounds__(1024) void route_kernel(const RouteArgs a) {
 
 }  // namespace
 
+template <typename T>
+static void launch_route_t(const RouteArgs& a, hipStream_t s) {
+  // as many tokens' hidden states in LDS together as fit in 32 KB
+  int ntok = 1;
+  while (ntok < a.B && ntok < SMOE_MAX_BATCH && (size_t)(2 * ntok) * a.H * sizeof(float) <= 32 * 1024)
+    ntok *= 2;
+  const size_t lds = (size_t)ntok * a.H * sizeof(float);
+  switch (ntok) {
+    case 1: hipLaunchKernelGGL((route_kernel<T, 1>), dim3(1), dim3(1024), lds, s, a); break;
+    case 2: hipLaunchKernelGGL((route_kernel<T, 2>), dim3(1), dim3(1024), lds, s, a); break;
+    case 4: hipLaunchKernelGGL((route_kernel<T, 4>), dim3(1), dim3(1024), lds, s, a); break;
+    default: hipLaunchKernelGGL((route_kernel<T, 8>), dim3(1), dim3(1024), lds, s, a); break;
+  }
+}
+
 void launch_route(const RouteArgs& a, int dtype, hipStream_t s) {
-  if (dtype == SMOE_DTYPE_FP32)
-    hipLaunchKernelGGL(route_kernel<float>, dim3(1), dim3(1024), 0, s, a);
-  else
-    hipLaunchKernelGGL(route_kernel<bf16_t>, dim3(1), dim3(1024), 0, s, a);
+  if (dtype == SMOE_DTYPE_FP32) launch_route_t<float>(a, s);
+  else launch_route_t<bf16_t>(a, s);
 }
 
 }  // namespace smoe

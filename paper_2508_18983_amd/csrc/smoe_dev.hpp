@@ -9,8 +9,8 @@ namespace smoe {
 
 constexpr int kWave = 64;
 constexpr int kMaxTasks = SMOE_MAX_BATCH * (SMOE_MAX_TOPK + SMOE_MAX_SHARED);
-constexpr int kMaxChunks = 8;          // F-chunks of the down projection
-constexpr int kChunkElems = 4096;      // fp32 activations one down-projection block keeps in LDS
+constexpr int kStageElems = 16384;     // fp32 activations a down-projection block can hold in LDS
+constexpr int kChunkElems = 8192;      // default chunk when the activations do not fit at once
 
 // Routing decision of one token, written by the router kernel to device memory
 // (read by the FFN kernels) and to a pinned host mirror (read by the scheduler).
@@ -34,6 +34,7 @@ struct RouteArgs {
   StepRec* rec_host;    // device-visible address of the pinned mirror
   int32_t B, H, E, k;
   int32_t renorm, subst_key;
+  int32_t nseg;         // segments each gate row is split into (power of two, <= 8)
   float alpha;
   uint64_t resident;                  // bit e = expert e is in the HBM cache
   int8_t slot_of[SMOE_MAX_EXPERTS];   // layer-local slot of each resident expert
@@ -49,8 +50,7 @@ struct FfnArgs {
   const char* slab;         // cache slab base
   const char* shared;       // this layer's shared experts, or null
   float* act;               // [task][Fmax] weighted SwiGLU activations
-  float* partial;           // [task][kMaxChunks][H]
-  uint32_t* counters;       // [B][htiles]
+  float* ysum;              // [B][H] fp32 sums of pass 0 for tokens that still wait for loads
   int64_t expert_bytes;     // bytes of one routed expert
   int64_t shared_bytes;     // bytes of one shared expert
   int32_t B, H, F, Fs, k, ns;
@@ -58,8 +58,8 @@ struct FfnArgs {
   int32_t slot_base;        // layer * cache_cap
   int32_t pass;             // 0: routed tasks whose expert is resident + shared; 1: slot_override >= 0 only
   int32_t TF, tilesR, tilesS;              // up: f-rows per block, blocks per routed / shared task
-  int32_t RB, htiles;                      // down: output rows per block
-  int32_t chunksR, chunksS, fcR, fcS;      // down: F-chunks per task and their length
+  int32_t R, htiles;                       // down: rows per wave, row tiles (4*R rows each) per token
+  int32_t stage_all, chunk, down_lds_floats;  // down: all activations in LDS at once, else chunked
   int32_t slot_override[kMaxTasks];        // pass 1: global slot per task, -1 = not in this pass
 };
 
@@ -67,6 +67,5 @@ void launch_route(const RouteArgs& a, int dtype, hipStream_t s);
 void launch_ffn_up(const FfnArgs& a, int dtype, hipStream_t s);
 void launch_ffn_down(const FfnArgs& a, int dtype, hipStream_t s);
 void launch_copy(void* dst, const void* src, int64_t n_bytes, hipStream_t s);
-void launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t s);
 
 }  // namespace smoe

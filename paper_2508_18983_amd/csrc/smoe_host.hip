@@ -63,11 +63,9 @@ struct moe_handle {
   StepRec* rec_host = nullptr;           // pinned
   StepRec* rec_host_dev = nullptr;       // its device-visible address
   float* act = nullptr;
-  float* partial = nullptr;
-  uint32_t* counters = nullptr;
-  int counters_n = 0;
+  float* ysum = nullptr;
   // launch geometry
-  int TF = 0, tilesR = 0, tilesS = 0, RB = 0, htiles = 0, chunksR = 0, chunksS = 0, fcR = 0, fcS = 0;
+  int TF = 0, tilesR = 0, tilesS = 0, R = 0, htiles = 0, stage_all = 0, chunk = 0, down_lds = 0;
   // profiling
   bool prof_on = false;
   ProfKind prof[SMOE_PROF_KINDS];
@@ -81,19 +79,10 @@ int env_int(const char* name, int dflt) {
   return std::atoi(v);
 }
 
-void chunking(int F, int elem_units, int& chunks, int& fc) {
-  if (F <= 0) { chunks = 0; fc = 0; return; }
-  chunks = (F + kChunkElems - 1) / kChunkElems;
-  const int q = 64 * elem_units;                      // one wave pass
-  fc = ((F + chunks - 1) / chunks + q - 1) / q * q;
-  if (fc > kChunkElems) fc = kChunkElems;
-  chunks = (F + fc - 1) / fc;
-}
-
 void plan_geometry(moe_handle* h) {
   const moe_cfg_t& c = h->cfg;
-  const int n = c.dtype == SMOE_DTYPE_FP32 ? 4 : 8;
   const long total_f = (long)c.top_k * c.ffn + (long)c.n_shared * c.shared_ffn;
+  // up: TF rows of W1 and W3 per block, enough blocks to fill 256 CUs several times
   int tf = total_f >= 32 * 1024 ? 32 : (total_f >= 16 * 1024 ? 16 : 8);
   tf = env_int("SMOE_TF", tf);
   if (tf < 8) tf = 8;
@@ -101,15 +90,16 @@ void plan_geometry(moe_handle* h) {
   h->TF = tf;
   h->tilesR = (c.ffn + tf - 1) / tf;
   h->tilesS = c.n_shared ? (c.shared_ffn + tf - 1) / tf : 0;
-  chunking(c.ffn, n, h->chunksR, h->fcR);
-  chunking(c.n_shared ? c.shared_ffn : 0, n, h->chunksS, h->fcS);
-  const long pairs = (long)c.top_k * h->chunksR + (long)c.n_shared * h->chunksS;
-  int rb = (pairs * ((c.hidden + 31) / 32) >= 1024) ? 32 : 16;
-  rb = env_int("SMOE_RB", rb);
-  if (rb < 16) rb = 16;
-  rb = rb / 16 * 16;
-  h->RB = rb;
-  h->htiles = (c.hidden + rb - 1) / rb;
+  // down: R rows per wave, 4 waves per block
+  int r = (c.hidden / 4 >= 2048) ? 2 : 1;
+  r = env_int("SMOE_R", r);
+  h->R = r >= 4 ? 4 : (r >= 2 ? 2 : 1);
+  h->htiles = (c.hidden + 4 * h->R - 1) / (4 * h->R);
+  h->stage_all = total_f <= kStageElems;
+  int chunk = env_int("SMOE_CHUNK", kChunkElems);
+  chunk = std::max(512, std::min(kStageElems, chunk / 512 * 512));
+  h->chunk = chunk;
+  h->down_lds = h->stage_all ? (int)total_f : chunk;
 }
 
 int upload_initial(moe_handle* h) {
@@ -135,9 +125,6 @@ int upload_initial(moe_handle* h) {
     }
   }
   HIP_TRY(hipStreamSynchronize(h->s_copy));
-  launch_fill_u32(h->counters, h->counters_n, 0u, h->s_compute);
-  HIP_TRY(hipGetLastError());
-  HIP_TRY(hipStreamSynchronize(h->s_compute));
   return SMOE_OK;
 }
 
@@ -151,8 +138,7 @@ void free_all(moe_handle* h) {
   if (h->rec_dev) (void)hipFree(h->rec_dev);
   if (h->rec_host) (void)hipHostFree(h->rec_host);
   if (h->act) (void)hipFree(h->act);
-  if (h->partial) (void)hipFree(h->partial);
-  if (h->counters) (void)hipFree(h->counters);
+  if (h->ysum) (void)hipFree(h->ysum);
   delete h;
 }
 
@@ -233,7 +219,6 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
 
   const int nj = c.top_k + c.n_shared;
   const size_t sim_bytes = (size_t)c.n_layers * c.n_experts * c.n_experts * sizeof(float);
-  h->counters_n = c.max_batch * h->htiles;
   int rc = [&]() -> int {
     HIP_TRY(hipEventCreateWithFlags(&h->ev_route, hipEventDisableTiming));
     HIP_TRY(hipEventCreateWithFlags(&h->ev_copy, hipEventDisableTiming));
@@ -246,12 +231,10 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
     HIP_TRY(hipHostGetDevicePointer(&dp, h->rec_host, 0));
     h->rec_host_dev = static_cast<StepRec*>(dp);
     HIP_TRY(hipMalloc(&h->act, (size_t)c.max_batch * nj * h->Fmax * sizeof(float)));
-    HIP_TRY(hipMalloc(&h->partial, (size_t)c.max_batch * nj * kMaxChunks * c.hidden * sizeof(float)));
-    HIP_TRY(hipMalloc(&h->counters, (size_t)h->counters_n * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&h->ysum, (size_t)c.max_batch * c.hidden * sizeof(float)));
     return upload_initial(h);
   }();
   if (rc != SMOE_OK) { free_all(h); return rc; }
-  if (h->chunksR > kMaxChunks || h->chunksS > kMaxChunks) { free_all(h); return SMOE_EINVAL; }
   *out = h;
   return SMOE_OK;
 }
@@ -273,6 +256,8 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   ra.rec_host = h->rec_host_dev;
   ra.B = B; ra.H = c.hidden; ra.E = E; ra.k = k;
   ra.renorm = c.renorm_topk; ra.subst_key = c.subst_key; ra.alpha = c.alpha;
+  ra.nseg = 1;
+  while (ra.nseg < 8 && E * ra.nseg < 32 && c.hidden / (ra.nseg * 2) >= 512) ra.nseg *= 2;
   ra.resident = ls.resident;
   std::memcpy(ra.slot_of, ls.slot_of, sizeof(ra.slot_of));
   EventPair* pr = prof_begin(h, SMOE_PROF_ROUTE, h->s_compute);
@@ -290,15 +275,15 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   fa.shared = c.n_shared ? static_cast<const char*>(h->buf.shared_dev) +
                                (int64_t)layer * c.n_shared * h->shared_bytes
                          : nullptr;
-  fa.act = h->act; fa.partial = h->partial; fa.counters = h->counters;
+  fa.act = h->act; fa.ysum = h->ysum;
   fa.expert_bytes = h->expert_bytes; fa.shared_bytes = h->shared_bytes;
   fa.B = B; fa.H = c.hidden; fa.F = c.ffn; fa.Fs = c.n_shared ? c.shared_ffn : 0;
   fa.k = k; fa.ns = c.n_shared; fa.Fmax = h->Fmax;
   fa.slot_base = layer * c.cache_cap;
   fa.pass = 0;
   fa.TF = h->TF; fa.tilesR = h->tilesR; fa.tilesS = h->tilesS;
-  fa.RB = h->RB; fa.htiles = h->htiles;
-  fa.chunksR = h->chunksR; fa.chunksS = h->chunksS; fa.fcR = h->fcR; fa.fcS = h->fcS;
+  fa.R = h->R; fa.htiles = h->htiles;
+  fa.stage_all = h->stage_all; fa.chunk = h->chunk; fa.down_lds_floats = h->down_lds;
   for (int i = 0; i < kMaxTasks; ++i) fa.slot_override[i] = -1;
   EventPair* pu = prof_begin(h, SMOE_PROF_UP, h->s_compute);
   launch_ffn_up(fa, c.dtype, h->s_compute);
