@@ -32,12 +32,17 @@ def run_tokens(ses, x_dev, y_dev, t0: int, t1: int, n_layers: int) -> None:
             ses.decode(l, x_dev[t, l], y_dev[l])
 
 
-def timed_run(ses, x_dev, y_dev, warmup: int, steps: int, n_layers: int, prof_launches: int):
+PROF_UP_AND_COPY = (1 << 1) | (1 << 3)
+PROF_ALL = (1 << 6) - 1
+
+
+def timed_run(ses, x_dev, y_dev, warmup: int, steps: int, n_layers: int, prof_launches: int,
+              prof_mask: int = PROF_UP_AND_COPY):
     import paper_2508_18983_amd as M
     run_tokens(ses, x_dev, y_dev, 0, warmup, n_layers)
     ses.sync()
     st0 = ses.stats()
-    M.moe_profile_enable(ses.handle, 1, prof_launches)
+    M.moe_profile_enable(ses.handle, prof_mask, prof_launches)
     ses.sync()
     t_begin = time.perf_counter()
     run_tokens(ses, x_dev, y_dev, warmup, warmup + steps, n_layers)
@@ -133,11 +138,9 @@ def main() -> int:
         elapsed, prof, st = timed_run(ses, x_dev, y_dev, args.warmup, args.steps, L, prof_launches)
     tok_s = args.steps / elapsed
     up = prof["up"]
-    down = prof["down"]
     up_avg_s = up["ms"] / max(up["launches"], 1) * 1e-3
     up_bytes_per_launch = up["bytes"] / max(up["launches"], 1)
     achieved = up_bytes_per_launch / up_avg_s / 1e9 if up_avg_s > 0 else 0.0
-    down_gbs = (down["bytes"] / (down["ms"] * 1e-3) / 1e9) if down["ms"] > 0 else 0.0
     copy = prof["copy"]
     host_link = (copy["bytes"] / (copy["ms"] * 1e-3) / 1e9) if copy["ms"] > 0 else None
 
@@ -147,10 +150,6 @@ def main() -> int:
         "substitutions_per_token": st["substitutions"] / args.steps,
         "fetches_per_token": st["fetches"] / args.steps,
         "host_link_GBs": host_link,
-        "kernel_avg_us": {k: (v["ms"] * 1e3 / v["launches"] if v["launches"] else None)
-                          for k, v in prof.items()},
-        "down_kernel_GBs": down_gbs,
-        "down_kernel_frac": down_gbs / HBM_PEAK_GBS,
         "layer_bytes": s.layer_bytes(),
         "hbm_roofline_tokens_per_s": HBM_PEAK_GBS * 1e9 / (s.layer_bytes() * L),
     }
@@ -164,12 +163,18 @@ def main() -> int:
             with session_from_workload(wl_full, max_batch=1) as ses2:
                 x_dev = wl.x.to(ses2.device).contiguous()
                 y_dev = torch.empty(L, 1, s.hidden, dtype=ses2.tdtype, device=ses2.device)
-                e2, p2, _ = timed_run(ses2, x_dev, y_dev, min(args.warmup, 4), args.steps, L, prof_launches)
-            extra["miss_free_tokens_per_s"] = args.steps / e2
-            extra["miss_free_frac_of_hbm_roofline"] = (args.steps / e2) / extra["hbm_roofline_tokens_per_s"]
-            u2, d2 = p2["up"], p2["down"]
-            extra["miss_free_up_GBs"] = u2["bytes"] / (u2["ms"] * 1e-3) / 1e9
-            extra["miss_free_down_GBs"] = d2["bytes"] / (d2["ms"] * 1e-3) / 1e9
+                e2, p2, _ = timed_run(ses2, x_dev, y_dev, min(args.warmup, 4), args.steps, L, prof_launches,
+                                      prof_mask=0)
+                extra["miss_free_tokens_per_s"] = args.steps / e2
+                extra["miss_free_frac_of_hbm_roofline"] = (args.steps / e2) / extra["hbm_roofline_tokens_per_s"]
+                # a short pass with an event pair around every launch: per-kernel durations
+                n_short = min(args.steps, 16)
+                _, p3, _ = timed_run(ses2, x_dev, y_dev, 0, n_short, L, n_short * L + 8, prof_mask=PROF_ALL)
+            for kind in ("route", "up", "down"):
+                v = p3[kind]
+                if v["launches"]:
+                    extra[f"miss_free_{kind}_us"] = v["ms"] * 1e3 / v["launches"]
+                    extra[f"miss_free_{kind}_GBs"] = v["bytes"] / (v["ms"] * 1e-3) / 1e9
         except Exception as exc:            # e.g. not enough HBM for every expert
             extra["miss_free_error"] = repr(exc)
 

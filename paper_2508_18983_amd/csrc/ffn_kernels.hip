@@ -263,6 +263,187 @@ __global__ __launch_bounds__(256) void ffn_down_kernel(const FfnArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// Register-resident fast paths.  A lane always multiplies the same columns, so
+// its slice of the activation vector stays in registers for every row it
+// streams: no LDS traffic, no block-wide barrier inside the row loop.
+// ---------------------------------------------------------------------------
+
+// Up projection with x in registers: one wave owns whole rows (H/N <= 64*UPL
+// units).  Per f it has 2*UPL independent 128-bit loads in flight.
+template <typename T, int UPL>
+__global__ __launch_bounds__(256) void ffn_up_reg_kernel(const FfnArgs a) {
+  constexpr int N = Unit<T>::N;
+  using raw = typename Unit<T>::raw;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+  const int nj = a.k + a.ns;
+  const int bpt = a.k * a.tilesR + a.ns * a.tilesS;
+  const int t = blockIdx.x / bpt;
+  int r = blockIdx.x - t * bpt, j, tile;
+  if (r < a.k * a.tilesR) { j = r / a.tilesR; tile = r - j * a.tilesR; }
+  else { r -= a.k * a.tilesR; j = a.k + r / a.tilesS; tile = r - (j - a.k) * a.tilesS; }
+  const int task = t * nj + j;
+  int F; float wgt;
+  const char* base = task_weights(a, t, j, task, F, wgt);
+  if (base == nullptr) return;
+  const int H = a.H;
+  const int units = H / N;
+  const T* W1 = reinterpret_cast<const T*>(base);
+  const T* W3 = W1 + (size_t)F * H;
+
+  float xr[UPL][N];
+  const T* x = static_cast<const T*>(a.x) + (size_t)t * H;
+#pragma unroll
+  for (int i = 0; i < UPL; ++i) {
+    const int u = i * kWave + lane;
+    if (u < units) {
+      const raw q = *reinterpret_cast<const raw*>(x + (size_t)u * N);
+      Unit<T>::widen(q, xr[i]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < N; ++e) xr[i][e] = 0.f;
+    }
+  }
+
+  const int per_wave = a.TF >> 2;
+  const int f_begin = tile * a.TF + wave * per_wave;
+  float* act = a.act + (size_t)task * a.Fmax;
+  for (int i = 0; i < per_wave; ++i) {
+    const int f = f_begin + i;
+    if (f >= F) break;
+    const T* g = W1 + (size_t)f * H;
+    const T* up = W3 + (size_t)f * H;
+    raw qg[UPL], qu[UPL];
+#pragma unroll
+    for (int s = 0; s < UPL; ++s) {
+      const int u = s * kWave + lane;
+      if (u < units) {
+        qg[s] = Unit<T>::load(g + (size_t)u * N);
+        qu[s] = Unit<T>::load(up + (size_t)u * N);
+      } else {
+        qg[s] = raw{};
+        qu[s] = raw{};
+      }
+    }
+    float ag = 0.f, au = 0.f;
+#pragma unroll
+    for (int s = 0; s < UPL; ++s) {
+      float wg[N], wu[N];
+      Unit<T>::widen(qg[s], wg);
+      Unit<T>::widen(qu[s], wu);
+#pragma unroll
+      for (int e = 0; e < N; ++e) {
+        ag = fmaf(wg[e], xr[s][e], ag);
+        au = fmaf(wu[e], xr[s][e], au);
+      }
+    }
+    ag = wave_sum(ag);
+    au = wave_sum(au);
+    if (lane == 0) act[f] = wgt * (ag / (1.0f + expf(-ag))) * au;
+  }
+}
+
+// Down projection with the activations in registers.  A block owns RB output
+// rows of one token.  Per task the row is cut into nseg in {1, 2, 4} column
+// segments of <= 64*UPL units; wave w works on segment w % nseg for the rows
+// w / nseg, w / nseg + 4 / nseg, ...  Every (task, segment, row) partial sum is
+// produced by exactly one wave and parked in LDS; after one barrier the block
+// adds them in fixed (task, segment) order.  R rows are streamed at a time.
+template <typename T, int UPL, int R>
+__global__ __launch_bounds__(256) void ffn_down_reg_kernel(const FfnArgs a) {
+  extern __shared__ __align__(16) float part[];       // [nj][4][RB]
+  constexpr int N = Unit<T>::N;
+  using raw = typename Unit<T>::raw;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+  const int nj = a.k + a.ns;
+  const int RB = a.RB;
+  const int t = blockIdx.x / a.htiles;
+  const int ht = blockIdx.x - t * a.htiles;
+  const int H = a.H;
+  const int hb = ht * RB;
+
+  bool any_miss = false;
+  for (int q = 0; q < a.k; ++q) any_miss |= (a.rec->tok[t].slot[q] < 0);
+  if (a.pass == 1 && !any_miss) return;
+
+  for (int i = tid; i < nj * 4 * RB; i += 256) part[i] = 0.f;
+  __syncthreads();
+
+  for (int j = 0; j < nj; ++j) {
+    int F; float wgt;
+    const char* base = task_weights(a, t, j, t * nj + j, F, wgt);
+    if (base == nullptr) continue;
+    const int nseg = j < a.k ? a.nsegR : a.nsegS;
+    const int units = F / N;
+    const int seg_units = (units + nseg - 1) / nseg;          // units per segment
+    const int seg = wave % nseg, rsub = wave / nseg, rstep = 4 / nseg;
+    const int ubeg = seg * seg_units;
+    const int uend = min(units, ubeg + seg_units);
+    const T* W2 = reinterpret_cast<const T*>(base) + 2 * (size_t)F * H;
+    const float* act = a.act + (size_t)(t * nj + j) * a.Fmax;
+
+    float ar[UPL][N];
+#pragma unroll
+    for (int i = 0; i < UPL; ++i) {
+      const int u = ubeg + i * kWave + lane;
+      if (u < uend) {
+#pragma unroll
+        for (int e = 0; e < N; e += 4) {
+          const float4 v = *reinterpret_cast<const float4*>(act + (size_t)u * N + e);
+          ar[i][e] = v.x; ar[i][e + 1] = v.y; ar[i][e + 2] = v.z; ar[i][e + 3] = v.w;
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < N; ++e) ar[i][e] = 0.f;
+      }
+    }
+
+    float* prow = part + ((size_t)j * 4 + seg) * RB;
+    for (int rr = rsub * R; rr < RB; rr += rstep * R) {
+      if (hb + rr >= H) break;
+      raw q[R][UPL];
+#pragma unroll
+      for (int r2 = 0; r2 < R; ++r2) {
+        const T* row = W2 + (size_t)min(hb + rr + r2, H - 1) * F;
+#pragma unroll
+        for (int s = 0; s < UPL; ++s) {
+          const int u = ubeg + s * kWave + lane;
+          q[r2][s] = (u < uend) ? Unit<T>::load(row + (size_t)u * N) : raw{};
+        }
+      }
+#pragma unroll
+      for (int r2 = 0; r2 < R; ++r2) {
+        float acc = 0.f;
+#pragma unroll
+        for (int s = 0; s < UPL; ++s) {
+          float w[N];
+          Unit<T>::widen(q[r2][s], w);
+#pragma unroll
+          for (int e = 0; e < N; ++e) acc = fmaf(w[e], ar[s][e], acc);
+        }
+        acc = wave_sum(acc);
+        if (lane == 0 && rr + r2 < RB) prow[rr + r2] = acc;
+      }
+    }
+  }
+  __syncthreads();
+  for (int row = tid; row < RB; row += 256) {
+    const int h = hb + row;
+    if (h >= H) break;
+    float sum = 0.f;
+    for (int j = 0; j < nj; ++j)
+      for (int sg = 0; sg < 4; ++sg) sum += part[((size_t)j * 4 + sg) * RB + row];
+    T* y = static_cast<T*>(a.y) + (size_t)t * H;
+    float* ysum = a.ysum + (size_t)t * H;
+    if (a.pass == 0) {
+      if (any_miss) ysum[h] = sum;
+      else y[h] = Unit<T>::narrow(sum);
+    } else {
+      y[h] = Unit<T>::narrow(ysum[h] + sum);
+    }
+  }
+}
+
 __global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst,
                                                    const uint4* __restrict__ src, int64_t n) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -272,18 +453,40 @@ __global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst,
 
 }  // namespace
 
-void launch_ffn_up(const FfnArgs& a, int dtype, hipStream_t s) {
+template <typename T>
+static void launch_up_t(const FfnArgs& a, hipStream_t s) {
   const int grid = a.B * (a.k * a.tilesR + a.ns * a.tilesS);
+  switch (a.up_upl) {
+    case 1: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 1>), dim3(grid), dim3(256), 0, s, a); return;
+    case 2: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 2>), dim3(grid), dim3(256), 0, s, a); return;
+    case 4: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 4>), dim3(grid), dim3(256), 0, s, a); return;
+    case 8: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 8>), dim3(grid), dim3(256), 0, s, a); return;
+    default: break;
+  }
   const size_t lds = (size_t)a.H * sizeof(float);
-  if (dtype == SMOE_DTYPE_FP32)
-    hipLaunchKernelGGL(ffn_up_kernel<float>, dim3(grid), dim3(256), lds, s, a);
-  else
-    hipLaunchKernelGGL(ffn_up_kernel<bf16_t>, dim3(grid), dim3(256), lds, s, a);
+  hipLaunchKernelGGL(ffn_up_kernel<T>, dim3(grid), dim3(256), lds, s, a);
+}
+
+void launch_ffn_up(const FfnArgs& a, int dtype, hipStream_t s) {
+  if (dtype == SMOE_DTYPE_FP32) launch_up_t<float>(a, s);
+  else launch_up_t<bf16_t>(a, s);
 }
 
 template <typename T>
 static void launch_down_t(const FfnArgs& a, hipStream_t s) {
   const int grid = a.B * a.htiles;
+  if (a.down_upl > 0) {
+    const size_t lds = (size_t)(a.k + a.ns) * 4 * a.RB * sizeof(float);
+    switch (a.down_upl) {
+      case 2: hipLaunchKernelGGL((ffn_down_reg_kernel<T, 2, 4>), dim3(grid), dim3(256), lds, s, a); return;
+      case 4: hipLaunchKernelGGL((ffn_down_reg_kernel<T, 4, 2>), dim3(grid), dim3(256), lds, s, a); return;
+      case 6: hipLaunchKernelGGL((ffn_down_reg_kernel<T, 6, 2>), dim3(grid), dim3(256), lds, s, a); return;
+      case 8: hipLaunchKernelGGL((ffn_down_reg_kernel<T, 8, 1>), dim3(grid), dim3(256), lds, s, a); return;
+      case 10: hipLaunchKernelGGL((ffn_down_reg_kernel<T, 10, 1>), dim3(grid), dim3(256), lds, s, a); return;
+      case 12: hipLaunchKernelGGL((ffn_down_reg_kernel<T, 12, 1>), dim3(grid), dim3(256), lds, s, a); return;
+      default: break;
+    }
+  }
   const size_t lds = (size_t)a.down_lds_floats * sizeof(float);
   if (a.R == 1) hipLaunchKernelGGL((ffn_down_kernel<T, 1>), dim3(grid), dim3(256), lds, s, a);
   else if (a.R == 2) hipLaunchKernelGGL((ffn_down_kernel<T, 2>), dim3(grid), dim3(256), lds, s, a);

@@ -205,6 +205,9 @@ __global__ __launch_bounds__(1024) void route_kernel(const RouteArgs a) {
     }
     a.rec_host->tok[t].scores[lane] = lane < E ? s : 0.f;
   }
+  // publish: every store of this wave to the mirror is complete before seq changes
+  __threadfence_system();
+  if (lane == 0) __hip_atomic_store(&a.rec_host->seq, a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 }  // namespace

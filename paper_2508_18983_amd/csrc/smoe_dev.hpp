@@ -24,6 +24,7 @@ struct TokRec {
 };
 struct StepRec {
   TokRec tok[SMOE_MAX_BATCH];
+  int32_t seq;                     // host mirror only: call number, written last
 };
 
 struct RouteArgs {
@@ -35,6 +36,7 @@ struct RouteArgs {
   int32_t B, H, E, k;
   int32_t renorm, subst_key;
   int32_t nseg;         // segments each gate row is split into (power of two, <= 8)
+  int32_t seq;          // call number published to the host mirror when the record is complete
   float alpha;
   uint64_t resident;                  // bit e = expert e is in the HBM cache
   int8_t slot_of[SMOE_MAX_EXPERTS];   // layer-local slot of each resident expert
@@ -59,7 +61,10 @@ struct FfnArgs {
   int32_t pass;             // 0: routed tasks whose expert is resident + shared; 1: slot_override >= 0 only
   int32_t TF, tilesR, tilesS;              // up: f-rows per block, blocks per routed / shared task
   int32_t R, htiles;                       // down: rows per wave, row tiles (4*R rows each) per token
-  int32_t stage_all, chunk, down_lds_floats;  // down: all activations in LDS at once, else chunked
+  int32_t stage_all, chunk, down_lds_floats;  // down (LDS path): all activations in LDS at once, else chunked
+  int32_t up_upl;                          // up: 128-bit units of x per lane held in registers, 0 = LDS path
+  int32_t down_upl, RB, nsegR, nsegS;      // down register path: units per lane (0 = LDS path), rows per
+                                           // block, column segments of a routed / shared row
   int32_t slot_override[kMaxTasks];        // pass 1: global slot per task, -1 = not in this pass
 };
 

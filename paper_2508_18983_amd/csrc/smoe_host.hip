@@ -66,8 +66,11 @@ struct moe_handle {
   float* ysum = nullptr;
   // launch geometry
   int TF = 0, tilesR = 0, tilesS = 0, R = 0, htiles = 0, stage_all = 0, chunk = 0, down_lds = 0;
+  int up_upl = 0, down_upl = 0, RB = 0, nsegR = 1, nsegS = 1;
   // profiling
-  bool prof_on = false;
+  int32_t seq = 0;                       // number of the last decode call
+  long spin_limit = 4000000;             // polls of the mirror before falling back to the event
+  uint32_t prof_mask = 0;                // bit i: record kind i
   ProfKind prof[SMOE_PROF_KINDS];
 };
 
@@ -100,6 +103,32 @@ void plan_geometry(moe_handle* h) {
   chunk = std::max(512, std::min(kStageElems, chunk / 512 * 512));
   h->chunk = chunk;
   h->down_lds = h->stage_all ? (int)total_f : chunk;
+
+  // register-resident fast paths (SMOE_REGPATH=0 forces the LDS kernels)
+  const int n = c.dtype == SMOE_DTYPE_FP32 ? 4 : 8;
+  h->up_upl = 0;
+  h->down_upl = 0;
+  if (env_int("SMOE_REGPATH", 1) == 0) return;
+  const int xu = (c.hidden / n + kWave - 1) / kWave;           // units of x per lane
+  h->up_upl = xu <= 1 ? 1 : (xu <= 2 ? 2 : (xu <= 4 ? 4 : (xu <= 8 ? 8 : 0)));
+  auto seg_plan = [&](int F, int& nseg) -> int {               // -> units per lane
+    const int per_lane = (F / n + kWave - 1) / kWave;
+    nseg = per_lane <= 12 ? 1 : (per_lane <= 24 ? 2 : 4);
+    return ((F / n + nseg - 1) / nseg + kWave - 1) / kWave;
+  };
+  int need = seg_plan(c.ffn, h->nsegR);
+  if (c.n_shared) need = std::max(need, seg_plan(c.shared_ffn, h->nsegS));
+  if (need <= 12) {
+    const int upl = need <= 2 ? 2 : (need <= 4 ? 4 : (need <= 6 ? 6 : (need <= 8 ? 8 : (need <= 10 ? 10 : 12))));
+    const int rows_at_once = upl <= 2 ? 4 : (upl <= 6 ? 2 : 1);
+    int rb = 4 * rows_at_once;
+    if (c.hidden / rb > 2048) rb *= 2;
+    rb = env_int("SMOE_RB", rb);
+    rb = std::max(4 * rows_at_once, rb / (4 * rows_at_once) * (4 * rows_at_once));
+    h->down_upl = upl;
+    h->RB = rb;
+    h->htiles = (c.hidden + rb - 1) / rb;
+  }
 }
 
 int upload_initial(moe_handle* h) {
@@ -144,7 +173,7 @@ void free_all(moe_handle* h) {
 
 // Event pair around one launch while profiling; nullptr when not recording.
 EventPair* prof_begin(moe_handle* h, int kind, hipStream_t s) {
-  if (!h->prof_on) return nullptr;
+  if (!((h->prof_mask >> kind) & 1u)) return nullptr;
   ProfKind& k = h->prof[kind];
   if (k.used >= k.ev.size()) return nullptr;
   EventPair* p = &k.ev[k.used++];
@@ -227,6 +256,7 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
     HIP_TRY(hipMalloc(&h->rec_dev, sizeof(StepRec)));
     HIP_TRY(hipHostMalloc(&h->rec_host, sizeof(StepRec), hipHostMallocDefault));
     std::memset(h->rec_host, 0, sizeof(StepRec));
+    h->spin_limit = env_int("SMOE_SPIN_LIMIT", 4000000);
     void* dp = nullptr;
     HIP_TRY(hipHostGetDevicePointer(&dp, h->rec_host, 0));
     h->rec_host_dev = static_cast<StepRec*>(dp);
@@ -256,6 +286,7 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   ra.rec_host = h->rec_host_dev;
   ra.B = B; ra.H = c.hidden; ra.E = E; ra.k = k;
   ra.renorm = c.renorm_topk; ra.subst_key = c.subst_key; ra.alpha = c.alpha;
+  ra.seq = ++h->seq;
   ra.nseg = 1;
   while (ra.nseg < 8 && E * ra.nseg < 32 && c.hidden / (ra.nseg * 2) >= 512) ra.nseg *= 2;
   ra.resident = ls.resident;
@@ -284,6 +315,8 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   fa.TF = h->TF; fa.tilesR = h->tilesR; fa.tilesS = h->tilesS;
   fa.R = h->R; fa.htiles = h->htiles;
   fa.stage_all = h->stage_all; fa.chunk = h->chunk; fa.down_lds_floats = h->down_lds;
+  fa.up_upl = h->up_upl; fa.down_upl = h->down_upl; fa.RB = h->RB;
+  fa.nsegR = h->nsegR; fa.nsegS = h->nsegS;
   for (int i = 0; i < kMaxTasks; ++i) fa.slot_override[i] = -1;
   EventPair* pu = prof_begin(h, SMOE_PROF_UP, h->s_compute);
   launch_ffn_up(fa, c.dtype, h->s_compute);
@@ -294,7 +327,16 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   HIP_TRY(hipGetLastError());
 
   // ---- the decision reaches the host -----------------------------------------
-  HIP_TRY(hipEventSynchronize(h->ev_route));
+  // Poll the pinned mirror (the router kernel publishes its call number last);
+  // after spin_limit polls fall back to waiting on the event.
+  {
+    const volatile int32_t* seq = &h->rec_host->seq;
+    long spins = 0;
+    while (*seq != h->seq && spins < h->spin_limit) ++spins;
+    if (*seq != h->seq) HIP_TRY(hipEventSynchronize(h->ev_route));
+    __atomic_thread_fence(__ATOMIC_ACQUIRE);
+    if (*seq != h->seq) return SMOE_ESTATE;
+  }
   const StepRec& rec = *h->rec_host;
 
   // history: one entry per step, the batch mean of the score vectors (Eq. 3 window)
@@ -382,7 +424,7 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
     prof_end(pd2, h->s_compute);
     HIP_TRY(hipGetLastError());
   }
-  if (h->prof_on) {
+  if (h->prof_mask) {
     // algorithmic bytes each timed launch was asked to stream
     const int64_t miss_slots = (int64_t)B * k - hits;
     const int64_t up_r = 2ll * c.hidden * c.ffn * h->esize, up_s = 2ll * c.hidden * c.shared_ffn * h->esize;
@@ -464,12 +506,13 @@ int moe_cache_destroy(moe_handle_t* h) {
 }
 
 int moe_profile_enable(moe_handle_t* h, int32_t enable, int32_t max_launches) {
-  if (!h || (enable && max_launches < 1)) return SMOE_EINVAL;
+  if (!h || enable < 0 || enable >= (1 << SMOE_PROF_KINDS) || (enable && max_launches < 1)) return SMOE_EINVAL;
   HIP_TRY(hipStreamSynchronize(h->s_compute));
   HIP_TRY(hipStreamSynchronize(h->s_copy));
   if (enable) {
-    for (auto& k : h->prof) {
-      while ((int)k.ev.size() < max_launches) {
+    for (int kind = 0; kind < SMOE_PROF_KINDS; ++kind) {
+      ProfKind& k = h->prof[kind];
+      while (((enable >> kind) & 1) && (int)k.ev.size() < max_launches) {
         EventPair p{};
         HIP_TRY(hipEventCreate(&p.a));
         HIP_TRY(hipEventCreate(&p.b));
@@ -479,7 +522,7 @@ int moe_profile_enable(moe_handle_t* h, int32_t enable, int32_t max_launches) {
       k.bytes = 0;
     }
   }
-  h->prof_on = enable != 0;
+  h->prof_mask = (uint32_t)enable;
   return SMOE_OK;
 }
 

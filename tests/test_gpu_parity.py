@@ -120,3 +120,16 @@ def test_error_paths_and_reset():
             assert ses.stats()["tokens"] == 0
         assert torch.equal(outs[0][0], outs[1][0])
         assert outs[0][1] == outs[1][1] and outs[0][2] == outs[1][2]
+
+
+@pytest.mark.parametrize("env", [dict(SMOE_REGPATH="0"), dict(SMOE_REGPATH="0", SMOE_R="2", SMOE_CHUNK="1024"),
+                                 dict(SMOE_RB="16", SMOE_TF="64"), dict(SMOE_SPIN_LIMIT="0")])
+def test_alternative_kernel_paths_and_launch_shapes(env, monkeypatch):
+    """The LDS-staged kernels (fallback for very wide layers), other tile
+    shapes, and the event-wait fallback of the host must give the same answers."""
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    wl = make_workload(SHAPES["c2"].with_(seed=4), n_layers=2, tokens=24)
+    run_parity(wl, y_every=2, label=f"c2-{env}")
+    wl = make_workload(SHAPES["c5"].with_(seed=4, ffn=640, shared_ffn=20480), n_layers=1, tokens=10)
+    run_parity(wl, y_every=2, label=f"c5-{env}")
