@@ -90,6 +90,8 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=None, help="override layer count (diagnostic only)")
     ap.add_argument("--cpu-budget", type=float, default=20.0, help="seconds of oracle timing; 0 = skip")
     ap.add_argument("--no-miss-free", action="store_true", help="skip the all-resident reference run")
+    ap.add_argument("--calib-copies", type=int, default=3,
+                    help="launches of the known-size (1 GiB) copy kernel that hardware counters are scaled by")
     ap.add_argument("--pin-budget-gb", type=float, default=60.0,
                     help="page-locked host memory the box lets one process hold for expert storage")
     args = ap.parse_args()
@@ -129,6 +131,18 @@ def main() -> int:
                        host_alloc=pinned_empty, distinct_layers=distinct)
     s = wl.shape
     log(f"inputs ready in {time.perf_counter() - t0:.1f} s (margin audit redrew {wl.redraws} token-layers)")
+
+    if args.calib_copies > 0:
+        # known-size traffic for counter calibration: 1 GiB read + 1 GiB written per launch
+        n_cal = 1 << 30
+        src = torch.ones(n_cal, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(args.calib_copies):
+            M.moe_calib_copy(dst.data_ptr(), src.data_ptr(), n_cal, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
 
     prof_launches = args.steps * L + 8
     with session_from_workload(wl, max_batch=1) as ses:

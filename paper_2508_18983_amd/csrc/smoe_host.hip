@@ -122,7 +122,7 @@ void plan_geometry(moe_handle* h) {
     const int upl = need <= 2 ? 2 : (need <= 4 ? 4 : (need <= 6 ? 6 : (need <= 8 ? 8 : (need <= 10 ? 10 : 12))));
     const int rows_at_once = upl <= 2 ? 4 : (upl <= 6 ? 2 : 1);
     int rb = 4 * rows_at_once;
-    if (c.hidden / rb > 2048) rb *= 2;
+    if (c.hidden / rb > 512) rb *= 2;                 // keep ~512..1024 blocks per token
     rb = env_int("SMOE_RB", rb);
     rb = std::max(4 * rows_at_once, rb / (4 * rows_at_once) * (4 * rows_at_once));
     h->down_upl = upl;
