@@ -60,13 +60,17 @@ __device__ __forceinline__ float wave_sum(float v) {
 }
 
 // Weights of task (t, j): null when the task is not part of this pass.
+// PASS 0: routed slots whose expert is resident + shared experts; PASS 1: the
+// slots whose expert has just been loaded (slot_override >= 0).  The pass is a
+// template parameter so the two show up as separate kernels in profiles.
+template <int PASS>
 __device__ __forceinline__ const char* task_weights(const FfnArgs& a, int t, int j, int task,
                                                     int& F, float& wgt) {
   if (j < a.k) {
     F = a.F;
     wgt = a.rec->tok[t].w[j];
     int g;
-    if (a.pass == 0) {
+    if (PASS == 0) {
       const int s = a.rec->tok[t].slot[j];
       if (s < 0) return nullptr;
       g = a.slot_base + s;
@@ -76,7 +80,7 @@ __device__ __forceinline__ const char* task_weights(const FfnArgs& a, int t, int
     }
     return a.slab + (int64_t)g * a.expert_bytes;
   }
-  if (a.pass != 0) return nullptr;
+  if (PASS != 0) return nullptr;
   F = a.Fs;
   wgt = 1.0f;
   return a.shared + (int64_t)(j - a.k) * a.shared_bytes;
@@ -129,7 +133,7 @@ __device__ __forceinline__ void dot_rows(const T* const (&row)[ROWS], const floa
   }
 }
 
-template <typename T>
+template <typename T, int PASS>
 __global__ __launch_bounds__(256) void ffn_up_kernel(const FfnArgs a) {
   extern __shared__ __align__(16) float xs[];       // H floats
   constexpr int N = Unit<T>::N;
@@ -142,7 +146,7 @@ __global__ __launch_bounds__(256) void ffn_up_kernel(const FfnArgs a) {
   else { r -= a.k * a.tilesR; j = a.k + r / a.tilesS; tile = r - (j - a.k) * a.tilesS; }
   const int task = t * nj + j;
   int F; float wgt;
-  const char* base = task_weights(a, t, j, task, F, wgt);
+  const char* base = task_weights<PASS>(a, t, j, task, F, wgt);
   if (base == nullptr) return;
   const int H = a.H;
   const T* W1 = reinterpret_cast<const T*>(base);
@@ -179,7 +183,7 @@ __global__ __launch_bounds__(256) void ffn_up_kernel(const FfnArgs a) {
 // chunks of `chunk` floats.  Pass 0 writes y when the token has no missing
 // expert, else fp32 sums to `ysum`; pass 1 adds the loaded experts to `ysum`
 // and writes y.
-template <typename T, int R>
+template <typename T, int R, int PASS>
 __global__ __launch_bounds__(256) void ffn_down_kernel(const FfnArgs a) {
   extern __shared__ __align__(16) float as[];
   constexpr int N = Unit<T>::N;
@@ -192,7 +196,7 @@ __global__ __launch_bounds__(256) void ffn_down_kernel(const FfnArgs a) {
 
   bool any_miss = false;
   for (int q = 0; q < a.k; ++q) any_miss |= (a.rec->tok[t].slot[q] < 0);
-  if (a.pass == 1 && !any_miss) return;               // y of this token is already final
+  if (PASS == 1 && !any_miss) return;               // y of this token is already final
 
   float acc[R];
 #pragma unroll
@@ -202,7 +206,7 @@ __global__ __launch_bounds__(256) void ffn_down_kernel(const FfnArgs a) {
     int off = 0;
     for (int j = 0; j < nj; ++j) {
       int F; float wgt;
-      if (task_weights(a, t, j, t * nj + j, F, wgt) == nullptr) continue;
+      if (task_weights<PASS>(a, t, j, t * nj + j, F, wgt) == nullptr) continue;
       const float* act = a.act + (size_t)(t * nj + j) * a.Fmax;
       for (int i = tid; i < F; i += 256) as[off + i] = act[i];
       off += F;
@@ -211,7 +215,7 @@ __global__ __launch_bounds__(256) void ffn_down_kernel(const FfnArgs a) {
     off = 0;
     for (int j = 0; j < nj; ++j) {
       int F; float wgt;
-      const char* base = task_weights(a, t, j, t * nj + j, F, wgt);
+      const char* base = task_weights<PASS>(a, t, j, t * nj + j, F, wgt);
       if (base == nullptr) continue;
       if (h0 < H) {
         const T* W2 = reinterpret_cast<const T*>(base) + 2 * (size_t)F * H;
@@ -225,7 +229,7 @@ __global__ __launch_bounds__(256) void ffn_down_kernel(const FfnArgs a) {
   } else {
     for (int j = 0; j < nj; ++j) {
       int F; float wgt;
-      const char* base = task_weights(a, t, j, t * nj + j, F, wgt);
+      const char* base = task_weights<PASS>(a, t, j, t * nj + j, F, wgt);
       if (base == nullptr) continue;
       const T* W2 = reinterpret_cast<const T*>(base) + 2 * (size_t)F * H;
       const float* act = a.act + (size_t)(t * nj + j) * a.Fmax;
@@ -253,7 +257,7 @@ __global__ __launch_bounds__(256) void ffn_down_kernel(const FfnArgs a) {
     for (int r = 0; r < R; ++r) {
       const int h = h0 + r;
       if (h >= H) break;
-      if (a.pass == 0) {
+      if (PASS == 0) {
         if (any_miss) ysum[h] = acc[r];
         else y[h] = Unit<T>::narrow(acc[r]);
       } else {
@@ -271,7 +275,7 @@ __global__ __launch_bounds__(256) void ffn_down_kernel(const FfnArgs a) {
 
 // Up projection with x in registers: one wave owns whole rows (H/N <= 64*UPL
 // units).  Per f it has 2*UPL independent 128-bit loads in flight.
-template <typename T, int UPL>
+template <typename T, int UPL, int PASS>
 __global__ __launch_bounds__(256) void ffn_up_reg_kernel(const FfnArgs a) {
   constexpr int N = Unit<T>::N;
   using raw = typename Unit<T>::raw;
@@ -284,7 +288,7 @@ __global__ __launch_bounds__(256) void ffn_up_reg_kernel(const FfnArgs a) {
   else { r -= a.k * a.tilesR; j = a.k + r / a.tilesS; tile = r - (j - a.k) * a.tilesS; }
   const int task = t * nj + j;
   int F; float wgt;
-  const char* base = task_weights(a, t, j, task, F, wgt);
+  const char* base = task_weights<PASS>(a, t, j, task, F, wgt);
   if (base == nullptr) return;
   const int H = a.H;
   const int units = H / N;
@@ -349,7 +353,7 @@ __global__ __launch_bounds__(256) void ffn_up_reg_kernel(const FfnArgs a) {
 // w / nseg, w / nseg + 4 / nseg, ...  Every (task, segment, row) partial sum is
 // produced by exactly one wave and parked in LDS; after one barrier the block
 // adds them in fixed (task, segment) order.  R rows are streamed at a time.
-template <typename T, int UPL, int R>
+template <typename T, int UPL, int R, int PASS>
 __global__ __launch_bounds__(256) void ffn_down_reg_kernel(const FfnArgs a) {
   extern __shared__ __align__(16) float part[];       // [nj][4][RB]
   constexpr int N = Unit<T>::N;
@@ -364,14 +368,14 @@ __global__ __launch_bounds__(256) void ffn_down_reg_kernel(const FfnArgs a) {
 
   bool any_miss = false;
   for (int q = 0; q < a.k; ++q) any_miss |= (a.rec->tok[t].slot[q] < 0);
-  if (a.pass == 1 && !any_miss) return;
+  if (PASS == 1 && !any_miss) return;
 
   for (int i = tid; i < nj * 4 * RB; i += 256) part[i] = 0.f;
   __syncthreads();
 
   for (int j = 0; j < nj; ++j) {
     int F; float wgt;
-    const char* base = task_weights(a, t, j, t * nj + j, F, wgt);
+    const char* base = task_weights<PASS>(a, t, j, t * nj + j, F, wgt);
     if (base == nullptr) continue;
     const int nseg = j < a.k ? a.nsegR : a.nsegS;
     const int units = F / N;
@@ -435,7 +439,7 @@ __global__ __launch_bounds__(256) void ffn_down_reg_kernel(const FfnArgs a) {
       for (int sg = 0; sg < 4; ++sg) sum += part[((size_t)j * 4 + sg) * RB + row];
     T* y = static_cast<T*>(a.y) + (size_t)t * H;
     float* ysum = a.ysum + (size_t)t * H;
-    if (a.pass == 0) {
+    if (PASS == 0) {
       if (any_miss) ysum[h] = sum;
       else y[h] = Unit<T>::narrow(sum);
     } else {
@@ -453,49 +457,55 @@ __global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst,
 
 }  // namespace
 
-template <typename T>
+template <typename T, int PASS>
 static void launch_up_t(const FfnArgs& a, hipStream_t s) {
   const int grid = a.B * (a.k * a.tilesR + a.ns * a.tilesS);
   switch (a.up_upl) {
-    case 1: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 1>), dim3(grid), dim3(256), 0, s, a); return;
-    case 2: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 2>), dim3(grid), dim3(256), 0, s, a); return;
-    case 4: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 4>), dim3(grid), dim3(256), 0, s, a); return;
-    case 8: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 8>), dim3(grid), dim3(256), 0, s, a); return;
+    case 1: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 1, PASS>), dim3(grid), dim3(256), 0, s, a); return;
+    case 2: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 2, PASS>), dim3(grid), dim3(256), 0, s, a); return;
+    case 4: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 4, PASS>), dim3(grid), dim3(256), 0, s, a); return;
+    case 8: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 8, PASS>), dim3(grid), dim3(256), 0, s, a); return;
     default: break;
   }
   const size_t lds = (size_t)a.H * sizeof(float);
-  hipLaunchKernelGGL(ffn_up_kernel<T>, dim3(grid), dim3(256), lds, s, a);
+  hipLaunchKernelGGL((ffn_up_kernel<T, PASS>), dim3(grid), dim3(256), lds, s, a);
 }
 
 void launch_ffn_up(const FfnArgs& a, int dtype, hipStream_t s) {
-  if (dtype == SMOE_DTYPE_FP32) launch_up_t<float>(a, s);
-  else launch_up_t<bf16_t>(a, s);
+  if (dtype == SMOE_DTYPE_FP32) {
+    if (a.pass == 0) launch_up_t<float, 0>(a, s); else launch_up_t<float, 1>(a, s);
+  } else {
+    if (a.pass == 0) launch_up_t<bf16_t, 0>(a, s); else launch_up_t<bf16_t, 1>(a, s);
+  }
 }
 
-template <typename T>
+template <typename T, int PASS>
 static void launch_down_t(const FfnArgs& a, hipStream_t s) {
   const int grid = a.B * a.htiles;
   if (a.down_upl > 0) {
     const size_t lds = (size_t)(a.k + a.ns) * 4 * a.RB * sizeof(float);
     switch (a.down_upl) {
-      case 2: hipLaunchKernelGGL((ffn_down_reg_kernel<T, 2, 4>), dim3(grid), dim3(256), lds, s, a); return;
-      case 4: hipLaunchKernelGGL((ffn_down_reg_kernel<T, 4, 2>), dim3(grid), dim3(256), lds, s, a); return;
-      case 6: hipLaunchKernelGGL((ffn_down_reg_kernel<T, 6, 2>), dim3(grid), dim3(256), lds, s, a); return;
-      case 8: hipLaunchKernelGGL((ffn_down_reg_kernel<T, 8, 1>), dim3(grid), dim3(256), lds, s, a); return;
-      case 10: hipLaunchKernelGGL((ffn_down_reg_kernel<T, 10, 1>), dim3(grid), dim3(256), lds, s, a); return;
-      case 12: hipLaunchKernelGGL((ffn_down_reg_kernel<T, 12, 1>), dim3(grid), dim3(256), lds, s, a); return;
+      case 2: hipLaunchKernelGGL((ffn_down_reg_kernel<T, 2, 4, PASS>), dim3(grid), dim3(256), lds, s, a); return;
+      case 4: hipLaunchKernelGGL((ffn_down_reg_kernel<T, 4, 2, PASS>), dim3(grid), dim3(256), lds, s, a); return;
+      case 6: hipLaunchKernelGGL((ffn_down_reg_kernel<T, 6, 2, PASS>), dim3(grid), dim3(256), lds, s, a); return;
+      case 8: hipLaunchKernelGGL((ffn_down_reg_kernel<T, 8, 1, PASS>), dim3(grid), dim3(256), lds, s, a); return;
+      case 10: hipLaunchKernelGGL((ffn_down_reg_kernel<T, 10, 1, PASS>), dim3(grid), dim3(256), lds, s, a); return;
+      case 12: hipLaunchKernelGGL((ffn_down_reg_kernel<T, 12, 1, PASS>), dim3(grid), dim3(256), lds, s, a); return;
       default: break;
     }
   }
   const size_t lds = (size_t)a.down_lds_floats * sizeof(float);
-  if (a.R == 1) hipLaunchKernelGGL((ffn_down_kernel<T, 1>), dim3(grid), dim3(256), lds, s, a);
-  else if (a.R == 2) hipLaunchKernelGGL((ffn_down_kernel<T, 2>), dim3(grid), dim3(256), lds, s, a);
-  else hipLaunchKernelGGL((ffn_down_kernel<T, 4>), dim3(grid), dim3(256), lds, s, a);
+  if (a.R == 1) hipLaunchKernelGGL((ffn_down_kernel<T, 1, PASS>), dim3(grid), dim3(256), lds, s, a);
+  else if (a.R == 2) hipLaunchKernelGGL((ffn_down_kernel<T, 2, PASS>), dim3(grid), dim3(256), lds, s, a);
+  else hipLaunchKernelGGL((ffn_down_kernel<T, 4, PASS>), dim3(grid), dim3(256), lds, s, a);
 }
 
 void launch_ffn_down(const FfnArgs& a, int dtype, hipStream_t s) {
-  if (dtype == SMOE_DTYPE_FP32) launch_down_t<float>(a, s);
-  else launch_down_t<bf16_t>(a, s);
+  if (dtype == SMOE_DTYPE_FP32) {
+    if (a.pass == 0) launch_down_t<float, 0>(a, s); else launch_down_t<float, 1>(a, s);
+  } else {
+    if (a.pass == 0) launch_down_t<bf16_t, 0>(a, s); else launch_down_t<bf16_t, 1>(a, s);
+  }
 }
 
 void launch_copy(void* dst, const void* src, int64_t n_bytes, hipStream_t s) {
