@@ -20,6 +20,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+# HBM bytes per launch of the resident-pass up kernel / its algorithmic bytes, from the two
+# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) summarised in profiles/c3_ffn_hbm_traffic_pmc.md
+MEASURED_TRAFFIC_RATIO = {"c3-mixtral8x7b-shaped": 1.0004}
 
 
 def log(msg: str) -> None:
@@ -209,7 +212,9 @@ def main() -> int:
                    "zipf_s": s.zipf_s, "seed": s.seed, "host_expert_storage": host_note},
         "roofline": {"bound": "hbm", "kernel": "ffn_up_kernel (resident pass)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": (MEASURED_TRAFFIC_RATIO[s.name] * up_bytes_per_launch
+                                 if s.name in MEASURED_TRAFFIC_RATIO else None),
                      "bytes_per_launch": up_bytes_per_launch, "avg_launch_us": up_avg_s * 1e6,
                      "launches": up["launches"]},
         "cpu_baseline": cpu,
