@@ -10,6 +10,7 @@
 //          one wave produces y[h] for its rows over all tasks in a fixed
 //          order: no partial buffers, atomics or fences.
 #include "smoe_dev.hpp"
+#include "wave_ops.hpp"
 
 namespace smoe {
 namespace {
@@ -17,6 +18,7 @@ namespace {
 struct bf16_t { uint16_t v; };
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 template <typename T> struct Unit;
 template <> struct Unit<float> {
@@ -30,6 +32,12 @@ template <> struct Unit<float> {
   }
   __device__ static __forceinline__ float widen1(float s) { return s; }
   __device__ static __forceinline__ float narrow(float s) { return s; }
+  // acc + w . x for one unit, x in its stored form
+  __device__ static __forceinline__ float dot(const raw& w, const raw& x, float acc) {
+    acc = fmaf(w.x, x.x, acc); acc = fmaf(w.y, x.y, acc);
+    acc = fmaf(w.z, x.z, acc); acc = fmaf(w.w, x.w, acc);
+    return acc;
+  }
 };
 template <> struct Unit<bf16_t> {
   static constexpr int N = 8;
@@ -51,13 +59,16 @@ template <> struct Unit<bf16_t> {
     u += 0x7fffu + ((u >> 16) & 1u);
     return bf16_t{uint16_t(u >> 16)};
   }
+  // acc + w . x for one unit of 8 bf16 pairs: both operands stay packed and go
+  // through the 2-way bf16 dot instruction (products exact in fp32, fp32 sum)
+  __device__ static __forceinline__ float dot(const raw& w, const raw& x, float acc) {
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w.x), __builtin_bit_cast(bf16x2, x.x), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w.y), __builtin_bit_cast(bf16x2, x.y), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w.z), __builtin_bit_cast(bf16x2, x.z), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w.w), __builtin_bit_cast(bf16x2, x.w), acc, false);
+    return acc;
+  }
 };
-
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-  return v;
-}
 
 // Weights of task (t, j): null when the task is not part of this pass.
 // PASS 0: routed slots whose expert is resident + shared experts; PASS 1: the
@@ -295,18 +306,12 @@ __global__ __launch_bounds__(256) void ffn_up_reg_kernel(const FfnArgs a) {
   const T* W1 = reinterpret_cast<const T*>(base);
   const T* W3 = W1 + (size_t)F * H;
 
-  float xr[UPL][N];
+  raw xr[UPL];                                          // this lane's slice of x, as stored
   const T* x = static_cast<const T*>(a.x) + (size_t)t * H;
 #pragma unroll
   for (int i = 0; i < UPL; ++i) {
     const int u = i * kWave + lane;
-    if (u < units) {
-      const raw q = *reinterpret_cast<const raw*>(x + (size_t)u * N);
-      Unit<T>::widen(q, xr[i]);
-    } else {
-#pragma unroll
-      for (int e = 0; e < N; ++e) xr[i][e] = 0.f;
-    }
+    xr[i] = (u < units) ? *reinterpret_cast<const raw*>(x + (size_t)u * N) : raw{};
   }
 
   const int per_wave = a.TF >> 2;
@@ -332,14 +337,8 @@ __global__ __launch_bounds__(256) void ffn_up_reg_kernel(const FfnArgs a) {
     float ag = 0.f, au = 0.f;
 #pragma unroll
     for (int s = 0; s < UPL; ++s) {
-      float wg[N], wu[N];
-      Unit<T>::widen(qg[s], wg);
-      Unit<T>::widen(qu[s], wu);
-#pragma unroll
-      for (int e = 0; e < N; ++e) {
-        ag = fmaf(wg[e], xr[s][e], ag);
-        au = fmaf(wu[e], xr[s][e], au);
-      }
+      ag = Unit<T>::dot(qg[s], xr[s], ag);
+      au = Unit<T>::dot(qu[s], xr[s], au);
     }
     ag = wave_sum(ag);
     au = wave_sum(au);

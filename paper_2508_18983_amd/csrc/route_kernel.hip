@@ -13,35 +13,12 @@
 // of the block.  Decisions go to device memory for the FFN kernels and to a
 // pinned host mirror for the cache scheduler.
 #include "smoe_dev.hpp"
+#include "wave_ops.hpp"
 
 namespace smoe {
 namespace {
 
 struct bf16_t { uint16_t v; };
-
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-  return v;
-}
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
-  return v;
-}
-// Lane holding the largest value among lanes with valid set; lower lane wins
-// ties; -1 when no lane is valid.  Result is uniform across the wave.
-__device__ __forceinline__ int wave_argmax(float v, bool valid, int lane) {
-  float val = valid ? v : -INFINITY;
-  int idx = valid ? lane : kWave;
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    float ov = __shfl_xor(val, o, kWave);
-    int oi = __shfl_xor(idx, o, kWave);
-    if (ov > val || (ov == val && oi < idx)) { val = ov; idx = oi; }
-  }
-  return idx == kWave ? -1 : idx;
-}
 
 template <typename T> struct GateUnit;
 template <> struct GateUnit<float> {
