@@ -21,8 +21,18 @@ namespace {
 struct bf16_t { uint16_t v; };
 
 template <typename T> struct GateUnit;
+typedef unsigned int gu32x4 __attribute__((ext_vector_type(4)));
+typedef float gf32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 gbf16x2 __attribute__((ext_vector_type(2)));
+
 template <> struct GateUnit<float> {
   static constexpr int N = 4;
+  using raw = gf32x4;
+  __device__ static __forceinline__ float dot(const raw& w, const raw& x, float acc) {
+    acc = fmaf(w.x, x.x, acc); acc = fmaf(w.y, x.y, acc);
+    acc = fmaf(w.z, x.z, acc); acc = fmaf(w.w, x.w, acc);
+    return acc;
+  }
   __device__ static __forceinline__ void load(const float* p, float (&v)[4]) {
     const float4 q = *reinterpret_cast<const float4*>(p);
     v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
@@ -31,6 +41,18 @@ template <> struct GateUnit<float> {
 };
 template <> struct GateUnit<bf16_t> {
   static constexpr int N = 8;
+  using raw = gu32x4;
+  // packed bf16 pairs through the 2-way bf16 dot instruction (elements copied to
+  // scalars before the bit cast)
+  __device__ static __forceinline__ float dot(const raw& w, const raw& x, float acc) {
+    const unsigned w0 = w.x, w1 = w.y, w2 = w.z, w3 = w.w;
+    const unsigned x0 = x.x, x1 = x.y, x2 = x.z, x3 = x.w;
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(gbf16x2, w0), __builtin_bit_cast(gbf16x2, x0), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(gbf16x2, w1), __builtin_bit_cast(gbf16x2, x1), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(gbf16x2, w2), __builtin_bit_cast(gbf16x2, x2), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(gbf16x2, w3), __builtin_bit_cast(gbf16x2, x3), acc, false);
+    return acc;
+  }
   __device__ static __forceinline__ void load(const bf16_t* p, float (&v)[8]) {
     const uint4 q = *reinterpret_cast<const uint4*>(p);
     v[0] = __uint_as_float(q.x << 16); v[1] = __uint_as_float(q.x & 0xffff0000u);
@@ -41,75 +63,24 @@ template <> struct GateUnit<bf16_t> {
   __device__ static __forceinline__ float widen1(bf16_t s) { return __uint_as_float(uint32_t(s.v) << 16); }
 };
 
-constexpr int kMaxSeg = 8;   // a gate row is split into at most this many segments
+// Shared memory the selection stage works in.
+struct SelectSmem {
+  float lg[SMOE_MAX_BATCH][kWave];
+  float sc[SMOE_MAX_BATCH][kWave];
+  int rk[SMOE_MAX_BATCH][kWave];
+  int tk[SMOE_MAX_BATCH][SMOE_MAX_TOPK];
+  float thr_r[SMOE_MAX_BATCH];
+  unsigned long long top_m_sh[SMOE_MAX_BATCH];
+  int slot_of[kWave];
+};
 
-// NTOK = tokens whose hidden states sit in LDS together (dynamic LDS: NTOK*H floats).
-template <typename T, int NTOK>
-__global__ __launch_bounds__(1024) void route_kernel(const RouteArgs a) {
-  extern __shared__ __align__(16) float xs[];                 // [NTOK][H]
-  __shared__ float part[SMOE_MAX_BATCH][kWave][kMaxSeg];
-  __shared__ float lg[SMOE_MAX_BATCH][kWave];
-  __shared__ float sc[SMOE_MAX_BATCH][kWave];
-  __shared__ int rk[SMOE_MAX_BATCH][kWave];
-  __shared__ int tk[SMOE_MAX_BATCH][SMOE_MAX_TOPK];
-  __shared__ float thr_r[SMOE_MAX_BATCH];
-  __shared__ unsigned long long top_m_sh[SMOE_MAX_BATCH];
-  __shared__ int slot_of[kWave];
-
-  constexpr int N = GateUnit<T>::N;
-  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
-  const int nw = blockDim.x >> 6;
-  const int H = a.H, E = a.E, k = a.k, B = a.B;
-  if (tid < kWave) slot_of[tid] = a.slot_of[tid];
-
-  // ---- gate GEMV: logits[t][e] = Wg[e] . x[t] --------------------------------
-  // work item = (expert row, segment of the row); segments are summed in a fixed order
-  const T* wg = static_cast<const T*>(a.gate_w);
-  const T* x = static_cast<const T*>(a.x);
-  const int units = H / N;
-  const int nseg = a.nseg;
-  const int items = E * nseg;
-  for (int t0 = 0; t0 < B; t0 += NTOK) {
-    const int nt = min(NTOK, B - t0);
-    __syncthreads();
-    for (int i = tid; i < nt * H; i += blockDim.x) xs[i] = GateUnit<T>::widen1(x[(size_t)t0 * H + i]);
-    __syncthreads();
-    for (int it = wave; it < items; it += nw) {
-      const int e = it / nseg, sg = it - e * nseg;
-      const int u0 = (int)((long)units * sg / nseg), u1 = (int)((long)units * (sg + 1) / nseg);
-      const T* row = wg + (size_t)e * H;
-      float acc[NTOK];
-#pragma unroll
-      for (int q = 0; q < NTOK; ++q) acc[q] = 0.f;
-#pragma unroll 4
-      for (int u = u0 + lane; u < u1; u += kWave) {
-        float w[N];
-        GateUnit<T>::load(row + (size_t)u * N, w);
-#pragma unroll
-        for (int q = 0; q < NTOK; ++q) {
-          if (q < nt) {
-            const float* xv = xs + (size_t)q * H + (size_t)u * N;
-#pragma unroll
-            for (int i = 0; i < N; ++i) acc[q] = fmaf(w[i], xv[i], acc[q]);
-          }
-        }
-      }
-#pragma unroll
-      for (int q = 0; q < NTOK; ++q) {
-        const float v = wave_sum(acc[q]);
-        if (lane == 0 && q < nt) part[t0 + q][e][sg] = v;
-      }
-    }
-  }
-  __syncthreads();
-  if (wave != 0) return;
-  for (int t = 0; t < B; ++t) {
-    float v = 0.f;
-    if (lane < E)
-      for (int sg = 0; sg < nseg; ++sg) v += part[t][lane][sg];
-    lg[t][lane] = v;
-  }
-
+// Runs on wave 0 with all 64 lanes active: logits in sm.lg -> decision record.
+// `sim` is this layer's similarity table (global or LDS).
+__device__ __forceinline__ void select_and_publish(const RouteArgs& a, SelectSmem& sm, const float* sim,
+                                                   int lane) {
+  const int E = a.E, k = a.k, B = a.B;
+  auto& lg = sm.lg; auto& sc = sm.sc; auto& rk = sm.rk; auto& tk = sm.tk;
+  auto& thr_r = sm.thr_r; auto& top_m_sh = sm.top_m_sh; auto& slot_of = sm.slot_of;
   // ---- pass 1: scores, top-(k+1), alpha classes, batch top-score set C ------
   const bool has_pivot = E > k;
   unsigned long long c_mask = 0;
@@ -162,7 +133,7 @@ __global__ __launch_bounds__(1024) void route_kernel(const RouteArgs a) {
       if (!cand_m) break;
       const bool is_cand = (cand_m >> lane) & 1ull;
       float key = s;
-      if (a.subst_key == 0) key = is_cand ? a.sim[(size_t)b * E + lane] : 0.f;
+      if (a.subst_key == 0) key = is_cand ? sim[(size_t)b * E + lane] : 0.f;
       const int c = wave_argmax(key, is_cand, lane);
       if (lane == r) { myfin = c; mysub = 1; }
       cand_m &= ~(1ull << c);
@@ -187,10 +158,151 @@ __global__ __launch_bounds__(1024) void route_kernel(const RouteArgs a) {
   if (lane == 0) __hip_atomic_store(&a.rec_host->seq, a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
+constexpr int kMaxSeg = 8;   // a gate row is split into at most this many segments
+
+// NTOK = tokens whose hidden states sit in LDS together (dynamic LDS: NTOK*H floats).
+template <typename T, int NTOK>
+__global__ __launch_bounds__(1024) void route_kernel(const RouteArgs a) {
+  extern __shared__ __align__(16) float xs[];                 // [NTOK][H]
+  __shared__ float part[SMOE_MAX_BATCH][kWave][kMaxSeg];
+  __shared__ SelectSmem sm;
+
+  constexpr int N = GateUnit<T>::N;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+  const int nw = blockDim.x >> 6;
+  const int H = a.H, E = a.E, B = a.B;
+  if (tid < kWave) sm.slot_of[tid] = a.slot_of[tid];
+
+  // ---- gate GEMV: logits[t][e] = Wg[e] . x[t] --------------------------------
+  // work item = (expert row, segment of the row); segments are summed in a fixed order
+  const T* wg = static_cast<const T*>(a.gate_w);
+  const T* x = static_cast<const T*>(a.x);
+  const int units = H / N;
+  const int nseg = a.nseg;
+  const int items = E * nseg;
+  for (int t0 = 0; t0 < B; t0 += NTOK) {
+    const int nt = min(NTOK, B - t0);
+    __syncthreads();
+    for (int i = tid; i < nt * H; i += blockDim.x) xs[i] = GateUnit<T>::widen1(x[(size_t)t0 * H + i]);
+    __syncthreads();
+    for (int it = wave; it < items; it += nw) {
+      const int e = it / nseg, sg = it - e * nseg;
+      const int u0 = (int)((long)units * sg / nseg), u1 = (int)((long)units * (sg + 1) / nseg);
+      const T* row = wg + (size_t)e * H;
+      float acc[NTOK];
+#pragma unroll
+      for (int q = 0; q < NTOK; ++q) acc[q] = 0.f;
+#pragma unroll 4
+      for (int u = u0 + lane; u < u1; u += kWave) {
+        float w[N];
+        GateUnit<T>::load(row + (size_t)u * N, w);
+#pragma unroll
+        for (int q = 0; q < NTOK; ++q) {
+          if (q < nt) {
+            const float* xv = xs + (size_t)q * H + (size_t)u * N;
+#pragma unroll
+            for (int i = 0; i < N; ++i) acc[q] = fmaf(w[i], xv[i], acc[q]);
+          }
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < NTOK; ++q) {
+        const float v = wave_sum(acc[q]);
+        if (lane == 0 && q < nt) part[t0 + q][e][sg] = v;
+      }
+    }
+  }
+  __syncthreads();
+  if (wave != 0) return;
+  for (int t = 0; t < B; ++t) {
+    float v = 0.f;
+    if (lane < E)
+      for (int sg = 0; sg < nseg; ++sg) v += part[t][lane][sg];
+    sm.lg[t][lane] = v;
+  }
+
+  select_and_publish(a, sm, a.sim, lane);
+}
+
+// Batch-1 fast path.  No staging of x: a wave owns up to four gate rows (or
+// row segments) at once, loads its slice of x and of those rows straight into
+// registers so that all loads of the GEMV are in flight together, and the
+// similarity table is copied to LDS meanwhile.  UPI = 128-bit units of one
+// item per lane.
+template <typename T, int UPI>
+__global__ __launch_bounds__(1024) void route_b1_kernel(const RouteArgs a) {
+  __shared__ SelectSmem sm;
+  __shared__ float part[kWave][kMaxSeg];
+  __shared__ float sim_sh[SMOE_MAX_EXPERTS * SMOE_MAX_EXPERTS];
+  constexpr int N = GateUnit<T>::N;
+  using raw = typename GateUnit<T>::raw;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+  const int H = a.H, E = a.E;
+  const int nseg = a.nseg;                       // power of two <= 8, divides the 16 waves
+  const int items = E * nseg;
+  const int units = H / N;
+  const T* wg = static_cast<const T*>(a.gate_w);
+  const T* x = static_cast<const T*>(a.x);
+
+  // this wave's segment of x (the same for all of its items: 16 is a multiple of nseg)
+  const int sg = wave & (nseg - 1);
+  const int u0 = (int)((long)units * sg / nseg), u1 = (int)((long)units * (sg + 1) / nseg);
+  raw xr[UPI];
+#pragma unroll
+  for (int i = 0; i < UPI; ++i) {
+    const int u = u0 + i * kWave + lane;
+    xr[i] = (u < u1) ? *reinterpret_cast<const raw*>(x + (size_t)u * N) : raw{};
+  }
+  if (a.subst_key == 0)
+    for (int i = tid; i < E * E; i += 1024) sim_sh[i] = a.sim[i];
+  if (tid < kWave) sm.slot_of[tid] = a.slot_of[tid];
+
+  for (int base = 0; base < items; base += 4 * 16) {
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < UPI; ++i) {
+      const int u = u0 + i * kWave + lane;
+      raw q[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int it = base + r * 16 + wave;
+        q[r] = (it < items && u < u1) ? *reinterpret_cast<const raw*>(wg + (size_t)(it / nseg) * H + (size_t)u * N)
+                                      : raw{};
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[r] = GateUnit<T>::dot(q[r], xr[i], acc[r]);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int it = base + r * 16 + wave;
+      const float v = wave_sum(acc[r]);
+      if (lane == 0 && it < items) part[it / nseg][sg] = v;
+    }
+  }
+  __syncthreads();
+  if (wave != 0) return;
+  {
+    float v = 0.f;
+    if (lane < E)
+      for (int s2 = 0; s2 < nseg; ++s2) v += part[lane][s2];
+    sm.lg[0][lane] = v;
+  }
+  select_and_publish(a, sm, sim_sh, lane);
+}
+
 }  // namespace
 
 template <typename T>
 static void launch_route_t(const RouteArgs& a, hipStream_t s) {
+  if (a.B == 1 && a.fast_upi > 0) {
+    switch (a.fast_upi) {
+      case 1: hipLaunchKernelGGL((route_b1_kernel<T, 1>), dim3(1), dim3(1024), 0, s, a); return;
+      case 2: hipLaunchKernelGGL((route_b1_kernel<T, 2>), dim3(1), dim3(1024), 0, s, a); return;
+      case 4: hipLaunchKernelGGL((route_b1_kernel<T, 4>), dim3(1), dim3(1024), 0, s, a); return;
+      case 8: hipLaunchKernelGGL((route_b1_kernel<T, 8>), dim3(1), dim3(1024), 0, s, a); return;
+      default: break;
+    }
+  }
   // as many tokens' hidden states in LDS together as fit in 32 KB
   int ntok = 1;
   while (ntok < a.B && ntok < SMOE_MAX_BATCH && (size_t)(2 * ntok) * a.H * sizeof(float) <= 32 * 1024)

@@ -37,6 +37,7 @@ struct RouteArgs {
   int32_t renorm, subst_key;
   int32_t nseg;         // segments each gate row is split into (power of two, <= 8)
   int32_t seq;          // call number published to the host mirror when the record is complete
+  int32_t fast_upi;     // batch-1 fast path: 128-bit units of one row segment per lane (0 = off)
   float alpha;
   uint64_t resident;                  // bit e = expert e is in the HBM cache
   int8_t slot_of[SMOE_MAX_EXPERTS];   // layer-local slot of each resident expert

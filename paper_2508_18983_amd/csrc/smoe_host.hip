@@ -69,6 +69,7 @@ struct moe_handle {
   int up_upl = 0, down_upl = 0, RB = 0, nsegR = 1, nsegS = 1;
   // profiling
   int32_t seq = 0;                       // number of the last decode call
+  int route_fast = 1;                    // use the batch-1 router kernel
   long spin_limit = 4000000;             // polls of the mirror before falling back to the event
   uint32_t prof_mask = 0;                // bit i: record kind i
   ProfKind prof[SMOE_PROF_KINDS];
@@ -257,6 +258,7 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
     HIP_TRY(hipHostMalloc(&h->rec_host, sizeof(StepRec), hipHostMallocDefault));
     std::memset(h->rec_host, 0, sizeof(StepRec));
     h->spin_limit = env_int("SMOE_SPIN_LIMIT", 4000000);
+    h->route_fast = env_int("SMOE_ROUTE_FAST", 1);
     void* dp = nullptr;
     HIP_TRY(hipHostGetDevicePointer(&dp, h->rec_host, 0));
     h->rec_host_dev = static_cast<StepRec*>(dp);
@@ -288,7 +290,18 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   ra.renorm = c.renorm_topk; ra.subst_key = c.subst_key; ra.alpha = c.alpha;
   ra.seq = ++h->seq;
   ra.nseg = 1;
-  while (ra.nseg < 8 && E * ra.nseg < 32 && c.hidden / (ra.nseg * 2) >= 512) ra.nseg *= 2;
+  ra.fast_upi = 0;
+  const int gate_units = c.hidden / (c.dtype == SMOE_DTYPE_FP32 ? 4 : 8);
+  if (B == 1 && h->route_fast) {
+    // one row segment per wave and pass: 16 waves x 4 rows; keep a segment <= 8 units per lane
+    while (ra.nseg < 8 && (E * ra.nseg * 2 <= 16 || gate_units / ra.nseg > 8 * kWave)) ra.nseg *= 2;
+    const int per_lane = ((gate_units + ra.nseg - 1) / ra.nseg + kWave - 1) / kWave;
+    ra.fast_upi = per_lane <= 1 ? 1 : (per_lane <= 2 ? 2 : (per_lane <= 4 ? 4 : (per_lane <= 8 ? 8 : 0)));
+  }
+  if (ra.fast_upi == 0) {
+    ra.nseg = 1;
+    while (ra.nseg < 8 && E * ra.nseg < 32 && c.hidden / (ra.nseg * 2) >= 512) ra.nseg *= 2;
+  }
   ra.resident = ls.resident;
   std::memcpy(ra.slot_of, ls.slot_of, sizeof(ra.slot_of));
   EventPair* pr = prof_begin(h, SMOE_PROF_ROUTE, h->s_compute);
