@@ -318,47 +318,58 @@ __global__ __launch_bounds__(256) void ffn_up_reg_kernel(const FfnArgs a) {
     xr[i] = (u < units) ? *reinterpret_cast<const raw*>(x + (size_t)u * N) : raw{};
   }
 
+  // FPI f-rows (each = one W1 row + one W3 row) in flight per iteration
+  constexpr int FPI = UPL >= 8 ? 1 : 2;
   const int per_wave = a.TF >> 2;
   const int f_begin = tile * a.TF + wave * per_wave;
   float* act = a.act + (size_t)task * a.Fmax;
-  for (int i = 0; i < per_wave; ++i) {
+  for (int i = 0; i < per_wave; i += FPI) {
     const int f = f_begin + i;
     if (f >= F) break;
-    const T* g = W1 + (size_t)f * H;
-    const T* up = W3 + (size_t)f * H;
-    raw qg[UPL], qu[UPL];
+    raw qg[FPI][UPL], qu[FPI][UPL];
 #pragma unroll
-    for (int s = 0; s < UPL; ++s) {
-      const int u = s * kWave + lane;
-      if (u < units) {
-        qg[s] = Unit<T>::load(g + (size_t)u * N);
-        qu[s] = Unit<T>::load(up + (size_t)u * N);
-      } else {
-        qg[s] = raw{};
-        qu[s] = raw{};
+    for (int p = 0; p < FPI; ++p) {
+      const bool live = (i + p < per_wave) && (f + p < F);
+      const T* g = W1 + (size_t)(live ? f + p : f) * H;
+      const T* up = W3 + (size_t)(live ? f + p : f) * H;
+#pragma unroll
+      for (int s = 0; s < UPL; ++s) {
+        const int u = s * kWave + lane;
+        if (live && u < units) {
+          qg[p][s] = Unit<T>::load(g + (size_t)u * N);
+          qu[p][s] = Unit<T>::load(up + (size_t)u * N);
+        } else {
+          qg[p][s] = raw{};
+          qu[p][s] = raw{};
+        }
       }
     }
-    float ag = 0.f, au = 0.f;
 #pragma unroll
-    for (int s = 0; s < UPL; ++s) {
-      ag = Unit<T>::dot(qg[s], xr[s], ag);
-      au = Unit<T>::dot(qu[s], xr[s], au);
+    for (int p = 0; p < FPI; ++p) {
+      float ag = 0.f, au = 0.f;
+#pragma unroll
+      for (int s = 0; s < UPL; ++s) {
+        ag = Unit<T>::dot(qg[p][s], xr[s], ag);
+        au = Unit<T>::dot(qu[p][s], xr[s], au);
+      }
+      ag = wave_sum(ag);
+      au = wave_sum(au);
+      if (lane == 0 && i + p < per_wave && f + p < F) act[f + p] = wgt * (ag / (1.0f + expf(-ag))) * au;
     }
-    ag = wave_sum(ag);
-    au = wave_sum(au);
-    if (lane == 0) act[f] = wgt * (ag / (1.0f + expf(-ag))) * au;
   }
 }
 
 // Down projection with the activations in registers.  A block owns RB output
-// rows of one token.  Per task the row is cut into nseg in {1, 2, 4} column
-// segments of <= 64*UPL units; wave w works on segment w % nseg for the rows
-// w / nseg, w / nseg + 4 / nseg, ...  Every (task, segment, row) partial sum is
-// produced by exactly one wave and parked in LDS; after one barrier the block
-// adds them in fixed (task, segment) order.  R rows are streamed at a time.
+// rows of one token.  A row of task j is cut into nseg in {1, 2, 4} column
+// segments of <= 64*UPL units; a work item is (task, segment) and the four
+// waves take the items round-robin.  For its item a wave loads its slice of
+// the activations once and streams the RB rows, R at a time.  Every (item,
+// row) partial sum is produced by exactly one wave and parked in LDS; after
+// one barrier the block adds them in item order, so y does not depend on
+// scheduling.
 template <typename T, int UPL, int R, int PASS>
 __global__ __launch_bounds__(256) void ffn_down_reg_kernel(const FfnArgs a) {
-  extern __shared__ __align__(16) float part[];       // [nj][4][RB]
+  extern __shared__ __align__(16) float part[];       // [items][RB]
   constexpr int N = Unit<T>::N;
   using raw = typename Unit<T>::raw;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
@@ -368,22 +379,26 @@ __global__ __launch_bounds__(256) void ffn_down_reg_kernel(const FfnArgs a) {
   const int ht = blockIdx.x - t * a.htiles;
   const int H = a.H;
   const int hb = ht * RB;
+  const int items_r = a.k * a.nsegR;
+  const int n_items = items_r + a.ns * a.nsegS;
 
   bool any_miss = false;
   for (int q = 0; q < a.k; ++q) any_miss |= (a.rec->tok[t].slot[q] < 0);
   if (PASS == 1 && !any_miss) return;
 
-  for (int i = tid; i < nj * 4 * RB; i += 256) part[i] = 0.f;
-  __syncthreads();
-
-  for (int j = 0; j < nj; ++j) {
+  for (int it = wave; it < n_items; it += 4) {
+    int j, seg, nseg;
+    if (it < items_r) { nseg = a.nsegR; j = it / nseg; seg = it - j * nseg; }
+    else { nseg = a.nsegS; const int q = it - items_r; j = q / nseg; seg = q - j * nseg; j += a.k; }
+    float* prow = part + (size_t)it * RB;
     int F; float wgt;
     const char* base = task_weights<PASS>(a, t, j, t * nj + j, F, wgt);
-    if (base == nullptr) continue;
-    const int nseg = j < a.k ? a.nsegR : a.nsegS;
+    if (base == nullptr) {                            // not in this pass: contributes 0
+      for (int r = lane; r < RB; r += kWave) prow[r] = 0.f;
+      continue;
+    }
     const int units = F / N;
-    const int seg_units = (units + nseg - 1) / nseg;          // units per segment
-    const int seg = wave % nseg, rsub = wave / nseg, rstep = 4 / nseg;
+    const int seg_units = (units + nseg - 1) / nseg;
     const int ubeg = seg * seg_units;
     const int uend = min(units, ubeg + seg_units);
     const T* W2 = reinterpret_cast<const T*>(base) + 2 * (size_t)F * H;
@@ -405,9 +420,7 @@ __global__ __launch_bounds__(256) void ffn_down_reg_kernel(const FfnArgs a) {
       }
     }
 
-    float* prow = part + ((size_t)j * 4 + seg) * RB;
-    for (int rr = rsub * R; rr < RB; rr += rstep * R) {
-      if (hb + rr >= H) break;
+    for (int rr = 0; rr < RB; rr += R) {
       raw q[R][UPL];
 #pragma unroll
       for (int r2 = 0; r2 < R; ++r2) {
@@ -438,8 +451,7 @@ __global__ __launch_bounds__(256) void ffn_down_reg_kernel(const FfnArgs a) {
     const int h = hb + row;
     if (h >= H) break;
     float sum = 0.f;
-    for (int j = 0; j < nj; ++j)
-      for (int sg = 0; sg < 4; ++sg) sum += part[((size_t)j * 4 + sg) * RB + row];
+    for (int it = 0; it < n_items; ++it) sum += part[(size_t)it * RB + row];
     T* y = static_cast<T*>(a.y) + (size_t)t * H;
     float* ysum = a.ysum + (size_t)t * H;
     if (PASS == 0) {
@@ -486,7 +498,7 @@ template <typename T, int PASS>
 static void launch_down_t(const FfnArgs& a, hipStream_t s) {
   const int grid = a.B * a.htiles;
   if (a.down_upl > 0) {
-    const size_t lds = (size_t)(a.k + a.ns) * 4 * a.RB * sizeof(float);
+    const size_t lds = (size_t)(a.k * a.nsegR + a.ns * a.nsegS) * a.RB * sizeof(float);
     switch (a.down_upl) {
       case 2: hipLaunchKernelGGL((ffn_down_reg_kernel<T, 2, 4, PASS>), dim3(grid), dim3(256), lds, s, a); return;
       case 4: hipLaunchKernelGGL((ffn_down_reg_kernel<T, 4, 2, PASS>), dim3(grid), dim3(256), lds, s, a); return;

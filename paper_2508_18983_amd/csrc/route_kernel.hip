@@ -257,23 +257,27 @@ __global__ __launch_bounds__(1024) void route_b1_kernel(const RouteArgs a) {
     for (int i = tid; i < E * E; i += 1024) sim_sh[i] = a.sim[i];
   if (tid < kWave) sm.slot_of[tid] = a.slot_of[tid];
 
-  for (int base = 0; base < items; base += 4 * 16) {
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  // RPP rows in flight per wave and pass (fewer when a row segment is long, to stay in registers)
+  constexpr int RPP = UPI >= 8 ? 2 : 4;
+  for (int base = 0; base < items; base += RPP * 16) {
+    float acc[RPP];
+#pragma unroll
+    for (int r = 0; r < RPP; ++r) acc[r] = 0.f;
 #pragma unroll
     for (int i = 0; i < UPI; ++i) {
       const int u = u0 + i * kWave + lane;
-      raw q[4];
+      raw q[RPP];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
+      for (int r = 0; r < RPP; ++r) {
         const int it = base + r * 16 + wave;
         q[r] = (it < items && u < u1) ? *reinterpret_cast<const raw*>(wg + (size_t)(it / nseg) * H + (size_t)u * N)
                                       : raw{};
       }
 #pragma unroll
-      for (int r = 0; r < 4; ++r) acc[r] = GateUnit<T>::dot(q[r], xr[i], acc[r]);
+      for (int r = 0; r < RPP; ++r) acc[r] = GateUnit<T>::dot(q[r], xr[i], acc[r]);
     }
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
+    for (int r = 0; r < RPP; ++r) {
       const int it = base + r * 16 + wave;
       const float v = wave_sum(acc[r]);
       if (lane == 0 && it < items) part[it / nseg][sg] = v;

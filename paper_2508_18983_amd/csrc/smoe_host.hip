@@ -87,10 +87,10 @@ void plan_geometry(moe_handle* h) {
   const moe_cfg_t& c = h->cfg;
   const long total_f = (long)c.top_k * c.ffn + (long)c.n_shared * c.shared_ffn;
   // up: TF rows of W1 and W3 per block, enough blocks to fill 256 CUs several times
-  int tf = total_f >= 32 * 1024 ? 32 : (total_f >= 16 * 1024 ? 16 : 8);
-  tf = env_int("SMOE_TF", tf);
-  if (tf < 8) tf = 8;
-  tf = tf / 8 * 8;
+  int tf = (int)((total_f + 1023) / 1024 + 3) / 4 * 4;         // ~1024 blocks per token
+  tf = env_int("SMOE_TF", std::max(8, tf));
+  if (tf < 4) tf = 4;
+  tf = tf / 4 * 4;
   h->TF = tf;
   h->tilesR = (c.ffn + tf - 1) / tf;
   h->tilesS = c.n_shared ? (c.shared_ffn + tf - 1) / tf : 0;
@@ -122,10 +122,10 @@ void plan_geometry(moe_handle* h) {
   if (need <= 12) {
     const int upl = need <= 2 ? 2 : (need <= 4 ? 4 : (need <= 6 ? 6 : (need <= 8 ? 8 : (need <= 10 ? 10 : 12))));
     const int rows_at_once = upl <= 2 ? 4 : (upl <= 6 ? 2 : 1);
-    int rb = 4 * rows_at_once;
-    if (c.hidden / rb > 512) rb *= 2;                 // keep ~512..1024 blocks per token
+    int rb = rows_at_once;
+    while (c.hidden / (rb * 2) >= 512) rb *= 2;       // >= 512 blocks per token
     rb = env_int("SMOE_RB", rb);
-    rb = std::max(4 * rows_at_once, rb / (4 * rows_at_once) * (4 * rows_at_once));
+    rb = std::max(rows_at_once, std::min(256, rb) / rows_at_once * rows_at_once);
     h->down_upl = upl;
     h->RB = rb;
     h->htiles = (c.hidden + rb - 1) / rb;
