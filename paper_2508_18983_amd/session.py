@@ -26,6 +26,14 @@ def pinned_empty(n_elems: int, dtype: torch.dtype) -> torch.Tensor:
     return t
 
 
+def pinned_free_all() -> None:
+    """Release every block handed out by pinned_empty().  Tensors created from
+    them must not be touched afterwards."""
+    for ptr in list(_PINNED_BLOCKS):
+        _PINNED_BLOCKS.pop(ptr)
+        B.moe_host_free(ptr)
+
+
 def _is_pinned(t: torch.Tensor) -> bool:
     return t.data_ptr() in _PINNED_BLOCKS or any(
         base <= t.data_ptr() < base + len(raw) for base, raw in _PINNED_BLOCKS.items()) or t.is_pinned()

@@ -133,3 +133,52 @@ def test_alternative_kernel_paths_and_launch_shapes(env, monkeypatch):
     run_parity(wl, y_every=2, label=f"c2-{env}")
     wl = make_workload(SHAPES["c5"].with_(seed=4, ffn=640, shared_ffn=20480), n_layers=1, tokens=10)
     run_parity(wl, y_every=2, label=f"c5-{env}")
+
+
+@pytest.mark.parametrize("batch", [2, 3, 4, 8])
+def test_batched_decode_cross_token_substitution_and_staging(batch):
+    """Batch > 1: a token's low-score expert may be kept or replaced through the
+    batch's top-score set; distinct misses are loaded once; when every resident
+    expert is shielded the load is computed from a transient slot."""
+    shp = SHAPES["c5"].with_(ffn=512, shared_ffn=1024, cache_cap=12, seed=batch)
+    wl = make_workload(shp, n_layers=2, tokens=20, batch=batch)
+    r = run_parity(wl, y_every=2, batch=batch, session_kw=dict(n_stage=batch * shp.top_k),
+                   label=f"c5-b{batch}")
+    assert r["stats"]["substitutions"] > 0 and r["stats"]["misses"] > 0
+    if batch >= 4:
+        assert r["stats"]["staged"] > 0
+
+
+def test_batch_fp32_and_running_out_of_staging_slots():
+    import paper_2508_18983_amd as M
+    from paper_2508_18983_amd.session import session_from_workload
+    wl = make_workload(SHAPES["c1"].with_(tokens=6, seed=9), batch=4)
+    run_parity(wl, batch=4, session_kw=dict(n_stage=8), label="c1-b4")
+    # capacity 4, batch 4 x top-2: with no staging slots a step that shields every resident fails cleanly
+    with session_from_workload(wl, max_batch=4, n_stage=0) as ses:
+        x = wl.x.to(ses.device)
+        with pytest.raises(M.SmoeError) as ei:
+            for t in range(6):
+                for l in range(2):
+                    ses.decode(l, x[t, l])
+        assert ei.value.code == -4
+        ses.reset()
+
+
+def test_c3_full_size_in_the_benchmark_launch_configuration():
+    """All 32 layers at the real shape, host expert storage and launch geometry
+    exactly as bench.py sets them up (16 pinned layer blocks shared by 32
+    layers): every decision of every call is compared, y on sampled calls."""
+    import gc
+    from paper_2508_18983_amd.session import pinned_empty, pinned_free_all
+    wl = make_workload(SHAPES["c3"], device="cuda", tokens=40, host_alloc=pinned_empty, distinct_layers=16)
+    try:
+        r = run_parity(wl, y_every=197, label="c3-full")
+        assert r["n_y"] >= 6
+        assert r["stats"]["substitutions"] > 0 and r["stats"]["misses"] > 0
+        assert r["stats"]["hits"] + r["stats"]["misses"] == 40 * 32 * 2
+    finally:
+        del wl
+        gc.collect()
+        torch.cuda.empty_cache()
+        pinned_free_all()
