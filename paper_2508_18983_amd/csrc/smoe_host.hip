@@ -51,7 +51,7 @@ struct moe_handle {
   moe_cfg_t cfg{};
   moe_buffers_t buf{};
   hipStream_t s_compute = nullptr, s_copy = nullptr;
-  hipEvent_t ev_route = nullptr, ev_copy = nullptr;
+  hipEvent_t ev_copy = nullptr;
   int64_t esize = 0, expert_bytes = 0, shared_bytes = 0;
   int Fmax = 0;
   std::vector<LayerState> layers;
@@ -162,7 +162,6 @@ void free_all(moe_handle* h) {
   if (!h) return;
   for (auto& k : h->prof)
     for (auto& p : k.ev) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
-  if (h->ev_route) (void)hipEventDestroy(h->ev_route);
   if (h->ev_copy) (void)hipEventDestroy(h->ev_copy);
   if (h->sim_dev) (void)hipFree(h->sim_dev);
   if (h->rec_dev) (void)hipFree(h->rec_dev);
@@ -250,7 +249,6 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
   const int nj = c.top_k + c.n_shared;
   const size_t sim_bytes = (size_t)c.n_layers * c.n_experts * c.n_experts * sizeof(float);
   int rc = [&]() -> int {
-    HIP_TRY(hipEventCreateWithFlags(&h->ev_route, hipEventDisableTiming));
     HIP_TRY(hipEventCreateWithFlags(&h->ev_copy, hipEventDisableTiming));
     HIP_TRY(hipMalloc(&h->sim_dev, sim_bytes));
     HIP_TRY(hipMemcpy(h->sim_dev, buf->sim_host, sim_bytes, hipMemcpyHostToDevice));
@@ -308,7 +306,8 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   launch_route(ra, c.dtype, h->s_compute);
   prof_end(pr, h->s_compute);
   HIP_TRY(hipGetLastError());
-  HIP_TRY(hipEventRecord(h->ev_route, h->s_compute));
+  // (no event after the router kernel: an event record costs several microseconds of
+  // stream time between the router and the FFN; the host polls the mirror instead)
 
   // ---- FFN over what is already resident (+ shared experts), enqueued before
   //      the host knows the routing result ------------------------------------
@@ -341,12 +340,12 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
 
   // ---- the decision reaches the host -----------------------------------------
   // Poll the pinned mirror (the router kernel publishes its call number last);
-  // after spin_limit polls fall back to waiting on the event.
+  // after spin_limit polls fall back to draining the compute stream.
   {
     const volatile int32_t* seq = &h->rec_host->seq;
     long spins = 0;
     while (*seq != h->seq && spins < h->spin_limit) ++spins;
-    if (*seq != h->seq) HIP_TRY(hipEventSynchronize(h->ev_route));
+    if (*seq != h->seq) HIP_TRY(hipStreamSynchronize(h->s_compute));
     __atomic_thread_fence(__ATOMIC_ACQUIRE);
     if (*seq != h->seq) return SMOE_ESTATE;
   }

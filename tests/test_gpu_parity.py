@@ -126,7 +126,7 @@ def test_error_paths_and_reset():
                                  dict(SMOE_RB="16", SMOE_TF="64"), dict(SMOE_SPIN_LIMIT="0")])
 def test_alternative_kernel_paths_and_launch_shapes(env, monkeypatch):
     """The LDS-staged kernels (fallback for very wide layers), other tile
-    shapes, and the event-wait fallback of the host must give the same answers."""
+    shapes, and the stream-drain fallback of the host must give the same answers."""
     for k, v in env.items():
         monkeypatch.setenv(k, v)
     wl = make_workload(SHAPES["c2"].with_(seed=4), n_layers=2, tokens=24)
