@@ -22,7 +22,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the resident-pass up kernel / its algorithmic bytes, from the two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) summarised in profiles/c3_ffn_hbm_traffic_pmc.md
-MEASURED_TRAFFIC_RATIO = {"c3-mixtral8x7b-shaped": 1.0004}
+MEASURED_TRAFFIC_RATIO = {"c3-mixtral8x7b-shaped": 1.0003}
 
 
 def log(msg: str) -> None:
