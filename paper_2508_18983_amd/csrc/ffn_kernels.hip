@@ -463,6 +463,264 @@ __global__ __launch_bounds__(256) void ffn_down_reg_kernel(const FfnArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// Batch > 1: grouped kernels.  A task is one distinct expert of the step (a
+// record group) or a shared expert, with the list of tokens that compute it;
+// the expert's weights are streamed from HBM once per group of up to kGrpTok
+// tokens (a group with more tokens is done in two token passes) and every
+// loaded unit is multiplied with all of those tokens' vectors.
+// ---------------------------------------------------------------------------
+constexpr int kGrpTok = 4;       // tokens per pass over the weights
+constexpr int kGrpUpl = 2;       // down: 128-bit units of a row segment per lane
+constexpr int kGrpRows = 2;      // down: rows in flight
+
+struct GrpTask {
+  const char* base;              // expert weights, null = not in this pass
+  int F;
+  int ntok;
+  int tok[SMOE_MAX_BATCH];
+  float w[SMOE_MAX_BATCH];
+  float* act;                    // [SMOE_MAX_BATCH][F] activations of this task
+};
+
+// task index: [0, maxg) record groups, then the shared experts
+template <int PASS>
+__device__ __forceinline__ GrpTask grp_task(const FfnArgs& a, int task) {
+  GrpTask g;
+  g.base = nullptr;
+  g.F = 0;
+  g.ntok = 0;
+  g.act = nullptr;
+#pragma unroll
+  for (int i = 0; i < SMOE_MAX_BATCH; ++i) { g.tok[i] = 0; g.w[i] = 0.f; }
+  if (task < a.maxg) {
+    if (task >= a.rec->n_groups) return g;
+    const GroupTask& r = a.rec->grp[task];
+    int gs;
+    if (PASS == 0) {
+      if (r.slot < 0) return g;
+      gs = a.slot_base + r.slot;
+    } else {
+      gs = a.slot_override[task];
+      if (gs < 0) return g;
+    }
+    g.base = a.slab + (int64_t)gs * a.expert_bytes;
+    g.F = a.F;
+    g.ntok = r.ntok;
+#pragma unroll
+    for (int i = 0; i < SMOE_MAX_BATCH; ++i) { g.tok[i] = r.tok[i]; g.w[i] = r.w[i]; }
+    g.act = a.act + (size_t)task * SMOE_MAX_BATCH * a.F;
+  } else {
+    if (PASS != 0) return g;
+    const int sidx = task - a.maxg;
+    g.base = a.shared + (int64_t)sidx * a.shared_bytes;
+    g.F = a.Fs;
+    g.ntok = a.B;
+#pragma unroll
+    for (int i = 0; i < SMOE_MAX_BATCH; ++i) { g.tok[i] = i; g.w[i] = 1.0f; }
+    g.act = a.act + a.act_shared_off + (size_t)sidx * SMOE_MAX_BATCH * a.Fs;
+  }
+  return g;
+}
+
+// Up projection for a task and one token pass.  The hidden states of the up
+// to kGrpTok tokens sit in LDS as stored; a wave owns whole rows and keeps the
+// 2*UPL loaded units of one f-row pair in registers while it walks the tokens.
+template <typename T, int UPL, int PASS>
+__global__ __launch_bounds__(256) void ffn_up_grp_kernel(const FfnArgs a) {
+  extern __shared__ __align__(16) unsigned char xs_raw[];      // [kGrpTok][H] elements of T
+  constexpr int N = Unit<T>::N;
+  using raw = typename Unit<T>::raw;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+  const int routed_blocks = a.maxg * 2 * a.tilesR;
+  int task, tpass, tile;
+  if ((int)blockIdx.x < routed_blocks) {
+    task = blockIdx.x / (2 * a.tilesR);
+    const int r = blockIdx.x - task * 2 * a.tilesR;
+    tpass = r / a.tilesR; tile = r - tpass * a.tilesR;
+  } else {
+    const int b = blockIdx.x - routed_blocks;
+    const int sidx = b / (2 * a.tilesS);
+    const int r = b - sidx * 2 * a.tilesS;
+    tpass = r / a.tilesS; tile = r - tpass * a.tilesS;
+    task = a.maxg + sidx;
+  }
+  const GrpTask g = grp_task<PASS>(a, task);
+  const int t0 = tpass * kGrpTok;
+  if (g.base == nullptr || t0 >= g.ntok) return;
+  const int nt = min(kGrpTok, g.ntok - t0);
+  const int H = a.H, F = g.F;
+  const int units = H / N;
+  const T* W1 = reinterpret_cast<const T*>(g.base);
+  const T* W3 = W1 + (size_t)F * H;
+  raw* xs = reinterpret_cast<raw*>(xs_raw);                    // [kGrpTok][units]
+
+  int toks[kGrpTok]; float wts[kGrpTok];
+#pragma unroll
+  for (int i = 0; i < kGrpTok; ++i) {
+    toks[i] = 0; wts[i] = 0.f;
+#pragma unroll
+    for (int q = 0; q < SMOE_MAX_BATCH; ++q)
+      if (q == t0 + i) { toks[i] = g.tok[q]; wts[i] = g.w[q]; }
+  }
+#pragma unroll
+  for (int i = 0; i < kGrpTok; ++i)
+    if (i < nt) {
+      const T* x = static_cast<const T*>(a.x) + (size_t)toks[i] * H;
+      for (int u = tid; u < units; u += 256) xs[i * units + u] = *reinterpret_cast<const raw*>(x + (size_t)u * N);
+    }
+  __syncthreads();
+
+  const int per_wave = a.TF >> 2;
+  const int f_begin = tile * a.TF + wave * per_wave;
+  for (int fi = 0; fi < per_wave; ++fi) {
+    const int f = f_begin + fi;
+    if (f >= F) break;
+    const T* gr = W1 + (size_t)f * H;
+    const T* ur = W3 + (size_t)f * H;
+    raw qg[UPL], qu[UPL];
+#pragma unroll
+    for (int s = 0; s < UPL; ++s) {
+      const int u = s * kWave + lane;
+      if (u < units) { qg[s] = Unit<T>::load(gr + (size_t)u * N); qu[s] = Unit<T>::load(ur + (size_t)u * N); }
+      else { qg[s] = raw{}; qu[s] = raw{}; }
+    }
+#pragma unroll
+    for (int i = 0; i < kGrpTok; ++i) {
+      if (i < nt) {                                            // uniform
+        float ag = 0.f, au = 0.f;
+#pragma unroll
+        for (int s = 0; s < UPL; ++s) {
+          const int u = s * kWave + lane;
+          const raw xv = (u < units) ? xs[i * units + u] : raw{};
+          ag = Unit<T>::dot(qg[s], xv, ag);
+          au = Unit<T>::dot(qu[s], xv, au);
+        }
+        ag = wave_sum(ag);
+        au = wave_sum(au);
+        if (lane == 0) g.act[(size_t)(t0 + i) * F + f] = wts[i] * (ag / (1.0f + expf(-ag))) * au;
+      }
+    }
+  }
+}
+
+// Down projection + combine for all tokens of the step.  A block owns RBG
+// output rows.  Work item = (task, column segment of 64*kGrpUpl units); the
+// four waves take items round-robin, keep the item's activation slices of up
+// to kGrpTok tokens in registers and stream the block's rows.  Partial sums go
+// to LDS [item][token slot][row]; after one barrier they are added per token
+// in item order.
+template <typename T, int PASS>
+__global__ __launch_bounds__(256) void ffn_down_grp_kernel(const FfnArgs a) {
+  extern __shared__ __align__(16) float part[];       // [items][SMOE_MAX_BATCH][RBG]
+  constexpr int N = Unit<T>::N;
+  constexpr int UPL = kGrpUpl, R = kGrpRows;
+  using raw = typename Unit<T>::raw;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+  const int RB = a.RBG, H = a.H;
+  const int hb = blockIdx.x * RB;
+  const int n_groups = min(a.rec->n_groups, a.maxg);
+  const int items_r = n_groups * a.nsegGR;
+  const int n_items = items_r + a.ns * a.nsegGS;
+
+  for (int i = tid; i < n_items * SMOE_MAX_BATCH * RB; i += 256) part[i] = 0.f;
+  __syncthreads();
+
+  for (int it = wave; it < n_items; it += 4) {
+    int task, seg;
+    if (it < items_r) { task = it / a.nsegGR; seg = it - task * a.nsegGR; }
+    else { const int q = it - items_r; const int sidx = q / a.nsegGS; seg = q - sidx * a.nsegGS; task = a.maxg + sidx; }
+    const GrpTask g = grp_task<PASS>(a, task);
+    if (g.base == nullptr) continue;
+    const int F = g.F;
+    const int units = F / N;
+    const int ubeg = seg * kWave * UPL;
+    const int uend = min(units, ubeg + kWave * UPL);
+    const T* W2 = reinterpret_cast<const T*>(g.base) + 2 * (size_t)F * H;
+    float* pitem = part + (size_t)it * SMOE_MAX_BATCH * RB;
+    for (int t0 = 0; t0 < g.ntok; t0 += kGrpTok) {
+      const int nt = min(kGrpTok, g.ntok - t0);
+      float ar[kGrpTok][UPL][N];
+#pragma unroll
+      for (int i = 0; i < kGrpTok; ++i)
+#pragma unroll
+        for (int s = 0; s < UPL; ++s) {
+          const int u = ubeg + s * kWave + lane;
+          if (i < nt && u < uend) {
+            const float* ap = g.act + (size_t)(t0 + i) * F + (size_t)u * N;
+#pragma unroll
+            for (int e = 0; e < N; e += 4) {
+              const float4 v = *reinterpret_cast<const float4*>(ap + e);
+              ar[i][s][e] = v.x; ar[i][s][e + 1] = v.y; ar[i][s][e + 2] = v.z; ar[i][s][e + 3] = v.w;
+            }
+          } else {
+#pragma unroll
+            for (int e = 0; e < N; ++e) ar[i][s][e] = 0.f;
+          }
+        }
+      for (int rr = 0; rr < RB; rr += R) {
+        raw q[R][UPL];
+#pragma unroll
+        for (int r2 = 0; r2 < R; ++r2) {
+          const T* row = W2 + (size_t)min(hb + rr + r2, H - 1) * F;
+#pragma unroll
+          for (int s = 0; s < UPL; ++s) {
+            const int u = ubeg + s * kWave + lane;
+            q[r2][s] = (u < uend) ? Unit<T>::load(row + (size_t)u * N) : raw{};
+          }
+        }
+#pragma unroll
+        for (int r2 = 0; r2 < R; ++r2) {
+          float w[UPL][N];
+#pragma unroll
+          for (int s = 0; s < UPL; ++s) Unit<T>::widen(q[r2][s], w[s]);
+#pragma unroll
+          for (int i = 0; i < kGrpTok; ++i) {
+            if (i < nt) {                                      // uniform
+              float acc = 0.f;
+#pragma unroll
+              for (int s = 0; s < UPL; ++s)
+#pragma unroll
+                for (int e = 0; e < N; ++e) acc = fmaf(w[s][e], ar[i][s][e], acc);
+              acc = wave_sum(acc);
+              if (lane == 0 && rr + r2 < RB) pitem[(size_t)(t0 + i) * RB + rr + r2] = acc;
+            }
+          }
+        }
+      }
+    }
+  }
+  __syncthreads();
+  for (int idx = tid; idx < a.B * RB; idx += 256) {
+    const int t = idx / RB, row = idx - t * RB;
+    const int h = hb + row;
+    if (h >= H) continue;
+    bool any_miss = false;
+    for (int q = 0; q < a.k; ++q) any_miss |= (a.rec->tok[t].slot[q] < 0);
+    if (PASS == 1 && !any_miss) continue;
+    float sum = 0.f;
+    for (int gi = 0; gi < n_groups; ++gi) {
+      const GroupTask& r = a.rec->grp[gi];
+      int pos = -1;
+      for (int i = 0; i < r.ntok; ++i) pos = (r.tok[i] == t) ? i : pos;
+      if (pos < 0) continue;
+      for (int sg = 0; sg < a.nsegGR; ++sg)
+        sum += part[((size_t)(gi * a.nsegGR + sg) * SMOE_MAX_BATCH + pos) * RB + row];
+    }
+    for (int sidx = 0; sidx < a.ns; ++sidx)
+      for (int sg = 0; sg < a.nsegGS; ++sg)
+        sum += part[((size_t)(items_r + sidx * a.nsegGS + sg) * SMOE_MAX_BATCH + t) * RB + row];
+    T* y = static_cast<T*>(a.y) + (size_t)t * H;
+    float* ysum = a.ysum + (size_t)t * H;
+    if (PASS == 0) {
+      if (any_miss) ysum[h] = sum;
+      else y[h] = Unit<T>::narrow(sum);
+    } else {
+      y[h] = Unit<T>::narrow(ysum[h] + sum);
+    }
+  }
+}
+
 __global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst,
                                                    const uint4* __restrict__ src, int64_t n) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -474,6 +732,16 @@ __global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst,
 
 template <typename T, int PASS>
 static void launch_up_t(const FfnArgs& a, hipStream_t s) {
+  if (a.grouped) {
+    const int grid = a.maxg * 2 * a.tilesR + a.ns * 2 * a.tilesS;
+    const size_t lds = (size_t)kGrpTok * a.H * sizeof(T);
+    switch (a.up_upl) {
+      case 1: hipLaunchKernelGGL((ffn_up_grp_kernel<T, 1, PASS>), dim3(grid), dim3(256), lds, s, a); return;
+      case 2: hipLaunchKernelGGL((ffn_up_grp_kernel<T, 2, PASS>), dim3(grid), dim3(256), lds, s, a); return;
+      case 4: hipLaunchKernelGGL((ffn_up_grp_kernel<T, 4, PASS>), dim3(grid), dim3(256), lds, s, a); return;
+      default: hipLaunchKernelGGL((ffn_up_grp_kernel<T, 8, PASS>), dim3(grid), dim3(256), lds, s, a); return;
+    }
+  }
   const int grid = a.B * (a.k * a.tilesR + a.ns * a.tilesS);
   switch (a.up_upl) {
     case 1: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 1, PASS>), dim3(grid), dim3(256), 0, s, a); return;
@@ -496,6 +764,11 @@ void launch_ffn_up(const FfnArgs& a, int dtype, hipStream_t s) {
 
 template <typename T, int PASS>
 static void launch_down_t(const FfnArgs& a, hipStream_t s) {
+  if (a.grouped) {
+    const int grid = (a.H + a.RBG - 1) / a.RBG;
+    hipLaunchKernelGGL((ffn_down_grp_kernel<T, PASS>), dim3(grid), dim3(256), grouped_down_lds_bytes(a), s, a);
+    return;
+  }
   const int grid = a.B * a.htiles;
   if (a.down_upl > 0) {
     const size_t lds = (size_t)(a.k * a.nsegR + a.ns * a.nsegS) * a.RB * sizeof(float);
@@ -521,6 +794,10 @@ void launch_ffn_down(const FfnArgs& a, int dtype, hipStream_t s) {
   } else {
     if (a.pass == 0) launch_down_t<bf16_t, 0>(a, s); else launch_down_t<bf16_t, 1>(a, s);
   }
+}
+
+size_t grouped_down_lds_bytes(const FfnArgs& a) {
+  return (size_t)(a.maxg * a.nsegGR + a.ns * a.nsegGS) * SMOE_MAX_BATCH * a.RBG * sizeof(float);
 }
 
 void launch_copy(void* dst, const void* src, int64_t n_bytes, hipStream_t s) {

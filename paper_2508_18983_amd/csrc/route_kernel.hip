@@ -72,6 +72,8 @@ struct SelectSmem {
   float thr_r[SMOE_MAX_BATCH];
   unsigned long long top_m_sh[SMOE_MAX_BATCH];
   int slot_of[kWave];
+  int fin[SMOE_MAX_BATCH][SMOE_MAX_TOPK];     // final expert per (token, slot)
+  float wsl[SMOE_MAX_BATCH][SMOE_MAX_TOPK];   // combine weight per (token, slot)
 };
 
 // Runs on wave 0 with all 64 lanes active: logits in sm.lg -> decision record.
@@ -150,8 +152,32 @@ __device__ __forceinline__ void select_and_publish(const RouteArgs& a, SelectSme
       d->slot[lane] = slot;    hrec->slot[lane] = slot;
       d->subst[lane] = mysub;  hrec->subst[lane] = mysub;
       d->w[lane] = w;          hrec->w[lane] = w;
+      sm.fin[t][lane] = myfin;
+      sm.wsl[t][lane] = w;
     }
     a.rec_host->tok[t].scores[lane] = lane < E ? s : 0.f;
+  }
+  if (B > 1) {
+    // expert groups for the batched FFN: lane e collects the tokens that compute expert e
+    GroupTask g;
+    g.expert = lane;
+    g.slot = ((a.resident >> lane) & 1ull) ? slot_of[lane] : -1;
+    g.ntok = 0;
+    g.pad_ = 0;
+#pragma unroll
+    for (int i = 0; i < SMOE_MAX_BATCH; ++i) { g.tok[i] = 0; g.w[i] = 0.f; }
+    for (int t = 0; t < B; ++t)
+      for (int j = 0; j < k; ++j)
+        if (sm.fin[t][j] == lane) {
+#pragma unroll
+          for (int i = 0; i < SMOE_MAX_BATCH; ++i)
+            if (i == g.ntok) { g.tok[i] = t; g.w[i] = sm.wsl[t][j]; }
+          ++g.ntok;
+        }
+    const unsigned long long has_m = __ballot(g.ntok > 0);
+    const int idx = __popcll(has_m & ((1ull << lane) - 1ull));
+    if (g.ntok > 0) a.rec_dev->grp[idx] = g;
+    if (lane == 0) a.rec_dev->n_groups = __popcll(has_m);
   }
   // publish: every store of this wave to the mirror is complete before seq changes
   __threadfence_system();

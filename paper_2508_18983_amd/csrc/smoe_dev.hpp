@@ -22,8 +22,21 @@ struct TokRec {
   float   w[SMOE_MAX_TOPK];        // combine weight
   float   scores[SMOE_MAX_EXPERTS];
 };
+// Batch > 1: one entry per distinct expert of the step, ascending expert id,
+// with the tokens that compute it (device copy of the record only).
+struct GroupTask {
+  int32_t expert;
+  int32_t slot;                    // layer-local cache slot, -1 when not resident
+  int32_t ntok;
+  int32_t pad_;
+  int32_t tok[SMOE_MAX_BATCH];     // tokens using this expert, ascending
+  float   w[SMOE_MAX_BATCH];       // their combine weights
+};
 struct StepRec {
   TokRec tok[SMOE_MAX_BATCH];
+  int32_t n_groups;
+  int32_t pad_[3];
+  GroupTask grp[SMOE_MAX_EXPERTS];
   int32_t seq;                     // host mirror only: call number, written last
 };
 
@@ -66,12 +79,17 @@ struct FfnArgs {
   int32_t up_upl;                          // up: 128-bit units of x per lane held in registers, 0 = LDS path
   int32_t down_upl, RB, nsegR, nsegS;      // down register path: units per lane (0 = LDS path), rows per
                                            // block, column segments of a routed / shared row
-  int32_t slot_override[kMaxTasks];        // pass 1: global slot per task, -1 = not in this pass
+  int32_t grouped;                         // batch > 1: tasks are the record's expert groups (+ shared)
+  int32_t maxg;                            // grouped: upper bound of groups = min(E, B*k)
+  int32_t nsegGR, nsegGS, RBG;             // grouped down kernel: segments per routed / shared row, rows per block
+  int64_t act_shared_off;                  // grouped: float offset of the shared experts' activations in act
+  int32_t slot_override[kMaxTasks];        // pass 1: global slot per task (grouped: per group), -1 = not in this pass
 };
 
 void launch_route(const RouteArgs& a, int dtype, hipStream_t s);
 void launch_ffn_up(const FfnArgs& a, int dtype, hipStream_t s);
 void launch_ffn_down(const FfnArgs& a, int dtype, hipStream_t s);
+size_t grouped_down_lds_bytes(const FfnArgs& a);
 void launch_copy(void* dst, const void* src, int64_t n_bytes, hipStream_t s);
 
 }  // namespace smoe

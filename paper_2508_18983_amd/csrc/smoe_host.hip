@@ -67,6 +67,8 @@ struct moe_handle {
   // launch geometry
   int TF = 0, tilesR = 0, tilesS = 0, R = 0, htiles = 0, stage_all = 0, chunk = 0, down_lds = 0;
   int up_upl = 0, down_upl = 0, RB = 0, nsegR = 1, nsegS = 1;
+  int grouped_ok = 0, nsegGR = 0, nsegGS = 0, RBG = 0;   // batch > 1: grouped kernels
+  int64_t act_floats = 0;
   // profiling
   int32_t seq = 0;                       // number of the last decode call
   int route_fast = 1;                    // use the batch-1 router kernel
@@ -105,8 +107,23 @@ void plan_geometry(moe_handle* h) {
   h->chunk = chunk;
   h->down_lds = h->stage_all ? (int)total_f : chunk;
 
-  // register-resident fast paths (SMOE_REGPATH=0 forces the LDS kernels)
   const int n = c.dtype == SMOE_DTYPE_FP32 ? 4 : 8;
+  // batch > 1: grouped kernels stream an expert once for up to 4 of its tokens
+  h->grouped_ok = 0;
+  if (c.max_batch > 1 && env_int("SMOE_GROUPED", 1) != 0) {
+    const int esz = c.dtype == SMOE_DTYPE_FP32 ? 4 : 2;
+    const int maxg = std::min(c.n_experts, c.max_batch * c.top_k);
+    h->nsegGR = (c.ffn / n + 127) / 128;
+    h->nsegGS = c.n_shared ? (c.shared_ffn / n + 127) / 128 : 0;
+    const long items = (long)maxg * h->nsegGR + (long)c.n_shared * h->nsegGS;
+    int rbg = 4;
+    while (rbg > 2 && items * SMOE_MAX_BATCH * rbg * 4 > 60 * 1024) rbg /= 2;
+    const bool lds_ok = items * SMOE_MAX_BATCH * rbg * 4 <= 60 * 1024 && 4L * c.hidden * esz <= 60 * 1024;
+    const int xu0 = (c.hidden / n + kWave - 1) / kWave;
+    if (lds_ok && xu0 <= 8) { h->grouped_ok = 1; h->RBG = rbg; }
+  }
+
+  // register-resident fast paths (SMOE_REGPATH=0 forces the LDS kernels)
   h->up_upl = 0;
   h->down_upl = 0;
   if (env_int("SMOE_REGPATH", 1) == 0) return;
@@ -260,7 +277,12 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
     void* dp = nullptr;
     HIP_TRY(hipHostGetDevicePointer(&dp, h->rec_host, 0));
     h->rec_host_dev = static_cast<StepRec*>(dp);
-    HIP_TRY(hipMalloc(&h->act, (size_t)c.max_batch * nj * h->Fmax * sizeof(float)));
+    {
+      const int64_t maxg = std::min(c.n_experts, c.max_batch * c.top_k);
+      const int64_t grouped = maxg * SMOE_MAX_BATCH * c.ffn + (int64_t)c.n_shared * SMOE_MAX_BATCH * c.shared_ffn;
+      h->act_floats = std::max<int64_t>((int64_t)c.max_batch * nj * h->Fmax, grouped);
+    }
+    HIP_TRY(hipMalloc(&h->act, (size_t)h->act_floats * sizeof(float)));
     HIP_TRY(hipMalloc(&h->ysum, (size_t)c.max_batch * c.hidden * sizeof(float)));
     return upload_initial(h);
   }();
@@ -330,6 +352,15 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   fa.up_upl = h->up_upl; fa.down_upl = h->down_upl; fa.RB = h->RB;
   fa.nsegR = h->nsegR; fa.nsegS = h->nsegS;
   for (int i = 0; i < kMaxTasks; ++i) fa.slot_override[i] = -1;
+  fa.grouped = (B > 1 && h->grouped_ok) ? 1 : 0;
+  fa.maxg = std::min(E, B * k);
+  fa.nsegGR = h->nsegGR; fa.nsegGS = h->nsegGS; fa.RBG = h->RBG;
+  fa.act_shared_off = (int64_t)fa.maxg * SMOE_MAX_BATCH * c.ffn;
+  if (fa.grouped && fa.up_upl == 0) {                 // grouped up kernel needs units per lane
+    const int n = c.dtype == SMOE_DTYPE_FP32 ? 4 : 8;
+    const int xu = (c.hidden / n + kWave - 1) / kWave;
+    fa.up_upl = xu <= 1 ? 1 : (xu <= 2 ? 2 : (xu <= 4 ? 4 : 8));
+  }
   EventPair* pu = prof_begin(h, SMOE_PROF_UP, h->s_compute);
   launch_ffn_up(fa, c.dtype, h->s_compute);
   prof_end(pu, h->s_compute);
@@ -421,13 +452,21 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
     HIP_TRY(hipStreamWaitEvent(h->s_compute, h->ev_copy, 0));
     // second FFN pass: only the slots whose expert has just been loaded
     fa.pass = 1;
-    for (int t = 0; t < B; ++t)
-      for (int j = 0; j < k; ++j) {
-        const int e = rec.tok[t].final_[j];
-        if ((before >> e) & 1ull) continue;
-        for (int i = 0; i < n_fetch; ++i)
-          if (fetched[i] == e) fa.slot_override[t * nj + j] = gslot[i];
+    if (fa.grouped) {
+      // group index of an expert = its rank among the distinct experts of the step (ascending id)
+      for (int i = 0; i < n_fetch; ++i) {
+        const int gi = __builtin_popcountll(shield & ((1ull << fetched[i]) - 1ull));
+        fa.slot_override[gi] = gslot[i];
       }
+    } else {
+      for (int t = 0; t < B; ++t)
+        for (int j = 0; j < k; ++j) {
+          const int e = rec.tok[t].final_[j];
+          if ((before >> e) & 1ull) continue;
+          for (int i = 0; i < n_fetch; ++i)
+            if (fetched[i] == e) fa.slot_override[t * nj + j] = gslot[i];
+        }
+    }
     EventPair* pu2 = prof_begin(h, SMOE_PROF_UP_LOADED, h->s_compute);
     launch_ffn_up(fa, c.dtype, h->s_compute);
     prof_end(pu2, h->s_compute);
@@ -438,11 +477,17 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   }
   if (h->prof_mask) {
     // algorithmic bytes each timed launch was asked to stream
-    const int64_t miss_slots = (int64_t)B * k - hits;
+    int64_t miss_slots = (int64_t)B * k - hits;
+    int64_t res_slots = hits, shared_times = B;
+    if (fa.grouped) {                                 // weights are streamed once per distinct expert
+      res_slots = __builtin_popcountll(shield & before);
+      miss_slots = n_fetch;
+      shared_times = 1;
+    }
     const int64_t up_r = 2ll * c.hidden * c.ffn * h->esize, up_s = 2ll * c.hidden * c.shared_ffn * h->esize;
     h->prof[SMOE_PROF_ROUTE].bytes += (int64_t)E * c.hidden * h->esize;
-    h->prof[SMOE_PROF_UP].bytes += hits * up_r + (int64_t)B * c.n_shared * up_s;
-    h->prof[SMOE_PROF_DOWN].bytes += (hits * up_r + (int64_t)B * c.n_shared * up_s) / 2;
+    h->prof[SMOE_PROF_UP].bytes += res_slots * up_r + shared_times * c.n_shared * up_s;
+    h->prof[SMOE_PROF_DOWN].bytes += (res_slots * up_r + shared_times * c.n_shared * up_s) / 2;
     h->prof[SMOE_PROF_COPY].bytes += (int64_t)n_fetch * h->expert_bytes;
     h->prof[SMOE_PROF_UP_LOADED].bytes += miss_slots * up_r;
     h->prof[SMOE_PROF_DOWN_LOADED].bytes += miss_slots * up_r / 2;

@@ -149,6 +149,14 @@ def test_batched_decode_cross_token_substitution_and_staging(batch):
         assert r["stats"]["staged"] > 0
 
 
+def test_batched_decode_without_expert_grouping(monkeypatch):
+    """The per-(token, slot) task path stays available (SMOE_GROUPED=0)."""
+    monkeypatch.setenv("SMOE_GROUPED", "0")
+    shp = SHAPES["c5"].with_(ffn=512, shared_ffn=1024, cache_cap=12, seed=21)
+    wl = make_workload(shp, n_layers=2, tokens=12, batch=4)
+    run_parity(wl, y_every=2, batch=4, session_kw=dict(n_stage=32), label="c5-b4-ungrouped")
+
+
 def test_batch_fp32_and_running_out_of_staging_slots():
     import paper_2508_18983_amd as M
     from paper_2508_18983_amd.session import session_from_workload
