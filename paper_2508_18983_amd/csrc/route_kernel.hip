@@ -78,15 +78,16 @@ struct SelectSmem {
 
 // Runs on wave 0 with all 64 lanes active: logits in sm.lg -> decision record.
 // `sim` is this layer's similarity table (global or LDS).
-__device__ __forceinline__ void select_and_publish(const RouteArgs& a, SelectSmem& sm, const float* sim,
-                                                   int lane) {
-  const int E = a.E, k = a.k, B = a.B;
+// Pass 1 for tokens [t_begin, t_end): scores, top-(k+1), alpha classes.  Returns
+// the union of their top-score masks.
+__device__ __forceinline__ unsigned long long select_pass1(const RouteArgs& a, SelectSmem& sm, int lane,
+                                                           int t_begin, int t_end) {
+  const int E = a.E, k = a.k;
   auto& lg = sm.lg; auto& sc = sm.sc; auto& rk = sm.rk; auto& tk = sm.tk;
-  auto& thr_r = sm.thr_r; auto& top_m_sh = sm.top_m_sh; auto& slot_of = sm.slot_of;
-  // ---- pass 1: scores, top-(k+1), alpha classes, batch top-score set C ------
+  auto& thr_r = sm.thr_r; auto& top_m_sh = sm.top_m_sh;
   const bool has_pivot = E > k;
   unsigned long long c_mask = 0;
-  for (int t = 0; t < B; ++t) {
+  for (int t = t_begin; t < t_end; ++t) {
     const bool in = lane < E;
     const float l = in ? lg[t][lane] : -INFINITY;
     const float m = wave_max(l);
@@ -114,8 +115,17 @@ __device__ __forceinline__ void select_and_publish(const RouteArgs& a, SelectSme
     rk[t][lane] = myrank;
     if (lane == 0) { thr_r[t] = R; top_m_sh[t] = top_m; }
   }
+  return c_mask;
+}
 
-  // ---- pass 2: substitution and the decision record -------------------------
+// Pass 2: substitution against residency and the batch top-score set C, the
+// decision record, the expert groups, and the publication to the host mirror.
+__device__ __forceinline__ void select_pass2(const RouteArgs& a, SelectSmem& sm, const float* sim,
+                                             unsigned long long c_mask, int lane) {
+  const int E = a.E, k = a.k, B = a.B;
+  auto& sc = sm.sc; auto& rk = sm.rk; auto& tk = sm.tk;
+  auto& thr_r = sm.thr_r; auto& top_m_sh = sm.top_m_sh; auto& slot_of = sm.slot_of;
+  const bool has_pivot = E > k;
   const unsigned long long avail = a.resident | c_mask;
   for (int t = 0; t < B; ++t) {
     const float s = sc[t][lane];
@@ -182,6 +192,12 @@ __device__ __forceinline__ void select_and_publish(const RouteArgs& a, SelectSme
   // publish: every store of this wave to the mirror is complete before seq changes
   __threadfence_system();
   if (lane == 0) __hip_atomic_store(&a.rec_host->seq, a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+__device__ __forceinline__ void select_and_publish(const RouteArgs& a, SelectSmem& sm, const float* sim,
+                                                   int lane) {
+  const unsigned long long c_mask = select_pass1(a, sm, lane, 0, a.B);
+  select_pass2(a, sm, sim, c_mask, lane);
 }
 
 constexpr int kMaxSeg = 8;   // a gate row is split into at most this many segments
@@ -268,7 +284,8 @@ __global__ __launch_bounds__(1024) void route_b1_kernel(const RouteArgs a) {
   const int items = E * nseg;
   const int units = H / N;
   const T* wg = static_cast<const T*>(a.gate_w);
-  const T* x = static_cast<const T*>(a.x);
+  const int tok = blockIdx.x;                    // one block per token
+  const T* x = static_cast<const T*>(a.x) + (size_t)tok * H;
 
   // this wave's segment of x (the same for all of its items: 16 is a multiple of nseg)
   const int sg = wave & (nseg - 1);
@@ -279,7 +296,7 @@ __global__ __launch_bounds__(1024) void route_b1_kernel(const RouteArgs a) {
     const int u = u0 + i * kWave + lane;
     xr[i] = (u < u1) ? *reinterpret_cast<const raw*>(x + (size_t)u * N) : raw{};
   }
-  if (a.subst_key == 0)
+  if (a.subst_key == 0 && gridDim.x == 1)
     for (int i = tid; i < E * E; i += 1024) sim_sh[i] = a.sim[i];
   if (tid < kWave) sm.slot_of[tid] = a.slot_of[tid];
 
@@ -315,22 +332,60 @@ __global__ __launch_bounds__(1024) void route_b1_kernel(const RouteArgs a) {
     float v = 0.f;
     if (lane < E)
       for (int s2 = 0; s2 < nseg; ++s2) v += part[lane][s2];
-    sm.lg[0][lane] = v;
+    sm.lg[tok][lane] = v;
   }
-  select_and_publish(a, sm, sim_sh, lane);
+  if (gridDim.x == 1) {
+    select_and_publish(a, sm, sim_sh, lane);
+    return;
+  }
+  // batch > 1: leave this token's pass-1 state for the merge kernel
+  select_pass1(a, sm, lane, tok, tok + 1);
+  RouteTmp* o = a.tmp + tok;
+  o->sc[lane] = sm.sc[tok][lane];
+  o->rk[lane] = sm.rk[tok][lane];
+  if (lane < SMOE_MAX_TOPK) o->tk[lane] = lane < a.k ? sm.tk[tok][lane] : -1;
+  if (lane == 0) { o->thr_r = sm.thr_r[tok]; o->top_m = sm.top_m_sh[tok]; }
+}
+
+// Batch > 1, second launch: one wave gathers the per-token pass-1 state, forms
+// the batch top-score set and runs pass 2.
+__global__ __launch_bounds__(64) void route_merge_kernel(const RouteArgs a) {
+  __shared__ SelectSmem sm;
+  __shared__ float sim_sh[SMOE_MAX_EXPERTS * SMOE_MAX_EXPERTS];
+  const int lane = threadIdx.x;
+  const int E = a.E;
+  if (a.subst_key == 0)
+    for (int i = lane; i < E * E; i += kWave) sim_sh[i] = a.sim[i];
+  sm.slot_of[lane] = a.slot_of[lane];
+  unsigned long long c_mask = 0;
+  for (int t = 0; t < a.B; ++t) {
+    const RouteTmp* o = a.tmp + t;
+    sm.sc[t][lane] = o->sc[lane];
+    sm.rk[t][lane] = o->rk[lane];
+    if (lane < SMOE_MAX_TOPK) sm.tk[t][lane] = o->tk[lane];
+    if (lane == 0) { sm.thr_r[t] = o->thr_r; sm.top_m_sh[t] = o->top_m; }
+    c_mask |= o->top_m;
+  }
+  select_pass2(a, sm, sim_sh, c_mask, lane);
 }
 
 }  // namespace
 
 template <typename T>
 static void launch_route_t(const RouteArgs& a, hipStream_t s) {
-  if (a.B == 1 && a.fast_upi > 0) {
+  if (a.fast_upi > 0) {
+    // one block per token; with more than one token a second launch merges them
+    bool launched = true;
     switch (a.fast_upi) {
-      case 1: hipLaunchKernelGGL((route_b1_kernel<T, 1>), dim3(1), dim3(1024), 0, s, a); return;
-      case 2: hipLaunchKernelGGL((route_b1_kernel<T, 2>), dim3(1), dim3(1024), 0, s, a); return;
-      case 4: hipLaunchKernelGGL((route_b1_kernel<T, 4>), dim3(1), dim3(1024), 0, s, a); return;
-      case 8: hipLaunchKernelGGL((route_b1_kernel<T, 8>), dim3(1), dim3(1024), 0, s, a); return;
-      default: break;
+      case 1: hipLaunchKernelGGL((route_b1_kernel<T, 1>), dim3(a.B), dim3(1024), 0, s, a); break;
+      case 2: hipLaunchKernelGGL((route_b1_kernel<T, 2>), dim3(a.B), dim3(1024), 0, s, a); break;
+      case 4: hipLaunchKernelGGL((route_b1_kernel<T, 4>), dim3(a.B), dim3(1024), 0, s, a); break;
+      case 8: hipLaunchKernelGGL((route_b1_kernel<T, 8>), dim3(a.B), dim3(1024), 0, s, a); break;
+      default: launched = false; break;
+    }
+    if (launched) {
+      if (a.B > 1) hipLaunchKernelGGL(route_merge_kernel, dim3(1), dim3(64), 0, s, a);
+      return;
     }
   }
   // as many tokens' hidden states in LDS together as fit in 32 KB

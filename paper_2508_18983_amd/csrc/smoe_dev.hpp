@@ -40,12 +40,23 @@ struct StepRec {
   int32_t seq;                     // host mirror only: call number, written last
 };
 
+// Per-token state between the two router launches of a batched step.
+struct RouteTmp {
+  float sc[kWave];
+  int32_t rk[kWave];
+  int32_t tk[SMOE_MAX_TOPK];
+  float thr_r;
+  int32_t pad_;
+  unsigned long long top_m;
+};
+
 struct RouteArgs {
   const void* gate_w;   // [E][H] of this layer
   const void* x;        // [B][H]
   const float* sim;     // [E][E] of this layer (device)
   StepRec* rec_dev;
   StepRec* rec_host;    // device-visible address of the pinned mirror
+  RouteTmp* tmp;        // [B] scratch of the batched router
   int32_t B, H, E, k;
   int32_t renorm, subst_key;
   int32_t nseg;         // segments each gate row is split into (power of two, <= 8)

@@ -64,6 +64,7 @@ struct moe_handle {
   StepRec* rec_host_dev = nullptr;       // its device-visible address
   float* act = nullptr;
   float* ysum = nullptr;
+  RouteTmp* route_tmp = nullptr;
   // launch geometry
   int TF = 0, tilesR = 0, tilesS = 0, R = 0, htiles = 0, stage_all = 0, chunk = 0, down_lds = 0;
   int up_upl = 0, down_upl = 0, RB = 0, nsegR = 1, nsegS = 1;
@@ -185,6 +186,7 @@ void free_all(moe_handle* h) {
   if (h->rec_host) (void)hipHostFree(h->rec_host);
   if (h->act) (void)hipFree(h->act);
   if (h->ysum) (void)hipFree(h->ysum);
+  if (h->route_tmp) (void)hipFree(h->route_tmp);
   delete h;
 }
 
@@ -284,6 +286,7 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
     }
     HIP_TRY(hipMalloc(&h->act, (size_t)h->act_floats * sizeof(float)));
     HIP_TRY(hipMalloc(&h->ysum, (size_t)c.max_batch * c.hidden * sizeof(float)));
+    HIP_TRY(hipMalloc(&h->route_tmp, (size_t)SMOE_MAX_BATCH * sizeof(RouteTmp)));
     return upload_initial(h);
   }();
   if (rc != SMOE_OK) { free_all(h); return rc; }
@@ -306,13 +309,14 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   ra.sim = h->sim_dev + (size_t)layer * E * E;
   ra.rec_dev = h->rec_dev;
   ra.rec_host = h->rec_host_dev;
+  ra.tmp = h->route_tmp;
   ra.B = B; ra.H = c.hidden; ra.E = E; ra.k = k;
   ra.renorm = c.renorm_topk; ra.subst_key = c.subst_key; ra.alpha = c.alpha;
   ra.seq = ++h->seq;
   ra.nseg = 1;
   ra.fast_upi = 0;
   const int gate_units = c.hidden / (c.dtype == SMOE_DTYPE_FP32 ? 4 : 8);
-  if (B == 1 && h->route_fast) {
+  if (h->route_fast) {
     // one row segment per wave and pass: 16 waves x 4 rows; keep a segment <= 8 units per lane
     while (ra.nseg < 8 && (E * ra.nseg * 2 <= 16 || gate_units / ra.nseg > 8 * kWave)) ra.nseg *= 2;
     const int per_lane = ((gate_units + ra.nseg - 1) / ra.nseg + kWave - 1) / kWave;
