@@ -121,13 +121,13 @@ __device__ __forceinline__ unsigned long long select_pass1(const RouteArgs& a, S
 // Pass 2: substitution against residency and the batch top-score set C, the
 // decision record, the expert groups, and the publication to the host mirror.
 __device__ __forceinline__ void select_pass2(const RouteArgs& a, SelectSmem& sm, const float* sim,
-                                             unsigned long long c_mask, int lane) {
-  const int E = a.E, k = a.k, B = a.B;
+                                             unsigned long long c_mask, int lane, int t_begin, int t_end) {
+  const int E = a.E, k = a.k;
   auto& sc = sm.sc; auto& rk = sm.rk; auto& tk = sm.tk;
   auto& thr_r = sm.thr_r; auto& top_m_sh = sm.top_m_sh; auto& slot_of = sm.slot_of;
   const bool has_pivot = E > k;
   const unsigned long long avail = a.resident | c_mask;
-  for (int t = 0; t < B; ++t) {
+  for (int t = t_begin; t < t_end; ++t) {
     const float s = sc[t][lane];
     const int myrank = rk[t][lane];
     const bool active = myrank < k;
@@ -167,6 +167,13 @@ __device__ __forceinline__ void select_pass2(const RouteArgs& a, SelectSmem& sm,
     }
     a.rec_host->tok[t].scores[lane] = lane < E ? s : 0.f;
   }
+}
+
+// Last step, one wave, after every token's pass 2: the expert groups of a
+// batched step, then the publication of the call number to the host mirror.
+__device__ __forceinline__ void publish(const RouteArgs& a, SelectSmem& sm, int lane) {
+  const int k = a.k, B = a.B;
+  auto& slot_of = sm.slot_of;
   if (B > 1) {
     // expert groups for the batched FFN: lane e collects the tokens that compute expert e
     GroupTask g;
@@ -197,7 +204,8 @@ __device__ __forceinline__ void select_pass2(const RouteArgs& a, SelectSmem& sm,
 __device__ __forceinline__ void select_and_publish(const RouteArgs& a, SelectSmem& sm, const float* sim,
                                                    int lane) {
   const unsigned long long c_mask = select_pass1(a, sm, lane, 0, a.B);
-  select_pass2(a, sm, sim, c_mask, lane);
+  select_pass2(a, sm, sim, c_mask, lane, 0, a.B);
+  publish(a, sm, lane);
 }
 
 constexpr int kMaxSeg = 8;   // a gate row is split into at most this many segments
@@ -347,26 +355,31 @@ __global__ __launch_bounds__(1024) void route_b1_kernel(const RouteArgs a) {
   if (lane == 0) { o->thr_r = sm.thr_r[tok]; o->top_m = sm.top_m_sh[tok]; }
 }
 
-// Batch > 1, second launch: one wave gathers the per-token pass-1 state, forms
-// the batch top-score set and runs pass 2.
-__global__ __launch_bounds__(64) void route_merge_kernel(const RouteArgs a) {
+// Batch > 1, second launch: wave t runs pass 2 for token t against the batch
+// top-score set; wave 0 then builds the expert groups and publishes.
+__global__ __launch_bounds__(64 * SMOE_MAX_BATCH) void route_merge_kernel(const RouteArgs a) {
   __shared__ SelectSmem sm;
   __shared__ float sim_sh[SMOE_MAX_EXPERTS * SMOE_MAX_EXPERTS];
-  const int lane = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
   const int E = a.E;
   if (a.subst_key == 0)
-    for (int i = lane; i < E * E; i += kWave) sim_sh[i] = a.sim[i];
-  sm.slot_of[lane] = a.slot_of[lane];
+    for (int i = tid; i < E * E; i += blockDim.x) sim_sh[i] = a.sim[i];
+  if (tid < kWave) sm.slot_of[tid] = a.slot_of[tid];
   unsigned long long c_mask = 0;
-  for (int t = 0; t < a.B; ++t) {
-    const RouteTmp* o = a.tmp + t;
-    sm.sc[t][lane] = o->sc[lane];
-    sm.rk[t][lane] = o->rk[lane];
-    if (lane < SMOE_MAX_TOPK) sm.tk[t][lane] = o->tk[lane];
-    if (lane == 0) { sm.thr_r[t] = o->thr_r; sm.top_m_sh[t] = o->top_m; }
-    c_mask |= o->top_m;
+  for (int t = 0; t < a.B; ++t) c_mask |= a.tmp[t].top_m;
+  if (wave < a.B) {
+    const RouteTmp* o = a.tmp + wave;
+    sm.sc[wave][lane] = o->sc[lane];
+    sm.rk[wave][lane] = o->rk[lane];
+    if (lane < SMOE_MAX_TOPK) sm.tk[wave][lane] = o->tk[lane];
+    if (lane == 0) { sm.thr_r[wave] = o->thr_r; sm.top_m_sh[wave] = o->top_m; }
   }
-  select_pass2(a, sm, sim_sh, c_mask, lane);
+  __syncthreads();
+  if (wave < a.B) select_pass2(a, sm, sim_sh, c_mask, lane, wave, wave + 1);
+  __syncthreads();
+  __threadfence_system();                       // each wave's stores to the mirror are out
+  __syncthreads();
+  if (wave == 0) publish(a, sm, lane);
 }
 
 }  // namespace
@@ -384,7 +397,7 @@ static void launch_route_t(const RouteArgs& a, hipStream_t s) {
       default: launched = false; break;
     }
     if (launched) {
-      if (a.B > 1) hipLaunchKernelGGL(route_merge_kernel, dim3(1), dim3(64), 0, s, a);
+      if (a.B > 1) hipLaunchKernelGGL(route_merge_kernel, dim3(1), dim3(64 * a.B), 0, s, a);
       return;
     }
   }
