@@ -56,6 +56,17 @@ extern "C" {
 #define SMOE_DTYPE_FP32 0
 #define SMOE_DTYPE_BF16 1
 
+/* Replacement policies.  SCORE is the paper's (Eq. 3: lowest mean gate score over
+ * the last n+1 steps); the others are the recency / frequency baselines its
+ * ablation compares against (Section VI-C, "+CE" step).  Every policy skips the
+ * experts the current step computes (protection shield) and breaks ties towards
+ * the lower expert id.  A "use" is one (token, slot) of a step computing the
+ * expert; uses and loads are stamped step * 64 + token * k + slot. */
+#define SMOE_EVICT_SCORE 0
+#define SMOE_EVICT_LRU   1   /* least recently used                                  */
+#define SMOE_EVICT_FIFO  2   /* earliest loaded (initial residents: in slot order)   */
+#define SMOE_EVICT_LFU   3   /* fewest uses since it was loaded, then least recent   */
+
 typedef struct moe_handle moe_handle_t;   /* opaque, library-owned */
 
 typedef struct {
@@ -77,6 +88,7 @@ typedef struct {
   int32_t evict_window;  /* n of Eq. 3: the mean runs over the last n+1 steps        */
   int32_t n_stage;       /* transient slots after the L*cap cache slots, used when a
                             missing expert finds no evictable resident (batch > 1)   */
+  int32_t evict_policy;  /* SMOE_EVICT_*: which unshielded resident a load replaces   */
 } moe_cfg_t;
 
 typedef struct {

@@ -196,6 +196,29 @@ def pick_victim(mean_scores: np.ndarray, evictable: Sequence[int]):
     return victim, float(gap)
 
 
+# Baseline replacement policies of the paper's ablation (Section VI-C compares the
+# score-based eviction with recency / frequency caches).  A "use" is one (token,
+# slot) computing the expert; uses and loads carry the stamp
+# step * 64 + token * k + slot; every policy ignores shielded experts and breaks
+# ties towards the lower expert id (*convention*).
+EVICT_SCORE, EVICT_LRU, EVICT_FIFO, EVICT_LFU = 0, 1, 2, 3
+
+
+def pick_victim_baseline(policy: int, evictable: Sequence[int], last_use: Dict[int, int],
+                         load_stamp: Dict[int, int], use_count: Dict[int, int]) -> int:
+    """LRU: least recent use; FIFO: earliest load; LFU: fewest uses since its
+    load, then least recent use."""
+    if policy == EVICT_LRU:
+        key = lambda e: (last_use[e], e)
+    elif policy == EVICT_FIFO:
+        key = lambda e: (load_stamp[e], e)
+    elif policy == EVICT_LFU:
+        key = lambda e: (use_count[e], last_use[e], e)
+    else:
+        raise ValueError("not a baseline policy")
+    return min(evictable, key=key)
+
+
 # --------------------------------------------------------------------------
 # expert FFN
 # --------------------------------------------------------------------------
@@ -220,6 +243,10 @@ class LayerCache:
     window: int
     slot_expert: List[int]                       # slot -> expert id
     history: deque = field(default_factory=deque)
+    step: int = 0
+    last_use: Dict[int, int] = field(default_factory=dict)
+    load_stamp: Dict[int, int] = field(default_factory=dict)
+    use_count: Dict[int, int] = field(default_factory=dict)
 
     @property
     def resident(self) -> Set[int]:
@@ -269,7 +296,7 @@ class SMoEOracle:
                  sim: np.ndarray, shared: Optional[np.ndarray] = None, n_shared: int = 0,
                  shared_ffn: int = 0, subst_key: int = 0, renorm_topk: int = 1,
                  evict_window: int = 3, init_resident: Optional[np.ndarray] = None,
-                 elem_bytes: int = 2, widen_cache_bytes: int = 6 << 30):
+                 elem_bytes: int = 2, widen_cache_bytes: int = 6 << 30, evict_policy: int = EVICT_SCORE):
         if not (top_k <= cache_cap <= n_experts):
             raise ValueError("need top_k <= cache_cap <= n_experts")
         self.L, self.H, self.E, self.F, self.k = n_layers, hidden, n_experts, ffn, top_k
@@ -277,6 +304,7 @@ class SMoEOracle:
         self.gate_w, self.experts, self.sim, self.shared = gate_w, experts, sim, shared
         self.n_shared, self.Fs = n_shared, shared_ffn
         self.subst_key, self.renorm, self.window = subst_key, renorm_topk, evict_window
+        self.evict_policy = evict_policy
         self.expert_bytes = 3 * hidden * ffn * elem_bytes
         self._init_resident = init_resident
         self._wcache: Dict = {}          # fp64 copies of recently used experts (memo only)
@@ -294,7 +322,11 @@ class SMoEOracle:
                 ids = list(range(self.cap))
             else:
                 ids = [int(v) for v in self._init_resident[l]]
-            self.layers.append(LayerCache(self.cap, self.window, ids))
+            lc = LayerCache(self.cap, self.window, ids)
+            for slot, e in enumerate(ids):          # resident before step 0, loaded in slot order
+                lc.last_use[e] = lc.load_stamp[e] = slot - self.cap
+                lc.use_count[e] = 0
+            self.layers.append(lc)
         self.stats_per_layer = [Stats() for _ in range(self.L)]
 
     def stats(self, layer: int = -1) -> Stats:
@@ -378,17 +410,27 @@ class SMoEOracle:
 
         shield = set(int(e) for e in final.reshape(-1))
         fetched: List[int] = []
-        for e in final.reshape(-1):
+        for pos, e in enumerate(final.reshape(-1)):          # (token, slot) order
             e = int(e)
+            stamp = cache.step * 64 + pos
             if e not in G_before and e not in fetched:
                 fetched.append(e)
+                cache.load_stamp[e] = stamp
+                cache.use_count[e] = 0
+            cache.last_use[e] = stamp
+            cache.use_count[e] = cache.use_count.get(e, 0) + 1
+        cache.step += 1
         victims: List[int] = []
         evict_margin = np.inf
         for m in fetched:
             evictable = [e for e in cache.slot_expert if e not in shield]
             if evictable:
-                v, gap = pick_victim(means, evictable)
-                evict_margin = min(evict_margin, gap)
+                if self.evict_policy == EVICT_SCORE:
+                    v, gap = pick_victim(means, evictable)
+                    evict_margin = min(evict_margin, gap)
+                else:
+                    v = pick_victim_baseline(self.evict_policy, evictable, cache.last_use,
+                                             cache.load_stamp, cache.use_count)
                 cache.slot_expert[cache.slot_expert.index(v)] = m
                 victims.append(v)
                 st.evictions += 1
@@ -437,6 +479,6 @@ def oracle_from_workload(wl, **override) -> SMoEOracle:
               gate_w=view(wl.gate_w), experts=[view(b) for b in wl.experts], sim=view(wl.sim),
               shared=view(wl.shared), n_shared=s.n_shared, shared_ffn=s.shared_ffn,
               subst_key=s.subst_key, renorm_topk=s.renorm_topk, evict_window=s.evict_window,
-              elem_bytes=s.elem_bytes)
+              elem_bytes=s.elem_bytes, evict_policy=getattr(s, "evict_policy", 0))
     kw.update(override)
     return SMoEOracle(**kw)

@@ -29,7 +29,7 @@ class MoeCfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "hidden", "n_experts", "ffn", "top_k", "cache_cap", "n_shared",
         "shared_ffn", "dtype", "max_batch")] + [("alpha", C.c_float)] + [(n, C.c_int32) for n in (
-        "subst_key", "renorm_topk", "evict_window", "n_stage")]
+        "subst_key", "renorm_topk", "evict_window", "n_stage", "evict_policy")]
 
 
 class MoeBuffers(C.Structure):

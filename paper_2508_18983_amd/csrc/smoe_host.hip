@@ -35,6 +35,10 @@ struct LayerState {
   std::vector<int32_t> expert_of_slot;   // [cap]
   std::vector<double> hist;              // ring [(n+1)][E] of batch-mean score vectors
   int hist_count = 0, hist_head = 0;
+  int64_t step = 0;                      // calls of this layer so far
+  int64_t last_use[SMOE_MAX_EXPERTS];    // stamp of the latest use (recency policies)
+  int64_t load_stamp[SMOE_MAX_EXPERTS];  // stamp of the load that brought the expert in
+  int64_t use_count[SMOE_MAX_EXPERTS];   // uses since that load
   moe_stats_t st{};
 };
 
@@ -160,12 +164,15 @@ int upload_initial(moe_handle* h) {
     ls.hist.assign((size_t)(c.evict_window + 1) * c.n_experts, 0.0);
     ls.hist_count = 0;
     ls.hist_head = 0;
+    ls.step = 0;
+    for (int e = 0; e < SMOE_MAX_EXPERTS; ++e) { ls.last_use[e] = 0; ls.load_stamp[e] = 0; ls.use_count[e] = 0; }
     ls.st = moe_stats_t{};
     for (int s = 0; s < c.cache_cap; ++s) {
       const int e = h->init_resident[(size_t)l * c.cache_cap + s];
       ls.resident |= 1ull << e;
       ls.slot_of[e] = (int8_t)s;
       ls.expert_of_slot[s] = e;
+      ls.last_use[e] = ls.load_stamp[e] = (int64_t)s - c.cache_cap;   // before step 0, in slot order
       const char* src = h->experts_host[l] + (int64_t)e * h->expert_bytes;
       char* dst = static_cast<char*>(h->buf.cache_slab_dev) +
                   ((int64_t)l * c.cache_cap + s) * h->expert_bytes;
@@ -225,6 +232,7 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
   if (!(c.alpha >= 0.0f) || c.alpha >= 1.0f) return SMOE_EINVAL;
   if (c.subst_key != 0 && c.subst_key != 1) return SMOE_EINVAL;
   if (c.evict_window < 0 || c.evict_window > 1024 || c.n_stage < 0) return SMOE_EINVAL;
+  if (c.evict_policy < SMOE_EVICT_SCORE || c.evict_policy > SMOE_EVICT_LFU) return SMOE_EINVAL;
   if (!buf->gate_w_dev || !buf->experts_host || !buf->sim_host || !buf->cache_slab_dev) return SMOE_EINVAL;
   if (c.n_shared > 0 && !buf->shared_dev) return SMOE_EINVAL;
   if (buf->stream_compute == buf->stream_copy) return SMOE_EINVAL;
@@ -412,11 +420,24 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
       shield |= 1ull << e;
       raw_hits += (before >> rec.tok[t].topk[j]) & 1ull;
       subs += rec.tok[t].subst[j] != 0;
-      if ((before >> e) & 1ull) { ++hits; continue; }
+      const int64_t stamp = ls.step * 64 + (int64_t)t * k + j;
+      if ((before >> e) & 1ull) {
+        ++hits;
+        ls.last_use[e] = stamp;
+        ++ls.use_count[e];
+        continue;
+      }
       bool dup = false;
       for (int i = 0; i < n_fetch; ++i) dup |= fetched[i] == e;
-      if (!dup) fetched[n_fetch++] = e;
+      if (!dup) {
+        fetched[n_fetch++] = e;
+        ls.load_stamp[e] = stamp;
+        ls.use_count[e] = 0;
+      }
+      ls.last_use[e] = stamp;
+      ++ls.use_count[e];
     }
+  ++ls.step;
 
   int n_staged = 0, n_evict = 0;
   if (n_fetch > 0) {
@@ -430,7 +451,18 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
       int victim = -1;
       for (int e = 0; e < E; ++e) {
         if (!((ls.resident >> e) & 1ull) || ((shield >> e) & 1ull)) continue;
-        if (victim < 0 || mean[e] < mean[victim]) victim = e;
+        if (victim < 0) { victim = e; continue; }
+        bool better;
+        switch (c.evict_policy) {
+          case SMOE_EVICT_LRU:  better = ls.last_use[e] < ls.last_use[victim]; break;
+          case SMOE_EVICT_FIFO: better = ls.load_stamp[e] < ls.load_stamp[victim]; break;
+          case SMOE_EVICT_LFU:
+            better = ls.use_count[e] < ls.use_count[victim] ||
+                     (ls.use_count[e] == ls.use_count[victim] && ls.last_use[e] < ls.last_use[victim]);
+            break;
+          default:              better = mean[e] < mean[victim]; break;   // Eq. 3
+        }
+        if (better) victim = e;
       }
       victims[i] = victim;
       const int m = fetched[i];

@@ -77,7 +77,8 @@ class DecodeSession:
                    n_shared=shape.n_shared, shared_ffn=shape.shared_ffn,
                    dtype=0 if shape.dtype == "fp32" else 1, max_batch=max_batch,
                    alpha=float(shape.alpha), subst_key=shape.subst_key,
-                   renorm_topk=shape.renorm_topk, evict_window=shape.evict_window, n_stage=n_stage)
+                   renorm_topk=shape.renorm_topk, evict_window=shape.evict_window, n_stage=n_stage,
+                   evict_policy=getattr(shape, "evict_policy", 0))
         cfg.update(cfg_override)
         self.cfg = B.MoeCfg(**cfg)
         self.expert_bytes = 3 * cfg["hidden"] * cfg["ffn"] * esize

@@ -29,6 +29,7 @@ class MoEShape:
     renorm_topk: int = 1
     subst_key: int = 0   # 0: similarity table ranks candidates, 1: gate score
     evict_window: int = 3  # n of Eq. 3
+    evict_policy: int = 0  # 0 score (Eq. 3), 1 LRU, 2 FIFO, 3 LFU
     prior: str = "normal"  # "normal": x ~ N(0,1); "zipf": logits from a Zipf prior
     zipf_s: float = 0.0
     locality_p: float = 0.0      # P(boost previous token's top-k) per token-layer

@@ -192,3 +192,15 @@ def test_c3_full_size_in_the_benchmark_launch_configuration():
         gc.collect()
         torch.cuda.empty_cache()
         pinned_free_all()
+
+
+@pytest.mark.parametrize("policy", [1, 2, 3])
+def test_baseline_replacement_policies(policy):
+    """LRU / FIFO / LFU victims (the caches the paper's ablation compares its
+    score-based eviction against) match the oracle call by call."""
+    shp = SHAPES["c4"].with_(ffn=256, shared_ffn=128, evict_policy=policy, seed=30 + policy)
+    wl = make_workload(shp, n_layers=2, tokens=60)
+    r = run_parity(wl, y_every=7, label=f"policy{policy}")
+    assert r["stats"]["evictions"] > 20
+    wl = make_workload(shp.with_(cache_cap=10), n_layers=1, tokens=12, batch=4)
+    run_parity(wl, y_every=3, batch=4, session_kw=dict(n_stage=24), label=f"policy{policy}-b4")

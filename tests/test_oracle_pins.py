@@ -391,3 +391,96 @@ def test_shared_experts_and_bf16_path_against_dense_library_moe():
             res = orc.decode_layer(l, as_numpy(wl.x[t, l]))
             want = _dense_plain_moe(wl, l, wl.x[t, l, 0], shp.renorm_topk)
             np.testing.assert_allclose(res.y[0], want, rtol=1e-11, atol=1e-15)
+
+
+# ---------------------------------------------------------------- baseline replacement policies
+def _route_trace(wl):
+    """Experts the plain router activates per (token, layer): library top-k."""
+    s = wl.shape
+    logits = torch.einsum("leh,tlbh->tlbe", wl.gate_w.double(), wl.x.double())
+    return torch.topk(logits, s.top_k, dim=-1).indices[:, :, 0].tolist()      # [T][L][k]
+
+
+def test_lru_and_fifo_match_textbook_caches_when_nothing_is_substituted():
+    """alpha = 0, batch 1: the expert cache is an ordinary cache over the router's
+    access sequence (with the current step's experts pinned), so LRU must equal an
+    OrderedDict LRU and FIFO a queue."""
+    from collections import OrderedDict, deque
+    wl = make_workload(SHAPES["c1"].with_(tokens=64, seed=8, alpha=0.0))
+    s = wl.shape
+    trace = _route_trace(wl)
+    for policy in (O.EVICT_LRU, O.EVICT_FIFO):
+        orc = O.oracle_from_workload(wl, evict_policy=policy)
+        caches = []
+        for l in range(s.n_layers):
+            caches.append(OrderedDict((e, None) for e in range(s.cache_cap)) if policy == O.EVICT_LRU
+                          else deque(range(s.cache_cap)))
+        misses = 0
+        for t in range(s.tokens):
+            for l in range(s.n_layers):
+                res = orc.decode_layer(l, as_numpy(wl.x[t, l]), compute_y=False)
+                want_victims = []
+                c = caches[l]
+                cur = trace[t][l]
+                # the step's experts are pinned (protection shield): evict from the old end,
+                # skipping them; afterwards they become the most recent, in slot order
+                for e in cur:
+                    if e not in c:
+                        v = next(x for x in c if x not in cur)
+                        want_victims.append(v)
+                        if policy == O.EVICT_LRU:
+                            del c[v]
+                            c[e] = None
+                        else:
+                            c.remove(v)
+                            c.append(e)
+                if policy == O.EVICT_LRU:
+                    for e in cur:
+                        c.move_to_end(e)
+                assert res.victims == want_victims, (policy, t, l)
+                assert set(orc.layers[l].slot_expert) == set(c)
+                misses += len(want_victims)
+        assert misses > 20 and orc.stats().misses == misses
+
+
+def test_lfu_evicts_fewest_uses_bruteforce():
+    wl = make_workload(SHAPES["c1"].with_(tokens=64, seed=8, alpha=0.0))
+    s = wl.shape
+    trace = _route_trace(wl)
+    orc = O.oracle_from_workload(wl, evict_policy=O.EVICT_LFU)
+    for l in range(s.n_layers):
+        cached = {e: dict(cnt=0, last=e - s.cache_cap) for e in range(s.cache_cap)}
+        n = 0
+        for t in range(s.tokens):
+            res = orc.decode_layer(l, as_numpy(wl.x[t, l]), compute_y=False)
+            cur = set(trace[t][l])
+            want = []
+            for j, e in enumerate(trace[t][l]):
+                stamp = t * 64 + j
+                if e not in cached:
+                    cand = [c for c in cached if c not in cur]
+                    v = min(cand, key=lambda c: (cached[c]["cnt"], cached[c]["last"], c))
+                    want.append(v)
+                    del cached[v]
+                    cached[e] = dict(cnt=0, last=stamp)
+                cached[e]["cnt"] += 1
+                cached[e]["last"] = stamp
+            assert res.victims == want, (t, l)
+            n += len(want)
+        assert n > 5
+
+
+def test_score_eviction_beats_lru_on_skewed_popularity():
+    """Shape of the ablation's "+CE" step: with a Zipf-skewed router the score
+    history keeps popular experts better than recency does."""
+    shp = SHAPES["c4"].with_(ffn=32, shared_ffn=32, alpha=0.0, seed=12)
+    wl = make_workload(shp, n_layers=4, tokens=160)
+    rates = {}
+    for policy in (O.EVICT_LRU, O.EVICT_SCORE):
+        orc = O.oracle_from_workload(wl, evict_policy=policy)
+        for t in range(160):
+            for l in range(4):
+                orc.decode_layer(l, as_numpy(wl.x[t, l]), compute_y=False)
+        st = orc.stats()
+        rates[policy] = st.hits / st.slots
+    assert rates[O.EVICT_SCORE] > rates[O.EVICT_LRU]
