@@ -1,0 +1,170 @@
+// Expert-cache bookkeeping of one layer: residency, score history, protection
+// shield, victim selection, counters (Section IV-B "Cache eviction", Eq. 3;
+// Section V-B dependency 1).  Plain C++ with no HIP dependency, so the same
+// code runs inside libsmoe and inside the CPU test shim.
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "smoe.h"
+
+namespace smoe {
+
+struct CacheParams {
+  int n_experts, top_k, cache_cap, evict_window, evict_policy, n_stage;
+};
+
+// What the router decided for one step (B tokens), as read from the mirror.
+struct StepDecision {
+  int B;
+  const int32_t* topk[SMOE_MAX_BATCH];     // [k] experts by descending score
+  const int32_t* final_[SMOE_MAX_BATCH];   // [k] expert per slot after substitution
+  const int32_t* subst[SMOE_MAX_BATCH];    // [k] 1 where replaced
+  const float* scores[SMOE_MAX_BATCH];     // [E]
+};
+
+// What the scheduler has to do for that step.
+struct StepPlan {
+  uint64_t before = 0;     // residency when the step started
+  uint64_t shield = 0;     // every expert the step computes
+  int n_fetch = 0, n_evict = 0, n_staged = 0;
+  int fetched[SMOE_MAX_BATCH * SMOE_MAX_TOPK];   // distinct missing experts, (token, slot) order
+  int victims[SMOE_MAX_BATCH * SMOE_MAX_TOPK];   // expert evicted for each, -1 = staged
+  int slot[SMOE_MAX_BATCH * SMOE_MAX_TOPK];      // layer-local cache slot, or -(1 + staging index)
+  int64_t raw_hits = 0, hits = 0, subs = 0;
+};
+
+struct CacheLayer {
+  uint64_t resident = 0;
+  int8_t slot_of[SMOE_MAX_EXPERTS];
+  std::vector<int32_t> expert_of_slot;   // [cap]
+  std::vector<double> hist;              // ring [(n+1)][E] of batch-mean score vectors
+  int hist_count = 0, hist_head = 0;
+  int64_t step = 0;                      // steps of this layer so far
+  int64_t last_use[SMOE_MAX_EXPERTS];    // stamp of the latest use (recency policies)
+  int64_t load_stamp[SMOE_MAX_EXPERTS];  // stamp of the load that brought the expert in
+  int64_t use_count[SMOE_MAX_EXPERTS];   // uses since that load
+  moe_stats_t st{};
+
+  // Initial residency: expert ids per slot (distinct, validated by the caller).
+  void reset(const CacheParams& p, const int32_t* init_ids) {
+    resident = 0;
+    for (int e = 0; e < SMOE_MAX_EXPERTS; ++e) {
+      slot_of[e] = -1;
+      last_use[e] = load_stamp[e] = use_count[e] = 0;
+    }
+    expert_of_slot.assign(p.cache_cap, -1);
+    hist.assign((size_t)(p.evict_window + 1) * p.n_experts, 0.0);
+    hist_count = hist_head = 0;
+    step = 0;
+    st = moe_stats_t{};
+    for (int s = 0; s < p.cache_cap; ++s) {
+      const int e = init_ids[s];
+      resident |= 1ull << e;
+      slot_of[e] = (int8_t)s;
+      expert_of_slot[s] = e;
+      last_use[e] = load_stamp[e] = (int64_t)s - p.cache_cap;   // before step 0, in slot order
+    }
+  }
+
+  // One step: push the scores into the history (before victims are chosen),
+  // shield what the step computes, pick a victim for every distinct missing
+  // expert, update residency and counters.  Returns SMOE_OK, SMOE_ESTATE when
+  // the decision is malformed or the step needs more staging slots than exist
+  // (the state is then not usable until the next reset).
+  int plan_step(const CacheParams& p, const StepDecision& d, int64_t expert_bytes, StepPlan& out) {
+    const int E = p.n_experts, k = p.top_k, B = d.B;
+    {
+      double* row = &hist[(size_t)hist_head * E];
+      for (int e = 0; e < E; ++e) {
+        double s = 0.0;
+        for (int t = 0; t < B; ++t) s += (double)d.scores[t][e];
+        row[e] = s / B;
+      }
+      hist_head = (hist_head + 1) % (p.evict_window + 1);
+      if (hist_count < p.evict_window + 1) ++hist_count;
+    }
+    out = StepPlan{};
+    out.before = resident;
+    for (int t = 0; t < B; ++t)
+      for (int j = 0; j < k; ++j) {
+        const int e = d.final_[t][j];
+        const int e0 = d.topk[t][j];
+        if (e < 0 || e >= E || e0 < 0 || e0 >= E) return SMOE_ESTATE;
+        out.shield |= 1ull << e;
+        out.raw_hits += (out.before >> e0) & 1ull;
+        out.subs += d.subst[t][j] != 0;
+        const int64_t stamp = step * 64 + (int64_t)t * k + j;
+        if ((out.before >> e) & 1ull) {
+          ++out.hits;
+        } else {
+          bool dup = false;
+          for (int i = 0; i < out.n_fetch; ++i) dup |= out.fetched[i] == e;
+          if (!dup) {
+            out.fetched[out.n_fetch++] = e;
+            load_stamp[e] = stamp;
+            use_count[e] = 0;
+          }
+        }
+        last_use[e] = stamp;
+        ++use_count[e];
+      }
+    ++step;
+
+    if (out.n_fetch > 0) {
+      double mean[SMOE_MAX_EXPERTS];
+      for (int e = 0; e < E; ++e) {
+        double s = 0.0;
+        for (int i = 0; i < hist_count; ++i) s += hist[(size_t)i * E + e];
+        mean[e] = s / hist_count;
+      }
+      for (int i = 0; i < out.n_fetch; ++i) {
+        int victim = -1;
+        for (int e = 0; e < E; ++e) {
+          if (!((resident >> e) & 1ull) || ((out.shield >> e) & 1ull)) continue;
+          if (victim < 0) { victim = e; continue; }
+          bool better;
+          switch (p.evict_policy) {
+            case SMOE_EVICT_LRU:  better = last_use[e] < last_use[victim]; break;
+            case SMOE_EVICT_FIFO: better = load_stamp[e] < load_stamp[victim]; break;
+            case SMOE_EVICT_LFU:
+              better = use_count[e] < use_count[victim] ||
+                       (use_count[e] == use_count[victim] && last_use[e] < last_use[victim]);
+              break;
+            default:              better = mean[e] < mean[victim]; break;   // Eq. 3
+          }
+          if (better) victim = e;
+        }
+        out.victims[i] = victim;
+        const int m = out.fetched[i];
+        if (victim >= 0) {
+          const int s = slot_of[victim];
+          resident = (resident & ~(1ull << victim)) | (1ull << m);
+          slot_of[victim] = -1;
+          slot_of[m] = (int8_t)s;
+          expert_of_slot[s] = m;
+          out.slot[i] = s;
+          ++out.n_evict;
+        } else {
+          if (out.n_staged >= p.n_stage) return SMOE_ESTATE;   // out of transient slots
+          out.slot[i] = -(1 + out.n_staged++);
+        }
+      }
+    }
+    st.tokens += B;
+    st.slots += (int64_t)B * k;
+    st.raw_hits += out.raw_hits;
+    st.hits += out.hits;
+    st.misses += (int64_t)B * k - out.hits;
+    st.substitutions += out.subs;
+    st.evictions += out.n_evict;
+    st.staged += out.n_staged;
+    st.fetches += out.n_fetch;
+    st.bytes_fetched += (int64_t)out.n_fetch * expert_bytes;
+    return SMOE_OK;
+  }
+};
+
+}  // namespace smoe

@@ -1,0 +1,77 @@
+// CPU-only test shim around the expert-cache bookkeeping (cache_state.hpp):
+// lets the scheduler's decisions be replayed and checked without a GPU.  Built
+// with g++ into libsmoe_hostlogic.so; not used by libsmoe itself.
+#include <stddef.h>
+
+#include <new>
+#include <vector>
+
+#include "cache_state.hpp"
+
+using namespace smoe;
+
+struct hl_handle {
+  CacheParams p;
+  int n_layers;
+  int64_t expert_bytes;
+  std::vector<CacheLayer> layers;
+};
+
+extern "C" {
+
+// init_resident: [n_layers][cache_cap] or null for 0..cap-1.  Returns null on bad arguments.
+hl_handle* smoe_hl_create(int n_layers, int n_experts, int top_k, int cache_cap, int evict_window,
+                          int evict_policy, int n_stage, int64_t expert_bytes, const int32_t* init_resident) {
+  if (n_layers < 1 || n_experts < 1 || n_experts > SMOE_MAX_EXPERTS || top_k < 1 || top_k > SMOE_MAX_TOPK ||
+      cache_cap < top_k || cache_cap > n_experts || evict_window < 0 || n_stage < 0 ||
+      evict_policy < SMOE_EVICT_SCORE || evict_policy > SMOE_EVICT_LFU)
+    return nullptr;
+  hl_handle* h = new (std::nothrow) hl_handle();
+  if (!h) return nullptr;
+  h->p = CacheParams{n_experts, top_k, cache_cap, evict_window, evict_policy, n_stage};
+  h->n_layers = n_layers;
+  h->expert_bytes = expert_bytes;
+  h->layers.resize(n_layers);
+  std::vector<int32_t> ids(cache_cap);
+  for (int l = 0; l < n_layers; ++l) {
+    for (int s = 0; s < cache_cap; ++s) ids[s] = init_resident ? init_resident[(size_t)l * cache_cap + s] : s;
+    h->layers[l].reset(h->p, ids.data());
+  }
+  return h;
+}
+
+void smoe_hl_destroy(hl_handle* h) { delete h; }
+
+// topk / final_ / subst: [B][k] int32; scores: [B][E] fp32.  Outputs (each sized B*k):
+// fetched experts, victims (-1 = staged), slots (>= 0 cache slot, < 0 staging).  Returns the
+// number of loads, or a negative SMOE_E* code.
+int smoe_hl_step(hl_handle* h, int layer, int B, const int32_t* topk, const int32_t* final_,
+                 const int32_t* subst, const float* scores, int32_t* fetched, int32_t* victims,
+                 int32_t* slots) {
+  if (!h || layer < 0 || layer >= h->n_layers || B < 1 || B > SMOE_MAX_BATCH) return SMOE_EINVAL;
+  StepDecision d{};
+  d.B = B;
+  for (int t = 0; t < B; ++t) {
+    d.topk[t] = topk + (size_t)t * h->p.top_k;
+    d.final_[t] = final_ + (size_t)t * h->p.top_k;
+    d.subst[t] = subst + (size_t)t * h->p.top_k;
+    d.scores[t] = scores + (size_t)t * h->p.n_experts;
+  }
+  StepPlan plan;
+  const int rc = h->layers[layer].plan_step(h->p, d, h->expert_bytes, plan);
+  if (rc != SMOE_OK) return rc;
+  for (int i = 0; i < plan.n_fetch; ++i) {
+    fetched[i] = plan.fetched[i];
+    victims[i] = plan.victims[i];
+    slots[i] = plan.slot[i];
+  }
+  return plan.n_fetch;
+}
+
+void smoe_hl_residency(const hl_handle* h, int layer, int32_t* out_slots) {
+  for (int s = 0; s < h->p.cache_cap; ++s) out_slots[s] = h->layers[layer].expert_of_slot[s];
+}
+
+void smoe_hl_stats(const hl_handle* h, int layer, moe_stats_t* out) { *out = h->layers[layer].st; }
+
+}  // extern "C"

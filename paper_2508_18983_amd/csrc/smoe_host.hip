@@ -13,6 +13,7 @@
 
 #include "smoe.h"
 #include "smoe_dev.hpp"
+#include "cache_state.hpp"
 
 using namespace smoe;
 
@@ -28,19 +29,6 @@ thread_local int g_last_hip = 0;
       return SMOE_EHIP;                       \
     }                                         \
   } while (0)
-
-struct LayerState {
-  uint64_t resident = 0;
-  int8_t slot_of[SMOE_MAX_EXPERTS];
-  std::vector<int32_t> expert_of_slot;   // [cap]
-  std::vector<double> hist;              // ring [(n+1)][E] of batch-mean score vectors
-  int hist_count = 0, hist_head = 0;
-  int64_t step = 0;                      // calls of this layer so far
-  int64_t last_use[SMOE_MAX_EXPERTS];    // stamp of the latest use (recency policies)
-  int64_t load_stamp[SMOE_MAX_EXPERTS];  // stamp of the load that brought the expert in
-  int64_t use_count[SMOE_MAX_EXPERTS];   // uses since that load
-  moe_stats_t st{};
-};
 
 struct EventPair { hipEvent_t a, b; };
 struct ProfKind {
@@ -58,7 +46,8 @@ struct moe_handle {
   hipEvent_t ev_copy = nullptr;
   int64_t esize = 0, expert_bytes = 0, shared_bytes = 0;
   int Fmax = 0;
-  std::vector<LayerState> layers;
+  std::vector<CacheLayer> layers;
+  CacheParams cp{};
   std::vector<int32_t> init_resident;    // [L][cap]
   std::vector<const char*> experts_host; // [L] pinned blocks of E experts
   // device scratch
@@ -157,22 +146,9 @@ void plan_geometry(moe_handle* h) {
 int upload_initial(moe_handle* h) {
   const moe_cfg_t& c = h->cfg;
   for (int l = 0; l < c.n_layers; ++l) {
-    LayerState& ls = h->layers[l];
-    ls.resident = 0;
-    std::memset(ls.slot_of, -1, sizeof(ls.slot_of));
-    ls.expert_of_slot.assign(c.cache_cap, -1);
-    ls.hist.assign((size_t)(c.evict_window + 1) * c.n_experts, 0.0);
-    ls.hist_count = 0;
-    ls.hist_head = 0;
-    ls.step = 0;
-    for (int e = 0; e < SMOE_MAX_EXPERTS; ++e) { ls.last_use[e] = 0; ls.load_stamp[e] = 0; ls.use_count[e] = 0; }
-    ls.st = moe_stats_t{};
+    h->layers[l].reset(h->cp, &h->init_resident[(size_t)l * c.cache_cap]);
     for (int s = 0; s < c.cache_cap; ++s) {
       const int e = h->init_resident[(size_t)l * c.cache_cap + s];
-      ls.resident |= 1ull << e;
-      ls.slot_of[e] = (int8_t)s;
-      ls.expert_of_slot[s] = e;
-      ls.last_use[e] = ls.load_stamp[e] = (int64_t)s - c.cache_cap;   // before step 0, in slot order
       const char* src = h->experts_host[l] + (int64_t)e * h->expert_bytes;
       char* dst = static_cast<char*>(h->buf.cache_slab_dev) +
                   ((int64_t)l * c.cache_cap + s) * h->expert_bytes;
@@ -257,6 +233,7 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
   h->shared_bytes = 3ll * c.hidden * c.shared_ffn * h->esize;
   h->Fmax = std::max(c.ffn, c.n_shared ? c.shared_ffn : 0);
   h->layers.resize(c.n_layers);
+  h->cp = CacheParams{c.n_experts, c.top_k, c.cache_cap, c.evict_window, c.evict_policy, c.n_stage};
   for (int l = 0; l < c.n_layers; ++l)
     h->experts_host.push_back(static_cast<const char*>(buf->experts_host[l]));
   h->buf.experts_host = nullptr;
@@ -307,7 +284,7 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   if (!h || !x_dev || !y_dev) return SMOE_EINVAL;
   const moe_cfg_t& c = h->cfg;
   if (layer < 0 || layer >= c.n_layers || batch < 1 || batch > c.max_batch) return SMOE_EINVAL;
-  LayerState& ls = h->layers[layer];
+  CacheLayer& ls = h->layers[layer];
   const int k = c.top_k, E = c.n_experts, B = batch, nj = k + c.n_shared;
 
   // ---- router + expert-cache router ------------------------------------------
@@ -394,90 +371,33 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   }
   const StepRec& rec = *h->rec_host;
 
-  // history: one entry per step, the batch mean of the score vectors (Eq. 3 window)
-  {
-    double* row = &ls.hist[(size_t)ls.hist_head * E];
-    for (int e = 0; e < E; ++e) {
-      double s = 0.0;
-      for (int t = 0; t < B; ++t) s += (double)rec.tok[t].scores[e];
-      row[e] = s / B;
-    }
-    ls.hist_head = (ls.hist_head + 1) % (c.evict_window + 1);
-    if (ls.hist_count < c.evict_window + 1) ++ls.hist_count;
+  // ---- cache bookkeeping: history, shield, victims, residency, counters -------
+  StepDecision dec{};
+  dec.B = B;
+  for (int t = 0; t < B; ++t) {
+    dec.topk[t] = rec.tok[t].topk;
+    dec.final_[t] = rec.tok[t].final_;
+    dec.subst[t] = rec.tok[t].subst;
+    dec.scores[t] = rec.tok[t].scores;
   }
-
-  // shield = every expert this step computes; misses in (token, slot) order
-  const uint64_t before = ls.resident;
-  uint64_t shield = 0;
-  int fetched[SMOE_MAX_BATCH * SMOE_MAX_TOPK], victims[SMOE_MAX_BATCH * SMOE_MAX_TOPK];
+  StepPlan plan;
+  {
+    const int rc = ls.plan_step(h->cp, dec, h->expert_bytes, plan);
+    if (rc != SMOE_OK) return rc;
+  }
+  const uint64_t before = plan.before, shield = plan.shield;
+  const int n_fetch = plan.n_fetch;
+  const int64_t hits = plan.hits;
+  const int* fetched = plan.fetched;
+  const int* victims = plan.victims;
   int gslot[SMOE_MAX_BATCH * SMOE_MAX_TOPK];
-  int n_fetch = 0;
-  int64_t raw_hits = 0, hits = 0, subs = 0;
-  for (int t = 0; t < B; ++t)
-    for (int j = 0; j < k; ++j) {
-      const int e = rec.tok[t].final_[j];
-      if (e < 0 || e >= E) return SMOE_ESTATE;
-      shield |= 1ull << e;
-      raw_hits += (before >> rec.tok[t].topk[j]) & 1ull;
-      subs += rec.tok[t].subst[j] != 0;
-      const int64_t stamp = ls.step * 64 + (int64_t)t * k + j;
-      if ((before >> e) & 1ull) {
-        ++hits;
-        ls.last_use[e] = stamp;
-        ++ls.use_count[e];
-        continue;
-      }
-      bool dup = false;
-      for (int i = 0; i < n_fetch; ++i) dup |= fetched[i] == e;
-      if (!dup) {
-        fetched[n_fetch++] = e;
-        ls.load_stamp[e] = stamp;
-        ls.use_count[e] = 0;
-      }
-      ls.last_use[e] = stamp;
-      ++ls.use_count[e];
-    }
-  ++ls.step;
 
-  int n_staged = 0, n_evict = 0;
   if (n_fetch > 0) {
-    double mean[SMOE_MAX_EXPERTS];
-    for (int e = 0; e < E; ++e) {
-      double s = 0.0;
-      for (int i = 0; i < ls.hist_count; ++i) s += ls.hist[(size_t)i * E + e];
-      mean[e] = s / ls.hist_count;
-    }
+    // ---- loads on the copy stream; the second FFN pass waits for them ---------
     for (int i = 0; i < n_fetch; ++i) {
-      int victim = -1;
-      for (int e = 0; e < E; ++e) {
-        if (!((ls.resident >> e) & 1ull) || ((shield >> e) & 1ull)) continue;
-        if (victim < 0) { victim = e; continue; }
-        bool better;
-        switch (c.evict_policy) {
-          case SMOE_EVICT_LRU:  better = ls.last_use[e] < ls.last_use[victim]; break;
-          case SMOE_EVICT_FIFO: better = ls.load_stamp[e] < ls.load_stamp[victim]; break;
-          case SMOE_EVICT_LFU:
-            better = ls.use_count[e] < ls.use_count[victim] ||
-                     (ls.use_count[e] == ls.use_count[victim] && ls.last_use[e] < ls.last_use[victim]);
-            break;
-          default:              better = mean[e] < mean[victim]; break;   // Eq. 3
-        }
-        if (better) victim = e;
-      }
-      victims[i] = victim;
       const int m = fetched[i];
-      if (victim >= 0) {
-        const int s = ls.slot_of[victim];
-        ls.resident = (ls.resident & ~(1ull << victim)) | (1ull << m);
-        ls.slot_of[victim] = -1;
-        ls.slot_of[m] = (int8_t)s;
-        ls.expert_of_slot[s] = m;
-        gslot[i] = layer * c.cache_cap + s;
-        ++n_evict;
-      } else {
-        if (n_staged >= c.n_stage) return SMOE_ESTATE;   // out of transient slots
-        gslot[i] = c.n_layers * c.cache_cap + n_staged++;
-      }
+      gslot[i] = plan.slot[i] >= 0 ? layer * c.cache_cap + plan.slot[i]
+                                   : c.n_layers * c.cache_cap + (-plan.slot[i] - 1);
       const char* src = h->experts_host[layer] + (int64_t)m * h->expert_bytes;
       char* dst = static_cast<char*>(h->buf.cache_slab_dev) + (int64_t)gslot[i] * h->expert_bytes;
       EventPair* pc = prof_begin(h, SMOE_PROF_COPY, h->s_copy);
@@ -529,17 +449,6 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
     h->prof[SMOE_PROF_DOWN_LOADED].bytes += miss_slots * up_r / 2;
   }
 
-  ls.st.tokens += B;
-  ls.st.slots += (int64_t)B * k;
-  ls.st.raw_hits += raw_hits;
-  ls.st.hits += hits;
-  ls.st.misses += (int64_t)B * k - hits;
-  ls.st.substitutions += subs;
-  ls.st.evictions += n_evict;
-  ls.st.staged += n_staged;
-  ls.st.fetches += n_fetch;
-  ls.st.bytes_fetched += (int64_t)n_fetch * h->expert_bytes;
-
   if (trace) {
     for (int t = 0; t < B; ++t)
       for (int j = 0; j < k; ++j) {
@@ -578,7 +487,7 @@ int moe_cache_stats(const moe_handle_t* h, int32_t layer, moe_stats_t* out) {
 
 int moe_cache_residency(const moe_handle_t* h, int32_t layer, int32_t* out_slots) {
   if (!h || !out_slots || layer < 0 || layer >= h->cfg.n_layers) return SMOE_EINVAL;
-  const LayerState& ls = h->layers[layer];
+  const CacheLayer& ls = h->layers[layer];
   for (int s = 0; s < h->cfg.cache_cap; ++s) out_slots[s] = ls.expert_of_slot[s];
   return SMOE_OK;
 }

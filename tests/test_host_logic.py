@@ -1,0 +1,128 @@
+"""The library's cache bookkeeping (history ring, Eq. 3 / baseline victims,
+protection shield, slot map, counters) replayed on the CPU: the HIP-free
+scheduler code is built into a small shim and fed the oracle's routing
+decisions; its victims, residency and counters must equal the oracle's."""
+import ctypes as C
+import os
+
+import numpy as np
+import pytest
+
+from oracle import smoe_oracle as O
+from smoe_inputs import SHAPES, make_workload, as_numpy
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SHIM = os.path.join(ROOT, "paper_2508_18983_amd", "libsmoe_hostlogic.so")
+
+
+class Stats(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("tokens", "slots", "raw_hits", "hits", "misses", "substitutions",
+                                         "evictions", "staged", "fetches", "bytes_fetched")]
+
+
+@pytest.fixture(scope="module")
+def shim():
+    if not os.path.exists(SHIM):
+        pytest.fail(f"{SHIM} missing: run python -m paper_2508_18983_amd.build")
+    lib = C.CDLL(SHIM)
+    lib.smoe_hl_create.restype = C.c_void_p
+    lib.smoe_hl_create.argtypes = [C.c_int] * 7 + [C.c_int64, C.c_void_p]
+    lib.smoe_hl_destroy.argtypes = [C.c_void_p]
+    lib.smoe_hl_step.argtypes = [C.c_void_p, C.c_int, C.c_int] + [C.c_void_p] * 7
+    lib.smoe_hl_residency.argtypes = [C.c_void_p, C.c_int, C.c_void_p]
+    lib.smoe_hl_stats.argtypes = [C.c_void_p, C.c_int, C.POINTER(Stats)]
+    return lib
+
+
+def replay(lib, wl, batch=1, n_stage=0, **oracle_kw):
+    s = wl.shape
+    orc = O.oracle_from_workload(wl, **oracle_kw)
+    h = lib.smoe_hl_create(s.n_layers, s.n_experts, s.top_k, orc.cap, orc.window, orc.evict_policy,
+                           n_stage, s.expert_bytes, None)
+    assert h
+    nk = batch * s.top_k
+    fetched = np.zeros(nk, np.int32); victims = np.zeros(nk, np.int32); slots = np.zeros(nk, np.int32)
+    res_slots = np.zeros(orc.cap, np.int32)
+    loads = 0
+    try:
+        for t in range(s.tokens):
+            for l in range(s.n_layers):
+                r = orc.decode_layer(l, as_numpy(wl.x[t, l]), compute_y=False)
+                topk = np.ascontiguousarray(r.topk, np.int32)
+                fin = np.ascontiguousarray(r.final, np.int32)
+                sub = np.ascontiguousarray(r.substituted, np.int32)
+                sc = np.ascontiguousarray(r.scores, np.float32)
+                n = lib.smoe_hl_step(h, l, batch, topk.ctypes.data, fin.ctypes.data, sub.ctypes.data,
+                                     sc.ctypes.data, fetched.ctypes.data, victims.ctypes.data, slots.ctypes.data)
+                assert n == len(r.fetched), (t, l, n)
+                assert fetched[:n].tolist() == r.fetched and victims[:n].tolist() == r.victims, (t, l)
+                assert [v >= 0 for v in victims[:n]] == [sl >= 0 for sl in slots[:n]]
+                lib.smoe_hl_residency(h, l, res_slots.ctypes.data)
+                assert res_slots.tolist() == orc.layers[l].slot_expert, (t, l)
+                loads += n
+        for l in range(s.n_layers):
+            st = Stats()
+            lib.smoe_hl_stats(h, l, C.byref(st))
+            assert {n: getattr(st, n) for n, _ in Stats._fields_} == orc.stats(l).as_dict()
+    finally:
+        lib.smoe_hl_destroy(h)
+    return loads, orc.stats()
+
+
+@pytest.mark.parametrize("policy", [0, 1, 2, 3])
+def test_scheduler_replay_matches_oracle(shim, policy):
+    wl = make_workload(SHAPES["c1"].with_(tokens=40, seed=policy))
+    loads, st = replay(shim, wl, evict_policy=policy)
+    assert loads > 10 and st.substitutions > 0
+    shp = SHAPES["c4"].with_(ffn=32, shared_ffn=32, seed=40 + policy)
+    wl = make_workload(shp, n_layers=3, tokens=60)
+    loads, st = replay(shim, wl, evict_policy=policy)
+    assert loads > 50
+
+
+@pytest.mark.parametrize("window", [0, 1, 7])
+def test_scheduler_window_lengths(shim, window):
+    wl = make_workload(SHAPES["c1"].with_(tokens=40, seed=3))
+    replay(shim, wl, evict_window=window)
+
+
+def test_scheduler_batch_and_staging(shim):
+    shp = SHAPES["c5"].with_(ffn=32, shared_ffn=32, cache_cap=12, seed=5)
+    wl = make_workload(shp, n_layers=2, tokens=20, batch=4)
+    loads, st = replay(shim, wl, batch=4, n_stage=32)
+    assert st.staged > 0
+    # without staging slots the same step is refused with SMOE_ESTATE (-4)
+    s = wl.shape
+    orc = O.oracle_from_workload(wl)
+    h = shim.smoe_hl_create(s.n_layers, s.n_experts, s.top_k, s.cache_cap, 3, 0, 0, s.expert_bytes, None)
+    rc = 0
+    buf = np.zeros(64, np.int32)
+    for t in range(s.tokens):
+        for l in range(s.n_layers):
+            r = orc.decode_layer(l, as_numpy(wl.x[t, l]), compute_y=False)
+            a_topk = np.ascontiguousarray(r.topk, np.int32)       # keep the arrays alive over the call
+            a_fin = np.ascontiguousarray(r.final, np.int32)
+            a_sub = np.ascontiguousarray(r.substituted, np.int32)
+            a_sc = np.ascontiguousarray(r.scores, np.float32)
+            rc = shim.smoe_hl_step(h, l, 4, a_topk.ctypes.data, a_fin.ctypes.data, a_sub.ctypes.data,
+                                   a_sc.ctypes.data, buf.ctypes.data, buf.ctypes.data, buf.ctypes.data)
+            if rc < 0 or -1 in r.victims:
+                break
+        if rc < 0 or -1 in r.victims:
+            break
+    assert rc == -4
+    shim.smoe_hl_destroy(h)
+
+
+def test_scheduler_rejects_bad_arguments_and_malformed_decisions(shim):
+    assert not shim.smoe_hl_create(1, 65, 2, 4, 3, 0, 0, 100, None)      # too many experts
+    assert not shim.smoe_hl_create(1, 8, 2, 1, 3, 0, 0, 100, None)       # cap < k
+    assert not shim.smoe_hl_create(1, 8, 2, 4, 3, 9, 0, 100, None)       # unknown policy
+    h = shim.smoe_hl_create(1, 8, 2, 4, 3, 0, 0, 100, None)
+    topk = np.array([[0, 1]], np.int32); bad = np.array([[0, 9]], np.int32); sub = np.zeros((1, 2), np.int32)
+    sc = np.full((1, 8), 0.125, np.float32); o = np.zeros(2, np.int32)
+    assert shim.smoe_hl_step(h, 0, 1, topk.ctypes.data, bad.ctypes.data, sub.ctypes.data, sc.ctypes.data,
+                             o.ctypes.data, o.ctypes.data, o.ctypes.data) == -4
+    assert shim.smoe_hl_step(h, 3, 1, topk.ctypes.data, topk.ctypes.data, sub.ctypes.data, sc.ctypes.data,
+                             o.ctypes.data, o.ctypes.data, o.ctypes.data) == -1
+    shim.smoe_hl_destroy(h)
