@@ -123,9 +123,14 @@ void plan_geometry(moe_handle* h) {
   if (env_int("SMOE_REGPATH", 1) == 0) return;
   const int xu = (c.hidden / n + kWave - 1) / kWave;           // units of x per lane
   h->up_upl = xu <= 1 ? 1 : (xu <= 2 ? 2 : (xu <= 4 ? 4 : (xu <= 8 ? 8 : 0)));
+  // Column segments per row: aim at the same number of units per lane (4..8) for the
+  // routed and the shared rows, so one kernel instance keeps enough loads in flight for both.
+  auto per_lane_of = [&](int F) { return (F / n + kWave - 1) / kWave; };
+  int target = per_lane_of(c.ffn);
+  if (c.n_shared) target = std::min(target, per_lane_of(c.shared_ffn));
+  target = std::max(4, std::min(8, target));
   auto seg_plan = [&](int F, int& nseg) -> int {               // -> units per lane
-    const int per_lane = (F / n + kWave - 1) / kWave;
-    nseg = per_lane <= 12 ? 1 : (per_lane <= 24 ? 2 : 4);
+    nseg = std::max(1, std::min(8, (per_lane_of(F) + target - 1) / target));
     return ((F / n + nseg - 1) / nseg + kWave - 1) / kWave;
   };
   int need = seg_plan(c.ffn, h->nsegR);

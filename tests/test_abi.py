@@ -65,3 +65,9 @@ def test_session_refuses_to_run_without_a_gpu():
     from paper_2508_18983_amd.session import session_from_workload
     with pytest.raises(RuntimeError):
         session_from_workload(make_workload(SHAPES["c1"].with_(tokens=1)))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, cwd=ROOT)
+    assert r.returncode == 2 and "one-GPU" in r.stderr and r.stdout.strip() == ""
