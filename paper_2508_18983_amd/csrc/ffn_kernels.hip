@@ -598,7 +598,19 @@ __global__ __launch_bounds__(256) void ffn_up_grp_kernel(const FfnArgs a) {
         }
         ag = wave_sum(ag);
         au = wave_sum(au);
-        if (lane == 0) g.act[(size_t)(t0 + i) * F + f] = wts[i] * (ag / (1.0f + expf(-ag))) * au;
+        if (lane == 0) {
+          const float v = wts[i] * (ag / (1.0f + expf(-ag))) * au;
+          if (a.mfma_down) {
+            // the MFMA down kernel takes the activation as two bf16 terms, hi + lo (|error| <= 2^-17 |v|):
+            // the row of F floats holds hi[F] followed by lo[F]
+            uint16_t* row16 = reinterpret_cast<uint16_t*>(g.act + (size_t)(t0 + i) * F);
+            const bf16_t hi = Unit<bf16_t>::narrow(v);
+            row16[f] = hi.v;
+            row16[F + f] = Unit<bf16_t>::narrow(v - Unit<bf16_t>::widen1(hi)).v;
+          } else {
+            g.act[(size_t)(t0 + i) * F + f] = v;
+          }
+        }
       }
     }
   }
@@ -721,6 +733,119 @@ __global__ __launch_bounds__(256) void ffn_down_grp_kernel(const FfnArgs a) {
   }
 }
 
+// Batch > 1, bf16: down projection + combine on the matrix cores.  With several
+// tokens per expert the product W2[rows, cols] x act[cols, tokens] is a real
+// contraction; on the vector ALUs it costs one cross-lane reduction per (row,
+// token), on MFMA none.  A block owns 16 output rows (the M of the 16x16x32
+// tile), the 16 tile columns are the step's tokens (column j = token j), K runs
+// over an item = (task, 256-column segment).  The eight waves take items
+// round-robin; each stages its 16 x 256 weight tile through a private, padded
+// LDS region (coalesced 128-bit global loads in, MFMA operand order out), takes
+// the activations as two bf16 terms (hi + lo) written by the up kernel, and
+// accumulates ONE 16 x 16 fp32 tile over all of its items.  The eight tiles are
+// then added in wave order.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+constexpr int kMfmaCols = 256;                  // columns per item
+constexpr int kMfmaRowBytes = 2 * kMfmaCols + 16;   // staged row + pad against bank conflicts
+constexpr int kMfmaWaves = 8;
+constexpr int kMfmaLdsBytes = kMfmaWaves * 16 * kMfmaRowBytes;
+
+template <int PASS>
+__global__ __launch_bounds__(64 * kMfmaWaves) void ffn_down_mfma_kernel(const FfnArgs a) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+  const int i16 = lane & 15, g4 = lane >> 4;     // tile row / column index, K sub-block
+  const int H = a.H;
+  const int hb = blockIdx.x * 16;
+  const int n_groups = min(a.rec->n_groups, a.maxg);
+  const int nsegR = (a.F + kMfmaCols - 1) / kMfmaCols;
+  const int nsegS = a.ns ? (a.Fs + kMfmaCols - 1) / kMfmaCols : 0;
+  const int items_r = n_groups * nsegR;
+  const int n_items = items_r + a.ns * nsegS;
+  unsigned char* stage = lds + (size_t)wave * 16 * kMfmaRowBytes;
+
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int it = wave; it < n_items; it += kMfmaWaves) {
+    int task, seg;
+    if (it < items_r) { task = it / nsegR; seg = it - task * nsegR; }
+    else { const int q = it - items_r; const int sidx = q / nsegS; seg = q - sidx * nsegS; task = a.maxg + sidx; }
+    const GrpTask g = grp_task<PASS>(a, task);
+    if (g.base == nullptr) continue;
+    const int F = g.F;
+    const int c0 = seg * kMfmaCols;
+    const int ncols = min(kMfmaCols, F - c0);
+    const bf16_t* W2 = reinterpret_cast<const bf16_t*>(g.base) + 2 * (size_t)F * H;
+    // this lane's tile column is token i16: where is it in the task's token list?
+    int pos = -1;
+#pragma unroll
+    for (int q = 0; q < SMOE_MAX_BATCH; ++q) pos = (q < g.ntok && g.tok[q] == i16) ? q : pos;
+
+    // weights: 8 coalesced loads, two rows of 512 bytes per instruction
+    u32x4 wreg[8];
+    const int unit = lane & 31, rsub = lane >> 5;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const int r = 2 * q + rsub;
+      wreg[q] = (unit * 8 < ncols)
+                    ? Unit<bf16_t>::load(W2 + (size_t)min(hb + r, H - 1) * F + c0 + unit * 8)
+                    : u32x4{};
+    }
+    // activations of my token: hi and lo terms, 8 K-steps of 8 columns each
+    u32x4 bhi[8], blo[8];
+    const uint16_t* arow = reinterpret_cast<const uint16_t*>(g.act + (size_t)max(pos, 0) * F);
+#pragma unroll
+    for (int st = 0; st < 8; ++st) {
+      const int col = 32 * st + 8 * g4;
+      if (pos >= 0 && col < ncols) {
+        bhi[st] = *reinterpret_cast<const u32x4*>(arow + c0 + col);
+        blo[st] = *reinterpret_cast<const u32x4*>(arow + F + c0 + col);
+      } else {
+        bhi[st] = u32x4{};
+        blo[st] = u32x4{};
+      }
+    }
+    // stage the tile: row r at r * kMfmaRowBytes, 16 bytes per unit
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+      *reinterpret_cast<u32x4*>(stage + (2 * q + rsub) * kMfmaRowBytes + unit * 16) = wreg[q];
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int st = 0; st < 8; ++st) {
+      const u32x4 af = *reinterpret_cast<const u32x4*>(stage + i16 * kMfmaRowBytes + (4 * st + g4) * 16);
+      const bf16x8 av = __builtin_bit_cast(bf16x8, af);
+      const u32x4 h4 = bhi[st], l4 = blo[st];
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, h4), acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, l4), acc, 0, 0, 0);
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
+
+  // ---- add the eight tiles in wave order; lane holds rows 4*g4 + r, column i16 ----
+  __syncthreads();
+  float* red = reinterpret_cast<float*>(lds);           // [wave][16 rows][16 cols]
+#pragma unroll
+  for (int r = 0; r < 4; ++r) red[(wave * 16 + 4 * g4 + r) * 16 + i16] = acc[r];
+  __syncthreads();
+  for (int idx = tid; idx < 16 * a.B; idx += 64 * kMfmaWaves) {
+    const int t = idx >> 4, row = idx & 15;
+    const int h = hb + row;
+    if (h >= H) continue;
+    bool any_miss = false;
+    for (int q = 0; q < a.k; ++q) any_miss |= (a.rec->tok[t].slot[q] < 0);
+    if (PASS == 1 && !any_miss) continue;
+    float sum = 0.f;
+    for (int w = 0; w < kMfmaWaves; ++w) sum += red[(w * 16 + row) * 16 + t];
+    bf16_t* y = static_cast<bf16_t*>(a.y) + (size_t)t * H;
+    float* ysum = a.ysum + (size_t)t * H;
+    if (PASS == 0) {
+      if (any_miss) ysum[h] = sum;
+      else y[h] = Unit<bf16_t>::narrow(sum);
+    } else {
+      y[h] = Unit<bf16_t>::narrow(ysum[h] + sum);
+    }
+  }
+}
+
 __global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst,
                                                    const uint4* __restrict__ src, int64_t n) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -765,6 +890,17 @@ void launch_ffn_up(const FfnArgs& a, int dtype, hipStream_t s) {
 template <typename T, int PASS>
 static void launch_down_t(const FfnArgs& a, hipStream_t s) {
   if (a.grouped) {
+    if (a.mfma_down) {
+      static bool lds_opted_in[2] = {false, false};   // the staging area is larger than the 64 KB default
+      if (!lds_opted_in[PASS]) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_down_mfma_kernel<PASS>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, kMfmaLdsBytes);
+        lds_opted_in[PASS] = true;
+      }
+      hipLaunchKernelGGL((ffn_down_mfma_kernel<PASS>), dim3((a.H + 15) / 16), dim3(64 * kMfmaWaves),
+                         kMfmaLdsBytes, s, a);
+      return;
+    }
     const int grid = (a.H + a.RBG - 1) / a.RBG;
     hipLaunchKernelGGL((ffn_down_grp_kernel<T, PASS>), dim3(grid), dim3(256), grouped_down_lds_bytes(a), s, a);
     return;

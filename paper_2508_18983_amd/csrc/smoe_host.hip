@@ -62,6 +62,7 @@ struct moe_handle {
   int TF = 0, tilesR = 0, tilesS = 0, R = 0, htiles = 0, stage_all = 0, chunk = 0, down_lds = 0;
   int up_upl = 0, down_upl = 0, RB = 0, nsegR = 1, nsegS = 1;
   int grouped_ok = 0, nsegGR = 0, nsegGS = 0, RBG = 0;   // batch > 1: grouped kernels
+  int mfma_ok = 1;                                       // SMOE_MFMA=0 keeps the vector-ALU down kernel
   int64_t act_floats = 0;
   // profiling
   int32_t seq = 0;                       // number of the last decode call
@@ -266,6 +267,7 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
     std::memset(h->rec_host, 0, sizeof(StepRec));
     h->spin_limit = env_int("SMOE_SPIN_LIMIT", 4000000);
     h->route_fast = env_int("SMOE_ROUTE_FAST", 1);
+    h->mfma_ok = env_int("SMOE_MFMA", 1);
     void* dp = nullptr;
     HIP_TRY(hipHostGetDevicePointer(&dp, h->rec_host, 0));
     h->rec_host_dev = static_cast<StepRec*>(dp);
@@ -348,6 +350,7 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   for (int i = 0; i < kMaxTasks; ++i) fa.slot_override[i] = -1;
   fa.grouped = (B > 1 && h->grouped_ok) ? 1 : 0;
   fa.maxg = std::min(E, B * k);
+  fa.mfma_down = (fa.grouped && c.dtype == SMOE_DTYPE_BF16 && h->mfma_ok) ? 1 : 0;
   fa.nsegGR = h->nsegGR; fa.nsegGS = h->nsegGS; fa.RBG = h->RBG;
   fa.act_shared_off = (int64_t)fa.maxg * SMOE_MAX_BATCH * c.ffn;
   if (fa.grouped && fa.up_upl == 0) {                 // grouped up kernel needs units per lane

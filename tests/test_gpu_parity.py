@@ -150,6 +150,20 @@ def test_batched_decode_cross_token_substitution_and_staging(batch):
         assert r["stats"]["staged"] > 0
 
 
+@pytest.mark.parametrize("env", [dict(), dict(SMOE_MFMA="0")])
+def test_batched_decode_ragged_shapes_matrix_core_and_vector_down_kernels(env, monkeypatch):
+    """bf16 batch with rows and columns that do not fill the 16 x 256 MFMA tiles,
+    and the vector-ALU grouped down kernel it replaces."""
+    for k_, v in env.items():
+        monkeypatch.setenv(k_, v)
+    shp = SHAPES["c4"].with_(hidden=264, ffn=520, shared_ffn=72, n_experts=12, top_k=3, cache_cap=5, seed=17)
+    wl = make_workload(shp, n_layers=2, tokens=16, batch=3)
+    run_parity(wl, batch=3, session_kw=dict(n_stage=9), label=f"ragged-b3-{env}")
+    shp = SHAPES["c5"].with_(ffn=512, shared_ffn=1024, cache_cap=12, seed=23)
+    wl = make_workload(shp, n_layers=1, tokens=10, batch=8)
+    run_parity(wl, y_every=2, batch=8, session_kw=dict(n_stage=64), label=f"c5-b8-{env}")
+
+
 def test_batched_decode_without_expert_grouping(monkeypatch):
     """The per-(token, slot) task path stays available (SMOE_GROUPED=0)."""
     monkeypatch.setenv("SMOE_GROUPED", "0")
