@@ -750,6 +750,99 @@ constexpr int kMfmaRowBytes = 2 * kMfmaCols + 16;   // staged row + pad against 
 constexpr int kMfmaWaves = 8;
 constexpr int kMfmaLdsBytes = kMfmaWaves * 16 * kMfmaRowBytes;
 
+// Batch > 1, bf16: up projection on the matrix cores.  A block = one task x 64
+// f-rows; each of its four waves owns 16 rows of W1 and the same 16 rows of W3
+// (M = 16), the tile columns are the step's tokens (B operand = x as stored,
+// bf16, so one MFMA per K-step is exact), K walks H in 256-column segments.
+// Both weight tiles of a segment are staged through the wave's private LDS
+// region; the loads of the next segment are issued right after staging.  The
+// epilogue applies w * silu(g) * u for the tokens of the task and writes the
+// activation as hi + lo bf16 terms for the MFMA down kernel.
+constexpr int kMfmaUpWaves = 4;
+constexpr int kMfmaUpLdsBytes = kMfmaUpWaves * 2 * 16 * kMfmaRowBytes;
+
+template <int PASS>
+__global__ __launch_bounds__(64 * kMfmaUpWaves) void ffn_up_mfma_kernel(const FfnArgs a) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+  const int i16 = lane & 15, g4 = lane >> 4;
+  const int tiles_r = (a.F + 63) / 64, tiles_s = a.ns ? (a.Fs + 63) / 64 : 0;
+  const int routed_blocks = a.maxg * tiles_r;
+  int task, tile;
+  if ((int)blockIdx.x < routed_blocks) { task = blockIdx.x / tiles_r; tile = blockIdx.x - task * tiles_r; }
+  else { const int b = blockIdx.x - routed_blocks; const int sidx = b / tiles_s; tile = b - sidx * tiles_s; task = a.maxg + sidx; }
+  const GrpTask g = grp_task<PASS>(a, task);
+  if (g.base == nullptr) return;
+  const int H = a.H, F = g.F;
+  const int f0 = tile * 64 + wave * 16;
+  if (f0 >= F) return;
+  const bf16_t* W1 = reinterpret_cast<const bf16_t*>(g.base);
+  const bf16_t* W3 = W1 + (size_t)F * H;
+  const bf16_t* x = static_cast<const bf16_t*>(a.x);
+  unsigned char* st1 = lds + (size_t)wave * 2 * 16 * kMfmaRowBytes;
+  unsigned char* st3 = st1 + 16 * kMfmaRowBytes;
+  const int unit = lane & 31, rsub = lane >> 5;
+  const int nseg = (H + kMfmaCols - 1) / kMfmaCols;
+
+  u32x4 w1reg[8], w3reg[8];
+  auto load_seg = [&](int sg) {
+    const int c0 = sg * kMfmaCols;
+    const bool live = sg < nseg && c0 + unit * 8 < H;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const size_t roff = (size_t)min(f0 + 2 * q + rsub, F - 1) * H + c0 + unit * 8;
+      w1reg[q] = live ? Unit<bf16_t>::load(W1 + roff) : u32x4{};
+      w3reg[q] = live ? Unit<bf16_t>::load(W3 + roff) : u32x4{};
+    }
+  };
+  f32x4 accg = {0.f, 0.f, 0.f, 0.f}, accu = {0.f, 0.f, 0.f, 0.f};
+  load_seg(0);
+  for (int sg = 0; sg < nseg; ++sg) {
+    const int c0 = sg * kMfmaCols;
+    u32x4 xf[8];                              // x of token i16, 8 K-steps of this segment
+#pragma unroll
+    for (int st = 0; st < 8; ++st) {
+      const int col = c0 + 32 * st + 8 * g4;
+      xf[st] = (i16 < a.B && col < H) ? *reinterpret_cast<const u32x4*>(x + (size_t)i16 * H + col) : u32x4{};
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      *reinterpret_cast<u32x4*>(st1 + (2 * q + rsub) * kMfmaRowBytes + unit * 16) = w1reg[q];
+      *reinterpret_cast<u32x4*>(st3 + (2 * q + rsub) * kMfmaRowBytes + unit * 16) = w3reg[q];
+    }
+    __builtin_amdgcn_wave_barrier();
+    load_seg(sg + 1);
+#pragma unroll
+    for (int st = 0; st < 8; ++st) {
+      const u32x4 a1 = *reinterpret_cast<const u32x4*>(st1 + i16 * kMfmaRowBytes + (4 * st + g4) * 16);
+      const u32x4 a3 = *reinterpret_cast<const u32x4*>(st3 + i16 * kMfmaRowBytes + (4 * st + g4) * 16);
+      const u32x4 xb = xf[st];
+      accg = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a1), __builtin_bit_cast(bf16x8, xb), accg, 0, 0, 0);
+      accu = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a3), __builtin_bit_cast(bf16x8, xb), accu, 0, 0, 0);
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
+  // lane holds rows f0 + 4*g4 + r of token i16: store if that token belongs to the task
+  int pos = -1; float wgt = 0.f;
+#pragma unroll
+  for (int q = 0; q < SMOE_MAX_BATCH; ++q)
+    if (q < g.ntok && g.tok[q] == i16) { pos = q; wgt = g.w[q]; }
+  if (pos >= 0) {
+    uint16_t* row16 = reinterpret_cast<uint16_t*>(g.act + (size_t)pos * F);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int f = f0 + 4 * g4 + r;
+      if (f < F) {
+        const float ag = accg[r], au = accu[r];
+        const float v = wgt * (ag / (1.0f + expf(-ag))) * au;
+        const bf16_t hi = Unit<bf16_t>::narrow(v);
+        row16[f] = hi.v;
+        row16[F + f] = Unit<bf16_t>::narrow(v - Unit<bf16_t>::widen1(hi)).v;
+      }
+    }
+  }
+}
+
 template <int PASS>
 __global__ __launch_bounds__(64 * kMfmaWaves) void ffn_down_mfma_kernel(const FfnArgs a) {
   extern __shared__ __align__(16) unsigned char lds[];
@@ -763,52 +856,80 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void ffn_down_mfma_kernel(const Ff
   const int items_r = n_groups * nsegR;
   const int n_items = items_r + a.ns * nsegS;
   unsigned char* stage = lds + (size_t)wave * 16 * kMfmaRowBytes;
+  int next_it = 0;                          // item index at which describe() last stopped
 
-  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  for (int it = wave; it < n_items; it += kMfmaWaves) {
-    int task, seg;
-    if (it < items_r) { task = it / nsegR; seg = it - task * nsegR; }
-    else { const int q = it - items_r; const int sidx = q / nsegS; seg = q - sidx * nsegS; task = a.maxg + sidx; }
-    const GrpTask g = grp_task<PASS>(a, task);
-    if (g.base == nullptr) continue;
-    const int F = g.F;
-    const int c0 = seg * kMfmaCols;
-    const int ncols = min(kMfmaCols, F - c0);
-    const bf16_t* W2 = reinterpret_cast<const bf16_t*>(g.base) + 2 * (size_t)F * H;
-    // this lane's tile column is token i16: where is it in the task's token list?
-    int pos = -1;
+  // One item: where its 16 x 256 weight tile and this lane's activation row live.
+  struct Item {
+    const bf16_t* w2;        // W2 + c0 of row 0 of the matrix
+    const uint16_t* arow;    // hi terms of my token's activation row (lo terms F further), at c0
+    int F, ncols, pos;
+    bool valid;
+  };
+  auto describe = [&](int it) -> Item {
+    Item d{nullptr, nullptr, 0, 0, -1, false};
+    // skip forward over items whose task is not part of this pass
+    for (; it < n_items; it += kMfmaWaves) {
+      int task, seg;
+      if (it < items_r) { task = it / nsegR; seg = it - task * nsegR; }
+      else { const int q = it - items_r; const int sidx = q / nsegS; seg = q - sidx * nsegS; task = a.maxg + sidx; }
+      const GrpTask g = grp_task<PASS>(a, task);
+      if (g.base == nullptr) continue;
+      const int c0 = seg * kMfmaCols;
+      int pos = -1;                       // this lane's tile column is token i16
 #pragma unroll
-    for (int q = 0; q < SMOE_MAX_BATCH; ++q) pos = (q < g.ntok && g.tok[q] == i16) ? q : pos;
-
-    // weights: 8 coalesced loads, two rows of 512 bytes per instruction
-    u32x4 wreg[8];
-    const int unit = lane & 31, rsub = lane >> 5;
+      for (int q = 0; q < SMOE_MAX_BATCH; ++q) pos = (q < g.ntok && g.tok[q] == i16) ? q : pos;
+      d.F = g.F;
+      d.ncols = min(kMfmaCols, g.F - c0);
+      d.w2 = reinterpret_cast<const bf16_t*>(g.base) + 2 * (size_t)g.F * H + c0;
+      d.arow = reinterpret_cast<const uint16_t*>(g.act + (size_t)max(pos, 0) * g.F) + c0;
+      d.pos = pos;
+      d.valid = true;
+      break;
+    }
+    d.ncols = d.valid ? d.ncols : 0;
+    d.F = d.valid ? d.F : 0;
+    d.pos = d.valid ? d.pos : -1;
+    // remember where the scan stopped
+    next_it = it;
+    return d;
+  };
+  const int unit = lane & 31, rsub = lane >> 5;
+  auto load_tile = [&](const Item& d, u32x4 (&wreg)[8]) {   // 8 coalesced loads, two 512-byte rows each
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
       const int r = 2 * q + rsub;
-      wreg[q] = (unit * 8 < ncols)
-                    ? Unit<bf16_t>::load(W2 + (size_t)min(hb + r, H - 1) * F + c0 + unit * 8)
+      wreg[q] = (d.valid && unit * 8 < d.ncols)
+                    ? Unit<bf16_t>::load(d.w2 + (size_t)min(hb + r, H - 1) * d.F + unit * 8)
                     : u32x4{};
     }
+  };
+
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  u32x4 wreg[8];
+  Item cur = describe(wave);
+  load_tile(cur, wreg);
+  while (cur.valid) {
+    const int after = next_it + kMfmaWaves;
     // activations of my token: hi and lo terms, 8 K-steps of 8 columns each
     u32x4 bhi[8], blo[8];
-    const uint16_t* arow = reinterpret_cast<const uint16_t*>(g.act + (size_t)max(pos, 0) * F);
 #pragma unroll
     for (int st = 0; st < 8; ++st) {
       const int col = 32 * st + 8 * g4;
-      if (pos >= 0 && col < ncols) {
-        bhi[st] = *reinterpret_cast<const u32x4*>(arow + c0 + col);
-        blo[st] = *reinterpret_cast<const u32x4*>(arow + F + c0 + col);
+      if (cur.pos >= 0 && col < cur.ncols) {
+        bhi[st] = *reinterpret_cast<const u32x4*>(cur.arow + col);
+        blo[st] = *reinterpret_cast<const u32x4*>(cur.arow + cur.F + col);
       } else {
         bhi[st] = u32x4{};
         blo[st] = u32x4{};
       }
     }
-    // stage the tile: row r at r * kMfmaRowBytes, 16 bytes per unit
+    // stage the tile (row r at r * kMfmaRowBytes), then start the next item's loads
 #pragma unroll
     for (int q = 0; q < 8; ++q)
       *reinterpret_cast<u32x4*>(stage + (2 * q + rsub) * kMfmaRowBytes + unit * 16) = wreg[q];
     __builtin_amdgcn_wave_barrier();
+    const Item nxt = describe(after);
+    load_tile(nxt, wreg);
 #pragma unroll
     for (int st = 0; st < 8; ++st) {
       const u32x4 af = *reinterpret_cast<const u32x4*>(stage + i16 * kMfmaRowBytes + (4 * st + g4) * 16);
@@ -818,6 +939,7 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void ffn_down_mfma_kernel(const Ff
       acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, l4), acc, 0, 0, 0);
     }
     __builtin_amdgcn_wave_barrier();
+    cur = nxt;
   }
 
   // ---- add the eight tiles in wave order; lane holds rows 4*g4 + r, column i16 ----
@@ -857,6 +979,17 @@ __global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst,
 
 template <typename T, int PASS>
 static void launch_up_t(const FfnArgs& a, hipStream_t s) {
+  if (a.grouped && a.mfma_down && a.mfma_up) {
+    static bool lds_opted_in[2] = {false, false};
+    if (!lds_opted_in[PASS]) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_up_mfma_kernel<PASS>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kMfmaUpLdsBytes);
+      lds_opted_in[PASS] = true;
+    }
+    const int grid = a.maxg * ((a.F + 63) / 64) + a.ns * ((a.Fs + 63) / 64);
+    hipLaunchKernelGGL((ffn_up_mfma_kernel<PASS>), dim3(grid), dim3(64 * kMfmaUpWaves), kMfmaUpLdsBytes, s, a);
+    return;
+  }
   if (a.grouped) {
     const int grid = a.maxg * 2 * a.tilesR + a.ns * 2 * a.tilesS;
     const size_t lds = (size_t)kGrpTok * a.H * sizeof(T);

@@ -267,7 +267,7 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
     std::memset(h->rec_host, 0, sizeof(StepRec));
     h->spin_limit = env_int("SMOE_SPIN_LIMIT", 4000000);
     h->route_fast = env_int("SMOE_ROUTE_FAST", 1);
-    h->mfma_ok = env_int("SMOE_MFMA", 1);
+    h->mfma_ok = env_int("SMOE_MFMA", 2);   // 0: vector ALUs, 1: MFMA down only, 2: MFMA up and down
     void* dp = nullptr;
     HIP_TRY(hipHostGetDevicePointer(&dp, h->rec_host, 0));
     h->rec_host_dev = static_cast<StepRec*>(dp);
@@ -351,6 +351,7 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   fa.grouped = (B > 1 && h->grouped_ok) ? 1 : 0;
   fa.maxg = std::min(E, B * k);
   fa.mfma_down = (fa.grouped && c.dtype == SMOE_DTYPE_BF16 && h->mfma_ok) ? 1 : 0;
+  fa.mfma_up = (fa.mfma_down && h->mfma_ok >= 2) ? 1 : 0;
   fa.nsegGR = h->nsegGR; fa.nsegGS = h->nsegGS; fa.RBG = h->RBG;
   fa.act_shared_off = (int64_t)fa.maxg * SMOE_MAX_BATCH * c.ffn;
   if (fa.grouped && fa.up_upl == 0) {                 // grouped up kernel needs units per lane

@@ -150,7 +150,7 @@ def test_batched_decode_cross_token_substitution_and_staging(batch):
         assert r["stats"]["staged"] > 0
 
 
-@pytest.mark.parametrize("env", [dict(), dict(SMOE_MFMA="0")])
+@pytest.mark.parametrize("env", [dict(), dict(SMOE_MFMA="1"), dict(SMOE_MFMA="0")])
 def test_batched_decode_ragged_shapes_matrix_core_and_vector_down_kernels(env, monkeypatch):
     """bf16 batch with rows and columns that do not fill the 16 x 256 MFMA tiles,
     and the vector-ALU grouped down kernel it replaces."""
