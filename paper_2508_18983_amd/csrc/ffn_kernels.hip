@@ -749,6 +749,7 @@ constexpr int kMfmaCols = 256;                  // columns per item
 constexpr int kMfmaRowBytes = 2 * kMfmaCols + 16;   // staged row + pad against bank conflicts
 constexpr int kMfmaWaves = 8;
 constexpr int kMfmaLdsBytes = kMfmaWaves * 16 * kMfmaRowBytes;
+constexpr int kMfmaTaskTabBytes = (SMOE_MAX_EXPERTS + SMOE_MAX_SHARED) * 48;
 
 // Batch > 1, bf16: up projection on the matrix cores.  A block = one task x 64
 // f-rows; each of its four waves owns 16 rows of W1 and the same 16 rows of W3
@@ -858,6 +859,34 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void ffn_down_mfma_kernel(const Ff
   unsigned char* stage = lds + (size_t)wave * 16 * kMfmaRowBytes;
   int next_it = 0;                          // item index at which describe() last stopped
 
+  // Task table in LDS (built once per block): decoding an item must not cost a
+  // round trip to the decision record in the middle of the pipeline.
+  struct TaskEnt {
+    const char* w2;          // W2 of the task, null = not in this pass
+    const float* act;        // its activation rows
+    int F, ntok;
+    signed char pos_of_tok[16];   // position of token j in the task's list, -1 = absent
+  };
+  static_assert(sizeof(TaskEnt) <= 48, "task table entry outgrew its LDS budget");
+  TaskEnt* ttab = reinterpret_cast<TaskEnt*>(lds + kMfmaLdsBytes);
+  const int n_tasks = a.maxg + a.ns;
+  for (int task = tid; task < n_tasks; task += 64 * kMfmaWaves) {
+    const GrpTask g = grp_task<PASS>(a, task);
+    TaskEnt e;
+    e.w2 = g.base ? g.base + 2 * (size_t)g.F * H * sizeof(bf16_t) : nullptr;
+    e.act = g.act;
+    e.F = g.F;
+    e.ntok = g.ntok;
+    for (int j = 0; j < 16; ++j) {
+      int pos = -1;
+#pragma unroll
+      for (int q = 0; q < SMOE_MAX_BATCH; ++q) pos = (q < g.ntok && g.tok[q] == j) ? q : pos;
+      e.pos_of_tok[j] = (signed char)pos;
+    }
+    ttab[task] = e;
+  }
+  __syncthreads();
+
   // One item: where its 16 x 256 weight tile and this lane's activation row live.
   struct Item {
     const bf16_t* w2;        // W2 + c0 of row 0 of the matrix
@@ -872,24 +901,18 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void ffn_down_mfma_kernel(const Ff
       int task, seg;
       if (it < items_r) { task = it / nsegR; seg = it - task * nsegR; }
       else { const int q = it - items_r; const int sidx = q / nsegS; seg = q - sidx * nsegS; task = a.maxg + sidx; }
-      const GrpTask g = grp_task<PASS>(a, task);
-      if (g.base == nullptr) continue;
+      const TaskEnt& e = ttab[task];
+      if (e.w2 == nullptr) continue;
       const int c0 = seg * kMfmaCols;
-      int pos = -1;                       // this lane's tile column is token i16
-#pragma unroll
-      for (int q = 0; q < SMOE_MAX_BATCH; ++q) pos = (q < g.ntok && g.tok[q] == i16) ? q : pos;
-      d.F = g.F;
-      d.ncols = min(kMfmaCols, g.F - c0);
-      d.w2 = reinterpret_cast<const bf16_t*>(g.base) + 2 * (size_t)g.F * H + c0;
-      d.arow = reinterpret_cast<const uint16_t*>(g.act + (size_t)max(pos, 0) * g.F) + c0;
+      const int pos = e.pos_of_tok[i16];
+      d.F = e.F;
+      d.ncols = min(kMfmaCols, e.F - c0);
+      d.w2 = reinterpret_cast<const bf16_t*>(e.w2) + c0;
+      d.arow = reinterpret_cast<const uint16_t*>(e.act + (size_t)max(pos, 0) * e.F) + c0;
       d.pos = pos;
       d.valid = true;
       break;
     }
-    d.ncols = d.valid ? d.ncols : 0;
-    d.F = d.valid ? d.F : 0;
-    d.pos = d.valid ? d.pos : -1;
-    // remember where the scan stopped
     next_it = it;
     return d;
   };
@@ -1027,11 +1050,12 @@ static void launch_down_t(const FfnArgs& a, hipStream_t s) {
       static bool lds_opted_in[2] = {false, false};   // the staging area is larger than the 64 KB default
       if (!lds_opted_in[PASS]) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_down_mfma_kernel<PASS>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, kMfmaLdsBytes);
+                                  hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  kMfmaLdsBytes + kMfmaTaskTabBytes);
         lds_opted_in[PASS] = true;
       }
       hipLaunchKernelGGL((ffn_down_mfma_kernel<PASS>), dim3((a.H + 15) / 16), dim3(64 * kMfmaWaves),
-                         kMfmaLdsBytes, s, a);
+                         kMfmaLdsBytes + kMfmaTaskTabBytes, s, a);
       return;
     }
     const int grid = (a.H + a.RBG - 1) / a.RBG;
