@@ -189,7 +189,8 @@ int moe_cache_destroy(moe_handle_t* h);
 
 /* Per-kernel timing.  enable = bit mask of SMOE_PROF_* kinds to record with
  * event pairs (bit i = kind i; at most max_launches launches per kind are
- * recorded; counters restart), enable = 0 stops.
+ * recorded, later ones add neither time nor bytes; counters restart),
+ * enable = 0 stops.
  * moe_profile_read drains the compute and copy streams and returns the totals
  * recorded since the last enable. */
 int moe_profile_enable(moe_handle_t* h, int32_t enable, int32_t max_launches);

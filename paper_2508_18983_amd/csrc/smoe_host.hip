@@ -400,6 +400,7 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   const int* fetched = plan.fetched;
   const int* victims = plan.victims;
   int gslot[SMOE_MAX_BATCH * SMOE_MAX_TOPK];
+  bool timed_up2 = false, timed_down2 = false;
 
   if (n_fetch > 0) {
     // ---- loads on the copy stream; the second FFN pass waits for them ---------
@@ -412,6 +413,7 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
       EventPair* pc = prof_begin(h, SMOE_PROF_COPY, h->s_copy);
       HIP_TRY(hipMemcpyAsync(dst, src, h->expert_bytes, hipMemcpyHostToDevice, h->s_copy));
       prof_end(pc, h->s_copy);
+      if (pc) h->prof[SMOE_PROF_COPY].bytes += h->expert_bytes;   // bytes of timed copies only
     }
     HIP_TRY(hipEventRecord(h->ev_copy, h->s_copy));
     HIP_TRY(hipStreamWaitEvent(h->s_compute, h->ev_copy, 0));
@@ -438,10 +440,13 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
     EventPair* pd2 = prof_begin(h, SMOE_PROF_DOWN_LOADED, h->s_compute);
     launch_ffn_down(fa, c.dtype, h->s_compute);
     prof_end(pd2, h->s_compute);
+    timed_up2 = pu2 != nullptr;
+    timed_down2 = pd2 != nullptr;
     HIP_TRY(hipGetLastError());
   }
   if (h->prof_mask) {
-    // algorithmic bytes each timed launch was asked to stream
+    // algorithmic bytes each timed launch was asked to stream (launches past the end of
+    // the event pool are not timed and add no bytes)
     int64_t miss_slots = (int64_t)B * k - hits;
     int64_t res_slots = hits, shared_times = B;
     if (fa.grouped) {                                 // weights are streamed once per distinct expert
@@ -450,12 +455,11 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
       shared_times = 1;
     }
     const int64_t up_r = 2ll * c.hidden * c.ffn * h->esize, up_s = 2ll * c.hidden * c.shared_ffn * h->esize;
-    h->prof[SMOE_PROF_ROUTE].bytes += (int64_t)E * c.hidden * h->esize;
-    h->prof[SMOE_PROF_UP].bytes += res_slots * up_r + shared_times * c.n_shared * up_s;
-    h->prof[SMOE_PROF_DOWN].bytes += (res_slots * up_r + shared_times * c.n_shared * up_s) / 2;
-    h->prof[SMOE_PROF_COPY].bytes += (int64_t)n_fetch * h->expert_bytes;
-    h->prof[SMOE_PROF_UP_LOADED].bytes += miss_slots * up_r;
-    h->prof[SMOE_PROF_DOWN_LOADED].bytes += miss_slots * up_r / 2;
+    if (pr) h->prof[SMOE_PROF_ROUTE].bytes += (int64_t)E * c.hidden * h->esize;
+    if (pu) h->prof[SMOE_PROF_UP].bytes += res_slots * up_r + shared_times * c.n_shared * up_s;
+    if (pd) h->prof[SMOE_PROF_DOWN].bytes += (res_slots * up_r + shared_times * c.n_shared * up_s) / 2;
+    if (timed_up2) h->prof[SMOE_PROF_UP_LOADED].bytes += miss_slots * up_r;
+    if (timed_down2) h->prof[SMOE_PROF_DOWN_LOADED].bytes += miss_slots * up_r / 2;
   }
 
   if (trace) {
