@@ -20,6 +20,9 @@ that depend on a convention alone are "parity unpinned" by the paper:
   the paper ranks by gate score (``subst_key=1``, pinned)     -- parity unpinned
 * eviction window n (default 3), initial residency, tie rules, staging when
   every resident expert is shielded, two-pass set C at batch>1 -- parity unpinned
+* top-score prefetch (``prefetch_layer``): the predicted hidden state is an
+  input; order of the prefetches, their cap, the shield of the predicted
+  actives and the stamps of a prefetch load are conventions   -- parity unpinned
 
 Inputs are the stored fp32 / bf16 values (bf16 arrives as raw uint16); all
 arithmetic is fp64 with no intermediate rounding.
@@ -247,6 +250,7 @@ class LayerCache:
     last_use: Dict[int, int] = field(default_factory=dict)
     load_stamp: Dict[int, int] = field(default_factory=dict)
     use_count: Dict[int, int] = field(default_factory=dict)
+    prefetched: Set[int] = field(default_factory=set)   # prefetched since the layer's last step
 
     @property
     def resident(self) -> Set[int]:
@@ -265,6 +269,9 @@ class Stats:
     staged: int = 0
     fetches: int = 0
     bytes_fetched: int = 0
+    prefetches: int = 0
+    prefetch_used: int = 0      # prefetched experts the layer's next step computed
+    prefetch_top: int = 0       # ... that were top-score experts of that step
 
     def add(self, o: "Stats") -> "Stats":
         return Stats(*[getattr(self, f) + getattr(o, f) for f in self.__dataclass_fields__])
@@ -284,6 +291,17 @@ class StepResult:
     fetched: List[int]            # distinct missing experts in fetch order
     victims: List[int]            # evicted expert per fetch, -1 when staged
     y: Optional[np.ndarray]       # [B, H] fp64 or None
+    route_margin: float
+    evict_margin: float
+
+
+@dataclass
+class PrefetchResult:
+    scores: np.ndarray            # [B, E] fp64 scores of the predicted hidden states
+    topk: np.ndarray              # [B, k] predicted active experts
+    wanted: List[int]             # predicted top-score experts that were not resident, in load order
+    prefetched: List[int]         # the ones that were loaded
+    victims: List[int]            # expert evicted for each
     route_margin: float
     evict_margin: float
 
@@ -358,6 +376,77 @@ class SMoEOracle:
         self._wcache_bytes += 24 * hf
         return w1, w3, w2
 
+    # -- top-score prefetch ------------------------------------------------
+    def prefetch_layer(self, layer: int, x_pred: np.ndarray, max_experts: int) -> PrefetchResult:
+        """Section IV-C ("Loading Top-score Expert Online"): the gate of a layer
+        that has not run yet is applied to a *predicted* hidden state, the
+        experts it ranks in the top-k are classified with the same threshold
+        T = (1+alpha) S_{k+1}, and only the top-score ones are loaded ahead of
+        time; low-score ones are left to the substitution of Algorithm 1.  How
+        the prediction is made (partial layer output -> next layer's attention)
+        lies outside this step: ``x_pred`` [B, H] is an input.
+
+        *Conventions*: loads go in descending predicted score (largest over the
+        batch, lower id on ties), at most ``max_experts`` of them; every
+        predicted active expert is shielded while victims are chosen with the
+        layer's eviction policy over its current history (an empty history
+        counts as mean 0 for everyone); when nothing is evictable the rest is
+        dropped; a prefetch load is stamped just before the layer's next step.
+        A wrong prediction is simply a resident expert nobody asked for: the
+        step itself then loads what it needs as usual."""
+        x_pred = np.atleast_2d(x_pred)
+        B = x_pred.shape[0]
+        k, E = self.k, self.E
+        cache = self.layers[layer]
+        st = self.stats_per_layer[layer]
+        G = cache.resident
+        infos = [route(softmax_scores(gate_logits(self.gate_w[layer], x_pred[t])), k, self.alpha)
+                 for t in range(B)]
+        route_margin = np.inf
+        best: Dict[int, float] = {}
+        shield: Set[int] = set()
+        for info in infos:
+            ls = np.log(info.scores[info.order[:min(E, k + 1)]])
+            if len(ls) > 1:
+                route_margin = min(route_margin, float(np.min(ls[:-1] - ls[1:])))
+            if info.T is not None:
+                for e in info.topk:
+                    route_margin = min(route_margin, abs(float(np.log(info.scores[e] / info.T))))
+            shield |= set(info.topk)
+            for e in info.top_score:
+                best[e] = max(best.get(e, -np.inf), float(info.scores[e]))
+        wanted = sorted((e for e in best if e not in G), key=lambda e: (-best[e], e))
+        if cache.history:
+            means = mean_window_scores(cache.history)
+        else:
+            means = np.zeros(E)
+        stamp = cache.step * 64 - 1
+        prefetched: List[int] = []
+        victims: List[int] = []
+        evict_margin = np.inf
+        for m in wanted[:max(0, max_experts)]:
+            evictable = [e for e in cache.slot_expert if e not in shield]
+            if not evictable:
+                break
+            if self.evict_policy == EVICT_SCORE:
+                v, gap = pick_victim(means, evictable)
+                if cache.history:
+                    evict_margin = min(evict_margin, gap)
+            else:
+                v = pick_victim_baseline(self.evict_policy, evictable, cache.last_use,
+                                         cache.load_stamp, cache.use_count)
+            cache.slot_expert[cache.slot_expert.index(v)] = m
+            cache.load_stamp[m] = cache.last_use[m] = stamp
+            cache.use_count[m] = 0
+            cache.prefetched.add(m)
+            prefetched.append(m)
+            victims.append(v)
+            st.evictions += 1
+            st.prefetches += 1
+        return PrefetchResult(np.stack([i.scores for i in infos]),
+                              np.array([i.topk for i in infos], dtype=np.int64),
+                              wanted, prefetched, victims, float(route_margin), float(evict_margin))
+
     # -- the step ---------------------------------------------------------
     def decode_layer(self, layer: int, x: np.ndarray, compute_y: bool = True) -> StepResult:
         """x: [B, H] stored values.  Order of operations (Section V-B,
@@ -409,6 +498,11 @@ class SMoEOracle:
         means = mean_window_scores(cache.history)
 
         shield = set(int(e) for e in final.reshape(-1))
+        # prefetch accuracy: a prefetched expert counts as used when the layer's
+        # next step computes it (Section VI reports this as prediction accuracy)
+        st.prefetch_used += len(cache.prefetched & shield)
+        st.prefetch_top += len(cache.prefetched & C)
+        cache.prefetched = set()
         fetched: List[int] = []
         for pos, e in enumerate(final.reshape(-1)):          # (token, slot) order
             e = int(e)

@@ -87,6 +87,7 @@ class Workload:
     sim: torch.Tensor                 # [L, E, E] fp32, host
     x: torch.Tensor                   # [T, L, B, H] storage dtype, host
     redraws: int                      # token-layers the margin audit redrew
+    x_pred: Optional[torch.Tensor] = None   # [T, L, B, H] predicted hidden states (prefetch input)
 
     def expert_mats(self, layer: int, e: int):
         s = self.shape
@@ -143,14 +144,21 @@ def _uniform_table(e: int, rng: np.random.Generator) -> torch.Tensor:
 def make_workload(shape: MoEShape, device: str = "cpu", n_layers: int | None = None,
                   tokens: int | None = None, batch: int | None = None,
                   host_alloc=None, distinct_layers: int | None = None,
-                  delta: float = LOGIT_DELTA) -> Workload:
+                  delta: float = LOGIT_DELTA, pred_noise: float | None = None) -> Workload:
     """Draw one workload.  ``device`` is where the normal deviates for the
     weights are drawn ("cuda" makes the 100 GB shapes practical); everything
     is returned in host memory.  ``host_alloc(n_elems, dtype)`` may supply the
     (pinned) storage of each layer's experts.  With ``distinct_layers = D < L``
     only D layers of expert weights are drawn and layer l uses the block of
     layer l mod D (for hosts that cannot pin the whole model); gate weights,
-    similarity tables and hidden states stay distinct per layer."""
+    similarity tables and hidden states stay distinct per layer.
+
+    ``pred_noise = sigma`` also draws the *predicted* hidden states a prefetcher
+    would be given (a stand-in for a predictor that sees the layer's input
+    before it exists): x_pred = x + sigma * N(0, 1), rounded to the storage
+    dtype, from a generator of its own so that x does not depend on it, and
+    audited like x (top-(k+1) order and the threshold T of the predicted
+    scores)."""
     L = shape.n_layers if n_layers is None else n_layers
     T = shape.tokens if tokens is None else tokens
     B = shape.batch if batch is None else batch
@@ -158,6 +166,7 @@ def make_workload(shape: MoEShape, device: str = "cpu", n_layers: int | None = N
     dt = _tdtype(shape)
     gen = torch.Generator(device=device)
     rng = np.random.default_rng([shape.seed, 0x5E0E])
+    rng_pred = np.random.default_rng([shape.seed, 0x9FE7])
 
     gate_w = torch.empty(L, E, H, dtype=dt)
     D = L if distinct_layers is None else max(1, min(L, distinct_layers))
@@ -184,6 +193,7 @@ def make_workload(shape: MoEShape, device: str = "cpu", n_layers: int | None = N
     # ---- hidden states -------------------------------------------------
     wg64 = _to_f64(gate_w)                                   # [L, E, H]
     x = torch.empty(T, L, B, H, dtype=dt)
+    x_pred = torch.empty(T, L, B, H, dtype=dt) if pred_noise is not None else None
     redraws = 0
     if shape.prior == "zipf":
         ranks = np.arange(1, E + 1, dtype=np.float64)
@@ -231,4 +241,24 @@ def make_workload(shape: MoEShape, device: str = "cpu", n_layers: int | None = N
             todo[li[good], bi[good]] = False
         x[t] = torch.from_numpy(xt).to(dt)
         prev_top = np.argsort(-lt, axis=2, kind="stable")[:, :, :k]
-    return Workload(shape.with_(n_layers=L, tokens=T, batch=B), gate_w, experts, shared, sim, x, redraws)
+        if x_pred is not None:
+            xq = x[t].to(torch.float64).numpy()                      # [L, B, H]
+            xp = np.empty((L, B, H))
+            todo = np.ones((L, B), dtype=bool)
+            attempt = 0
+            while todo.any():
+                attempt += 1
+                if attempt > 200:
+                    raise RuntimeError("margin audit of the predicted states keeps failing")
+                li, bi = np.nonzero(todo)
+                cand = xq[li, bi] + pred_noise * rng_pred.standard_normal((li.size, H))
+                c64 = torch.from_numpy(cand).to(dt).to(torch.float64).numpy()
+                logit = np.einsum("meh,mh->me", wg64[li], c64)
+                ok = logit_margin_ok(logit, k, shape.alpha, delta)
+                redraws += int((~ok).sum())
+                good = np.nonzero(ok)[0]
+                xp[li[good], bi[good]] = c64[good]
+                todo[li[good], bi[good]] = False
+            x_pred[t] = torch.from_numpy(xp).to(dt)
+    return Workload(shape.with_(n_layers=L, tokens=T, batch=B), gate_w, experts, shared, sim, x, redraws,
+                    x_pred)

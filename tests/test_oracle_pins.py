@@ -484,3 +484,128 @@ def test_score_eviction_beats_lru_on_skewed_popularity():
         st = orc.stats()
         rates[policy] = st.hits / st.slots
     assert rates[O.EVICT_SCORE] > rates[O.EVICT_LRU]
+
+
+# ---------------------------------------------------------------- top-score prefetch (Section IV-C)
+def _prefetch_workload(alpha, pred_noise, tokens=24, seed=3):
+    shp = SHAPES["c4"].with_(n_layers=2, hidden=256, ffn=8, shared_ffn=8, n_shared=0, n_experts=16,
+                             top_k=3, cache_cap=6, alpha=alpha, tokens=tokens, seed=seed)
+    return make_workload(shp, pred_noise=pred_noise)
+
+
+def test_prefetch_with_exact_prediction_leaves_only_low_score_misses():
+    """If the predicted state equals the real one and up to k experts may be
+    prefetched, every top-score expert is resident when its layer runs: what
+    is still loaded on demand are low-score experts only, every prefetched
+    expert is used, and each one is a top-score expert of the step."""
+    wl = _prefetch_workload(0.3, 0.0)
+    orc = O.oracle_from_workload(wl)
+    s = wl.shape
+    n_pref = 0
+    for t in range(s.tokens):
+        for l in range(s.n_layers):
+            x = as_numpy(wl.x[t, l])
+            pf = orc.prefetch_layer(l, x, s.top_k)
+            n_pref += len(pf.prefetched)
+            G = orc.layers[l].resident
+            res = orc.decode_layer(l, x, compute_y=False)
+            info = O.route(res.scores[0], s.top_k, orc.alpha)
+            assert set(info.top_score) <= G
+            assert set(res.fetched) <= set(info.low_score)
+            assert pf.topk[0].tolist() == info.topk
+    st = orc.stats()
+    assert n_pref == st.prefetches > 0
+    assert st.prefetch_used == st.prefetch_top == st.prefetches
+
+
+def test_prefetch_alpha_zero_exact_prediction_removes_every_miss():
+    """alpha = 0 makes every active expert top-score (s >= S_{k+1}), so an exact
+    prediction with a cap of k prefetches leaves nothing to load on demand."""
+    wl = _prefetch_workload(0.0, 0.0)
+    orc = O.oracle_from_workload(wl)
+    s = wl.shape
+    for t in range(s.tokens):
+        for l in range(s.n_layers):
+            x = as_numpy(wl.x[t, l])
+            orc.prefetch_layer(l, x, s.top_k)
+            res = orc.decode_layer(l, x, compute_y=False)
+            assert res.fetched == [] and res.hit.all()
+    st = orc.stats()
+    assert st.misses == 0 and st.fetches == 0 and st.hits == st.slots
+    assert st.evictions == st.prefetches
+
+
+def test_prefetch_cap_zero_changes_nothing():
+    wl = _prefetch_workload(0.25, 0.4)
+    a = O.oracle_from_workload(wl)
+    b = O.oracle_from_workload(wl)
+    s = wl.shape
+    for t in range(s.tokens):
+        for l in range(s.n_layers):
+            pf = b.prefetch_layer(l, as_numpy(wl.x_pred[t, l]), 0)
+            assert pf.prefetched == [] and pf.victims == []
+            ra = a.decode_layer(l, as_numpy(wl.x[t, l]), compute_y=False)
+            rb = b.decode_layer(l, as_numpy(wl.x[t, l]), compute_y=False)
+            assert ra.final.tolist() == rb.final.tolist() and ra.victims == rb.victims
+            assert a.layers[l].slot_expert == b.layers[l].slot_expert
+    assert a.stats().as_dict() == b.stats().as_dict()
+
+
+def test_prefetch_choice_order_shield_and_victim_bruteforce():
+    """Brute force over the stored history: the prefetched experts are the
+    non-resident ones among the predicted top-k whose predicted score reaches
+    (1+alpha) x the (k+1)-th, taken by descending score up to the cap; victims
+    are the unshielded residents with the smallest mean score over the last
+    n+1 steps of that layer; the cache keeps its size and no predicted active
+    expert is evicted."""
+    wl = _prefetch_workload(0.25, 0.5, tokens=40, seed=5)
+    orc = O.oracle_from_workload(wl)
+    s = wl.shape
+    k, cap_pf = s.top_k, 2
+    log = [[] for _ in range(s.n_layers)]            # full score log per layer
+    seen = 0
+    for t in range(s.tokens):
+        for l in range(s.n_layers):
+            G0 = list(orc.layers[l].slot_expert)
+            pf = orc.prefetch_layer(l, as_numpy(wl.x_pred[t, l]), cap_pf)
+            sc = scipy.special.softmax(
+                O.widen(as_numpy(wl.gate_w[l])) @ O.widen(as_numpy(wl.x_pred[t, l, 0])))
+            ranked = sorted(range(s.n_experts), key=lambda e: (-sc[e], e))
+            act, pivot = ranked[:k], sc[ranked[k]]
+            want = [e for e in act if sc[e] >= (1 + orc.alpha) * pivot and e not in G0]
+            assert pf.wanted == want
+            G = list(G0)
+            for m in want[:cap_pf]:
+                ev = [e for e in G if e not in act]
+                if not ev:
+                    break
+                window = log[l][-(s.evict_window + 1):]
+                mean = {e: (sum(v[e] for v in window) / len(window) if window else 0.0) for e in ev}
+                v = min(ev, key=lambda e: (mean[e], e))
+                G[G.index(v)] = m
+            assert orc.layers[l].slot_expert == G
+            assert len(set(G)) == s.cache_cap
+            assert all(e in G for e in act if e in G0)
+            seen += len(pf.prefetched)
+            res = orc.decode_layer(l, as_numpy(wl.x[t, l]), compute_y=False)
+            log[l].append(res.scores[0])
+    st = orc.stats()
+    assert seen == st.prefetches > 10
+    assert 0 < st.prefetch_top <= st.prefetch_used < st.prefetches   # noisy prediction: some are wasted
+
+
+def test_prefetch_raises_hit_rate_with_a_good_predictor():
+    """Section VI-C (+Pre): with an accurate predictor fewer experts are loaded
+    on demand and the cache hit rate goes up."""
+    wl = _prefetch_workload(0.2, 0.15, tokens=64, seed=7)
+    base = O.oracle_from_workload(wl)
+    pre = O.oracle_from_workload(wl)
+    s = wl.shape
+    for t in range(s.tokens):
+        for l in range(s.n_layers):
+            pre.prefetch_layer(l, as_numpy(wl.x_pred[t, l]), s.top_k)
+            base.decode_layer(l, as_numpy(wl.x[t, l]), compute_y=False)
+            pre.decode_layer(l, as_numpy(wl.x[t, l]), compute_y=False)
+    assert pre.stats().hits > base.stats().hits
+    assert pre.stats().fetches < base.stats().fetches
+    assert pre.stats().prefetch_used / pre.stats().prefetches > 0.7
