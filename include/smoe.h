@@ -16,6 +16,10 @@
  *   expert FFN        SwiGLU FFN of the chosen experts + shared experts and the
  *                     weighted combine (Section V-B GPU operations 2 and 4,
  *                     Section II-A for shared experts)
+ *   top-score         optional: the gate of a layer that has not run yet is applied
+ *   prefetch          to a predicted hidden state and its top-score experts are
+ *                     loaded behind the current layer's own loads (Section IV-C;
+ *                     Section V-B, "Prefetching Experts from Layer i+1")
  *
  * All entry points return 0 on success or a negative SMOE_E* code; nothing
  * throws across this boundary.  "device" pointers are HIP device pointers on
@@ -89,6 +93,8 @@ typedef struct {
   int32_t n_stage;       /* transient slots after the L*cap cache slots, used when a
                             missing expert finds no evictable resident (batch > 1)   */
   int32_t evict_policy;  /* SMOE_EVICT_*: which unshielded resident a load replaces   */
+  int32_t prefetch_max;  /* experts one moe_prefetch_layer call may load (0: prefetch
+                            is off and that call is refused)                          */
 } moe_cfg_t;
 
 typedef struct {
@@ -135,7 +141,22 @@ typedef struct {
   int64_t staged;         /* loads computed from a transient slot, not inserted            */
   int64_t fetches;        /* expert loads issued                                           */
   int64_t bytes_fetched;  /* fetches * expert bytes                                        */
+  int64_t prefetches;     /* experts loaded ahead of time by moe_prefetch_layer (each also
+                             counts as an eviction, none as a fetch)                       */
+  int64_t prefetch_used;  /* ... that the layer's next step computed                       */
+  int64_t prefetch_top;   /* ... that were top-score experts (s >= T) of that step         */
 } moe_stats_t;
+
+/* What the most recent prefetch did (moe_prefetch_last). */
+typedef struct {
+  int32_t layer;                                       /* -1: no prefetch so far           */
+  int32_t n_wanted;                                    /* predicted top-score experts that
+                                                          were not resident                */
+  int32_t n_loaded;                                    /* how many of them were loaded     */
+  int32_t wanted[SMOE_MAX_BATCH * SMOE_MAX_TOPK];      /* in load order                    */
+  int32_t victims[SMOE_MAX_BATCH * SMOE_MAX_TOPK];     /* expert evicted for wanted[i],
+                                                          i < n_loaded                     */
+} moe_prefetch_info_t;
 
 /* In-stream duration of the launches, measured with HIP events recorded on the
  * launching stream around every launch while profiling is enabled.  Kinds:
@@ -175,11 +196,35 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
 int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch,
                      const void* x_dev, void* y_dev, moe_trace_t* trace_or_null);
 
-/* Counters of one layer, or of all layers summed when layer == -1. */
-int moe_cache_stats(const moe_handle_t* h, int32_t layer, moe_stats_t* out);
+/* Top-score prefetch for a layer that has not run yet (Section IV-C).
+ *   x_pred_dev  device [batch][H] dtype: the caller's prediction of the hidden
+ *               state `layer` will see (read until the compute stream drains)
+ * Enqueues the gate of `layer` on x_pred (router kernel, compute stream) and
+ * returns at once.  The decision is taken by the next call on the handle:
+ * a moe_decode_layer of ANOTHER layer first queues its own loads and then the
+ * prefetch loads behind them on stream_copy (so a prefetch never delays a load
+ * the running layer waits for); any other call (a decode of `layer` itself,
+ * stats, residency, another prefetch, reset) settles it first.  Loaded are the
+ * experts the predicted scores rank in the top-k with score >= T = (1+alpha)
+ * S_{k+1} and that are not resident, in rank order (token by token), at most
+ * cfg.prefetch_max; each replaces the victim the eviction policy picks among
+ * the residents outside the predicted top-k; loading stops when none is left.
+ * The score history is not touched.  A later moe_decode_layer(layer) waits for
+ * these copies only if they have not completed.  A wrong prediction costs the
+ * copy and the evicted expert, nothing else: the layer loads what it needs on
+ * demand as always.
+ * SMOE_EINVAL for a bad layer / batch, NULL x_pred or prefetch_max == 0. */
+int moe_prefetch_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* x_pred_dev);
+
+/* Settles a pending prefetch and reports what the latest one decided. */
+int moe_prefetch_last(moe_handle_t* h, moe_prefetch_info_t* out);
+
+/* Counters of one layer, or of all layers summed when layer == -1.  (Takes a
+ * non-const handle since a pending prefetch is settled first.) */
+int moe_cache_stats(moe_handle_t* h, int32_t layer, moe_stats_t* out);
 
 /* Expert id held by each cache slot of `layer`: out_slots[cache_cap]. */
-int moe_cache_residency(const moe_handle_t* h, int32_t layer, int32_t* out_slots);
+int moe_cache_residency(moe_handle_t* h, int32_t layer, int32_t* out_slots);
 
 /* Drain both streams, reload the initial residents, zero history and counters. */
 int moe_cache_reset(moe_handle_t* h);

@@ -386,8 +386,8 @@ class SMoEOracle:
         the prediction is made (partial layer output -> next layer's attention)
         lies outside this step: ``x_pred`` [B, H] is an input.
 
-        *Conventions*: loads go in descending predicted score (largest over the
-        batch, lower id on ties), at most ``max_experts`` of them; every
+        *Conventions*: loads go in descending predicted score (batch > 1: token
+        by token, skipping repeats), at most ``max_experts`` of them; every
         predicted active expert is shielded while victims are chosen with the
         layer's eviction policy over its current history (an empty history
         counts as mean 0 for everyone); when nothing is evictable the rest is
@@ -403,7 +403,7 @@ class SMoEOracle:
         infos = [route(softmax_scores(gate_logits(self.gate_w[layer], x_pred[t])), k, self.alpha)
                  for t in range(B)]
         route_margin = np.inf
-        best: Dict[int, float] = {}
+        wanted: List[int] = []
         shield: Set[int] = set()
         for info in infos:
             ls = np.log(info.scores[info.order[:min(E, k + 1)]])
@@ -413,9 +413,9 @@ class SMoEOracle:
                 for e in info.topk:
                     route_margin = min(route_margin, abs(float(np.log(info.scores[e] / info.T))))
             shield |= set(info.topk)
-            for e in info.top_score:
-                best[e] = max(best.get(e, -np.inf), float(info.scores[e]))
-        wanted = sorted((e for e in best if e not in G), key=lambda e: (-best[e], e))
+            for e in info.topk:                       # rank order = descending score
+                if e in info.top_score and e not in G and e not in wanted:
+                    wanted.append(e)
         if cache.history:
             means = mean_window_scores(cache.history)
         else:

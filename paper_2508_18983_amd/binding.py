@@ -29,7 +29,7 @@ class MoeCfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "hidden", "n_experts", "ffn", "top_k", "cache_cap", "n_shared",
         "shared_ffn", "dtype", "max_batch")] + [("alpha", C.c_float)] + [(n, C.c_int32) for n in (
-        "subst_key", "renorm_topk", "evict_window", "n_stage", "evict_policy")]
+        "subst_key", "renorm_topk", "evict_window", "n_stage", "evict_policy", "prefetch_max")]
 
 
 class MoeBuffers(C.Structure):
@@ -47,10 +47,20 @@ class MoeTrace(C.Structure):
 class MoeStats(C.Structure):
     _fields_ = [(n, C.c_int64) for n in (
         "tokens", "slots", "raw_hits", "hits", "misses", "substitutions", "evictions", "staged",
-        "fetches", "bytes_fetched")]
+        "fetches", "bytes_fetched", "prefetches", "prefetch_used", "prefetch_top")]
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}
+
+
+class MoePrefetchInfo(C.Structure):
+    _fields_ = [("layer", C.c_int32), ("n_wanted", C.c_int32), ("n_loaded", C.c_int32),
+                ("wanted", C.c_int32 * 64), ("victims", C.c_int32 * 64)]
+
+    def as_dict(self):
+        return dict(layer=int(self.layer), wanted=[int(v) for v in self.wanted[:self.n_wanted]],
+                    loaded=[int(v) for v in self.wanted[:self.n_loaded]],
+                    victims=[int(v) for v in self.victims[:self.n_loaded]])
 
 
 class MoeProfile(C.Structure):
@@ -78,6 +88,8 @@ def load_library():
     P, I = C.c_void_p, C.c_int32
     lib.moe_cache_init.argtypes = [C.POINTER(MoeCfg), C.POINTER(MoeBuffers), C.POINTER(P)]
     lib.moe_decode_layer.argtypes = [P, I, I, P, P, C.POINTER(MoeTrace)]
+    lib.moe_prefetch_layer.argtypes = [P, I, I, P]
+    lib.moe_prefetch_last.argtypes = [P, C.POINTER(MoePrefetchInfo)]
     lib.moe_cache_stats.argtypes = [P, I, C.POINTER(MoeStats)]
     lib.moe_cache_residency.argtypes = [P, I, P]
     lib.moe_cache_reset.argtypes = [P]
@@ -88,7 +100,7 @@ def load_library():
     lib.moe_calib_copy.argtypes = [P, P, C.c_int64, P]
     lib.moe_host_alloc.argtypes = [C.c_int64, C.POINTER(P)]
     lib.moe_host_free.argtypes = [P]
-    for fn in ("moe_cache_init", "moe_decode_layer", "moe_cache_stats", "moe_cache_residency",
+    for fn in ("moe_cache_init", "moe_decode_layer", "moe_prefetch_layer", "moe_prefetch_last", "moe_cache_stats", "moe_cache_residency",
                "moe_cache_reset", "moe_cache_destroy", "moe_profile_enable", "moe_profile_read",
                "moe_last_hip_error", "moe_calib_copy", "moe_host_alloc", "moe_host_free"):
         getattr(lib, fn).restype = C.c_int
@@ -136,6 +148,16 @@ def moe_decode_layer(handle: int, layer: int, batch: int, x_dev: int, y_dev: int
                      trace: Optional[Trace] = None) -> None:
     tp = C.byref(trace.c) if trace is not None else None
     _check("moe_decode_layer", load_library().moe_decode_layer(handle, layer, batch, x_dev, y_dev, tp))
+
+
+def moe_prefetch_layer(handle: int, layer: int, batch: int, x_pred_dev: int) -> None:
+    _check("moe_prefetch_layer", load_library().moe_prefetch_layer(handle, layer, batch, x_pred_dev))
+
+
+def moe_prefetch_last(handle: int) -> MoePrefetchInfo:
+    info = MoePrefetchInfo()
+    _check("moe_prefetch_last", load_library().moe_prefetch_last(handle, C.byref(info)))
+    return info
 
 
 def moe_cache_stats(handle: int, layer: int = -1) -> MoeStats:

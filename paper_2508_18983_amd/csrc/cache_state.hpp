@@ -14,6 +14,8 @@ namespace smoe {
 
 struct CacheParams {
   int n_experts, top_k, cache_cap, evict_window, evict_policy, n_stage;
+  float alpha = 0.0f;        // threshold of the top-score / low-score split
+  int prefetch_max = 0;      // experts one prefetch call may load
 };
 
 // What the router decided for one step (B tokens), as read from the mirror.
@@ -36,8 +38,34 @@ struct StepPlan {
   int64_t raw_hits = 0, hits = 0, subs = 0;
 };
 
+// What a top-score prefetch has to load (Section IV-C).
+struct PrefetchPlan {
+  int n_wanted = 0, n = 0;
+  int wanted[SMOE_MAX_BATCH * SMOE_MAX_TOPK];    // predicted top-score experts that are not resident
+  int experts[SMOE_MAX_BATCH * SMOE_MAX_TOPK];   // the ones loaded (a prefix of wanted)
+  int victims[SMOE_MAX_BATCH * SMOE_MAX_TOPK];   // expert evicted for each
+  int slot[SMOE_MAX_BATCH * SMOE_MAX_TOPK];      // layer-local cache slot of each
+};
+
+// Active experts of one token whose score reaches T = (1 + alpha) * S_{k+1}
+// (Algorithm 1's threshold; all of them when there is no (k+1)-th expert).
+inline uint64_t top_score_mask(const float* scores, const int32_t* topk, int E, int k, float alpha) {
+  uint64_t active = 0;
+  for (int j = 0; j < k; ++j) active |= 1ull << topk[j];
+  if (E <= k) return active;
+  double s_k1 = -1.0;
+  for (int e = 0; e < E; ++e)
+    if (!((active >> e) & 1ull) && (double)scores[e] > s_k1) s_k1 = (double)scores[e];
+  const double T = (1.0 + (double)alpha) * s_k1;
+  uint64_t top = 0;
+  for (int j = 0; j < k; ++j)
+    if ((double)scores[topk[j]] >= T) top |= 1ull << topk[j];
+  return top;
+}
+
 struct CacheLayer {
   uint64_t resident = 0;
+  uint64_t prefetched = 0;               // prefetched since the layer's last step, not yet judged
   int8_t slot_of[SMOE_MAX_EXPERTS];
   std::vector<int32_t> expert_of_slot;   // [cap]
   std::vector<double> hist;              // ring [(n+1)][E] of batch-mean score vectors
@@ -51,6 +79,7 @@ struct CacheLayer {
   // Initial residency: expert ids per slot (distinct, validated by the caller).
   void reset(const CacheParams& p, const int32_t* init_ids) {
     resident = 0;
+    prefetched = 0;
     for (int e = 0; e < SMOE_MAX_EXPERTS; ++e) {
       slot_of[e] = -1;
       last_use[e] = load_stamp[e] = use_count[e] = 0;
@@ -66,6 +95,86 @@ struct CacheLayer {
       slot_of[e] = (int8_t)s;
       expert_of_slot[s] = e;
       last_use[e] = load_stamp[e] = (int64_t)s - p.cache_cap;   // before step 0, in slot order
+    }
+  }
+
+  // Mean score of every expert over the retained window (Eq. 3); zeros while
+  // the layer has no history.
+  void window_means(const CacheParams& p, double* mean) const {
+    for (int e = 0; e < p.n_experts; ++e) {
+      double s = 0.0;
+      for (int i = 0; i < hist_count; ++i) s += hist[(size_t)i * p.n_experts + e];
+      mean[e] = hist_count ? s / hist_count : 0.0;
+    }
+  }
+
+  // Victim among the resident experts outside `shield` under the configured
+  // policy, lower id on ties; -1 when nothing is evictable.
+  int choose_victim(const CacheParams& p, uint64_t shield, const double* mean) const {
+    int victim = -1;
+    for (int e = 0; e < p.n_experts; ++e) {
+      if (!((resident >> e) & 1ull) || ((shield >> e) & 1ull)) continue;
+      if (victim < 0) { victim = e; continue; }
+      bool better;
+      switch (p.evict_policy) {
+        case SMOE_EVICT_LRU:  better = last_use[e] < last_use[victim]; break;
+        case SMOE_EVICT_FIFO: better = load_stamp[e] < load_stamp[victim]; break;
+        case SMOE_EVICT_LFU:
+          better = use_count[e] < use_count[victim] ||
+                   (use_count[e] == use_count[victim] && last_use[e] < last_use[victim]);
+          break;
+        default:              better = mean[e] < mean[victim]; break;   // Eq. 3
+      }
+      if (better) victim = e;
+    }
+    return victim;
+  }
+
+  // Expert m takes the cache slot of `victim`.
+  int replace(int victim, int m) {
+    const int s = slot_of[victim];
+    resident = (resident & ~(1ull << victim)) | (1ull << m);
+    slot_of[victim] = -1;
+    slot_of[m] = (int8_t)s;
+    expert_of_slot[s] = m;
+    return s;
+  }
+
+  // Top-score prefetch (Section IV-C): `d` holds the router's scores and top-k
+  // of the *predicted* hidden states.  Predicted top-score experts that are not
+  // resident are loaded in rank order (token by token, repeats skipped), at most
+  // prefetch_max of them; every predicted active expert is shielded while the
+  // victims are chosen; loading stops when nothing is evictable.
+  void plan_prefetch(const CacheParams& p, const StepDecision& d, PrefetchPlan& out) {
+    out = PrefetchPlan{};
+    uint64_t shield = 0, listed = 0;
+    for (int t = 0; t < d.B; ++t) {
+      const uint64_t top = top_score_mask(d.scores[t], d.topk[t], p.n_experts, p.top_k, p.alpha);
+      for (int j = 0; j < p.top_k; ++j) {
+        const int e = d.topk[t][j];
+        shield |= 1ull << e;
+        if (((top >> e) & 1ull) && !((resident >> e) & 1ull) && !((listed >> e) & 1ull)) {
+          listed |= 1ull << e;
+          out.wanted[out.n_wanted++] = e;
+        }
+      }
+    }
+    double mean[SMOE_MAX_EXPERTS];
+    window_means(p, mean);
+    const int64_t stamp = step * 64 - 1;              // just before the layer's next step
+    for (int i = 0; i < out.n_wanted && i < p.prefetch_max; ++i) {
+      const int victim = choose_victim(p, shield, mean);
+      if (victim < 0) break;
+      const int m = out.wanted[i];
+      out.experts[out.n] = m;
+      out.victims[out.n] = victim;
+      out.slot[out.n] = replace(victim, m);
+      ++out.n;
+      load_stamp[m] = last_use[m] = stamp;
+      use_count[m] = 0;
+      prefetched |= 1ull << m;
+      ++st.evictions;
+      ++st.prefetches;
     }
   }
 
@@ -113,39 +222,25 @@ struct CacheLayer {
       }
     ++step;
 
+    if (prefetched) {
+      // prefetch accuracy: was a prefetched expert computed by this step, and was
+      // it one of the step's top-score experts
+      uint64_t top = 0;
+      for (int t = 0; t < B; ++t) top |= top_score_mask(d.scores[t], d.topk[t], E, k, p.alpha);
+      st.prefetch_used += __builtin_popcountll(prefetched & out.shield);
+      st.prefetch_top += __builtin_popcountll(prefetched & top);
+      prefetched = 0;
+    }
+
     if (out.n_fetch > 0) {
       double mean[SMOE_MAX_EXPERTS];
-      for (int e = 0; e < E; ++e) {
-        double s = 0.0;
-        for (int i = 0; i < hist_count; ++i) s += hist[(size_t)i * E + e];
-        mean[e] = s / hist_count;
-      }
+      window_means(p, mean);
       for (int i = 0; i < out.n_fetch; ++i) {
-        int victim = -1;
-        for (int e = 0; e < E; ++e) {
-          if (!((resident >> e) & 1ull) || ((out.shield >> e) & 1ull)) continue;
-          if (victim < 0) { victim = e; continue; }
-          bool better;
-          switch (p.evict_policy) {
-            case SMOE_EVICT_LRU:  better = last_use[e] < last_use[victim]; break;
-            case SMOE_EVICT_FIFO: better = load_stamp[e] < load_stamp[victim]; break;
-            case SMOE_EVICT_LFU:
-              better = use_count[e] < use_count[victim] ||
-                       (use_count[e] == use_count[victim] && last_use[e] < last_use[victim]);
-              break;
-            default:              better = mean[e] < mean[victim]; break;   // Eq. 3
-          }
-          if (better) victim = e;
-        }
+        const int victim = choose_victim(p, out.shield, mean);
         out.victims[i] = victim;
         const int m = out.fetched[i];
         if (victim >= 0) {
-          const int s = slot_of[victim];
-          resident = (resident & ~(1ull << victim)) | (1ull << m);
-          slot_of[victim] = -1;
-          slot_of[m] = (int8_t)s;
-          expert_of_slot[s] = m;
-          out.slot[i] = s;
+          out.slot[i] = replace(victim, m);
           ++out.n_evict;
         } else {
           if (out.n_staged >= p.n_stage) return SMOE_ESTATE;   // out of transient slots

@@ -21,14 +21,15 @@ extern "C" {
 
 // init_resident: [n_layers][cache_cap] or null for 0..cap-1.  Returns null on bad arguments.
 hl_handle* smoe_hl_create(int n_layers, int n_experts, int top_k, int cache_cap, int evict_window,
-                          int evict_policy, int n_stage, int64_t expert_bytes, const int32_t* init_resident) {
+                          int evict_policy, int n_stage, int64_t expert_bytes, const int32_t* init_resident,
+                          float alpha, int prefetch_max) {
   if (n_layers < 1 || n_experts < 1 || n_experts > SMOE_MAX_EXPERTS || top_k < 1 || top_k > SMOE_MAX_TOPK ||
       cache_cap < top_k || cache_cap > n_experts || evict_window < 0 || n_stage < 0 ||
       evict_policy < SMOE_EVICT_SCORE || evict_policy > SMOE_EVICT_LFU)
     return nullptr;
   hl_handle* h = new (std::nothrow) hl_handle();
   if (!h) return nullptr;
-  h->p = CacheParams{n_experts, top_k, cache_cap, evict_window, evict_policy, n_stage};
+  h->p = CacheParams{n_experts, top_k, cache_cap, evict_window, evict_policy, n_stage, alpha, prefetch_max};
   h->n_layers = n_layers;
   h->expert_bytes = expert_bytes;
   h->layers.resize(n_layers);
@@ -66,6 +67,29 @@ int smoe_hl_step(hl_handle* h, int layer, int B, const int32_t* topk, const int3
     slots[i] = plan.slot[i];
   }
   return plan.n_fetch;
+}
+
+// Top-score prefetch on predicted scores / top-k ([B][E], [B][k]).  Outputs sized B*k:
+// wanted experts, and for the loaded prefix the victims and slots.  Returns the number
+// loaded; *n_wanted gets the number of wanted experts.
+int smoe_hl_prefetch(hl_handle* h, int layer, int B, const int32_t* topk, const float* scores,
+                     int32_t* wanted, int32_t* n_wanted, int32_t* victims, int32_t* slots) {
+  if (!h || layer < 0 || layer >= h->n_layers || B < 1 || B > SMOE_MAX_BATCH) return SMOE_EINVAL;
+  StepDecision d{};
+  d.B = B;
+  for (int t = 0; t < B; ++t) {
+    d.topk[t] = topk + (size_t)t * h->p.top_k;
+    d.scores[t] = scores + (size_t)t * h->p.n_experts;
+  }
+  PrefetchPlan pp;
+  h->layers[layer].plan_prefetch(h->p, d, pp);
+  for (int i = 0; i < pp.n_wanted; ++i) wanted[i] = pp.wanted[i];
+  for (int i = 0; i < pp.n; ++i) {
+    victims[i] = pp.victims[i];
+    slots[i] = pp.slot[i];
+  }
+  *n_wanted = pp.n_wanted;
+  return pp.n;
 }
 
 void smoe_hl_residency(const hl_handle* h, int layer, int32_t* out_slots) {

@@ -58,6 +58,15 @@ struct moe_handle {
   float* act = nullptr;
   float* ysum = nullptr;
   RouteTmp* route_tmp = nullptr;
+  // top-score prefetch: the prediction has a decision record of its own
+  StepRec* pred_dev = nullptr;
+  StepRec* pred_host = nullptr;          // pinned
+  StepRec* pred_host_dev = nullptr;
+  int32_t pred_seq = 0;                  // number of the last prediction launched
+  int pending_layer = -1, pending_batch = 0;   // prediction launched, loads not queued yet
+  std::vector<hipEvent_t> ev_prefetch;   // [L] recorded behind a layer's prefetch copies
+  std::vector<uint8_t> pf_inflight;      // [L] 1 until that event has been waited for
+  moe_prefetch_info_t pf_last{};
   // launch geometry
   int TF = 0, tilesR = 0, tilesS = 0, R = 0, htiles = 0, stage_all = 0, chunk = 0, down_lds = 0;
   int up_upl = 0, down_upl = 0, RB = 0, nsegR = 1, nsegS = 1;
@@ -170,6 +179,9 @@ void free_all(moe_handle* h) {
   for (auto& k : h->prof)
     for (auto& p : k.ev) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
   if (h->ev_copy) (void)hipEventDestroy(h->ev_copy);
+  for (hipEvent_t e : h->ev_prefetch) (void)hipEventDestroy(e);
+  if (h->pred_dev) (void)hipFree(h->pred_dev);
+  if (h->pred_host) (void)hipHostFree(h->pred_host);
   if (h->sim_dev) (void)hipFree(h->sim_dev);
   if (h->rec_dev) (void)hipFree(h->rec_dev);
   if (h->rec_host) (void)hipHostFree(h->rec_host);
@@ -192,6 +204,92 @@ void prof_end(EventPair* p, hipStream_t s) {
   if (p) (void)hipEventRecord(p->b, s);
 }
 
+
+// Arguments of one router launch for `layer` on x (the decision record and the
+// call number are filled in by the caller).
+void fill_route_args(const moe_handle* h, int layer, int B, const void* x, RouteArgs& ra) {
+  const moe_cfg_t& c = h->cfg;
+  const int E = c.n_experts;
+  const CacheLayer& ls = h->layers[layer];
+  ra.gate_w = static_cast<const char*>(h->buf.gate_w_dev) + (int64_t)layer * E * c.hidden * h->esize;
+  ra.x = x;
+  ra.sim = h->sim_dev + (size_t)layer * E * E;
+  ra.tmp = h->route_tmp;
+  ra.B = B; ra.H = c.hidden; ra.E = E; ra.k = c.top_k;
+  ra.renorm = c.renorm_topk; ra.subst_key = c.subst_key; ra.alpha = c.alpha;
+  ra.nseg = 1;
+  ra.fast_upi = 0;
+  const int gate_units = c.hidden / (c.dtype == SMOE_DTYPE_FP32 ? 4 : 8);
+  if (h->route_fast) {
+    // one row segment per wave and pass: 16 waves x 4 rows; keep a segment <= 8 units per lane
+    while (ra.nseg < 8 && (E * ra.nseg * 2 <= 16 || gate_units / ra.nseg > 8 * kWave)) ra.nseg *= 2;
+    const int per_lane = ((gate_units + ra.nseg - 1) / ra.nseg + kWave - 1) / kWave;
+    ra.fast_upi = per_lane <= 1 ? 1 : (per_lane <= 2 ? 2 : (per_lane <= 4 ? 4 : (per_lane <= 8 ? 8 : 0)));
+  }
+  if (ra.fast_upi == 0) {
+    ra.nseg = 1;
+    while (ra.nseg < 8 && E * ra.nseg < 32 && c.hidden / (ra.nseg * 2) >= 512) ra.nseg *= 2;
+  }
+  ra.resident = ls.resident;
+  std::memcpy(ra.slot_of, ls.slot_of, sizeof(ra.slot_of));
+}
+
+// Wait until the router kernel that was given call number `want` has published
+// its record to the pinned mirror: bounded polling, then the stream.
+int await_record(moe_handle* h, const StepRec* mirror, int32_t want) {
+  const volatile int32_t* seq = &mirror->seq;
+  long spins = 0;
+  while (*seq != want && spins < h->spin_limit) ++spins;
+  if (*seq != want) HIP_TRY(hipStreamSynchronize(h->s_compute));
+  __atomic_thread_fence(__ATOMIC_ACQUIRE);
+  return *seq == want ? SMOE_OK : SMOE_ESTATE;
+}
+
+// Take the decision of a pending prefetch (Section IV-C): read the predicted
+// scores, pick what to load and whom to evict, queue the copies on the copy
+// stream.  The prediction kernel precedes every kernel launched since the
+// prefetch call on the compute stream, so once its record is visible the only
+// kernels that can still be running belong to the current call, which works on
+// another layer's slots.
+int settle_prefetch(moe_handle* h) {
+  if (h->pending_layer < 0) return SMOE_OK;
+  const int layer = h->pending_layer, B = h->pending_batch;
+  h->pending_layer = -1;
+  const moe_cfg_t& c = h->cfg;
+  {
+    const int rc = await_record(h, h->pred_host, h->pred_seq);
+    if (rc != SMOE_OK) return rc;
+  }
+  StepDecision dec{};
+  dec.B = B;
+  for (int t = 0; t < B; ++t) {
+    dec.topk[t] = h->pred_host->tok[t].topk;
+    dec.scores[t] = h->pred_host->tok[t].scores;
+  }
+  PrefetchPlan pp;
+  h->layers[layer].plan_prefetch(h->cp, dec, pp);
+  h->pf_last.layer = layer;
+  h->pf_last.n_wanted = pp.n_wanted;
+  h->pf_last.n_loaded = pp.n;
+  for (int i = 0; i < SMOE_MAX_BATCH * SMOE_MAX_TOPK; ++i) {
+    h->pf_last.wanted[i] = i < pp.n_wanted ? pp.wanted[i] : -1;
+    h->pf_last.victims[i] = i < pp.n ? pp.victims[i] : -1;
+  }
+  for (int i = 0; i < pp.n; ++i) {
+    const char* src = h->experts_host[layer] + (int64_t)pp.experts[i] * h->expert_bytes;
+    char* dst = static_cast<char*>(h->buf.cache_slab_dev) +
+                ((int64_t)layer * c.cache_cap + pp.slot[i]) * h->expert_bytes;
+    EventPair* pc = prof_begin(h, SMOE_PROF_COPY, h->s_copy);
+    HIP_TRY(hipMemcpyAsync(dst, src, h->expert_bytes, hipMemcpyHostToDevice, h->s_copy));
+    prof_end(pc, h->s_copy);
+    if (pc) h->prof[SMOE_PROF_COPY].bytes += h->expert_bytes;
+  }
+  if (pp.n > 0) {
+    HIP_TRY(hipEventRecord(h->ev_prefetch[layer], h->s_copy));
+    h->pf_inflight[layer] = 1;
+  }
+  return SMOE_OK;
+}
 }  // namespace
 
 extern "C" {
@@ -215,6 +313,7 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
   if (c.subst_key != 0 && c.subst_key != 1) return SMOE_EINVAL;
   if (c.evict_window < 0 || c.evict_window > 1024 || c.n_stage < 0) return SMOE_EINVAL;
   if (c.evict_policy < SMOE_EVICT_SCORE || c.evict_policy > SMOE_EVICT_LFU) return SMOE_EINVAL;
+  if (c.prefetch_max < 0 || c.prefetch_max > SMOE_MAX_BATCH * SMOE_MAX_TOPK) return SMOE_EINVAL;
   if (!buf->gate_w_dev || !buf->experts_host || !buf->sim_host || !buf->cache_slab_dev) return SMOE_EINVAL;
   if (c.n_shared > 0 && !buf->shared_dev) return SMOE_EINVAL;
   if (buf->stream_compute == buf->stream_copy) return SMOE_EINVAL;
@@ -239,7 +338,9 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
   h->shared_bytes = 3ll * c.hidden * c.shared_ffn * h->esize;
   h->Fmax = std::max(c.ffn, c.n_shared ? c.shared_ffn : 0);
   h->layers.resize(c.n_layers);
-  h->cp = CacheParams{c.n_experts, c.top_k, c.cache_cap, c.evict_window, c.evict_policy, c.n_stage};
+  h->cp = CacheParams{c.n_experts, c.top_k, c.cache_cap, c.evict_window, c.evict_policy, c.n_stage,
+                      c.alpha, c.prefetch_max};
+  h->pf_last.layer = -1;
   for (int l = 0; l < c.n_layers; ++l)
     h->experts_host.push_back(static_cast<const char*>(buf->experts_host[l]));
   h->buf.experts_host = nullptr;
@@ -279,6 +380,19 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
     HIP_TRY(hipMalloc(&h->act, (size_t)h->act_floats * sizeof(float)));
     HIP_TRY(hipMalloc(&h->ysum, (size_t)c.max_batch * c.hidden * sizeof(float)));
     HIP_TRY(hipMalloc(&h->route_tmp, (size_t)SMOE_MAX_BATCH * sizeof(RouteTmp)));
+    if (c.prefetch_max > 0) {
+      HIP_TRY(hipMalloc(&h->pred_dev, sizeof(StepRec)));
+      HIP_TRY(hipHostMalloc(&h->pred_host, sizeof(StepRec), hipHostMallocDefault));
+      std::memset(h->pred_host, 0, sizeof(StepRec));
+      HIP_TRY(hipHostGetDevicePointer(&dp, h->pred_host, 0));
+      h->pred_host_dev = static_cast<StepRec*>(dp);
+      h->pf_inflight.assign(c.n_layers, 0);
+      for (int l = 0; l < c.n_layers; ++l) {
+        hipEvent_t e = nullptr;
+        HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        h->ev_prefetch.push_back(e);
+      }
+    }
     return upload_initial(h);
   }();
   if (rc != SMOE_OK) { free_all(h); return rc; }
@@ -294,32 +408,26 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   CacheLayer& ls = h->layers[layer];
   const int k = c.top_k, E = c.n_experts, B = batch, nj = k + c.n_shared;
 
+  // ---- a prefetch for this very layer has to be decided before it is routed;
+  //      copies of an earlier prefetch for it must have landed -------------------
+  if (h->pending_layer == layer) {
+    const int rc = settle_prefetch(h);
+    if (rc != SMOE_OK) return rc;
+  }
+  if (!h->pf_inflight.empty() && h->pf_inflight[layer]) {
+    if (hipEventQuery(h->ev_prefetch[layer]) != hipSuccess) {
+      (void)hipGetLastError();                       // "not ready" is not an error here
+      HIP_TRY(hipStreamWaitEvent(h->s_compute, h->ev_prefetch[layer], 0));
+    }
+    h->pf_inflight[layer] = 0;
+  }
+
   // ---- router + expert-cache router ------------------------------------------
   RouteArgs ra{};
-  ra.gate_w = static_cast<const char*>(h->buf.gate_w_dev) + (int64_t)layer * E * c.hidden * h->esize;
-  ra.x = x_dev;
-  ra.sim = h->sim_dev + (size_t)layer * E * E;
+  fill_route_args(h, layer, B, x_dev, ra);
   ra.rec_dev = h->rec_dev;
   ra.rec_host = h->rec_host_dev;
-  ra.tmp = h->route_tmp;
-  ra.B = B; ra.H = c.hidden; ra.E = E; ra.k = k;
-  ra.renorm = c.renorm_topk; ra.subst_key = c.subst_key; ra.alpha = c.alpha;
   ra.seq = ++h->seq;
-  ra.nseg = 1;
-  ra.fast_upi = 0;
-  const int gate_units = c.hidden / (c.dtype == SMOE_DTYPE_FP32 ? 4 : 8);
-  if (h->route_fast) {
-    // one row segment per wave and pass: 16 waves x 4 rows; keep a segment <= 8 units per lane
-    while (ra.nseg < 8 && (E * ra.nseg * 2 <= 16 || gate_units / ra.nseg > 8 * kWave)) ra.nseg *= 2;
-    const int per_lane = ((gate_units + ra.nseg - 1) / ra.nseg + kWave - 1) / kWave;
-    ra.fast_upi = per_lane <= 1 ? 1 : (per_lane <= 2 ? 2 : (per_lane <= 4 ? 4 : (per_lane <= 8 ? 8 : 0)));
-  }
-  if (ra.fast_upi == 0) {
-    ra.nseg = 1;
-    while (ra.nseg < 8 && E * ra.nseg < 32 && c.hidden / (ra.nseg * 2) >= 512) ra.nseg *= 2;
-  }
-  ra.resident = ls.resident;
-  std::memcpy(ra.slot_of, ls.slot_of, sizeof(ra.slot_of));
   EventPair* pr = prof_begin(h, SMOE_PROF_ROUTE, h->s_compute);
   launch_route(ra, c.dtype, h->s_compute);
   prof_end(pr, h->s_compute);
@@ -371,12 +479,8 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   // Poll the pinned mirror (the router kernel publishes its call number last);
   // after spin_limit polls fall back to draining the compute stream.
   {
-    const volatile int32_t* seq = &h->rec_host->seq;
-    long spins = 0;
-    while (*seq != h->seq && spins < h->spin_limit) ++spins;
-    if (*seq != h->seq) HIP_TRY(hipStreamSynchronize(h->s_compute));
-    __atomic_thread_fence(__ATOMIC_ACQUIRE);
-    if (*seq != h->seq) return SMOE_ESTATE;
+    const int rc = await_record(h, h->rec_host, h->seq);
+    if (rc != SMOE_OK) return rc;
   }
   const StepRec& rec = *h->rec_host;
 
@@ -444,6 +548,12 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
     timed_down2 = pd2 != nullptr;
     HIP_TRY(hipGetLastError());
   }
+  // ---- a prefetch waiting for its decision (for another layer) is settled now:
+  //      its copies queue behind the loads this layer is waiting for --------------
+  {
+    const int rc = settle_prefetch(h);
+    if (rc != SMOE_OK) return rc;
+  }
   if (h->prof_mask) {
     // algorithmic bytes each timed launch was asked to stream (launches past the end of
     // the event pool are not timed and add no bytes)
@@ -484,8 +594,43 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   return SMOE_OK;
 }
 
-int moe_cache_stats(const moe_handle_t* h, int32_t layer, moe_stats_t* out) {
+int moe_prefetch_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* x_pred_dev) {
+  if (!h || !x_pred_dev) return SMOE_EINVAL;
+  const moe_cfg_t& c = h->cfg;
+  if (c.prefetch_max < 1 || layer < 0 || layer >= c.n_layers || batch < 1 || batch > c.max_batch)
+    return SMOE_EINVAL;
+  {
+    const int rc = settle_prefetch(h);      // one prediction may wait at a time
+    if (rc != SMOE_OK) return rc;
+  }
+  // The prediction is the router kernel itself on the predicted hidden state,
+  // writing to a record of its own; only its scores and top-k are used.
+  RouteArgs ra{};
+  fill_route_args(h, layer, batch, x_pred_dev, ra);
+  ra.rec_dev = h->pred_dev;
+  ra.rec_host = h->pred_host_dev;
+  ra.seq = ++h->pred_seq;
+  launch_route(ra, c.dtype, h->s_compute);
+  HIP_TRY(hipGetLastError());
+  h->pending_layer = layer;
+  h->pending_batch = batch;
+  return SMOE_OK;
+}
+
+int moe_prefetch_last(moe_handle_t* h, moe_prefetch_info_t* out) {
+  if (!h || !out) return SMOE_EINVAL;
+  const int rc = settle_prefetch(h);
+  if (rc != SMOE_OK) return rc;
+  *out = h->pf_last;
+  return SMOE_OK;
+}
+
+int moe_cache_stats(moe_handle_t* h, int32_t layer, moe_stats_t* out) {
   if (!h || !out || layer < -1 || layer >= h->cfg.n_layers) return SMOE_EINVAL;
+  {
+    const int rc = settle_prefetch(h);
+    if (rc != SMOE_OK) return rc;
+  }
   moe_stats_t s{};
   for (int l = 0; l < h->cfg.n_layers; ++l) {
     if (layer >= 0 && l != layer) continue;
@@ -493,13 +638,18 @@ int moe_cache_stats(const moe_handle_t* h, int32_t layer, moe_stats_t* out) {
     s.tokens += a.tokens; s.slots += a.slots; s.raw_hits += a.raw_hits; s.hits += a.hits;
     s.misses += a.misses; s.substitutions += a.substitutions; s.evictions += a.evictions;
     s.staged += a.staged; s.fetches += a.fetches; s.bytes_fetched += a.bytes_fetched;
+    s.prefetches += a.prefetches; s.prefetch_used += a.prefetch_used; s.prefetch_top += a.prefetch_top;
   }
   *out = s;
   return SMOE_OK;
 }
 
-int moe_cache_residency(const moe_handle_t* h, int32_t layer, int32_t* out_slots) {
+int moe_cache_residency(moe_handle_t* h, int32_t layer, int32_t* out_slots) {
   if (!h || !out_slots || layer < 0 || layer >= h->cfg.n_layers) return SMOE_EINVAL;
+  {
+    const int rc = settle_prefetch(h);
+    if (rc != SMOE_OK) return rc;
+  }
   const CacheLayer& ls = h->layers[layer];
   for (int s = 0; s < h->cfg.cache_cap; ++s) out_slots[s] = ls.expert_of_slot[s];
   return SMOE_OK;
@@ -509,6 +659,10 @@ int moe_cache_reset(moe_handle_t* h) {
   if (!h) return SMOE_EINVAL;
   HIP_TRY(hipStreamSynchronize(h->s_compute));
   HIP_TRY(hipStreamSynchronize(h->s_copy));
+  h->pending_layer = -1;                     // a prediction that was not acted on is dropped
+  h->pf_last.layer = -1;
+  h->pf_last.n_wanted = h->pf_last.n_loaded = 0;
+  std::fill(h->pf_inflight.begin(), h->pf_inflight.end(), (uint8_t)0);
   return upload_initial(h);
 }
 

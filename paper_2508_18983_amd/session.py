@@ -78,7 +78,7 @@ class DecodeSession:
                    dtype=0 if shape.dtype == "fp32" else 1, max_batch=max_batch,
                    alpha=float(shape.alpha), subst_key=shape.subst_key,
                    renorm_topk=shape.renorm_topk, evict_window=shape.evict_window, n_stage=n_stage,
-                   evict_policy=getattr(shape, "evict_policy", 0))
+                   evict_policy=getattr(shape, "evict_policy", 0), prefetch_max=0)
         cfg.update(cfg_override)
         self.cfg = B.MoeCfg(**cfg)
         self.expert_bytes = 3 * cfg["hidden"] * cfg["ffn"] * esize
@@ -110,6 +110,13 @@ class DecodeSession:
             y_dev = torch.empty_like(x_dev)
         B.moe_decode_layer(self.handle, layer, batch, x_dev.data_ptr(), y_dev.data_ptr(), trace)
         return y_dev
+
+    def prefetch(self, layer: int, x_pred_dev: torch.Tensor) -> None:
+        """Top-score prefetch for ``layer`` from the predicted states [B, H]."""
+        B.moe_prefetch_layer(self.handle, layer, x_pred_dev.shape[0], x_pred_dev.data_ptr())
+
+    def prefetch_last(self) -> dict:
+        return B.moe_prefetch_last(self.handle).as_dict()
 
     def sync(self) -> None:
         self.stream_compute.synchronize()

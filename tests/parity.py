@@ -21,20 +21,27 @@ def rel_errors(y, ref):
 
 
 def run_parity(wl, *, y_every=1, tokens=None, session_kw=None, oracle_kw=None, batch=None,
-               check_margins=True, label=""):
+               check_margins=True, label="", prefetch_max=0):
     """Decisions, counters and residency must match exactly on every call; y is
-    compared on every ``y_every``-th (token, layer).  Returns summary dict."""
+    compared on every ``y_every``-th (token, layer).  Returns summary dict.
+
+    With ``prefetch_max > 0`` every call is preceded by a top-score prefetch for
+    the layer that runs next (from ``wl.x_pred``), on both sides; what it wanted,
+    loaded and evicted must match as well."""
     s = wl.shape
     T = s.tokens if tokens is None else tokens
     B = s.batch if batch is None else batch
     session_kw = dict(session_kw or {})
     oracle_kw = dict(oracle_kw or {})
+    if prefetch_max:
+        session_kw["prefetch_max"] = prefetch_max
     orc = O.oracle_from_workload(wl, **oracle_kw)
     tol = TOL[s.dtype]
     worst = dict(l2=0.0, mx=0.0, route_margin=np.inf, evict_margin=np.inf)
     n_y = 0
     with session_from_workload(wl, max_batch=B, **session_kw) as ses:
         x_dev = wl.x[:T].to(ses.device)
+        xp_dev = wl.x_pred[:T].to(ses.device) if prefetch_max else None
         y_dev = torch.zeros(T, s.n_layers, B, s.hidden, dtype=ses.tdtype, device=ses.device)
         pending = []
         call = 0
@@ -42,6 +49,13 @@ def run_parity(wl, *, y_every=1, tokens=None, session_kw=None, oracle_kw=None, b
             for l in range(s.n_layers):
                 print(f"[parity {label}] t={t} l={l}", flush=True) if (t < 1 and l < 2) else None
                 tr = ses.new_trace(B)
+                pf = None
+                tn, ln = divmod(t * s.n_layers + l + 1, s.n_layers)
+                if prefetch_max and tn < T:
+                    ses.prefetch(ln, xp_dev[tn, ln])
+                    pf = orc.prefetch_layer(ln, as_numpy(wl.x_pred[tn, ln]), prefetch_max)
+                    worst["route_margin"] = min(worst["route_margin"], pf.route_margin)
+                    worst["evict_margin"] = min(worst["evict_margin"], pf.evict_margin)
                 ses.decode(l, x_dev[t, l], y_dev[t, l], tr)
                 want_y = (call % y_every) == 0
                 res = orc.decode_layer(l, as_numpy(wl.x[t, l]), compute_y=want_y)
@@ -60,6 +74,12 @@ def run_parity(wl, *, y_every=1, tokens=None, session_kw=None, oracle_kw=None, b
                 np.testing.assert_allclose(tr.weights, res.weights, rtol=2e-5, atol=1e-9,
                                            err_msg=f"weights {ctx}")
                 assert ses.residency(l).tolist() == orc.layers[l].slot_expert, ctx
+                if pf is not None:
+                    got_pf = ses.prefetch_last()
+                    assert got_pf == dict(layer=ln, wanted=pf.wanted, loaded=pf.prefetched,
+                                          victims=pf.victims), f"prefetch {ctx}: {got_pf} vs {pf}"
+                    if ln != l:
+                        assert ses.residency(ln).tolist() == orc.layers[ln].slot_expert, ctx
                 worst["route_margin"] = min(worst["route_margin"], res.route_margin)
                 worst["evict_margin"] = min(worst["evict_margin"], res.evict_margin)
                 if want_y:

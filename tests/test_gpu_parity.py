@@ -218,3 +218,100 @@ def test_baseline_replacement_policies(policy):
     assert r["stats"]["evictions"] > 20
     wl = make_workload(shp.with_(cache_cap=10), n_layers=1, tokens=12, batch=4)
     run_parity(wl, y_every=3, batch=4, session_kw=dict(n_stage=24), label=f"policy{policy}-b4")
+
+
+# ---------------------------------------------------------------- top-score prefetch (Section IV-C)
+def test_prefetch_parity_small_and_shared_shapes():
+    """Every call is preceded by a prefetch for the layer that runs next: what
+    it wanted, loaded and evicted, the residency of both layers, the following
+    routing decisions, the accuracy counters and y all match the oracle."""
+    wl = make_workload(SHAPES["c2"].with_(tokens=48), pred_noise=0.5)
+    r = run_parity(wl, label="c2-prefetch", prefetch_max=2)
+    st = r["stats"]
+    assert st["prefetches"] > 20 and 0 < st["prefetch_used"] <= st["prefetches"]
+    shp = SHAPES["c4"].with_(seed=41)
+    wl = make_workload(shp, n_layers=3, tokens=40, pred_noise=0.4)
+    r = run_parity(wl, y_every=3, label="c4-prefetch", prefetch_max=3)
+    assert r["stats"]["prefetches"] > 40 and r["stats"]["prefetch_top"] > 0
+
+
+def test_prefetch_for_the_same_layer_batched_and_fp32():
+    # one layer: the prefetch is for the very layer that is decoded next (settled before routing)
+    wl = make_workload(SHAPES["c1"].with_(n_layers=1, tokens=40, seed=11), n_layers=1, pred_noise=0.8)
+    r = run_parity(wl, label="c1-prefetch-1layer", prefetch_max=2)
+    assert r["stats"]["prefetches"] > 5
+    # batch 3 with staging, grouped MFMA kernels behind it
+    shp = SHAPES["c5"].with_(ffn=512, shared_ffn=1024, cache_cap=16, seed=27)
+    wl = make_workload(shp, n_layers=2, tokens=16, batch=3, pred_noise=0.5)
+    r = run_parity(wl, y_every=2, batch=3, session_kw=dict(n_stage=24), label="c5-b3-prefetch", prefetch_max=4)
+    assert r["stats"]["prefetches"] > 10
+
+
+def test_prefetch_free_running_matches_oracle_at_the_end():
+    """No trace, no query between the calls: prefetch copies are still in flight
+    when their layer is decoded (experts of 17 MB), so the layer has to wait for
+    them.  All outputs are compared after the run."""
+    from oracle import smoe_oracle as O
+    from paper_2508_18983_amd.session import session_from_workload
+    from smoe_inputs import as_numpy
+    from tests.parity import TOL, rel_errors
+    shp = SHAPES["c4"].with_(seed=43)
+    wl = make_workload(shp, n_layers=4, tokens=24, pred_noise=0.4)
+    s = wl.shape
+    L, T = s.n_layers, s.tokens
+    with session_from_workload(wl, prefetch_max=3) as ses:
+        x = wl.x.to(ses.device)
+        xp = wl.x_pred.to(ses.device)
+        y = torch.zeros(T, L, 1, s.hidden, dtype=ses.tdtype, device=ses.device)
+        for t in range(T):
+            for l in range(L):
+                tn, ln = divmod(t * L + l + 1, L)
+                if tn < T:
+                    ses.prefetch(ln, xp[tn, ln])
+                ses.decode(l, x[t, l], y[t, l])
+        ses.sync()
+        got = ses.stats()
+        res = [ses.residency(l).tolist() for l in range(L)]
+    orc = O.oracle_from_workload(wl)
+    y_host = y.to(torch.float64).cpu().numpy()
+    worst = 0.0
+    for t in range(T):
+        for l in range(L):
+            tn, ln = divmod(t * L + l + 1, L)
+            if tn < T:
+                orc.prefetch_layer(ln, as_numpy(wl.x_pred[tn, ln]), 3)
+            want_y = (t * L + l) % 5 == 0
+            r = orc.decode_layer(l, as_numpy(wl.x[t, l]), compute_y=want_y)
+            if want_y:
+                l2, mx = rel_errors(y_host[t, l], r.y)
+                assert l2 <= TOL["bf16"] and mx <= TOL["bf16"], (t, l, l2, mx)
+                worst = max(worst, l2)
+    assert got == orc.stats().as_dict()
+    assert res == [orc.layers[l].slot_expert for l in range(L)]
+    assert got["prefetches"] > 40
+    print(f"[prefetch free-running] ok, worst l2 {worst:.2e}, stats {got}", flush=True)
+
+
+def test_prefetch_refused_when_off_and_dropped_by_reset():
+    import paper_2508_18983_amd as M
+    from paper_2508_18983_amd.session import session_from_workload
+    wl = make_workload(SHAPES["c1"].with_(tokens=4), pred_noise=0.5)
+    with session_from_workload(wl) as ses:                      # prefetch_max = 0
+        xp = wl.x_pred.to(ses.device)
+        with pytest.raises(M.SmoeError) as ei:
+            ses.prefetch(0, xp[0, 0])
+        assert ei.value.code == -1
+    with session_from_workload(wl, prefetch_max=2) as ses:
+        xp = wl.x_pred.to(ses.device)
+        x = wl.x.to(ses.device)
+        with pytest.raises(M.SmoeError):
+            ses.prefetch(7, xp[0, 0])                           # no such layer
+        ses.prefetch(1, xp[0, 1])
+        ses.reset()                                             # pending prediction is dropped
+        assert ses.stats()["prefetches"] == 0 and ses.prefetch_last()["layer"] == -1
+        ses.prefetch(1, xp[0, 1])
+        first = ses.stats()                                     # settles it
+        assert ses.prefetch_last()["layer"] == 1
+        ses.decode(0, x[0, 0])
+        ses.sync()
+        assert ses.stats()["prefetches"] == first["prefetches"]

@@ -17,7 +17,8 @@ SHIM = os.path.join(ROOT, "paper_2508_18983_amd", "libsmoe_hostlogic.so")
 
 class Stats(C.Structure):
     _fields_ = [(n, C.c_int64) for n in ("tokens", "slots", "raw_hits", "hits", "misses", "substitutions",
-                                         "evictions", "staged", "fetches", "bytes_fetched")]
+                                         "evictions", "staged", "fetches", "bytes_fetched",
+                                         "prefetches", "prefetch_used", "prefetch_top")]
 
 
 @pytest.fixture(scope="module")
@@ -26,7 +27,8 @@ def shim():
         pytest.fail(f"{SHIM} missing: run python -m paper_2508_18983_amd.build")
     lib = C.CDLL(SHIM)
     lib.smoe_hl_create.restype = C.c_void_p
-    lib.smoe_hl_create.argtypes = [C.c_int] * 7 + [C.c_int64, C.c_void_p]
+    lib.smoe_hl_create.argtypes = [C.c_int] * 7 + [C.c_int64, C.c_void_p, C.c_float, C.c_int]
+    lib.smoe_hl_prefetch.argtypes = [C.c_void_p, C.c_int, C.c_int] + [C.c_void_p] * 6
     lib.smoe_hl_destroy.argtypes = [C.c_void_p]
     lib.smoe_hl_step.argtypes = [C.c_void_p, C.c_int, C.c_int] + [C.c_void_p] * 7
     lib.smoe_hl_residency.argtypes = [C.c_void_p, C.c_int, C.c_void_p]
@@ -34,19 +36,31 @@ def shim():
     return lib
 
 
-def replay(lib, wl, batch=1, n_stage=0, **oracle_kw):
+def replay(lib, wl, batch=1, n_stage=0, prefetch_max=0, **oracle_kw):
     s = wl.shape
     orc = O.oracle_from_workload(wl, **oracle_kw)
     h = lib.smoe_hl_create(s.n_layers, s.n_experts, s.top_k, orc.cap, orc.window, orc.evict_policy,
-                           n_stage, s.expert_bytes, None)
+                           n_stage, s.expert_bytes, None, orc.alpha, prefetch_max)
     assert h
     nk = batch * s.top_k
     fetched = np.zeros(nk, np.int32); victims = np.zeros(nk, np.int32); slots = np.zeros(nk, np.int32)
+    wanted = np.zeros(nk, np.int32); n_wanted = np.zeros(1, np.int32)
     res_slots = np.zeros(orc.cap, np.int32)
     loads = 0
     try:
         for t in range(s.tokens):
             for l in range(s.n_layers):
+                if prefetch_max:
+                    pf = orc.prefetch_layer(l, as_numpy(wl.x_pred[t, l]), prefetch_max)
+                    p_topk = np.ascontiguousarray(pf.topk, np.int32)
+                    p_sc = np.ascontiguousarray(pf.scores, np.float32)
+                    n = lib.smoe_hl_prefetch(h, l, batch, p_topk.ctypes.data, p_sc.ctypes.data,
+                                             wanted.ctypes.data, n_wanted.ctypes.data,
+                                             victims.ctypes.data, slots.ctypes.data)
+                    assert wanted[:n_wanted[0]].tolist() == pf.wanted, (t, l)
+                    assert n == len(pf.prefetched) and victims[:n].tolist() == pf.victims, (t, l)
+                    lib.smoe_hl_residency(h, l, res_slots.ctypes.data)
+                    assert res_slots.tolist() == orc.layers[l].slot_expert, (t, l)
                 r = orc.decode_layer(l, as_numpy(wl.x[t, l]), compute_y=False)
                 topk = np.ascontiguousarray(r.topk, np.int32)
                 fin = np.ascontiguousarray(r.final, np.int32)
@@ -94,7 +108,8 @@ def test_scheduler_batch_and_staging(shim):
     # without staging slots the same step is refused with SMOE_ESTATE (-4)
     s = wl.shape
     orc = O.oracle_from_workload(wl)
-    h = shim.smoe_hl_create(s.n_layers, s.n_experts, s.top_k, s.cache_cap, 3, 0, 0, s.expert_bytes, None)
+    h = shim.smoe_hl_create(s.n_layers, s.n_experts, s.top_k, s.cache_cap, 3, 0, 0, s.expert_bytes, None,
+                            0.25, 0)
     rc = 0
     buf = np.zeros(64, np.int32)
     for t in range(s.tokens):
@@ -114,11 +129,21 @@ def test_scheduler_batch_and_staging(shim):
     shim.smoe_hl_destroy(h)
 
 
+@pytest.mark.parametrize("policy,batch", [(0, 1), (1, 1), (2, 1), (3, 1), (0, 3)])
+def test_prefetch_replay_matches_oracle(shim, policy, batch):
+    """Top-score prefetch decisions (Section IV-C): what is wanted, what is
+    loaded, whom it evicts, and the accuracy counters at the next step."""
+    shp = SHAPES["c4"].with_(ffn=32, shared_ffn=32, seed=60 + policy, cache_cap=16)
+    wl = make_workload(shp, n_layers=2, tokens=50, batch=batch, pred_noise=0.6)
+    loads, st = replay(shim, wl, batch=batch, n_stage=batch * shp.top_k, prefetch_max=3, evict_policy=policy)
+    assert st.prefetches > 30 and 0 < st.prefetch_top <= st.prefetch_used < st.prefetches
+
+
 def test_scheduler_rejects_bad_arguments_and_malformed_decisions(shim):
-    assert not shim.smoe_hl_create(1, 65, 2, 4, 3, 0, 0, 100, None)      # too many experts
-    assert not shim.smoe_hl_create(1, 8, 2, 1, 3, 0, 0, 100, None)       # cap < k
-    assert not shim.smoe_hl_create(1, 8, 2, 4, 3, 9, 0, 100, None)       # unknown policy
-    h = shim.smoe_hl_create(1, 8, 2, 4, 3, 0, 0, 100, None)
+    assert not shim.smoe_hl_create(1, 65, 2, 4, 3, 0, 0, 100, None, 0.2, 0)      # too many experts
+    assert not shim.smoe_hl_create(1, 8, 2, 1, 3, 0, 0, 100, None, 0.2, 0)       # cap < k
+    assert not shim.smoe_hl_create(1, 8, 2, 4, 3, 9, 0, 100, None, 0.2, 0)       # unknown policy
+    h = shim.smoe_hl_create(1, 8, 2, 4, 3, 0, 0, 100, None, 0.2, 0)
     topk = np.array([[0, 1]], np.int32); bad = np.array([[0, 9]], np.int32); sub = np.zeros((1, 2), np.int32)
     sc = np.full((1, 8), 0.125, np.float32); o = np.zeros(2, np.int32)
     assert shim.smoe_hl_step(h, 0, 1, topk.ctypes.data, bad.ctypes.data, sub.ctypes.data, sc.ctypes.data,
