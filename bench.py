@@ -29,9 +29,20 @@ def log(msg: str) -> None:
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
-def run_tokens(ses, x_dev, y_dev, t0: int, t1: int, n_layers: int) -> None:
+PREFETCH_AHEAD = 1      # layer calls between a prefetch and the layer it is for (--prefetch-ahead)
+
+
+def run_tokens(ses, x_dev, y_dev, t0: int, t1: int, n_layers: int, xp_dev=None) -> None:
+    """Tokens t0..t1-1 through all layers.  With predicted states ``xp_dev`` every
+    layer call is preceded by the top-score prefetch for the layer that runs
+    PREFETCH_AHEAD calls later (1 = the next layer, as in the paper)."""
+    n_tok = x_dev.shape[0]
     for t in range(t0, t1):
         for l in range(n_layers):
+            if xp_dev is not None:
+                tn, ln = divmod(t * n_layers + l + PREFETCH_AHEAD, n_layers)
+                if tn < n_tok:
+                    ses.prefetch(ln, xp_dev[tn, ln])
             ses.decode(l, x_dev[t, l], y_dev[l])
 
 
@@ -40,15 +51,15 @@ PROF_ALL = (1 << 6) - 1
 
 
 def timed_run(ses, x_dev, y_dev, warmup: int, steps: int, n_layers: int, prof_launches: int,
-              prof_mask: int = PROF_UP_AND_COPY):
+              prof_mask: int = PROF_UP_AND_COPY, xp_dev=None):
     import paper_2508_18983_amd as M
-    run_tokens(ses, x_dev, y_dev, 0, warmup, n_layers)
+    run_tokens(ses, x_dev, y_dev, 0, warmup, n_layers, xp_dev)
     ses.sync()
     st0 = ses.stats()
     M.moe_profile_enable(ses.handle, prof_mask, prof_launches)
     ses.sync()
     t_begin = time.perf_counter()
-    run_tokens(ses, x_dev, y_dev, warmup, warmup + steps, n_layers)
+    run_tokens(ses, x_dev, y_dev, warmup, warmup + steps, n_layers, xp_dev)
     ses.sync()
     elapsed = time.perf_counter() - t_begin
     prof = M.moe_profile_read(ses.handle).as_dict()
@@ -96,9 +107,19 @@ def main() -> int:
     ap.add_argument("--no-miss-free", action="store_true", help="skip the all-resident reference run")
     ap.add_argument("--calib-copies", type=int, default=3,
                     help="launches of the known-size (1 GiB) copy kernel that hardware counters are scaled by")
+    ap.add_argument("--cache-cap", type=int, default=None,
+                    help="override the workload's HBM cache capacity per layer (diagnostic only)")
+    ap.add_argument("--prefetch", type=int, default=0,
+                    help="experts a top-score prefetch may load per layer (0 = off, the headline setting)")
+    ap.add_argument("--prefetch-ahead", type=int, default=1,
+                    help="how many layer calls ahead of its layer a prefetch is issued (paper: 1)")
+    ap.add_argument("--pred-noise", type=float, default=0.3,
+                    help="std of the noise that turns a hidden state into the prefetcher's predicted state")
     ap.add_argument("--pin-budget-gb", type=float, default=60.0,
                     help="page-locked host memory the box lets one process hold for expert storage")
     args = ap.parse_args()
+    global PREFETCH_AHEAD
+    PREFETCH_AHEAD = max(1, args.prefetch_ahead)
     if args.gpus != 1:
         print("bench.py: this build is a one-GPU path (no sharding, no collectives); run with --gpus 1",
               file=sys.stderr)
@@ -114,6 +135,8 @@ def main() -> int:
 
     M.load_library()
     shape = shape_by_name(args.workload)
+    if args.cache_cap is not None:
+        shape = shape.with_(cache_cap=args.cache_cap)
     n_tok = args.warmup + args.steps
     if n_tok > shape.tokens:
         print(f"bench.py: warmup+steps must be <= {shape.tokens} tokens of {shape.name}", file=sys.stderr)
@@ -133,7 +156,8 @@ def main() -> int:
                      f"load, separate HBM cache slots, gate weights and inputs per layer)")
     Bt = args.batch
     wl = make_workload(shape, device="cuda", n_layers=args.layers, tokens=n_tok, batch=Bt,
-                       host_alloc=pinned_empty, distinct_layers=distinct)
+                       host_alloc=pinned_empty, distinct_layers=distinct,
+                       pred_noise=args.pred_noise if args.prefetch > 0 else None)
     s = wl.shape
     log(f"inputs ready in {time.perf_counter() - t0:.1f} s (margin audit redrew {wl.redraws} token-layers)")
 
@@ -150,11 +174,14 @@ def main() -> int:
         torch.cuda.empty_cache()
 
     prof_launches = args.steps * L + 8
-    with session_from_workload(wl, max_batch=Bt, n_stage=(Bt * s.top_k if Bt > 1 else 0)) as ses:
+    with session_from_workload(wl, max_batch=Bt, n_stage=(Bt * s.top_k if Bt > 1 else 0),
+                               prefetch_max=args.prefetch) as ses:
         x_dev = wl.x.to(ses.device)[:, :, :, :].contiguous()
+        xp_dev = wl.x_pred.to(ses.device).contiguous() if args.prefetch > 0 else None
         y_dev = torch.empty(L, Bt, s.hidden, dtype=ses.tdtype, device=ses.device)
         log("timed run ...")
-        elapsed, prof, st = timed_run(ses, x_dev, y_dev, args.warmup, args.steps, L, prof_launches)
+        elapsed, prof, st = timed_run(ses, x_dev, y_dev, args.warmup, args.steps, L, prof_launches,
+                                      xp_dev=xp_dev)
     tok_s = args.steps * Bt / elapsed
     up = prof["up"]
     up_avg_s = up["ms"] / max(up["launches"], 1) * 1e-3
@@ -172,6 +199,12 @@ def main() -> int:
         "layer_bytes": s.layer_bytes(),
         "hbm_roofline_tokens_per_s": HBM_PEAK_GBS * 1e9 / (s.layer_bytes() * L),
     }
+    if args.prefetch > 0:
+        extra.update({
+            "prefetches_per_step": st["prefetches"] / args.steps,
+            "prefetch_used_frac": st["prefetch_used"] / max(st["prefetches"], 1),
+            "prefetch_top_frac": st["prefetch_top"] / max(st["prefetches"], 1),
+        })
 
     if not args.no_miss_free:
         # same tokens with every expert resident: the pure HBM path, no loads
@@ -211,7 +244,10 @@ def main() -> int:
         "config": {"workload": s.name, "layers": L, "hidden": s.hidden, "experts": s.n_experts,
                    "ffn": s.ffn, "top_k": s.top_k, "cache_cap": s.cache_cap, "alpha": s.alpha,
                    "n_shared": s.n_shared, "shared_ffn": s.shared_ffn, "batch": Bt,
-                   "zipf_s": s.zipf_s, "seed": s.seed, "host_expert_storage": host_note},
+                   "zipf_s": s.zipf_s, "seed": s.seed, "prefetch_max": args.prefetch,
+                   "prefetch_ahead": PREFETCH_AHEAD if args.prefetch > 0 else None,
+                   "pred_noise": args.pred_noise if args.prefetch > 0 else None,
+                   "host_expert_storage": host_note},
         "roofline": {"bound": "hbm", "kernel": "ffn_up_kernel (resident pass)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,

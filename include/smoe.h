@@ -209,8 +209,11 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch,
  * S_{k+1} and that are not resident, in rank order (token by token), at most
  * cfg.prefetch_max; each replaces the victim the eviction policy picks among
  * the residents outside the predicted top-k; loading stops when none is left.
- * The score history is not touched.  A later moe_decode_layer(layer) waits for
- * these copies only if they have not completed.  A wrong prediction costs the
+ * The score history is not touched.  If the copies are still running when
+ * moe_decode_layer(layer) is called, the prefetched experts count as resident
+ * for every decision but are computed in that call's second pass, behind the
+ * copy stream; neither the router nor the resident pass waits for them.  A
+ * wrong prediction costs the
  * copy and the evicted expert, nothing else: the layer loads what it needs on
  * demand as always.
  * SMOE_EINVAL for a bad layer / batch, NULL x_pred or prefetch_max == 0. */

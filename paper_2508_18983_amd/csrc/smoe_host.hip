@@ -65,7 +65,8 @@ struct moe_handle {
   int32_t pred_seq = 0;                  // number of the last prediction launched
   int pending_layer = -1, pending_batch = 0;   // prediction launched, loads not queued yet
   std::vector<hipEvent_t> ev_prefetch;   // [L] recorded behind a layer's prefetch copies
-  std::vector<uint8_t> pf_inflight;      // [L] 1 until that event has been waited for
+  std::vector<uint8_t> pf_inflight;      // [L] 1 until that event has completed or been waited for
+  std::vector<uint64_t> pf_mask;         // [L] experts whose prefetch copy may still be in flight
   moe_prefetch_info_t pf_last{};
   // launch geometry
   int TF = 0, tilesR = 0, tilesS = 0, R = 0, htiles = 0, stage_all = 0, chunk = 0, down_lds = 0;
@@ -287,6 +288,7 @@ int settle_prefetch(moe_handle* h) {
   if (pp.n > 0) {
     HIP_TRY(hipEventRecord(h->ev_prefetch[layer], h->s_copy));
     h->pf_inflight[layer] = 1;
+    for (int i = 0; i < pp.n; ++i) h->pf_mask[layer] |= 1ull << pp.experts[i];
   }
   return SMOE_OK;
 }
@@ -387,6 +389,7 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
       HIP_TRY(hipHostGetDevicePointer(&dp, h->pred_host, 0));
       h->pred_host_dev = static_cast<StepRec*>(dp);
       h->pf_inflight.assign(c.n_layers, 0);
+      h->pf_mask.assign(c.n_layers, 0);
       for (int l = 0; l < c.n_layers; ++l) {
         hipEvent_t e = nullptr;
         HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
@@ -414,12 +417,19 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
     const int rc = settle_prefetch(h);
     if (rc != SMOE_OK) return rc;
   }
+  // Experts of this layer whose prefetch copy may still be running: they count as
+  // resident for every decision, but the resident pass leaves them out (their slot
+  // is hidden from the kernels) and the second pass computes them after the copy
+  // stream has caught up, so neither the router nor the resident pass ever waits.
+  uint64_t deferred = 0;
   if (!h->pf_inflight.empty() && h->pf_inflight[layer]) {
-    if (hipEventQuery(h->ev_prefetch[layer]) != hipSuccess) {
+    if (hipEventQuery(h->ev_prefetch[layer]) == hipSuccess) {
+      h->pf_inflight[layer] = 0;
+      h->pf_mask[layer] = 0;
+    } else {
       (void)hipGetLastError();                       // "not ready" is not an error here
-      HIP_TRY(hipStreamWaitEvent(h->s_compute, h->ev_prefetch[layer], 0));
+      deferred = h->pf_mask[layer] & ls.resident;
     }
-    h->pf_inflight[layer] = 0;
   }
 
   // ---- router + expert-cache router ------------------------------------------
@@ -428,6 +438,8 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   ra.rec_dev = h->rec_dev;
   ra.rec_host = h->rec_host_dev;
   ra.seq = ++h->seq;
+  for (int e = 0; e < E; ++e)
+    if ((deferred >> e) & 1ull) ra.slot_of[e] = -1;
   EventPair* pr = prof_begin(h, SMOE_PROF_ROUTE, h->s_compute);
   launch_route(ra, c.dtype, h->s_compute);
   prof_end(pr, h->s_compute);
@@ -506,7 +518,8 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   int gslot[SMOE_MAX_BATCH * SMOE_MAX_TOPK];
   bool timed_up2 = false, timed_down2 = false;
 
-  if (n_fetch > 0) {
+  const uint64_t late = deferred & shield;   // prefetched experts this step computes in the second pass
+  if (n_fetch > 0 || late) {
     // ---- loads on the copy stream; the second FFN pass waits for them ---------
     for (int i = 0; i < n_fetch; ++i) {
       const int m = fetched[i];
@@ -519,8 +532,17 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
       prof_end(pc, h->s_copy);
       if (pc) h->prof[SMOE_PROF_COPY].bytes += h->expert_bytes;   // bytes of timed copies only
     }
-    HIP_TRY(hipEventRecord(h->ev_copy, h->s_copy));
-    HIP_TRY(hipStreamWaitEvent(h->s_compute, h->ev_copy, 0));
+    if (n_fetch > 0) {
+      // (this layer's prefetch copies precede these on the copy stream)
+      HIP_TRY(hipEventRecord(h->ev_copy, h->s_copy));
+      HIP_TRY(hipStreamWaitEvent(h->s_compute, h->ev_copy, 0));
+    } else {
+      HIP_TRY(hipStreamWaitEvent(h->s_compute, h->ev_prefetch[layer], 0));
+    }
+    if (deferred) {                              // the compute stream is now behind those copies
+      h->pf_inflight[layer] = 0;
+      h->pf_mask[layer] = 0;
+    }
     // second FFN pass: only the slots whose expert has just been loaded
     fa.pass = 1;
     if (fa.grouped) {
@@ -529,10 +551,16 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
         const int gi = __builtin_popcountll(shield & ((1ull << fetched[i]) - 1ull));
         fa.slot_override[gi] = gslot[i];
       }
+      for (int e = 0; e < E; ++e)
+        if ((late >> e) & 1ull) {
+          const int gi = __builtin_popcountll(shield & ((1ull << e) - 1ull));
+          fa.slot_override[gi] = layer * c.cache_cap + ls.slot_of[e];
+        }
     } else {
       for (int t = 0; t < B; ++t)
         for (int j = 0; j < k; ++j) {
           const int e = rec.tok[t].final_[j];
+          if ((late >> e) & 1ull) fa.slot_override[t * nj + j] = layer * c.cache_cap + ls.slot_of[e];
           if ((before >> e) & 1ull) continue;
           for (int i = 0; i < n_fetch; ++i)
             if (fetched[i] == e) fa.slot_override[t * nj + j] = gslot[i];
@@ -557,11 +585,14 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   if (h->prof_mask) {
     // algorithmic bytes each timed launch was asked to stream (launches past the end of
     // the event pool are not timed and add no bytes)
-    int64_t miss_slots = (int64_t)B * k - hits;
-    int64_t res_slots = hits, shared_times = B;
+    int64_t late_slots = 0;                           // slots the second pass took over from the first
+    for (int t = 0; t < B; ++t)
+      for (int j = 0; j < k; ++j) late_slots += (late >> rec.tok[t].final_[j]) & 1ull;
+    int64_t miss_slots = (int64_t)B * k - hits + late_slots;
+    int64_t res_slots = hits - late_slots, shared_times = B;
     if (fa.grouped) {                                 // weights are streamed once per distinct expert
-      res_slots = __builtin_popcountll(shield & before);
-      miss_slots = n_fetch;
+      res_slots = __builtin_popcountll(shield & before & ~late);
+      miss_slots = n_fetch + __builtin_popcountll(late);
       shared_times = 1;
     }
     const int64_t up_r = 2ll * c.hidden * c.ffn * h->esize, up_s = 2ll * c.hidden * c.shared_ffn * h->esize;
@@ -663,6 +694,7 @@ int moe_cache_reset(moe_handle_t* h) {
   h->pf_last.layer = -1;
   h->pf_last.n_wanted = h->pf_last.n_loaded = 0;
   std::fill(h->pf_inflight.begin(), h->pf_inflight.end(), (uint8_t)0);
+  std::fill(h->pf_mask.begin(), h->pf_mask.end(), (uint64_t)0);
   return upload_initial(h);
 }
 
