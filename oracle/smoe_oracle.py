@@ -20,6 +20,9 @@ that depend on a convention alone are "parity unpinned" by the paper:
   the paper ranks by gate score (``subst_key=1``, pinned)     -- parity unpinned
 * eviction window n (default 3), initial residency, tie rules, staging when
   every resident expert is shielded, two-pass set C at batch>1 -- parity unpinned
+* CPU-assisted scheduling (``split_load_cpu``): Algorithm 2 itself is pinned;
+  which experts count as its list S at batch > 1 and that a CPU-computed
+  expert leaves the cache untouched are conventions            -- parity unpinned
 * top-score prefetch (``prefetch_layer``): the predicted hidden state is an
   input; order of the prefetches, their cap, the shield of the predicted
   actives and the stamps of a prefetch load are conventions   -- parity unpinned
@@ -223,6 +226,32 @@ def pick_victim_baseline(policy: int, evictable: Sequence[int], last_use: Dict[i
 
 
 # --------------------------------------------------------------------------
+# CPU-assisted task load scheduling (Section V-A, Algorithm 2)
+# --------------------------------------------------------------------------
+def split_load_cpu(n_missing: int, c_load: float, c_cpu: float):
+    """Algorithm 2: the missing experts, sorted by descending score, are handed
+    out from both ends -- the front (highest scores) to the PCIe load queue, the
+    back (lowest scores) to the CPU -- always to the side whose accumulated time
+    is smaller (the load side on equality), adding C_load resp. C_CPU per expert.
+    Returns (n_load, n_CPU): the first n_load experts of the list are loaded,
+    the last n_CPU are computed on the CPU."""
+    t_cpu = 0.0
+    t_load = 0.0
+    n_load = n_cpu = 0
+    l, r = 0, n_missing - 1
+    while l <= r:
+        if t_load <= t_cpu:
+            t_load += c_load
+            n_load += 1
+            l += 1
+        else:
+            t_cpu += c_cpu
+            n_cpu += 1
+            r -= 1
+    return n_load, n_cpu
+
+
+# --------------------------------------------------------------------------
 # expert FFN
 # --------------------------------------------------------------------------
 def silu(z: np.ndarray) -> np.ndarray:
@@ -269,6 +298,7 @@ class Stats:
     staged: int = 0
     fetches: int = 0
     bytes_fetched: int = 0
+    cpu_computed: int = 0       # missing experts computed on the CPU instead of being loaded
     prefetches: int = 0
     prefetch_used: int = 0      # prefetched experts the layer's next step computed
     prefetch_top: int = 0       # ... that were top-score experts of that step
@@ -288,8 +318,9 @@ class StepResult:
     substituted: np.ndarray       # [B, k] bool
     hit: np.ndarray               # [B, k] bool  (slot served without a fetch)
     weights: np.ndarray           # [B, k] fp64 combine weights
-    fetched: List[int]            # distinct missing experts in fetch order
+    fetched: List[int]            # distinct missing experts that were loaded, in load order
     victims: List[int]            # evicted expert per fetch, -1 when staged
+    on_cpu: List[int]             # distinct missing experts computed on the CPU (Algorithm 2)
     y: Optional[np.ndarray]       # [B, H] fp64 or None
     route_margin: float
     evict_margin: float
@@ -314,7 +345,8 @@ class SMoEOracle:
                  sim: np.ndarray, shared: Optional[np.ndarray] = None, n_shared: int = 0,
                  shared_ffn: int = 0, subst_key: int = 0, renorm_topk: int = 1,
                  evict_window: int = 3, init_resident: Optional[np.ndarray] = None,
-                 elem_bytes: int = 2, widen_cache_bytes: int = 6 << 30, evict_policy: int = EVICT_SCORE):
+                 elem_bytes: int = 2, widen_cache_bytes: int = 6 << 30, evict_policy: int = EVICT_SCORE,
+                 cpu_assist: bool = False, c_load: float = 1.0, c_cpu: float = 1.0):
         if not (top_k <= cache_cap <= n_experts):
             raise ValueError("need top_k <= cache_cap <= n_experts")
         self.L, self.H, self.E, self.F, self.k = n_layers, hidden, n_experts, ffn, top_k
@@ -323,6 +355,7 @@ class SMoEOracle:
         self.n_shared, self.Fs = n_shared, shared_ffn
         self.subst_key, self.renorm, self.window = subst_key, renorm_topk, evict_window
         self.evict_policy = evict_policy
+        self.cpu_assist, self.c_load, self.c_cpu = bool(cpu_assist), float(c_load), float(c_cpu)
         self.expert_bytes = 3 * hidden * ffn * elem_bytes
         self._init_resident = init_resident
         self._wcache: Dict = {}          # fp64 copies of recently used experts (memo only)
@@ -514,6 +547,16 @@ class SMoEOracle:
             cache.last_use[e] = stamp
             cache.use_count[e] = cache.use_count.get(e, 0) + 1
         cache.step += 1
+        # CPU-assisted scheduling (Section V-A): the distinct missing experts, in
+        # descending score (batch 1: slot order is rank order; batch > 1: token by
+        # token, *convention*), are split by Algorithm 2.  The tail is computed on
+        # the CPU from the host copy of the weights: it is neither loaded nor
+        # cached, evicts nobody and needs no slot.
+        on_cpu: List[int] = []
+        if self.cpu_assist and fetched:
+            n_load, n_cpu = split_load_cpu(len(fetched), self.c_load, self.c_cpu)
+            fetched, on_cpu = fetched[:n_load], fetched[n_load:]
+            st.cpu_computed += n_cpu
         victims: List[int] = []
         evict_margin = np.inf
         for m in fetched:
@@ -551,7 +594,7 @@ class SMoEOracle:
                 for sidx in range(self.n_shared):
                     w1, w3, w2 = self._mats(layer, sidx, shared=True)
                     y[t] += swiglu_expert(w1, w3, w2, xt)
-        return StepResult(scores, topk, final, substituted, hit, weights, fetched, victims, y,
+        return StepResult(scores, topk, final, substituted, hit, weights, fetched, victims, on_cpu, y,
                           float(route_margin), float(evict_margin))
 
 

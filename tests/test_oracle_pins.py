@@ -609,3 +609,71 @@ def test_prefetch_raises_hit_rate_with_a_good_predictor():
     assert pre.stats().hits > base.stats().hits
     assert pre.stats().fetches < base.stats().fetches
     assert pre.stats().prefetch_used / pre.stats().prefetches > 0.7
+
+
+# ---------------------------------------------------------------- Algorithm 2 (CPU-assisted scheduling)
+def test_algorithm2_hand_worked_cases():
+    # equal costs: alternate, starting with a load
+    assert O.split_load_cpu(5, 1.0, 1.0) == (3, 2)
+    assert O.split_load_cpu(1, 1.0, 1e-9) == (1, 0)            # the first expert is always loaded
+    assert O.split_load_cpu(0, 1.0, 1.0) == (0, 0)
+    # a CPU expert costs a third of a load (the paper's S3 remark): load, cpu x3, load, cpu x3
+    assert O.split_load_cpu(8, 3.0, 1.0) == (2, 6)
+    assert O.split_load_cpu(4, 3.0, 1.0) == (1, 3)
+    # a CPU expert costs three loads: load, cpu, then loads until they catch up
+    assert O.split_load_cpu(5, 1.0, 3.0) == (4, 1)
+    assert O.split_load_cpu(6, 1.0, 3.0) == (4, 2)
+
+
+def test_algorithm2_balances_both_sides_and_is_near_the_best_split():
+    """Section V-A: the goal is min max(n_load C_load, n_CPU C_CPU).  The
+    two-pointer walk keeps the two sides within one item of each other and ends
+    within one item of the brute-force optimum."""
+    rng = np.random.default_rng(12)
+    for _ in range(500):
+        n = int(rng.integers(0, 65))
+        cl, cc = float(rng.uniform(0.1, 10)), float(rng.uniform(0.1, 10))
+        nl, ncpu = O.split_load_cpu(n, cl, cc)
+        assert nl + ncpu == n and nl >= min(n, 1)
+        big = max(cl, cc)
+        if ncpu > 0:
+            assert abs(nl * cl - ncpu * cc) <= big + 1e-9
+        best = min(max(i * cl, (n - i) * cc) for i in range(n + 1))
+        assert max(nl * cl, ncpu * cc) <= best + big + 1e-9
+
+
+def test_cpu_assist_keeps_top_of_the_list_for_loading_and_cache_untouched_by_the_rest():
+    """The highest-scoring missing experts are loaded (and cached), the
+    lowest-scoring ones are computed on the CPU: they evict nobody, stay
+    non-resident, and the layer output does not depend on where an expert ran."""
+    shp = SHAPES["c4"].with_(n_layers=2, hidden=64, ffn=16, shared_ffn=16, n_experts=24, top_k=6,
+                             cache_cap=8, alpha=0.1, tokens=30, seed=17)
+    wl = make_workload(shp)
+    a = O.oracle_from_workload(wl)
+    b = O.oracle_from_workload(wl, cpu_assist=True, c_load=2.0, c_cpu=1.0)
+    s = wl.shape
+    seen_cpu = 0
+    for t in range(s.tokens):
+        for l in range(s.n_layers):
+            G0 = set(b.layers[l].slot_expert)
+            rb = b.decode_layer(l, as_numpy(wl.x[t, l]))
+            missing = [int(e) for e in rb.final[0] if int(e) not in G0]
+            assert rb.fetched + rb.on_cpu == missing               # slot order = descending score
+            assert (len(rb.fetched), len(rb.on_cpu)) == O.split_load_cpu(len(missing), 2.0, 1.0)
+            sc = rb.scores[0]
+            if rb.fetched and rb.on_cpu:
+                assert min(sc[e] for e in rb.topk[0][[list(rb.final[0]).index(m) for m in rb.fetched]]) > \
+                       max(sc[e] for e in rb.topk[0][[list(rb.final[0]).index(m) for m in rb.on_cpu]])
+            G1 = set(b.layers[l].slot_expert)
+            assert not (set(rb.on_cpu) & G1) and set(rb.fetched) <= G1
+            assert len(rb.victims) == len(rb.fetched) and len(G1) == s.cache_cap
+            seen_cpu += len(rb.on_cpu)
+            if t == 0:
+                # before the caches diverge both oracles compute the same experts: same output
+                ra = a.decode_layer(l, as_numpy(wl.x[t, l]))
+                assert ra.final.tolist() == rb.final.tolist()
+                np.testing.assert_array_equal(ra.y, rb.y)
+    st = b.stats()
+    assert seen_cpu == st.cpu_computed > 20
+    assert st.fetches + st.cpu_computed == st.misses      # batch 1: every miss is loaded or computed
+    assert st.evictions == st.fetches
