@@ -16,6 +16,9 @@
  *   expert FFN        SwiGLU FFN of the chosen experts + shared experts and the
  *                     weighted combine (Section V-B GPU operations 2 and 4,
  *                     Section II-A for shared experts)
+ *   CPU-assisted      optional: Algorithm 2 leaves the lowest-scoring misses of a step
+ *   scheduling        to the host cores, which compute them from the host copy while
+ *                     the others are loaded (Section V-A; Section V-B CPU operations 2, 3)
  *   top-score         optional: the gate of a layer that has not run yet is applied
  *   prefetch          to a predicted hidden state and its top-score experts are
  *                     loaded behind the current layer's own loads (Section IV-C;
@@ -34,7 +37,9 @@
  * A handle is not thread-safe.  Work is enqueued on the caller's compute
  * stream; moe_decode_layer returns once the routing decision of this call has
  * reached the host (it waits for the router kernel only, the FFN kernels are
- * still in flight).  Calls on one handle that overlap race on its scratch.
+ * still in flight); with cpu_assist it also stays until the host cores have
+ * computed the experts Algorithm 2 left to them.  Calls on one handle that
+ * overlap race on its scratch.
  */
 #ifndef SMOE_H_
 #define SMOE_H_
@@ -95,6 +100,18 @@ typedef struct {
   int32_t evict_policy;  /* SMOE_EVICT_*: which unshielded resident a load replaces   */
   int32_t prefetch_max;  /* experts one moe_prefetch_layer call may load (0: prefetch
                             is off and that call is refused)                          */
+  int32_t cpu_assist;    /* 1: CPU-assisted task load scheduling (Section V-A): the
+                            missing experts of a step are split by Algorithm 2 between
+                            the load queue (highest scores, cached) and the host cores
+                            (lowest scores, computed from the host copy, not cached).
+                            0 (default): every miss is loaded, nothing of the method
+                            runs on the CPU                                           */
+  int32_t cpu_threads;   /* host threads of the expert FFN, the caller's included;
+                            0 = min(16, hardware threads)                             */
+  float   load_cost_us;  /* C_load of Algorithm 2 in microseconds; <= 0: measured (mean
+                            duration of the last 8 expert copies)                     */
+  float   cpu_cost_us;   /* C_CPU of Algorithm 2; <= 0: measured (mean wall time of the
+                            last 8 host-computed experts)                             */
 } moe_cfg_t;
 
 typedef struct {
@@ -127,7 +144,10 @@ typedef struct {
   int32_t* fetched;      /* [B*k]   distinct experts loaded by this call, in load order,
                                     -1 padded                                             */
   int32_t* victims;      /* [B*k]   expert evicted for each load, -1 = staged / padding   */
+  int32_t* on_cpu;       /* [B*k]   distinct missing experts computed by the host cores
+                                    (cpu_assist), in list order, -1 padded                */
   int32_t  n_fetched;    /* out: number of loads issued by this call                      */
+  int32_t  n_on_cpu;     /* out: number of experts left to the host cores                 */
 } moe_trace_t;
 
 typedef struct {
@@ -145,6 +165,7 @@ typedef struct {
                              counts as an eviction, none as a fetch)                       */
   int64_t prefetch_used;  /* ... that the layer's next step computed                       */
   int64_t prefetch_top;   /* ... that were top-score experts (s >= T) of that step         */
+  int64_t cpu_computed;   /* missing experts computed by the host cores instead of loaded  */
 } moe_stats_t;
 
 /* What the most recent prefetch did (moe_prefetch_last). */

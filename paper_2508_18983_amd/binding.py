@@ -29,7 +29,8 @@ class MoeCfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "hidden", "n_experts", "ffn", "top_k", "cache_cap", "n_shared",
         "shared_ffn", "dtype", "max_batch")] + [("alpha", C.c_float)] + [(n, C.c_int32) for n in (
-        "subst_key", "renorm_topk", "evict_window", "n_stage", "evict_policy", "prefetch_max")]
+        "subst_key", "renorm_topk", "evict_window", "n_stage", "evict_policy", "prefetch_max",
+        "cpu_assist", "cpu_threads")] + [("load_cost_us", C.c_float), ("cpu_cost_us", C.c_float)]
 
 
 class MoeBuffers(C.Structure):
@@ -41,13 +42,14 @@ class MoeBuffers(C.Structure):
 class MoeTrace(C.Structure):
     _fields_ = [("topk_idx", C.c_void_p), ("final_idx", C.c_void_p), ("substituted", C.c_void_p),
                 ("hit", C.c_void_p), ("scores", C.c_void_p), ("weights", C.c_void_p),
-                ("fetched", C.c_void_p), ("victims", C.c_void_p), ("n_fetched", C.c_int32)]
+                ("fetched", C.c_void_p), ("victims", C.c_void_p), ("on_cpu", C.c_void_p),
+                ("n_fetched", C.c_int32), ("n_on_cpu", C.c_int32)]
 
 
 class MoeStats(C.Structure):
     _fields_ = [(n, C.c_int64) for n in (
         "tokens", "slots", "raw_hits", "hits", "misses", "substitutions", "evictions", "staged",
-        "fetches", "bytes_fetched", "prefetches", "prefetch_used", "prefetch_top")]
+        "fetches", "bytes_fetched", "prefetches", "prefetch_used", "prefetch_top", "cpu_computed")]
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}
@@ -125,13 +127,18 @@ class Trace:
         self.weights = np.zeros((batch, k), np.float32)
         self.fetched = np.full(batch * k, -1, np.int32)
         self.victims = np.full(batch * k, -1, np.int32)
+        self.on_cpu = np.full(batch * k, -1, np.int32)
         self.c = MoeTrace(*(a.ctypes.data for a in (
             self.topk_idx, self.final_idx, self.substituted, self.hit, self.scores, self.weights,
-            self.fetched, self.victims)), 0)
+            self.fetched, self.victims, self.on_cpu)), 0, 0)
 
     @property
     def n_fetched(self) -> int:
         return int(self.c.n_fetched)
+
+    @property
+    def n_on_cpu(self) -> int:
+        return int(self.c.n_on_cpu)
 
 
 def moe_last_hip_error() -> int:

@@ -16,6 +16,7 @@ struct CacheParams {
   int n_experts, top_k, cache_cap, evict_window, evict_policy, n_stage;
   float alpha = 0.0f;        // threshold of the top-score / low-score split
   int prefetch_max = 0;      // experts one prefetch call may load
+  int cpu_assist = 0;        // 1: Algorithm 2 splits the misses between loading and the CPU
 };
 
 // What the router decided for one step (B tokens), as read from the mirror.
@@ -35,8 +36,24 @@ struct StepPlan {
   int fetched[SMOE_MAX_BATCH * SMOE_MAX_TOPK];   // distinct missing experts, (token, slot) order
   int victims[SMOE_MAX_BATCH * SMOE_MAX_TOPK];   // expert evicted for each, -1 = staged
   int slot[SMOE_MAX_BATCH * SMOE_MAX_TOPK];      // layer-local cache slot, or -(1 + staging index)
+  int n_cpu = 0;
+  int on_cpu[SMOE_MAX_BATCH * SMOE_MAX_TOPK];    // distinct missing experts left to the host cores
   int64_t raw_hits = 0, hits = 0, subs = 0;
 };
+
+// CPU-assisted task load scheduling (Section V-A, Algorithm 2): n missing experts
+// in descending score are handed out from both ends, the front to the load queue
+// and the back to the CPU, always to the side with the smaller accumulated time
+// (loading on equality).  Returns how many are loaded; the rest is computed.
+inline int split_load_cpu(int n, double c_load, double c_cpu) {
+  double t_load = 0.0, t_cpu = 0.0;
+  int n_load = 0;
+  for (int l = 0, r = n - 1; l <= r;) {
+    if (t_load <= t_cpu) { t_load += c_load; ++n_load; ++l; }
+    else { t_cpu += c_cpu; --r; }
+  }
+  return n_load;
+}
 
 // What a top-score prefetch has to load (Section IV-C).
 struct PrefetchPlan {
@@ -183,7 +200,8 @@ struct CacheLayer {
   // expert, update residency and counters.  Returns SMOE_OK, SMOE_ESTATE when
   // the decision is malformed or the step needs more staging slots than exist
   // (the state is then not usable until the next reset).
-  int plan_step(const CacheParams& p, const StepDecision& d, int64_t expert_bytes, StepPlan& out) {
+  int plan_step(const CacheParams& p, const StepDecision& d, int64_t expert_bytes, StepPlan& out,
+                double c_load = 1.0, double c_cpu = 1.0) {
     const int E = p.n_experts, k = p.top_k, B = d.B;
     {
       double* row = &hist[(size_t)hist_head * E];
@@ -221,6 +239,16 @@ struct CacheLayer {
         ++use_count[e];
       }
     ++step;
+
+    if (p.cpu_assist && out.n_fetch > 0) {
+      // the distinct misses are in descending score (batch 1: slot order is rank order;
+      // batch > 1: token by token): the tail goes to the host cores, which neither
+      // load nor cache it
+      const int n_load = split_load_cpu(out.n_fetch, c_load, c_cpu);
+      for (int i = n_load; i < out.n_fetch; ++i) out.on_cpu[out.n_cpu++] = out.fetched[i];
+      out.n_fetch = n_load;
+      st.cpu_computed += out.n_cpu;
+    }
 
     if (prefetched) {
       // prefetch accuracy: was a prefetched expert computed by this step, and was

@@ -998,6 +998,19 @@ __global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst,
     dst[i] = src[i];
 }
 
+// ysum[i] += part[i]: `part` is what the host cores computed for the experts that
+// Algorithm 2 gave to the CPU, read straight from pinned host memory.
+__global__ __launch_bounds__(256) void add_partial_kernel(float4* __restrict__ ysum,
+                                                          const float4* __restrict__ part, int n4) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n4) {
+    float4 a = ysum[i];
+    const float4 b = part[i];
+    a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    ysum[i] = a;
+  }
+}
+
 }  // namespace
 
 template <typename T, int PASS>
@@ -1100,6 +1113,12 @@ void launch_copy(void* dst, const void* src, int64_t n_bytes, hipStream_t s) {
   if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
                      static_cast<uint4*>(dst), static_cast<const uint4*>(src), n);
+}
+
+void launch_add_partial(float* ysum, const float* part, int n, hipStream_t s) {
+  const int n4 = n / 4;
+  hipLaunchKernelGGL(add_partial_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s,
+                     reinterpret_cast<float4*>(ysum), reinterpret_cast<const float4*>(part), n4);
 }
 
 }  // namespace smoe

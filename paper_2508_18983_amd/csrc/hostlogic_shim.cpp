@@ -7,6 +7,7 @@
 #include <vector>
 
 #include "cache_state.hpp"
+#include "cpu_expert.hpp"
 
 using namespace smoe;
 
@@ -14,6 +15,7 @@ struct hl_handle {
   CacheParams p;
   int n_layers;
   int64_t expert_bytes;
+  double c_load = 1.0, c_cpu = 1.0;      // costs of Algorithm 2
   std::vector<CacheLayer> layers;
 };
 
@@ -22,14 +24,17 @@ extern "C" {
 // init_resident: [n_layers][cache_cap] or null for 0..cap-1.  Returns null on bad arguments.
 hl_handle* smoe_hl_create(int n_layers, int n_experts, int top_k, int cache_cap, int evict_window,
                           int evict_policy, int n_stage, int64_t expert_bytes, const int32_t* init_resident,
-                          float alpha, int prefetch_max) {
+                          float alpha, int prefetch_max, int cpu_assist, double c_load, double c_cpu) {
   if (n_layers < 1 || n_experts < 1 || n_experts > SMOE_MAX_EXPERTS || top_k < 1 || top_k > SMOE_MAX_TOPK ||
       cache_cap < top_k || cache_cap > n_experts || evict_window < 0 || n_stage < 0 ||
       evict_policy < SMOE_EVICT_SCORE || evict_policy > SMOE_EVICT_LFU)
     return nullptr;
   hl_handle* h = new (std::nothrow) hl_handle();
   if (!h) return nullptr;
-  h->p = CacheParams{n_experts, top_k, cache_cap, evict_window, evict_policy, n_stage, alpha, prefetch_max};
+  h->p = CacheParams{n_experts, top_k, cache_cap, evict_window, evict_policy, n_stage, alpha, prefetch_max,
+                     cpu_assist};
+  h->c_load = c_load;
+  h->c_cpu = c_cpu;
   h->n_layers = n_layers;
   h->expert_bytes = expert_bytes;
   h->layers.resize(n_layers);
@@ -44,11 +49,11 @@ hl_handle* smoe_hl_create(int n_layers, int n_experts, int top_k, int cache_cap,
 void smoe_hl_destroy(hl_handle* h) { delete h; }
 
 // topk / final_ / subst: [B][k] int32; scores: [B][E] fp32.  Outputs (each sized B*k):
-// fetched experts, victims (-1 = staged), slots (>= 0 cache slot, < 0 staging).  Returns the
-// number of loads, or a negative SMOE_E* code.
+// fetched experts, victims (-1 = staged), slots (>= 0 cache slot, < 0 staging), experts left
+// to the host cores (count in *n_cpu).  Returns the number of loads, or a negative SMOE_E* code.
 int smoe_hl_step(hl_handle* h, int layer, int B, const int32_t* topk, const int32_t* final_,
                  const int32_t* subst, const float* scores, int32_t* fetched, int32_t* victims,
-                 int32_t* slots) {
+                 int32_t* slots, int32_t* on_cpu, int32_t* n_cpu) {
   if (!h || layer < 0 || layer >= h->n_layers || B < 1 || B > SMOE_MAX_BATCH) return SMOE_EINVAL;
   StepDecision d{};
   d.B = B;
@@ -59,8 +64,10 @@ int smoe_hl_step(hl_handle* h, int layer, int B, const int32_t* topk, const int3
     d.scores[t] = scores + (size_t)t * h->p.n_experts;
   }
   StepPlan plan;
-  const int rc = h->layers[layer].plan_step(h->p, d, h->expert_bytes, plan);
+  const int rc = h->layers[layer].plan_step(h->p, d, h->expert_bytes, plan, h->c_load, h->c_cpu);
   if (rc != SMOE_OK) return rc;
+  for (int i = 0; i < plan.n_cpu; ++i) on_cpu[i] = plan.on_cpu[i];
+  *n_cpu = plan.n_cpu;
   for (int i = 0; i < plan.n_fetch; ++i) {
     fetched[i] = plan.fetched[i];
     victims[i] = plan.victims[i];
@@ -90,6 +97,17 @@ int smoe_hl_prefetch(hl_handle* h, int layer, int B, const int32_t* topk, const 
   }
   *n_wanted = pp.n_wanted;
   return pp.n;
+}
+
+// The host-core expert FFN on its own: yacc[t] += w[t] * FFN_expert(x[t]), x and yacc
+// as [ntok][H] fp32 arrays.
+void smoe_hl_cpu_expert(const void* expert, int dtype, int H, int F, int ntok, const float* x,
+                        const float* w, float* yacc, int n_threads) {
+  CpuExperts pool(n_threads);
+  const float* xs[SMOE_MAX_BATCH];
+  float* ys[SMOE_MAX_BATCH];
+  for (int t = 0; t < ntok; ++t) { xs[t] = x + (size_t)t * H; ys[t] = yacc + (size_t)t * H; }
+  pool.run(expert, dtype, H, F, ntok, xs, w, ys);
 }
 
 void smoe_hl_residency(const hl_handle* h, int layer, int32_t* out_slots) {

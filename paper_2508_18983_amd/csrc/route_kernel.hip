@@ -196,6 +196,12 @@ __device__ __forceinline__ void publish(const RouteArgs& a, SelectSmem& sm, int 
     if (g.ntok > 0) a.rec_dev->grp[idx] = g;
     if (lane == 0) a.rec_dev->n_groups = __popcll(has_m);
   }
+  if (a.x_mirror != nullptr) {
+    // CPU-assisted scheduling: the host cores need the hidden states of this call
+    const gu32x4* src = static_cast<const gu32x4*>(a.x);
+    gu32x4* dst = static_cast<gu32x4*>(a.x_mirror);
+    for (int u = lane; u < a.x_units; u += kWave) dst[u] = src[u];
+  }
   // publish: every store of this wave to the mirror is complete before seq changes
   __threadfence_system();
   if (lane == 0) __hip_atomic_store(&a.rec_host->seq, a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);

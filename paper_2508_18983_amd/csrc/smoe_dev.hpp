@@ -57,6 +57,9 @@ struct RouteArgs {
   StepRec* rec_dev;
   StepRec* rec_host;    // device-visible address of the pinned mirror
   RouteTmp* tmp;        // [B] scratch of the batched router
+  void* x_mirror;       // device-visible pinned host copy of x for the host cores, or null
+  int32_t x_units;      // 16-byte units of x ([B][H] dtype) to mirror
+  int32_t pad_;
   int32_t B, H, E, k;
   int32_t renorm, subst_key;
   int32_t nseg;         // segments each gate row is split into (power of two, <= 8)
@@ -104,5 +107,7 @@ void launch_ffn_up(const FfnArgs& a, int dtype, hipStream_t s);
 void launch_ffn_down(const FfnArgs& a, int dtype, hipStream_t s);
 size_t grouped_down_lds_bytes(const FfnArgs& a);
 void launch_copy(void* dst, const void* src, int64_t n_bytes, hipStream_t s);
+// ysum[i] += part[i], i < n (n a multiple of 4): adds what the host cores computed
+void launch_add_partial(float* ysum, const float* part, int n, hipStream_t s);
 
 }  // namespace smoe

@@ -14,6 +14,10 @@
 #include "smoe.h"
 #include "smoe_dev.hpp"
 #include "cache_state.hpp"
+#include "cpu_expert.hpp"
+
+#include <chrono>
+#include <thread>
 
 using namespace smoe;
 
@@ -68,6 +72,22 @@ struct moe_handle {
   std::vector<uint8_t> pf_inflight;      // [L] 1 until that event has completed or been waited for
   std::vector<uint64_t> pf_mask;         // [L] experts whose prefetch copy may still be in flight
   moe_prefetch_info_t pf_last{};
+  // CPU-assisted scheduling (Section V-A): host-core FFN, the hidden states and the
+  // partial outputs it exchanges with the GPU, and the two costs of Algorithm 2
+  CpuExperts* cpu = nullptr;
+  void* x_host = nullptr;                // pinned [B][H] dtype, written by the router kernel
+  void* x_host_dev = nullptr;
+  float* ycpu_host = nullptr;            // pinned [B][H] fp32, read by the add kernel
+  float* ycpu_host_dev = nullptr;
+  std::vector<float> x_f32;              // [B][H] widened hidden states
+  double c_load_us = 0.0, c_cpu_us = 0.0;
+  static constexpr int kCostWindow = 8;  // "past p instances" of both costs
+  double cpu_hist[kCostWindow] = {0};
+  int cpu_hist_n = 0;
+  EventPair copy_ev[kCostWindow] = {};
+  bool copy_ev_pending[kCostWindow] = {false};
+  double copy_hist[kCostWindow] = {0};
+  int copy_ev_next = 0, copy_hist_n = 0;
   // launch geometry
   int TF = 0, tilesR = 0, tilesS = 0, R = 0, htiles = 0, stage_all = 0, chunk = 0, down_lds = 0;
   int up_upl = 0, down_upl = 0, RB = 0, nsegR = 1, nsegS = 1;
@@ -181,6 +201,13 @@ void free_all(moe_handle* h) {
     for (auto& p : k.ev) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
   if (h->ev_copy) (void)hipEventDestroy(h->ev_copy);
   for (hipEvent_t e : h->ev_prefetch) (void)hipEventDestroy(e);
+  delete h->cpu;
+  for (auto& p : h->copy_ev) {
+    if (p.a) (void)hipEventDestroy(p.a);
+    if (p.b) (void)hipEventDestroy(p.b);
+  }
+  if (h->x_host) (void)hipHostFree(h->x_host);
+  if (h->ycpu_host) (void)hipHostFree(h->ycpu_host);
   if (h->pred_dev) (void)hipFree(h->pred_dev);
   if (h->pred_host) (void)hipHostFree(h->pred_host);
   if (h->sim_dev) (void)hipFree(h->sim_dev);
@@ -205,6 +232,83 @@ void prof_end(EventPair* p, hipStream_t s) {
   if (p) (void)hipEventRecord(p->b, s);
 }
 
+
+inline float bf16_bits_to_float(uint16_t v) {
+  const uint32_t u = (uint32_t)v << 16;
+  float f;
+  std::memcpy(&f, &u, 4);
+  return f;
+}
+
+// C_load of Algorithm 2 when it is measured: fold in the copies that have completed.
+void refresh_load_cost(moe_handle* h) {
+  if (h->cfg.load_cost_us > 0.f) return;
+  for (int i = 0; i < moe_handle::kCostWindow; ++i) {
+    if (!h->copy_ev_pending[i]) continue;
+    if (hipEventQuery(h->copy_ev[i].b) != hipSuccess) { (void)hipGetLastError(); continue; }
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, h->copy_ev[i].a, h->copy_ev[i].b) == hipSuccess) {
+      h->copy_hist[i] = ms * 1e3;
+      if (h->copy_hist_n < moe_handle::kCostWindow) ++h->copy_hist_n;
+    } else {
+      (void)hipGetLastError();
+    }
+    h->copy_ev_pending[i] = false;
+  }
+  if (h->copy_hist_n > 0) {
+    double s = 0.0;
+    int n = 0;
+    for (int i = 0; i < moe_handle::kCostWindow; ++i)
+      if (h->copy_hist[i] > 0.0) { s += h->copy_hist[i]; ++n; }
+    if (n) h->c_load_us = s / n;
+  }
+}
+
+void note_cpu_cost(moe_handle* h, double us) {
+  if (h->cfg.cpu_cost_us > 0.f) return;
+  h->cpu_hist[h->cpu_hist_n % moe_handle::kCostWindow] = us;
+  ++h->cpu_hist_n;
+  const int n = std::min(h->cpu_hist_n, moe_handle::kCostWindow);
+  double s = 0.0;
+  for (int i = 0; i < n; ++i) s += h->cpu_hist[i];
+  h->c_cpu_us = s / n;
+}
+
+// The experts Algorithm 2 left to the host cores: ycpu[t] = sum over them of
+// w * FFN_e(x[t]) in fp32, from the hidden states the router kernel mirrored.
+void compute_on_cpu(moe_handle* h, int layer, int B, const StepRec& rec, const int* on_cpu, int n_cpu) {
+  const moe_cfg_t& c = h->cfg;
+  const int H = c.hidden, k = c.top_k;
+  for (int t = 0; t < B; ++t) {
+    float* xf = h->x_f32.data() + (size_t)t * H;
+    if (c.dtype == SMOE_DTYPE_FP32) {
+      std::memcpy(xf, static_cast<const float*>(h->x_host) + (size_t)t * H, sizeof(float) * H);
+    } else {
+      const uint16_t* xb = static_cast<const uint16_t*>(h->x_host) + (size_t)t * H;
+      for (int i = 0; i < H; ++i) xf[i] = bf16_bits_to_float(xb[i]);
+    }
+  }
+  std::memset(h->ycpu_host, 0, sizeof(float) * (size_t)B * H);
+  for (int i = 0; i < n_cpu; ++i) {
+    const int e = on_cpu[i];
+    const float* xs[SMOE_MAX_BATCH];
+    float ws[SMOE_MAX_BATCH];
+    float* ys[SMOE_MAX_BATCH];
+    int ntok = 0;
+    for (int t = 0; t < B; ++t)
+      for (int j = 0; j < k; ++j)
+        if (rec.tok[t].final_[j] == e) {
+          xs[ntok] = h->x_f32.data() + (size_t)t * H;
+          ws[ntok] = rec.tok[t].w[j];
+          ys[ntok] = h->ycpu_host + (size_t)t * H;
+          ++ntok;
+        }
+    const auto t0 = std::chrono::steady_clock::now();
+    h->cpu->run(h->experts_host[layer] + (int64_t)e * h->expert_bytes, c.dtype, H, c.ffn, ntok, xs, ws, ys);
+    const auto t1 = std::chrono::steady_clock::now();
+    note_cpu_cost(h, std::chrono::duration<double, std::micro>(t1 - t0).count());
+  }
+}
 
 // Arguments of one router launch for `layer` on x (the decision record and the
 // call number are filled in by the caller).
@@ -233,6 +337,8 @@ void fill_route_args(const moe_handle* h, int layer, int B, const void* x, Route
   }
   ra.resident = ls.resident;
   std::memcpy(ra.slot_of, ls.slot_of, sizeof(ra.slot_of));
+  ra.x_mirror = nullptr;
+  ra.x_units = 0;
 }
 
 // Wait until the router kernel that was given call number `want` has published
@@ -316,6 +422,7 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
   if (c.evict_window < 0 || c.evict_window > 1024 || c.n_stage < 0) return SMOE_EINVAL;
   if (c.evict_policy < SMOE_EVICT_SCORE || c.evict_policy > SMOE_EVICT_LFU) return SMOE_EINVAL;
   if (c.prefetch_max < 0 || c.prefetch_max > SMOE_MAX_BATCH * SMOE_MAX_TOPK) return SMOE_EINVAL;
+  if ((c.cpu_assist != 0 && c.cpu_assist != 1) || c.cpu_threads < 0 || c.cpu_threads > 256) return SMOE_EINVAL;
   if (!buf->gate_w_dev || !buf->experts_host || !buf->sim_host || !buf->cache_slab_dev) return SMOE_EINVAL;
   if (c.n_shared > 0 && !buf->shared_dev) return SMOE_EINVAL;
   if (buf->stream_compute == buf->stream_copy) return SMOE_EINVAL;
@@ -341,7 +448,7 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
   h->Fmax = std::max(c.ffn, c.n_shared ? c.shared_ffn : 0);
   h->layers.resize(c.n_layers);
   h->cp = CacheParams{c.n_experts, c.top_k, c.cache_cap, c.evict_window, c.evict_policy, c.n_stage,
-                      c.alpha, c.prefetch_max};
+                      c.alpha, c.prefetch_max, c.cpu_assist};
   h->pf_last.layer = -1;
   for (int l = 0; l < c.n_layers; ++l)
     h->experts_host.push_back(static_cast<const char*>(buf->experts_host[l]));
@@ -396,7 +503,50 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
         h->ev_prefetch.push_back(e);
       }
     }
-    return upload_initial(h);
+    if (c.cpu_assist) {
+      int nt = c.cpu_threads;
+      if (nt == 0) nt = (int)std::min(16u, std::max(1u, std::thread::hardware_concurrency()));
+      h->cpu = new CpuExperts(nt);
+      HIP_TRY(hipHostMalloc(&h->x_host, (size_t)c.max_batch * c.hidden * h->esize, hipHostMallocDefault));
+      HIP_TRY(hipHostGetDevicePointer(&h->x_host_dev, h->x_host, 0));
+      void* yp = nullptr;
+      HIP_TRY(hipHostMalloc(&yp, (size_t)c.max_batch * c.hidden * sizeof(float), hipHostMallocDefault));
+      h->ycpu_host = static_cast<float*>(yp);
+      HIP_TRY(hipHostGetDevicePointer(&yp, h->ycpu_host, 0));
+      h->ycpu_host_dev = static_cast<float*>(yp);
+      h->x_f32.assign((size_t)c.max_batch * c.hidden, 0.f);
+      for (auto& p : h->copy_ev) {
+        HIP_TRY(hipEventCreate(&p.a));
+        HIP_TRY(hipEventCreate(&p.b));
+      }
+    }
+    const auto up0 = std::chrono::steady_clock::now();
+    const int urc = upload_initial(h);
+    if (urc != SMOE_OK) return urc;
+    if (c.cpu_assist) {
+      // first estimates of the two costs of Algorithm 2: the initial upload gives the copy
+      // time of one expert, one run of the host FFN on zeros (after a warm-up run) its own
+      const auto up1 = std::chrono::steady_clock::now();
+      h->c_load_us = c.load_cost_us > 0.f
+                         ? c.load_cost_us
+                         : std::chrono::duration<double, std::micro>(up1 - up0).count() /
+                               ((double)c.n_layers * c.cache_cap);
+      if (c.cpu_cost_us > 0.f) {
+        h->c_cpu_us = c.cpu_cost_us;
+      } else {
+        const float* xs[1] = {h->x_f32.data()};
+        const float ws[1] = {1.0f};
+        float* ys[1] = {h->ycpu_host};
+        std::memset(h->ycpu_host, 0, sizeof(float) * c.hidden);
+        for (int rep = 0; rep < 2; ++rep) {
+          const auto t0 = std::chrono::steady_clock::now();
+          h->cpu->run(h->experts_host[0], c.dtype, c.hidden, c.ffn, 1, xs, ws, ys);
+          const auto t1 = std::chrono::steady_clock::now();
+          h->c_cpu_us = std::chrono::duration<double, std::micro>(t1 - t0).count();
+        }
+      }
+    }
+    return SMOE_OK;
   }();
   if (rc != SMOE_OK) { free_all(h); return rc; }
   *out = h;
@@ -440,6 +590,10 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   ra.seq = ++h->seq;
   for (int e = 0; e < E; ++e)
     if ((deferred >> e) & 1ull) ra.slot_of[e] = -1;
+  if (c.cpu_assist) {                    // the host cores may need x: the router kernel mirrors it
+    ra.x_mirror = h->x_host_dev;
+    ra.x_units = (int32_t)((int64_t)B * c.hidden * h->esize / 16);
+  }
   EventPair* pr = prof_begin(h, SMOE_PROF_ROUTE, h->s_compute);
   launch_route(ra, c.dtype, h->s_compute);
   prof_end(pr, h->s_compute);
@@ -507,7 +661,8 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   }
   StepPlan plan;
   {
-    const int rc = ls.plan_step(h->cp, dec, h->expert_bytes, plan);
+    if (c.cpu_assist) refresh_load_cost(h);
+    const int rc = ls.plan_step(h->cp, dec, h->expert_bytes, plan, h->c_load_us, h->c_cpu_us);
     if (rc != SMOE_OK) return rc;
   }
   const uint64_t before = plan.before, shield = plan.shield;
@@ -519,8 +674,10 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   bool timed_up2 = false, timed_down2 = false;
 
   const uint64_t late = deferred & shield;   // prefetched experts this step computes in the second pass
-  if (n_fetch > 0 || late) {
+  const int n_cpu = plan.n_cpu;
+  if (n_fetch > 0 || late || n_cpu > 0) {
     // ---- loads on the copy stream; the second FFN pass waits for them ---------
+    const bool time_copies = c.cpu_assist && c.load_cost_us <= 0.f;
     for (int i = 0; i < n_fetch; ++i) {
       const int m = fetched[i];
       gslot[i] = plan.slot[i] >= 0 ? layer * c.cache_cap + plan.slot[i]
@@ -528,18 +685,39 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
       const char* src = h->experts_host[layer] + (int64_t)m * h->expert_bytes;
       char* dst = static_cast<char*>(h->buf.cache_slab_dev) + (int64_t)gslot[i] * h->expert_bytes;
       EventPair* pc = prof_begin(h, SMOE_PROF_COPY, h->s_copy);
+      EventPair* cost = nullptr;                     // measured C_load: ring of the last copies
+      if (time_copies && !h->copy_ev_pending[h->copy_ev_next]) {
+        cost = &h->copy_ev[h->copy_ev_next];
+        HIP_TRY(hipEventRecord(cost->a, h->s_copy));
+      }
       HIP_TRY(hipMemcpyAsync(dst, src, h->expert_bytes, hipMemcpyHostToDevice, h->s_copy));
+      if (cost) {
+        HIP_TRY(hipEventRecord(cost->b, h->s_copy));
+        h->copy_ev_pending[h->copy_ev_next] = true;
+        h->copy_ev_next = (h->copy_ev_next + 1) % moe_handle::kCostWindow;
+      }
       prof_end(pc, h->s_copy);
       if (pc) h->prof[SMOE_PROF_COPY].bytes += h->expert_bytes;   // bytes of timed copies only
     }
+    if (n_fetch > 0) HIP_TRY(hipEventRecord(h->ev_copy, h->s_copy));
+    if (n_cpu > 0) {
+      // ---- CPU-assisted scheduling: while the copies run, the host cores compute the
+      //      experts Algorithm 2 left to them; a prefetch that is waiting goes onto the
+      //      copy stream first so that the link stays busy meanwhile.  The result is added
+      //      to the fp32 sums of the resident pass, and the second pass rounds y once.
+      const int prc = settle_prefetch(h);
+      if (prc != SMOE_OK) return prc;
+      compute_on_cpu(h, layer, B, rec, plan.on_cpu, n_cpu);
+      launch_add_partial(h->ysum, h->ycpu_host_dev, B * c.hidden, h->s_compute);
+      HIP_TRY(hipGetLastError());
+    }
     if (n_fetch > 0) {
-      // (this layer's prefetch copies precede these on the copy stream)
-      HIP_TRY(hipEventRecord(h->ev_copy, h->s_copy));
+      // (this layer's prefetch copies precede its loads on the copy stream)
       HIP_TRY(hipStreamWaitEvent(h->s_compute, h->ev_copy, 0));
-    } else {
+    } else if (late) {
       HIP_TRY(hipStreamWaitEvent(h->s_compute, h->ev_prefetch[layer], 0));
     }
-    if (deferred) {                              // the compute stream is now behind those copies
+    if (deferred && (n_fetch > 0 || late)) {     // the compute stream is now behind those copies
       h->pf_inflight[layer] = 0;
       h->pf_mask[layer] = 0;
     }
@@ -588,7 +766,11 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
     int64_t late_slots = 0;                           // slots the second pass took over from the first
     for (int t = 0; t < B; ++t)
       for (int j = 0; j < k; ++j) late_slots += (late >> rec.tok[t].final_[j]) & 1ull;
-    int64_t miss_slots = (int64_t)B * k - hits + late_slots;
+    int64_t cpu_slots = 0;                            // slots the host cores computed: no GPU bytes
+    for (int t = 0; t < B; ++t)
+      for (int j = 0; j < k; ++j)
+        for (int i = 0; i < n_cpu; ++i) cpu_slots += plan.on_cpu[i] == rec.tok[t].final_[j];
+    int64_t miss_slots = (int64_t)B * k - hits + late_slots - cpu_slots;
     int64_t res_slots = hits - late_slots, shared_times = B;
     if (fa.grouped) {                                 // weights are streamed once per distinct expert
       res_slots = __builtin_popcountll(shield & before & ~late);
@@ -619,8 +801,10 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
     for (int i = 0; i < B * k; ++i) {
       if (trace->fetched) trace->fetched[i] = i < n_fetch ? fetched[i] : -1;
       if (trace->victims) trace->victims[i] = i < n_fetch ? victims[i] : -1;
+      if (trace->on_cpu) trace->on_cpu[i] = i < n_cpu ? plan.on_cpu[i] : -1;
     }
     trace->n_fetched = n_fetch;
+    trace->n_on_cpu = n_cpu;
   }
   return SMOE_OK;
 }
@@ -670,6 +854,7 @@ int moe_cache_stats(moe_handle_t* h, int32_t layer, moe_stats_t* out) {
     s.misses += a.misses; s.substitutions += a.substitutions; s.evictions += a.evictions;
     s.staged += a.staged; s.fetches += a.fetches; s.bytes_fetched += a.bytes_fetched;
     s.prefetches += a.prefetches; s.prefetch_used += a.prefetch_used; s.prefetch_top += a.prefetch_top;
+    s.cpu_computed += a.cpu_computed;
   }
   *out = s;
   return SMOE_OK;

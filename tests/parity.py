@@ -69,6 +69,7 @@ def run_parity(wl, *, y_every=1, tokens=None, session_kw=None, oracle_kw=None, b
                 assert tr.n_fetched == len(res.fetched), ctx
                 assert tr.fetched[:tr.n_fetched].tolist() == res.fetched, ctx
                 assert tr.victims[:tr.n_fetched].tolist() == res.victims, ctx
+                assert tr.on_cpu[:tr.n_on_cpu].tolist() == res.on_cpu, ctx
                 np.testing.assert_allclose(tr.scores, res.scores, rtol=2e-5, atol=1e-9,
                                            err_msg=f"scores {ctx}")
                 np.testing.assert_allclose(tr.weights, res.weights, rtol=2e-5, atol=1e-9,

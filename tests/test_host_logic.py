@@ -18,7 +18,7 @@ SHIM = os.path.join(ROOT, "paper_2508_18983_amd", "libsmoe_hostlogic.so")
 class Stats(C.Structure):
     _fields_ = [(n, C.c_int64) for n in ("tokens", "slots", "raw_hits", "hits", "misses", "substitutions",
                                          "evictions", "staged", "fetches", "bytes_fetched",
-                                         "prefetches", "prefetch_used", "prefetch_top")]
+                                         "prefetches", "prefetch_used", "prefetch_top", "cpu_computed")]
 
 
 @pytest.fixture(scope="module")
@@ -27,10 +27,11 @@ def shim():
         pytest.fail(f"{SHIM} missing: run python -m paper_2508_18983_amd.build")
     lib = C.CDLL(SHIM)
     lib.smoe_hl_create.restype = C.c_void_p
-    lib.smoe_hl_create.argtypes = [C.c_int] * 7 + [C.c_int64, C.c_void_p, C.c_float, C.c_int]
+    lib.smoe_hl_create.argtypes = [C.c_int] * 7 + [C.c_int64, C.c_void_p, C.c_float, C.c_int, C.c_int,
+                                   C.c_double, C.c_double]
     lib.smoe_hl_prefetch.argtypes = [C.c_void_p, C.c_int, C.c_int] + [C.c_void_p] * 6
     lib.smoe_hl_destroy.argtypes = [C.c_void_p]
-    lib.smoe_hl_step.argtypes = [C.c_void_p, C.c_int, C.c_int] + [C.c_void_p] * 7
+    lib.smoe_hl_step.argtypes = [C.c_void_p, C.c_int, C.c_int] + [C.c_void_p] * 9
     lib.smoe_hl_residency.argtypes = [C.c_void_p, C.c_int, C.c_void_p]
     lib.smoe_hl_stats.argtypes = [C.c_void_p, C.c_int, C.POINTER(Stats)]
     return lib
@@ -40,11 +41,13 @@ def replay(lib, wl, batch=1, n_stage=0, prefetch_max=0, **oracle_kw):
     s = wl.shape
     orc = O.oracle_from_workload(wl, **oracle_kw)
     h = lib.smoe_hl_create(s.n_layers, s.n_experts, s.top_k, orc.cap, orc.window, orc.evict_policy,
-                           n_stage, s.expert_bytes, None, orc.alpha, prefetch_max)
+                           n_stage, s.expert_bytes, None, orc.alpha, prefetch_max,
+                           int(orc.cpu_assist), orc.c_load, orc.c_cpu)
     assert h
     nk = batch * s.top_k
     fetched = np.zeros(nk, np.int32); victims = np.zeros(nk, np.int32); slots = np.zeros(nk, np.int32)
     wanted = np.zeros(nk, np.int32); n_wanted = np.zeros(1, np.int32)
+    on_cpu = np.zeros(nk, np.int32); n_cpu = np.zeros(1, np.int32)
     res_slots = np.zeros(orc.cap, np.int32)
     loads = 0
     try:
@@ -67,8 +70,10 @@ def replay(lib, wl, batch=1, n_stage=0, prefetch_max=0, **oracle_kw):
                 sub = np.ascontiguousarray(r.substituted, np.int32)
                 sc = np.ascontiguousarray(r.scores, np.float32)
                 n = lib.smoe_hl_step(h, l, batch, topk.ctypes.data, fin.ctypes.data, sub.ctypes.data,
-                                     sc.ctypes.data, fetched.ctypes.data, victims.ctypes.data, slots.ctypes.data)
+                                     sc.ctypes.data, fetched.ctypes.data, victims.ctypes.data, slots.ctypes.data,
+                                     on_cpu.ctypes.data, n_cpu.ctypes.data)
                 assert n == len(r.fetched), (t, l, n)
+                assert on_cpu[:n_cpu[0]].tolist() == r.on_cpu, (t, l)
                 assert fetched[:n].tolist() == r.fetched and victims[:n].tolist() == r.victims, (t, l)
                 assert [v >= 0 for v in victims[:n]] == [sl >= 0 for sl in slots[:n]]
                 lib.smoe_hl_residency(h, l, res_slots.ctypes.data)
@@ -109,7 +114,7 @@ def test_scheduler_batch_and_staging(shim):
     s = wl.shape
     orc = O.oracle_from_workload(wl)
     h = shim.smoe_hl_create(s.n_layers, s.n_experts, s.top_k, s.cache_cap, 3, 0, 0, s.expert_bytes, None,
-                            0.25, 0)
+                            0.25, 0, 0, 1.0, 1.0)
     rc = 0
     buf = np.zeros(64, np.int32)
     for t in range(s.tokens):
@@ -120,7 +125,8 @@ def test_scheduler_batch_and_staging(shim):
             a_sub = np.ascontiguousarray(r.substituted, np.int32)
             a_sc = np.ascontiguousarray(r.scores, np.float32)
             rc = shim.smoe_hl_step(h, l, 4, a_topk.ctypes.data, a_fin.ctypes.data, a_sub.ctypes.data,
-                                   a_sc.ctypes.data, buf.ctypes.data, buf.ctypes.data, buf.ctypes.data)
+                                   a_sc.ctypes.data, buf.ctypes.data, buf.ctypes.data, buf.ctypes.data,
+                                   buf.ctypes.data, buf.ctypes.data)
             if rc < 0 or -1 in r.victims:
                 break
         if rc < 0 or -1 in r.victims:
@@ -139,15 +145,28 @@ def test_prefetch_replay_matches_oracle(shim, policy, batch):
     assert st.prefetches > 30 and 0 < st.prefetch_top <= st.prefetch_used < st.prefetches
 
 
+@pytest.mark.parametrize("costs,batch", [((2.0, 1.0), 1), ((1.0, 1.0), 1), ((1.0, 3.5), 1), ((3.0, 1.0), 3)])
+def test_cpu_assisted_scheduling_replay_matches_oracle(shim, costs, batch):
+    """Algorithm 2 inside the scheduler: which misses are loaded (and cached) and
+    which are left to the host cores, with and without a pending prefetch."""
+    shp = SHAPES["c4"].with_(ffn=32, shared_ffn=32, seed=80 + batch, cache_cap=12)
+    wl = make_workload(shp, n_layers=2, tokens=40, batch=batch, pred_noise=0.6)
+    for pf in (0, 2):
+        loads, st = replay(shim, wl, batch=batch, n_stage=batch * shp.top_k, prefetch_max=pf,
+                           cpu_assist=True, c_load=costs[0], c_cpu=costs[1])
+        assert st.cpu_computed > 20 and st.fetches > 20
+
+
 def test_scheduler_rejects_bad_arguments_and_malformed_decisions(shim):
-    assert not shim.smoe_hl_create(1, 65, 2, 4, 3, 0, 0, 100, None, 0.2, 0)      # too many experts
-    assert not shim.smoe_hl_create(1, 8, 2, 1, 3, 0, 0, 100, None, 0.2, 0)       # cap < k
-    assert not shim.smoe_hl_create(1, 8, 2, 4, 3, 9, 0, 100, None, 0.2, 0)       # unknown policy
-    h = shim.smoe_hl_create(1, 8, 2, 4, 3, 0, 0, 100, None, 0.2, 0)
+    tail = (0.2, 0, 0, 1.0, 1.0)
+    assert not shim.smoe_hl_create(1, 65, 2, 4, 3, 0, 0, 100, None, *tail)      # too many experts
+    assert not shim.smoe_hl_create(1, 8, 2, 1, 3, 0, 0, 100, None, *tail)       # cap < k
+    assert not shim.smoe_hl_create(1, 8, 2, 4, 3, 9, 0, 100, None, *tail)       # unknown policy
+    h = shim.smoe_hl_create(1, 8, 2, 4, 3, 0, 0, 100, None, *tail)
     topk = np.array([[0, 1]], np.int32); bad = np.array([[0, 9]], np.int32); sub = np.zeros((1, 2), np.int32)
     sc = np.full((1, 8), 0.125, np.float32); o = np.zeros(2, np.int32)
     assert shim.smoe_hl_step(h, 0, 1, topk.ctypes.data, bad.ctypes.data, sub.ctypes.data, sc.ctypes.data,
-                             o.ctypes.data, o.ctypes.data, o.ctypes.data) == -4
+                             o.ctypes.data, o.ctypes.data, o.ctypes.data, o.ctypes.data, o.ctypes.data) == -4
     assert shim.smoe_hl_step(h, 3, 1, topk.ctypes.data, topk.ctypes.data, sub.ctypes.data, sc.ctypes.data,
-                             o.ctypes.data, o.ctypes.data, o.ctypes.data) == -1
+                             o.ctypes.data, o.ctypes.data, o.ctypes.data, o.ctypes.data, o.ctypes.data) == -1
     shim.smoe_hl_destroy(h)
