@@ -111,6 +111,10 @@ def main() -> int:
                     help="override the workload's HBM cache capacity per layer (diagnostic only)")
     ap.add_argument("--prefetch", type=int, default=0,
                     help="experts a top-score prefetch may load per layer (0 = off, the headline setting)")
+    ap.add_argument("--cpu-assist", action="store_true",
+                    help="CPU-assisted task load scheduling (Algorithm 2) with measured costs: part of the "
+                         "misses is computed by the host cores instead of being loaded (off = headline)")
+    ap.add_argument("--cpu-threads", type=int, default=0, help="host threads of the expert FFN (0 = up to 16)")
     ap.add_argument("--prefetch-ahead", type=int, default=1,
                     help="how many layer calls ahead of its layer a prefetch is issued (paper: 1)")
     ap.add_argument("--pred-noise", type=float, default=0.3,
@@ -175,13 +179,15 @@ def main() -> int:
 
     prof_launches = args.steps * L + 8
     with session_from_workload(wl, max_batch=Bt, n_stage=(Bt * s.top_k if Bt > 1 else 0),
-                               prefetch_max=args.prefetch) as ses:
+                               prefetch_max=args.prefetch, cpu_assist=int(args.cpu_assist),
+                               cpu_threads=args.cpu_threads) as ses:
         x_dev = wl.x.to(ses.device)[:, :, :, :].contiguous()
         xp_dev = wl.x_pred.to(ses.device).contiguous() if args.prefetch > 0 else None
         y_dev = torch.empty(L, Bt, s.hidden, dtype=ses.tdtype, device=ses.device)
         log("timed run ...")
         elapsed, prof, st = timed_run(ses, x_dev, y_dev, args.warmup, args.steps, L, prof_launches,
                                       xp_dev=xp_dev)
+        cpu_costs = M.moe_cpu_assist_costs(ses.handle) if args.cpu_assist else None
     tok_s = args.steps * Bt / elapsed
     up = prof["up"]
     up_avg_s = up["ms"] / max(up["launches"], 1) * 1e-3
@@ -199,6 +205,9 @@ def main() -> int:
         "layer_bytes": s.layer_bytes(),
         "hbm_roofline_tokens_per_s": HBM_PEAK_GBS * 1e9 / (s.layer_bytes() * L),
     }
+    if args.cpu_assist:
+        extra["cpu_computed_per_step"] = st["cpu_computed"] / args.steps
+        extra["cpu_assist_costs"] = cpu_costs
     if args.prefetch > 0:
         extra.update({
             "prefetches_per_step": st["prefetches"] / args.steps,
@@ -244,7 +253,7 @@ def main() -> int:
         "config": {"workload": s.name, "layers": L, "hidden": s.hidden, "experts": s.n_experts,
                    "ffn": s.ffn, "top_k": s.top_k, "cache_cap": s.cache_cap, "alpha": s.alpha,
                    "n_shared": s.n_shared, "shared_ffn": s.shared_ffn, "batch": Bt,
-                   "zipf_s": s.zipf_s, "seed": s.seed, "prefetch_max": args.prefetch,
+                   "zipf_s": s.zipf_s, "seed": s.seed, "cpu_assist": bool(args.cpu_assist), "prefetch_max": args.prefetch,
                    "prefetch_ahead": PREFETCH_AHEAD if args.prefetch > 0 else None,
                    "pred_noise": args.pred_noise if args.prefetch > 0 else None,
                    "host_expert_storage": host_note},

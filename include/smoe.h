@@ -243,6 +243,14 @@ int moe_prefetch_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void
 /* Settles a pending prefetch and reports what the latest one decided. */
 int moe_prefetch_last(moe_handle_t* h, moe_prefetch_info_t* out);
 
+/* The two costs Algorithm 2 currently works with (cpu_assist): C_load and C_CPU in
+ * microseconds, fixed by cfg or measured over the last 8 copies / host-computed
+ * experts; plus the wall time the host cores have spent on experts so far and the
+ * number of experts they computed.  Any pointer may be NULL.  SMOE_ESTATE when
+ * cpu_assist is off. */
+int moe_cpu_assist_costs(const moe_handle_t* h, double* c_load_us, double* c_cpu_us,
+                         double* cpu_busy_us, int64_t* cpu_experts);
+
 /* Counters of one layer, or of all layers summed when layer == -1.  (Takes a
  * non-const handle since a pending prefetch is settled first.) */
 int moe_cache_stats(moe_handle_t* h, int32_t layer, moe_stats_t* out);

@@ -92,6 +92,8 @@ def load_library():
     lib.moe_decode_layer.argtypes = [P, I, I, P, P, C.POINTER(MoeTrace)]
     lib.moe_prefetch_layer.argtypes = [P, I, I, P]
     lib.moe_prefetch_last.argtypes = [P, C.POINTER(MoePrefetchInfo)]
+    lib.moe_cpu_assist_costs.argtypes = [P, C.POINTER(C.c_double), C.POINTER(C.c_double),
+                                         C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     lib.moe_cache_stats.argtypes = [P, I, C.POINTER(MoeStats)]
     lib.moe_cache_residency.argtypes = [P, I, P]
     lib.moe_cache_reset.argtypes = [P]
@@ -102,7 +104,7 @@ def load_library():
     lib.moe_calib_copy.argtypes = [P, P, C.c_int64, P]
     lib.moe_host_alloc.argtypes = [C.c_int64, C.POINTER(P)]
     lib.moe_host_free.argtypes = [P]
-    for fn in ("moe_cache_init", "moe_decode_layer", "moe_prefetch_layer", "moe_prefetch_last", "moe_cache_stats", "moe_cache_residency",
+    for fn in ("moe_cache_init", "moe_decode_layer", "moe_prefetch_layer", "moe_prefetch_last", "moe_cpu_assist_costs", "moe_cache_stats", "moe_cache_residency",
                "moe_cache_reset", "moe_cache_destroy", "moe_profile_enable", "moe_profile_read",
                "moe_last_hip_error", "moe_calib_copy", "moe_host_alloc", "moe_host_free"):
         getattr(lib, fn).restype = C.c_int
@@ -165,6 +167,13 @@ def moe_prefetch_last(handle: int) -> MoePrefetchInfo:
     info = MoePrefetchInfo()
     _check("moe_prefetch_last", load_library().moe_prefetch_last(handle, C.byref(info)))
     return info
+
+
+def moe_cpu_assist_costs(handle: int) -> dict:
+    cl, cc, busy, n = C.c_double(), C.c_double(), C.c_double(), C.c_int64()
+    _check("moe_cpu_assist_costs", load_library().moe_cpu_assist_costs(
+        handle, C.byref(cl), C.byref(cc), C.byref(busy), C.byref(n)))
+    return dict(c_load_us=cl.value, c_cpu_us=cc.value, cpu_busy_us=busy.value, cpu_experts=n.value)
 
 
 def moe_cache_stats(handle: int, layer: int = -1) -> MoeStats:

@@ -52,6 +52,8 @@ inline __attribute__((always_inline)) float dot(const W* __restrict w, const flo
 }
 
 struct Job {
+  const unsigned char* touch = nullptr;   // non-null: touch job over `touch_bytes` instead of an FFN
+  size_t touch_bytes = 0;
   const void* expert;
   int dtype, H, F, ntok;
   const float* x[kMaxTok];
@@ -103,6 +105,7 @@ struct CpuExperts::Impl {
   Job job{};
   std::vector<float> act;
   std::atomic<int> up_done{0}, all_done{0};
+  std::atomic<unsigned> touch_sink{0};
 
   static void wait_for(const std::atomic<int>& c, int want) {
     int spins = 0;
@@ -112,6 +115,16 @@ struct CpuExperts::Impl {
 
   void work(int id) {
     const Job& j = job;
+    if (j.touch != nullptr) {
+      // one read per 4 KiB page of this worker's share
+      const size_t pages = (j.touch_bytes + 4095) / 4096;
+      const size_t p0 = pages * id / n, p1 = pages * (id + 1) / n;
+      unsigned acc = 0;
+      for (size_t p = p0; p < p1; ++p) acc += *static_cast<const volatile unsigned char*>(j.touch + p * 4096);
+      touch_sink.fetch_add(acc, std::memory_order_relaxed);
+      all_done.fetch_add(1, std::memory_order_acq_rel);
+      return;
+    }
     const int f0 = (int)((int64_t)j.F * id / n), f1 = (int)((int64_t)j.F * (id + 1) / n);
     if (j.dtype == 0) up_rows_f32(j, f0, f1); else up_rows_bf16(j, f0, f1);
     up_done.fetch_add(1, std::memory_order_acq_rel);
@@ -150,6 +163,23 @@ CpuExperts::~CpuExperts() {
   delete impl_;
 }
 
+void CpuExperts::touch(const void* base, size_t bytes) {
+  if (!base || bytes == 0) return;
+  Impl& m = *impl_;
+  {
+    std::lock_guard<std::mutex> lk(m.mu);
+    m.job = Job{};
+    m.job.touch = static_cast<const unsigned char*>(base);
+    m.job.touch_bytes = bytes;
+    m.up_done.store(0, std::memory_order_relaxed);
+    m.all_done.store(0, std::memory_order_relaxed);
+    ++m.gen;
+  }
+  m.cv.notify_all();
+  m.work(0);
+  Impl::wait_for(m.all_done, m.n);
+}
+
 void CpuExperts::run(const void* expert, int dtype, int H, int F, int ntok, const float* const* x,
                      const float* w, float* const* yacc) {
   if (ntok < 1) return;
@@ -158,6 +188,7 @@ void CpuExperts::run(const void* expert, int dtype, int H, int F, int ntok, cons
   if (m.act.size() < (size_t)ntok * F) m.act.resize((size_t)ntok * F);
   {
     std::lock_guard<std::mutex> lk(m.mu);
+    m.job.touch = nullptr;
     m.job.expert = expert;
     m.job.dtype = dtype; m.job.H = H; m.job.F = F; m.job.ntok = ntok;
     for (int t = 0; t < ntok; ++t) { m.job.x[t] = x[t]; m.job.w[t] = w[t]; m.job.yacc[t] = yacc[t]; }

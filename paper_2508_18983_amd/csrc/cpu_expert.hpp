@@ -3,6 +3,7 @@
 // missing expert that Algorithm 2 assigns to the CPU is computed from its host
 // copy instead of being loaded.  Plain C++ threads, no HIP dependency.
 #pragma once
+#include <stddef.h>
 #include <stdint.h>
 
 namespace smoe {
@@ -23,6 +24,12 @@ class CpuExperts {
   // fp32 arithmetic throughout.  Blocks until done; not re-entrant.
   void run(const void* expert, int dtype, int H, int F, int ntok, const float* const* x,
            const float* w, float* const* yacc);
+
+  // Reads one byte of every 4 KiB page of [base, base + bytes) with all workers.
+  // Page-locked memory that so far only a device has written is mapped into the
+  // CPU's page tables page by page on first touch; doing that once up front keeps
+  // those faults (which cost several times the FFN itself) out of the decode path.
+  void touch(const void* base, size_t bytes);
 
  private:
   struct Impl;

@@ -110,6 +110,18 @@ void smoe_hl_cpu_expert(const void* expert, int dtype, int H, int F, int ntok, c
   pool.run(expert, dtype, H, F, ntok, xs, w, ys);
 }
 
+// A pool that outlives the call, as libsmoe keeps it.
+CpuExperts* smoe_hl_pool_create(int n_threads) { return new (std::nothrow) CpuExperts(n_threads); }
+void smoe_hl_pool_destroy(CpuExperts* p) { delete p; }
+void smoe_hl_pool_touch(CpuExperts* p, const void* base, size_t bytes) { p->touch(base, bytes); }
+void smoe_hl_pool_run(CpuExperts* pool, const void* expert, int dtype, int H, int F, int ntok, const float* x,
+                      const float* w, float* yacc) {
+  const float* xs[SMOE_MAX_BATCH];
+  float* ys[SMOE_MAX_BATCH];
+  for (int t = 0; t < ntok; ++t) { xs[t] = x + (size_t)t * H; ys[t] = yacc + (size_t)t * H; }
+  pool->run(expert, dtype, H, F, ntok, xs, w, ys);
+}
+
 void smoe_hl_residency(const hl_handle* h, int layer, int32_t* out_slots) {
   for (int s = 0; s < h->p.cache_cap; ++s) out_slots[s] = h->layers[layer].expert_of_slot[s];
 }

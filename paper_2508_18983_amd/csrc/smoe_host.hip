@@ -82,6 +82,8 @@ struct moe_handle {
   std::vector<float> x_f32;              // [B][H] widened hidden states
   double c_load_us = 0.0, c_cpu_us = 0.0;
   static constexpr int kCostWindow = 8;  // "past p instances" of both costs
+  double cpu_busy_us = 0.0;              // wall time spent in the host FFN so far
+  int64_t cpu_experts = 0;
   double cpu_hist[kCostWindow] = {0};
   int cpu_hist_n = 0;
   EventPair copy_ev[kCostWindow] = {};
@@ -265,6 +267,8 @@ void refresh_load_cost(moe_handle* h) {
 }
 
 void note_cpu_cost(moe_handle* h, double us) {
+  h->cpu_busy_us += us;
+  ++h->cpu_experts;
   if (h->cfg.cpu_cost_us > 0.f) return;
   h->cpu_hist[h->cpu_hist_n % moe_handle::kCostWindow] = us;
   ++h->cpu_hist_n;
@@ -507,6 +511,13 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
       int nt = c.cpu_threads;
       if (nt == 0) nt = (int)std::min(16u, std::max(1u, std::thread::hardware_concurrency()));
       h->cpu = new CpuExperts(nt);
+      // the host cores will read expert weights that may only ever have been written by a
+      // device: fault their pages into the CPU mapping now, not on the first use of each expert
+      for (int l = 0; l < c.n_layers; ++l) {
+        bool seen = false;
+        for (int q = 0; q < l; ++q) seen |= h->experts_host[q] == h->experts_host[l];
+        if (!seen) h->cpu->touch(h->experts_host[l], (size_t)c.n_experts * h->expert_bytes);
+      }
       HIP_TRY(hipHostMalloc(&h->x_host, (size_t)c.max_batch * c.hidden * h->esize, hipHostMallocDefault));
       HIP_TRY(hipHostGetDevicePointer(&h->x_host_dev, h->x_host, 0));
       void* yp = nullptr;
@@ -829,6 +840,17 @@ int moe_prefetch_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void
   HIP_TRY(hipGetLastError());
   h->pending_layer = layer;
   h->pending_batch = batch;
+  return SMOE_OK;
+}
+
+int moe_cpu_assist_costs(const moe_handle_t* h, double* c_load_us, double* c_cpu_us, double* cpu_busy_us,
+                         int64_t* cpu_experts) {
+  if (!h) return SMOE_EINVAL;
+  if (!h->cfg.cpu_assist) return SMOE_ESTATE;
+  if (c_load_us) *c_load_us = h->c_load_us;
+  if (c_cpu_us) *c_cpu_us = h->c_cpu_us;
+  if (cpu_busy_us) *cpu_busy_us = h->cpu_busy_us;
+  if (cpu_experts) *cpu_experts = h->cpu_experts;
   return SMOE_OK;
 }
 

@@ -47,3 +47,31 @@ def test_host_expert_ffn_matches_oracle_ffn(shim, dtype, H, F, ntok, threads):
         got = y[t].numpy().astype(np.float64)
         err = np.max(np.abs(got - ref)) / max(np.max(np.abs(ref)), 1e-30)
         assert err < 2e-6, (t, err)
+
+
+def test_pool_is_reused_across_jobs_and_touch_passes(shim):
+    """The library keeps one pool for its lifetime: FFN jobs, a page-touch pass
+    and more FFN jobs in a row, with tokens sharing one expert, give the same
+    result as fresh single-threaded runs."""
+    shim.smoe_hl_pool_create.restype = C.c_void_p
+    shim.smoe_hl_pool_create.argtypes = [C.c_int]
+    shim.smoe_hl_pool_destroy.argtypes = [C.c_void_p]
+    shim.smoe_hl_pool_touch.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
+    shim.smoe_hl_pool_run.argtypes = [C.c_void_p, C.c_void_p] + [C.c_int] * 4 + [C.c_void_p] * 3
+    H, F = 512, 384
+    g = torch.Generator().manual_seed(5)
+    experts = [(torch.randn(3 * H * F, generator=g) * 0.05).to(torch.bfloat16) for _ in range(3)]
+    x = torch.randn(2, H, generator=g)
+    w = torch.rand(2, generator=g)
+    pool = shim.smoe_hl_pool_create(5)
+    got = torch.zeros(2, H)
+    ref = torch.zeros(2, H)
+    for rep in range(3):
+        for e in experts:
+            shim.smoe_hl_pool_run(pool, e.data_ptr(), 1, H, F, 2, x.data_ptr(), w.data_ptr(), got.data_ptr())
+            shim.smoe_hl_cpu_expert(e.data_ptr(), 1, H, F, 2, x.data_ptr(), w.data_ptr(), ref.data_ptr(), 1)
+        shim.smoe_hl_pool_touch(pool, experts[rep].data_ptr(), experts[rep].numel() * 2)
+    shim.smoe_hl_pool_destroy(pool)
+    assert torch.isfinite(got).all() and float(got.abs().max()) > 0
+    # row ranges differ between 5 workers and 1, the per-row arithmetic does not
+    torch.testing.assert_close(got, ref, rtol=0, atol=0)
