@@ -107,13 +107,18 @@ def main() -> int:
     ap.add_argument("--no-miss-free", action="store_true", help="skip the all-resident reference run")
     ap.add_argument("--calib-copies", type=int, default=3,
                     help="launches of the known-size (1 GiB) copy kernel that hardware counters are scaled by")
+    ap.add_argument("--alpha", type=float, default=None,
+                    help="override the substitution threshold (diagnostic only; 0 = no substitution)")
+    ap.add_argument("--evict-policy", type=int, default=None,
+                    help="override the replacement policy: 0 score (Eq. 3), 1 LRU, 2 FIFO, 3 LFU (diagnostic only)")
     ap.add_argument("--cache-cap", type=int, default=None,
                     help="override the workload's HBM cache capacity per layer (diagnostic only)")
     ap.add_argument("--prefetch", type=int, default=0,
                     help="experts a top-score prefetch may load per layer (0 = off, the headline setting)")
-    ap.add_argument("--cpu-assist", action="store_true",
-                    help="CPU-assisted task load scheduling (Algorithm 2) with measured costs: part of the "
-                         "misses is computed by the host cores instead of being loaded (off = headline)")
+    ap.add_argument("--cpu-assist", type=int, nargs="?", const=1, default=0,
+                    help="CPU-assisted task load scheduling with measured costs: part of the misses is computed "
+                         "by the host cores instead of being loaded.  1 = Algorithm 2, 2 = min-max split "
+                         "(variant); 0 = off, the headline setting")
     ap.add_argument("--cpu-threads", type=int, default=0, help="host threads of the expert FFN (0 = up to 16)")
     ap.add_argument("--prefetch-ahead", type=int, default=1,
                     help="how many layer calls ahead of its layer a prefetch is issued (paper: 1)")
@@ -141,6 +146,10 @@ def main() -> int:
     shape = shape_by_name(args.workload)
     if args.cache_cap is not None:
         shape = shape.with_(cache_cap=args.cache_cap)
+    if args.alpha is not None:
+        shape = shape.with_(alpha=args.alpha)
+    if args.evict_policy is not None:
+        shape = shape.with_(evict_policy=args.evict_policy)
     n_tok = args.warmup + args.steps
     if n_tok > shape.tokens:
         print(f"bench.py: warmup+steps must be <= {shape.tokens} tokens of {shape.name}", file=sys.stderr)
@@ -253,7 +262,7 @@ def main() -> int:
         "config": {"workload": s.name, "layers": L, "hidden": s.hidden, "experts": s.n_experts,
                    "ffn": s.ffn, "top_k": s.top_k, "cache_cap": s.cache_cap, "alpha": s.alpha,
                    "n_shared": s.n_shared, "shared_ffn": s.shared_ffn, "batch": Bt,
-                   "zipf_s": s.zipf_s, "seed": s.seed, "cpu_assist": bool(args.cpu_assist), "prefetch_max": args.prefetch,
+                   "zipf_s": s.zipf_s, "seed": s.seed, "evict_policy": s.evict_policy, "cpu_assist": int(args.cpu_assist), "prefetch_max": args.prefetch,
                    "prefetch_ahead": PREFETCH_AHEAD if args.prefetch > 0 else None,
                    "pred_noise": args.pred_noise if args.prefetch > 0 else None,
                    "host_expert_storage": host_note},

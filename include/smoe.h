@@ -105,7 +105,11 @@ typedef struct {
                             the load queue (highest scores, cached) and the host cores
                             (lowest scores, computed from the host copy, not cached).
                             0 (default): every miss is loaded, nothing of the method
-                            runs on the CPU                                           */
+                            runs on the CPU.  2: variant of this library -- the split
+                            that minimises max(n_load C_load, n_CPU C_CPU) outright
+                            (Section V-A's objective) instead of the two-pointer walk,
+                            which always loads the first expert; of equal splits the
+                            one that loads more                                       */
   int32_t cpu_threads;   /* host threads of the expert FFN, the caller's included;
                             0 = min(16, hardware threads)                             */
   float   load_cost_us;  /* C_load of Algorithm 2 in microseconds; <= 0: measured (mean

@@ -251,6 +251,20 @@ def split_load_cpu(n_missing: int, c_load: float, c_cpu: float):
     return n_load, n_cpu
 
 
+def split_load_cpu_minmax(n_missing: int, c_load: float, c_cpu: float):
+    """The objective Section V-A states for the scheduler, min max(n_load C_load,
+    n_CPU C_CPU), solved outright over the n+1 possible splits (not the paper's
+    two-pointer walk, which always loads the first expert); of equally good
+    splits the one that loads -- and therefore caches -- more is taken.
+    *Variant of this build*, selected with cpu_assist = 2."""
+    best_i, best_t = 0, None
+    for i in range(n_missing + 1):
+        t = max(i * c_load, (n_missing - i) * c_cpu)
+        if best_t is None or t <= best_t:
+            best_i, best_t = i, t
+    return best_i, n_missing - best_i
+
+
 # --------------------------------------------------------------------------
 # expert FFN
 # --------------------------------------------------------------------------
@@ -346,7 +360,7 @@ class SMoEOracle:
                  shared_ffn: int = 0, subst_key: int = 0, renorm_topk: int = 1,
                  evict_window: int = 3, init_resident: Optional[np.ndarray] = None,
                  elem_bytes: int = 2, widen_cache_bytes: int = 6 << 30, evict_policy: int = EVICT_SCORE,
-                 cpu_assist: bool = False, c_load: float = 1.0, c_cpu: float = 1.0):
+                 cpu_assist: int = 0, c_load: float = 1.0, c_cpu: float = 1.0):
         if not (top_k <= cache_cap <= n_experts):
             raise ValueError("need top_k <= cache_cap <= n_experts")
         self.L, self.H, self.E, self.F, self.k = n_layers, hidden, n_experts, ffn, top_k
@@ -355,7 +369,8 @@ class SMoEOracle:
         self.n_shared, self.Fs = n_shared, shared_ffn
         self.subst_key, self.renorm, self.window = subst_key, renorm_topk, evict_window
         self.evict_policy = evict_policy
-        self.cpu_assist, self.c_load, self.c_cpu = bool(cpu_assist), float(c_load), float(c_cpu)
+        # 0 off, 1 Algorithm 2, 2 the min-max split (variant)
+        self.cpu_assist, self.c_load, self.c_cpu = int(cpu_assist), float(c_load), float(c_cpu)
         self.expert_bytes = 3 * hidden * ffn * elem_bytes
         self._init_resident = init_resident
         self._wcache: Dict = {}          # fp64 copies of recently used experts (memo only)
@@ -554,7 +569,8 @@ class SMoEOracle:
         # cached, evicts nobody and needs no slot.
         on_cpu: List[int] = []
         if self.cpu_assist and fetched:
-            n_load, n_cpu = split_load_cpu(len(fetched), self.c_load, self.c_cpu)
+            split = split_load_cpu if self.cpu_assist == 1 else split_load_cpu_minmax
+            n_load, n_cpu = split(len(fetched), self.c_load, self.c_cpu)
             fetched, on_cpu = fetched[:n_load], fetched[n_load:]
             st.cpu_computed += n_cpu
         victims: List[int] = []

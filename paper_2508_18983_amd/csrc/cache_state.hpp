@@ -16,7 +16,8 @@ struct CacheParams {
   int n_experts, top_k, cache_cap, evict_window, evict_policy, n_stage;
   float alpha = 0.0f;        // threshold of the top-score / low-score split
   int prefetch_max = 0;      // experts one prefetch call may load
-  int cpu_assist = 0;        // 1: Algorithm 2 splits the misses between loading and the CPU
+  int cpu_assist = 0;        // 1: Algorithm 2 splits the misses between loading and the CPU,
+                             // 2: the min-max split (variant)
 };
 
 // What the router decided for one step (B tokens), as read from the mirror.
@@ -78,6 +79,19 @@ inline uint64_t top_score_mask(const float* scores, const int32_t* topk, int E, 
   for (int j = 0; j < k; ++j)
     if ((double)scores[topk[j]] >= T) top |= 1ull << topk[j];
   return top;
+}
+
+// Variant (cpu_assist = 2): the stated objective min max(n_load C_load, n_CPU C_CPU)
+// solved over all n+1 splits; of equally good splits the one that loads more.
+inline int split_load_cpu_minmax(int n, double c_load, double c_cpu) {
+  int best_i = 0;
+  double best_t = -1.0;
+  for (int i = 0; i <= n; ++i) {
+    const double tl = i * c_load, tc = (n - i) * c_cpu;
+    const double t = tl > tc ? tl : tc;
+    if (best_t < 0.0 || t <= best_t) { best_i = i; best_t = t; }
+  }
+  return best_i;
 }
 
 struct CacheLayer {
@@ -244,7 +258,8 @@ struct CacheLayer {
       // the distinct misses are in descending score (batch 1: slot order is rank order;
       // batch > 1: token by token): the tail goes to the host cores, which neither
       // load nor cache it
-      const int n_load = split_load_cpu(out.n_fetch, c_load, c_cpu);
+      const int n_load = p.cpu_assist == 1 ? split_load_cpu(out.n_fetch, c_load, c_cpu)
+                                           : split_load_cpu_minmax(out.n_fetch, c_load, c_cpu);
       for (int i = n_load; i < out.n_fetch; ++i) out.on_cpu[out.n_cpu++] = out.fetched[i];
       out.n_fetch = n_load;
       st.cpu_computed += out.n_cpu;

@@ -426,7 +426,7 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
   if (c.evict_window < 0 || c.evict_window > 1024 || c.n_stage < 0) return SMOE_EINVAL;
   if (c.evict_policy < SMOE_EVICT_SCORE || c.evict_policy > SMOE_EVICT_LFU) return SMOE_EINVAL;
   if (c.prefetch_max < 0 || c.prefetch_max > SMOE_MAX_BATCH * SMOE_MAX_TOPK) return SMOE_EINVAL;
-  if ((c.cpu_assist != 0 && c.cpu_assist != 1) || c.cpu_threads < 0 || c.cpu_threads > 256) return SMOE_EINVAL;
+  if (c.cpu_assist < 0 || c.cpu_assist > 2 || c.cpu_threads < 0 || c.cpu_threads > 256) return SMOE_EINVAL;
   if (!buf->gate_w_dev || !buf->experts_host || !buf->sim_host || !buf->cache_slab_dev) return SMOE_EINVAL;
   if (c.n_shared > 0 && !buf->shared_dev) return SMOE_EINVAL;
   if (buf->stream_compute == buf->stream_copy) return SMOE_EINVAL;

@@ -318,9 +318,9 @@ def test_prefetch_refused_when_off_and_dropped_by_reset():
 
 
 # ---------------------------------------------------------------- CPU-assisted scheduling (Section V-A)
-def _cpu_kw(c_load, c_cpu, threads=4):
-    return (dict(cpu_assist=1, cpu_threads=threads, load_cost_us=c_load, cpu_cost_us=c_cpu),
-            dict(cpu_assist=True, c_load=c_load, c_cpu=c_cpu))
+def _cpu_kw(c_load, c_cpu, threads=4, mode=1):
+    return (dict(cpu_assist=mode, cpu_threads=threads, load_cost_us=c_load, cpu_cost_us=c_cpu),
+            dict(cpu_assist=mode, c_load=c_load, c_cpu=c_cpu))
 
 
 @pytest.mark.parametrize("costs", [(2.0, 1.0), (1.0, 3.0)])
@@ -337,6 +337,19 @@ def test_cpu_assist_parity_fixed_costs(costs):
     wl = make_workload(shp, n_layers=2, tokens=40)
     r = run_parity(wl, y_every=2, session_kw=ses_kw, oracle_kw=orc_kw, label=f"c4-cpu{costs}")
     assert r["stats"]["cpu_computed"] > 20 and r["stats"]["fetches"] > 20
+
+
+def test_cpu_assist_minmax_variant_parity():
+    """cpu_assist = 2: the split that minimises max(n_load C_load, n_CPU C_CPU);
+    with the host cores cheaper than a load a single miss is computed, not loaded."""
+    ses_kw, orc_kw = _cpu_kw(3.0, 1.0, mode=2)
+    wl = make_workload(SHAPES["c2"].with_(tokens=40, seed=4))
+    r = run_parity(wl, session_kw=ses_kw, oracle_kw=orc_kw, label="c2-cpu-minmax")
+    assert r["stats"]["cpu_computed"] > 20 and r["stats"]["fetches"] == 0
+    shp = SHAPES["c4"].with_(seed=52, cache_cap=12)
+    wl = make_workload(shp, n_layers=2, tokens=30)
+    r = run_parity(wl, y_every=2, session_kw=ses_kw, oracle_kw=orc_kw, label="c4-cpu-minmax")
+    assert r["stats"]["cpu_computed"] > 20 and r["stats"]["fetches"] > 0
 
 
 def test_cpu_assist_parity_batched_with_prefetch():

@@ -145,16 +145,21 @@ def test_prefetch_replay_matches_oracle(shim, policy, batch):
     assert st.prefetches > 30 and 0 < st.prefetch_top <= st.prefetch_used < st.prefetches
 
 
+@pytest.mark.parametrize("mode", [1, 2])
 @pytest.mark.parametrize("costs,batch", [((2.0, 1.0), 1), ((1.0, 1.0), 1), ((1.0, 3.5), 1), ((3.0, 1.0), 3)])
-def test_cpu_assisted_scheduling_replay_matches_oracle(shim, costs, batch):
+def test_cpu_assisted_scheduling_replay_matches_oracle(shim, costs, batch, mode):
     """Algorithm 2 inside the scheduler: which misses are loaded (and cached) and
     which are left to the host cores, with and without a pending prefetch."""
     shp = SHAPES["c4"].with_(ffn=32, shared_ffn=32, seed=80 + batch, cache_cap=12)
     wl = make_workload(shp, n_layers=2, tokens=40, batch=batch, pred_noise=0.6)
     for pf in (0, 2):
         loads, st = replay(shim, wl, batch=batch, n_stage=batch * shp.top_k, prefetch_max=pf,
-                           cpu_assist=True, c_load=costs[0], c_cpu=costs[1])
-        assert st.cpu_computed > 20 and st.fetches > 20
+                           cpu_assist=mode, c_load=costs[0], c_cpu=costs[1])
+        if mode == 1:
+            assert st.cpu_computed > 20 and st.fetches > 20
+        else:                       # the variant leans to whichever side is cheaper
+            assert st.cpu_computed + st.fetches > 40
+            assert (st.cpu_computed > st.fetches) == (costs[1] < costs[0]) or costs[0] == costs[1]
 
 
 def test_scheduler_rejects_bad_arguments_and_malformed_decisions(shim):

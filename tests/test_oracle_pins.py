@@ -677,3 +677,22 @@ def test_cpu_assist_keeps_top_of_the_list_for_loading_and_cache_untouched_by_the
     assert seen_cpu == st.cpu_computed > 20
     assert st.fetches + st.cpu_computed == st.misses      # batch 1: every miss is loaded or computed
     assert st.evictions == st.fetches
+
+
+def test_minmax_split_variant_is_the_brute_force_optimum_and_prefers_loading_on_ties():
+    rng = np.random.default_rng(21)
+    for _ in range(300):
+        n = int(rng.integers(0, 40))
+        cl, cc = float(rng.uniform(0.1, 10)), float(rng.uniform(0.1, 10))
+        nl, ncpu = O.split_load_cpu_minmax(n, cl, cc)
+        assert nl + ncpu == n
+        times = [max(i * cl, (n - i) * cc) for i in range(n + 1)]
+        assert max(nl * cl, ncpu * cc) == min(times)
+        assert nl == max(i for i, t in enumerate(times) if t == min(times))
+        # never worse than the two-pointer walk of Algorithm 2
+        al, ac = O.split_load_cpu(n, cl, cc)
+        assert max(nl * cl, ncpu * cc) <= max(al * cl, ac * cc) + 1e-12
+    assert O.split_load_cpu_minmax(1, 3.0, 1.0) == (0, 1)      # a single miss goes to the faster side
+    assert O.split_load_cpu_minmax(1, 1.0, 3.0) == (1, 0)
+    assert O.split_load_cpu_minmax(2, 1.0, 1.0) == (1, 1)
+    assert O.split_load_cpu_minmax(4, 3.0, 1.0) == (1, 3)
