@@ -248,6 +248,26 @@ def main() -> int:
         except Exception as exc:            # e.g. not enough HBM for every expert
             extra["miss_free_error"] = repr(exc)
 
+    if not args.no_miss_free and not args.cpu_assist and args.prefetch == 0:
+        # the same tokens with the paper's CPU-assisted scheduling switched on (reported beside the
+        # headline, never as `value`): Algorithm 2 as printed, and this build's min-max variant
+        for mode, key in ((1, "cpu_assist_algorithm2"), (2, "cpu_assist_minmax_variant")):
+            log(f"run with cpu_assist = {mode} ...")
+            try:
+                with session_from_workload(wl, max_batch=Bt, n_stage=(Bt * s.top_k if Bt > 1 else 0),
+                                           cpu_assist=mode, cpu_threads=args.cpu_threads) as ses3:
+                    x_dev = wl.x.to(ses3.device).contiguous()
+                    y_dev = torch.empty(L, Bt, s.hidden, dtype=ses3.tdtype, device=ses3.device)
+                    e3, _, st3 = timed_run(ses3, x_dev, y_dev, args.warmup, args.steps, L, 1, prof_mask=0)
+                    costs = M.moe_cpu_assist_costs(ses3.handle)
+                extra[key] = {"tokens_per_s": args.steps * Bt / e3,
+                              "hit_rate": st3["hits"] / max(st3["slots"], 1),
+                              "loads_per_step": st3["fetches"] / args.steps,
+                              "host_computed_per_step": st3["cpu_computed"] / args.steps,
+                              "c_load_us": costs["c_load_us"], "c_cpu_us": costs["c_cpu_us"]}
+            except Exception as exc:
+                extra[key] = {"error": repr(exc)}
+
     cpu = None
     if args.cpu_budget > 0:
         log("timing the CPU oracle ...")

@@ -361,6 +361,88 @@ __global__ __launch_bounds__(1024) void route_b1_kernel(const RouteArgs a) {
   if (lane == 0) { o->thr_r = sm.thr_r[tok]; o->top_m = sm.top_m_sh[tok]; }
 }
 
+// Batch 1, gate matrix too large for one compute unit to stream quickly (a
+// single block pulls a few tens of GB/s): the GEMV is spread over `split_nb`
+// blocks of four waves.  Work item = (row, segment); the waves of the whole
+// grid take items round-robin, RPP at a time, with their slice of x in
+// registers, and write each item's partial dot product to device scratch.  The
+// block that finishes last (agent-scope fence, then one atomic ticket per
+// block) sums the segments of every row in fixed order and runs the selection
+// and the publication exactly as the single-block kernel does; it also resets
+// the ticket counter for the next launch.
+template <typename T, int UPI>
+__global__ __launch_bounds__(256) void route_split_kernel(const RouteArgs a) {
+  __shared__ SelectSmem sm;
+  __shared__ float sim_sh[SMOE_MAX_EXPERTS * SMOE_MAX_EXPERTS];
+  __shared__ int is_last;
+  constexpr int N = GateUnit<T>::N;
+  using raw = typename GateUnit<T>::raw;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+  const int H = a.H, E = a.E;
+  const int nseg = a.nseg;                       // power of two <= 8; 4 * gridDim.x is a multiple of it
+  const int items = E * nseg;
+  const int units = H / N;
+  const int nw = 4 * gridDim.x;
+  const int gw = 4 * blockIdx.x + wave;
+  const T* wg = static_cast<const T*>(a.gate_w);
+  const T* x = static_cast<const T*>(a.x);
+
+  const int sg = gw & (nseg - 1);                // the same segment for every item of this wave
+  const int u0 = (int)((long)units * sg / nseg), u1 = (int)((long)units * (sg + 1) / nseg);
+  raw xr[UPI];
+#pragma unroll
+  for (int i = 0; i < UPI; ++i) {
+    const int u = u0 + i * kWave + lane;
+    xr[i] = (u < u1) ? *reinterpret_cast<const raw*>(x + (size_t)u * N) : raw{};
+  }
+  if (a.subst_key == 0)
+    for (int i = tid; i < E * E; i += 256) sim_sh[i] = a.sim[i];
+  if (tid < kWave) sm.slot_of[tid] = a.slot_of[tid];
+
+  constexpr int RPP = UPI >= 8 ? 2 : 4;
+  for (int base = 0; base < items; base += RPP * nw) {
+    float acc[RPP];
+#pragma unroll
+    for (int r = 0; r < RPP; ++r) acc[r] = 0.f;
+#pragma unroll
+    for (int i = 0; i < UPI; ++i) {
+      const int u = u0 + i * kWave + lane;
+      raw q[RPP];
+#pragma unroll
+      for (int r = 0; r < RPP; ++r) {
+        const int it = base + r * nw + gw;
+        q[r] = (it < items && u < u1) ? *reinterpret_cast<const raw*>(wg + (size_t)(it / nseg) * H + (size_t)u * N)
+                                      : raw{};
+      }
+#pragma unroll
+      for (int r = 0; r < RPP; ++r) acc[r] = GateUnit<T>::dot(q[r], xr[i], acc[r]);
+    }
+#pragma unroll
+    for (int r = 0; r < RPP; ++r) {
+      const int it = base + r * nw + gw;
+      const float v = wave_sum(acc[r]);
+      if (lane == 0 && it < items) a.split_part[it] = v;     // it = row * nseg + sg
+    }
+  }
+  // this block's partial sums are visible device-wide before its ticket is drawn
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) is_last = (atomicAdd(a.split_count, 1u) == gridDim.x - 1) ? 1 : 0;
+  __syncthreads();
+  if (!is_last) return;
+  __threadfence();                                // the other blocks' sums are visible to this one
+  if (wave != 0) return;
+  if (lane == 0) *a.split_count = 0u;             // stream order: the next launch starts after this one ends
+  {
+    float v = 0.f;
+    if (lane < E)
+      for (int s2 = 0; s2 < nseg; ++s2)
+        v += __builtin_nontemporal_load(a.split_part + lane * nseg + s2);
+    sm.lg[0][lane] = v;
+  }
+  select_and_publish(a, sm, sim_sh, lane);
+}
+
 // Batch > 1, second launch: wave t runs pass 2 for token t against the batch
 // top-score set; wave 0 then builds the expert groups and publishes.
 __global__ __launch_bounds__(64 * SMOE_MAX_BATCH) void route_merge_kernel(const RouteArgs a) {
@@ -392,6 +474,15 @@ __global__ __launch_bounds__(64 * SMOE_MAX_BATCH) void route_merge_kernel(const 
 
 template <typename T>
 static void launch_route_t(const RouteArgs& a, hipStream_t s) {
+  if (a.fast_upi > 0 && a.B == 1 && a.split_nb > 0) {
+    switch (a.fast_upi) {
+      case 1: hipLaunchKernelGGL((route_split_kernel<T, 1>), dim3(a.split_nb), dim3(256), 0, s, a); return;
+      case 2: hipLaunchKernelGGL((route_split_kernel<T, 2>), dim3(a.split_nb), dim3(256), 0, s, a); return;
+      case 4: hipLaunchKernelGGL((route_split_kernel<T, 4>), dim3(a.split_nb), dim3(256), 0, s, a); return;
+      case 8: hipLaunchKernelGGL((route_split_kernel<T, 8>), dim3(a.split_nb), dim3(256), 0, s, a); return;
+      default: break;
+    }
+  }
   if (a.fast_upi > 0) {
     // one block per token; with more than one token a second launch merges them
     bool launched = true;

@@ -59,7 +59,9 @@ struct RouteArgs {
   RouteTmp* tmp;        // [B] scratch of the batched router
   void* x_mirror;       // device-visible pinned host copy of x for the host cores, or null
   int32_t x_units;      // 16-byte units of x ([B][H] dtype) to mirror
-  int32_t pad_;
+  int32_t split_nb;     // batch 1: blocks the gate GEMV is spread over (0 = single-block kernels)
+  float* split_part;    // [E * 8] partial dot products of the spread GEMV (device scratch)
+  unsigned int* split_count;  // blocks of the spread GEMV that have finished (zero between launches)
   int32_t B, H, E, k;
   int32_t renorm, subst_key;
   int32_t nseg;         // segments each gate row is split into (power of two, <= 8)

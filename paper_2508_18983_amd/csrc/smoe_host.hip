@@ -62,6 +62,9 @@ struct moe_handle {
   float* act = nullptr;
   float* ysum = nullptr;
   RouteTmp* route_tmp = nullptr;
+  float* split_part = nullptr;           // scratch of the multi-block batch-1 router
+  unsigned int* split_count = nullptr;
+  int route_split = 1;                   // SMOE_ROUTE_SPLIT: 0 never, 1 for gate matrices >= 512 KiB, 2 always
   // top-score prefetch: the prediction has a decision record of its own
   StepRec* pred_dev = nullptr;
   StepRec* pred_host = nullptr;          // pinned
@@ -218,6 +221,8 @@ void free_all(moe_handle* h) {
   if (h->act) (void)hipFree(h->act);
   if (h->ysum) (void)hipFree(h->ysum);
   if (h->route_tmp) (void)hipFree(h->route_tmp);
+  if (h->split_part) (void)hipFree(h->split_part);
+  if (h->split_count) (void)hipFree(h->split_count);
   delete h;
 }
 
@@ -338,6 +343,27 @@ void fill_route_args(const moe_handle* h, int layer, int B, const void* x, Route
   if (ra.fast_upi == 0) {
     ra.nseg = 1;
     while (ra.nseg < 8 && E * ra.nseg < 32 && c.hidden / (ra.nseg * 2) >= 512) ra.nseg *= 2;
+  }
+  ra.split_nb = 0;
+  ra.split_part = h->split_part;
+  ra.split_count = h->split_count;
+  const int64_t gate_bytes = (int64_t)E * c.hidden * h->esize;
+  if (B == 1 && h->route_fast && (h->route_split >= 2 || (h->route_split == 1 && gate_bytes >= 512 * 1024))) {
+    // batch 1, large gate matrix: spread the GEMV over several blocks, about one (row, segment)
+    // item per wave.  Below ~0.5 MB the fence and the ticket cost more than one compute unit
+    // loses by streaming the matrix alone (measured: 64 x 8192 bf16 24 -> 18 us, 64 x 2048 no gain).
+    int nseg = 1;
+    while (nseg < 8 && (E * nseg < 64 || gate_units / nseg > 8 * kWave) && gate_units / (nseg * 2) >= kWave)
+      nseg *= 2;
+    const int per_lane = ((gate_units + nseg - 1) / nseg + kWave - 1) / kWave;
+    if (per_lane <= 8) {
+      ra.nseg = nseg;
+      ra.fast_upi = per_lane <= 1 ? 1 : (per_lane <= 2 ? 2 : (per_lane <= 4 ? 4 : 8));
+      const int items = E * nseg;
+      int nb = std::min(16, (items + 3) / 4);
+      nb = std::max(2, (nb + 1) / 2 * 2);            // 4 * nb waves: a multiple of nseg <= 8
+      ra.split_nb = nb;
+    }
   }
   ra.resident = ls.resident;
   std::memcpy(ra.slot_of, ls.slot_of, sizeof(ra.slot_of));
@@ -493,6 +519,10 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
     HIP_TRY(hipMalloc(&h->act, (size_t)h->act_floats * sizeof(float)));
     HIP_TRY(hipMalloc(&h->ysum, (size_t)c.max_batch * c.hidden * sizeof(float)));
     HIP_TRY(hipMalloc(&h->route_tmp, (size_t)SMOE_MAX_BATCH * sizeof(RouteTmp)));
+    HIP_TRY(hipMalloc(&h->split_part, (size_t)SMOE_MAX_EXPERTS * 8 * sizeof(float)));
+    HIP_TRY(hipMalloc(&h->split_count, sizeof(unsigned int)));
+    HIP_TRY(hipMemset(h->split_count, 0, sizeof(unsigned int)));
+    h->route_split = env_int("SMOE_ROUTE_SPLIT", 1);
     if (c.prefetch_max > 0) {
       HIP_TRY(hipMalloc(&h->pred_dev, sizeof(StepRec)));
       HIP_TRY(hipHostMalloc(&h->pred_host, sizeof(StepRec), hipHostMallocDefault));

@@ -124,10 +124,11 @@ def test_error_paths_and_reset():
 
 @pytest.mark.parametrize("env", [dict(SMOE_REGPATH="0"), dict(SMOE_REGPATH="0", SMOE_R="2", SMOE_CHUNK="1024"),
                                  dict(SMOE_RB="16", SMOE_TF="64"), dict(SMOE_SPIN_LIMIT="0"),
-                                 dict(SMOE_ROUTE_FAST="0")])
+                                 dict(SMOE_ROUTE_FAST="0"), dict(SMOE_ROUTE_SPLIT="2")])
 def test_alternative_kernel_paths_and_launch_shapes(env, monkeypatch):
     """The LDS-staged kernels (fallback for very wide layers), other tile
-    shapes, and the stream-drain fallback of the host must give the same answers."""
+    shapes, the generic and the multi-block router, and the stream-drain fallback
+    of the host must give the same answers."""
     for k, v in env.items():
         monkeypatch.setenv(k, v)
     wl = make_workload(SHAPES["c2"].with_(seed=4), n_layers=2, tokens=24)
