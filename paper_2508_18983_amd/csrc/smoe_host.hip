@@ -428,6 +428,188 @@ int settle_prefetch(moe_handle* h) {
   }
   return SMOE_OK;
 }
+// Experts of `layer` whose prefetch copy may still be running.  They count as
+// resident for every decision, but the resident pass leaves them out (their slot
+// is hidden from the kernels) and the second pass computes them after the copy
+// stream has caught up, so neither the router nor the resident pass ever waits.
+uint64_t prefetched_in_flight(moe_handle* h, int layer) {
+  if (h->pf_inflight.empty() || !h->pf_inflight[layer]) return 0;
+  if (hipEventQuery(h->ev_prefetch[layer]) == hipSuccess) {
+    h->pf_inflight[layer] = 0;
+    h->pf_mask[layer] = 0;
+    return 0;
+  }
+  (void)hipGetLastError();                           // "not ready" is not an error here
+  return h->pf_mask[layer] & h->layers[layer].resident;
+}
+
+// Arguments of the FFN launches of one call (resident pass; the second pass
+// changes `pass` and `slot_override` only).
+void fill_ffn_args(const moe_handle* h, int layer, int B, const void* x_dev, void* y_dev, FfnArgs& fa) {
+  const moe_cfg_t& c = h->cfg;
+  fa.rec = h->rec_dev;
+  fa.x = x_dev; fa.y = y_dev;
+  fa.slab = static_cast<const char*>(h->buf.cache_slab_dev);
+  fa.shared = c.n_shared ? static_cast<const char*>(h->buf.shared_dev) +
+                               (int64_t)layer * c.n_shared * h->shared_bytes
+                         : nullptr;
+  fa.act = h->act; fa.ysum = h->ysum;
+  fa.expert_bytes = h->expert_bytes; fa.shared_bytes = h->shared_bytes;
+  fa.B = B; fa.H = c.hidden; fa.F = c.ffn; fa.Fs = c.n_shared ? c.shared_ffn : 0;
+  fa.k = c.top_k; fa.ns = c.n_shared; fa.Fmax = h->Fmax;
+  fa.slot_base = layer * c.cache_cap;
+  fa.pass = 0;
+  fa.TF = h->TF; fa.tilesR = h->tilesR; fa.tilesS = h->tilesS;
+  fa.R = h->R; fa.htiles = h->htiles;
+  fa.stage_all = h->stage_all; fa.chunk = h->chunk; fa.down_lds_floats = h->down_lds;
+  fa.up_upl = h->up_upl; fa.down_upl = h->down_upl; fa.RB = h->RB;
+  fa.nsegR = h->nsegR; fa.nsegS = h->nsegS;
+  for (int i = 0; i < kMaxTasks; ++i) fa.slot_override[i] = -1;
+  fa.grouped = (B > 1 && h->grouped_ok) ? 1 : 0;
+  fa.maxg = std::min(c.n_experts, B * c.top_k);
+  fa.mfma_down = (fa.grouped && c.dtype == SMOE_DTYPE_BF16 && h->mfma_ok) ? 1 : 0;
+  fa.mfma_up = (fa.mfma_down && h->mfma_ok >= 2) ? 1 : 0;
+  fa.nsegGR = h->nsegGR; fa.nsegGS = h->nsegGS; fa.RBG = h->RBG;
+  fa.act_shared_off = (int64_t)fa.maxg * SMOE_MAX_BATCH * c.ffn;
+  if (fa.grouped && fa.up_upl == 0) {                 // grouped up kernel needs units per lane
+    const int n = c.dtype == SMOE_DTYPE_FP32 ? 4 : 8;
+    const int xu = (c.hidden / n + kWave - 1) / kWave;
+    fa.up_upl = xu <= 1 ? 1 : (xu <= 2 ? 2 : (xu <= 4 ? 4 : 8));
+  }
+}
+
+// One up + down launch pair; *timed_up / *timed_down tell whether the profiler
+// recorded them.
+int launch_ffn_pair(moe_handle* h, const FfnArgs& fa, int kind_up, int kind_down, bool* timed_up,
+                    bool* timed_down) {
+  EventPair* pu = prof_begin(h, kind_up, h->s_compute);
+  launch_ffn_up(fa, h->cfg.dtype, h->s_compute);
+  prof_end(pu, h->s_compute);
+  EventPair* pd = prof_begin(h, kind_down, h->s_compute);
+  launch_ffn_down(fa, h->cfg.dtype, h->s_compute);
+  prof_end(pd, h->s_compute);
+  *timed_up = pu != nullptr;
+  *timed_down = pd != nullptr;
+  HIP_TRY(hipGetLastError());
+  return SMOE_OK;
+}
+
+// Loads of the step's missing experts on the copy stream (Section V-B, "Loading
+// Experts from Layer i"); gslot[i] = global slot of load i.  Records ev_copy behind
+// them.  With measured Algorithm-2 costs each copy also goes into the ring of
+// timed copies.
+int enqueue_loads(moe_handle* h, int layer, const StepPlan& plan, int* gslot) {
+  const moe_cfg_t& c = h->cfg;
+  const bool time_copies = c.cpu_assist && c.load_cost_us <= 0.f;
+  for (int i = 0; i < plan.n_fetch; ++i) {
+    const int m = plan.fetched[i];
+    gslot[i] = plan.slot[i] >= 0 ? layer * c.cache_cap + plan.slot[i]
+                                 : c.n_layers * c.cache_cap + (-plan.slot[i] - 1);
+    const char* src = h->experts_host[layer] + (int64_t)m * h->expert_bytes;
+    char* dst = static_cast<char*>(h->buf.cache_slab_dev) + (int64_t)gslot[i] * h->expert_bytes;
+    EventPair* pc = prof_begin(h, SMOE_PROF_COPY, h->s_copy);
+    EventPair* cost = nullptr;
+    if (time_copies && !h->copy_ev_pending[h->copy_ev_next]) {
+      cost = &h->copy_ev[h->copy_ev_next];
+      HIP_TRY(hipEventRecord(cost->a, h->s_copy));
+    }
+    HIP_TRY(hipMemcpyAsync(dst, src, h->expert_bytes, hipMemcpyHostToDevice, h->s_copy));
+    if (cost) {
+      HIP_TRY(hipEventRecord(cost->b, h->s_copy));
+      h->copy_ev_pending[h->copy_ev_next] = true;
+      h->copy_ev_next = (h->copy_ev_next + 1) % moe_handle::kCostWindow;
+    }
+    prof_end(pc, h->s_copy);
+    if (pc) h->prof[SMOE_PROF_COPY].bytes += h->expert_bytes;   // bytes of timed copies only
+  }
+  if (plan.n_fetch > 0) HIP_TRY(hipEventRecord(h->ev_copy, h->s_copy));
+  return SMOE_OK;
+}
+
+// Second pass: which task computes from which global slot -- the experts this
+// call has loaded, and prefetched experts (`late`) whose copy was in flight when
+// the call began.
+void set_second_pass_slots(const moe_handle* h, int layer, int B, const StepRec& rec, const StepPlan& plan,
+                           const int* gslot, uint64_t late, FfnArgs& fa) {
+  const moe_cfg_t& c = h->cfg;
+  const CacheLayer& ls = h->layers[layer];
+  const int k = c.top_k, nj = k + c.n_shared;
+  fa.pass = 1;
+  if (fa.grouped) {
+    // group index of an expert = its rank among the distinct experts of the step (ascending id)
+    for (int i = 0; i < plan.n_fetch; ++i) {
+      const int gi = __builtin_popcountll(plan.shield & ((1ull << plan.fetched[i]) - 1ull));
+      fa.slot_override[gi] = gslot[i];
+    }
+    for (int e = 0; e < c.n_experts; ++e)
+      if ((late >> e) & 1ull) {
+        const int gi = __builtin_popcountll(plan.shield & ((1ull << e) - 1ull));
+        fa.slot_override[gi] = layer * c.cache_cap + ls.slot_of[e];
+      }
+    return;
+  }
+  for (int t = 0; t < B; ++t)
+    for (int j = 0; j < k; ++j) {
+      const int e = rec.tok[t].final_[j];
+      if ((late >> e) & 1ull) fa.slot_override[t * nj + j] = layer * c.cache_cap + ls.slot_of[e];
+      if ((plan.before >> e) & 1ull) continue;
+      for (int i = 0; i < plan.n_fetch; ++i)
+        if (plan.fetched[i] == e) fa.slot_override[t * nj + j] = gslot[i];
+    }
+}
+
+// Algorithmic bytes the timed launches of this call were asked to stream
+// (launches past the end of the event pool are not timed and add no bytes).
+void account_profile_bytes(moe_handle* h, int B, const StepRec& rec, const StepPlan& plan, uint64_t late,
+                           bool grouped, const bool (&timed)[5]) {
+  const moe_cfg_t& c = h->cfg;
+  const int k = c.top_k;
+  int64_t late_slots = 0, cpu_slots = 0;   // slots moved to the second pass / computed by the host cores
+  for (int t = 0; t < B; ++t)
+    for (int j = 0; j < k; ++j) {
+      const int e = rec.tok[t].final_[j];
+      late_slots += (late >> e) & 1ull;
+      for (int i = 0; i < plan.n_cpu; ++i) cpu_slots += plan.on_cpu[i] == e;
+    }
+  int64_t miss_slots = (int64_t)B * k - plan.hits + late_slots - cpu_slots;
+  int64_t res_slots = plan.hits - late_slots, shared_times = B;
+  if (grouped) {                                      // weights are streamed once per distinct expert
+    res_slots = __builtin_popcountll(plan.shield & plan.before & ~late);
+    miss_slots = plan.n_fetch + __builtin_popcountll(late);
+    shared_times = 1;
+  }
+  const int64_t up_r = 2ll * c.hidden * c.ffn * h->esize, up_s = 2ll * c.hidden * c.shared_ffn * h->esize;
+  const int64_t resident_up = res_slots * up_r + shared_times * c.n_shared * up_s;
+  if (timed[0]) h->prof[SMOE_PROF_ROUTE].bytes += (int64_t)c.n_experts * c.hidden * h->esize;
+  if (timed[1]) h->prof[SMOE_PROF_UP].bytes += resident_up;
+  if (timed[2]) h->prof[SMOE_PROF_DOWN].bytes += resident_up / 2;
+  if (timed[3]) h->prof[SMOE_PROF_UP_LOADED].bytes += miss_slots * up_r;
+  if (timed[4]) h->prof[SMOE_PROF_DOWN_LOADED].bytes += miss_slots * up_r / 2;
+}
+
+void fill_trace(const moe_handle* h, int B, const StepRec& rec, const StepPlan& plan, moe_trace_t* trace) {
+  const int k = h->cfg.top_k, E = h->cfg.n_experts;
+  for (int t = 0; t < B; ++t)
+    for (int j = 0; j < k; ++j) {
+      const int o = t * k + j;
+      if (trace->topk_idx) trace->topk_idx[o] = rec.tok[t].topk[j];
+      if (trace->final_idx) trace->final_idx[o] = rec.tok[t].final_[j];
+      if (trace->substituted) trace->substituted[o] = (uint8_t)(rec.tok[t].subst[j] != 0);
+      if (trace->hit) trace->hit[o] = (uint8_t)((plan.before >> rec.tok[t].final_[j]) & 1ull);
+      if (trace->weights) trace->weights[o] = rec.tok[t].w[j];
+    }
+  if (trace->scores)
+    for (int t = 0; t < B; ++t)
+      std::memcpy(trace->scores + (size_t)t * E, rec.tok[t].scores, sizeof(float) * E);
+  for (int i = 0; i < B * k; ++i) {
+    if (trace->fetched) trace->fetched[i] = i < plan.n_fetch ? plan.fetched[i] : -1;
+    if (trace->victims) trace->victims[i] = i < plan.n_fetch ? plan.victims[i] : -1;
+    if (trace->on_cpu) trace->on_cpu[i] = i < plan.n_cpu ? plan.on_cpu[i] : -1;
+  }
+  trace->n_fetched = plan.n_fetch;
+  trace->n_on_cpu = plan.n_cpu;
+}
+
 }  // namespace
 
 extern "C" {
@@ -600,28 +782,15 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   const moe_cfg_t& c = h->cfg;
   if (layer < 0 || layer >= c.n_layers || batch < 1 || batch > c.max_batch) return SMOE_EINVAL;
   CacheLayer& ls = h->layers[layer];
-  const int k = c.top_k, E = c.n_experts, B = batch, nj = k + c.n_shared;
+  const int E = c.n_experts, B = batch;
+  bool timed[5] = {false, false, false, false, false};   // route, up, down, up (2nd pass), down (2nd pass)
 
-  // ---- a prefetch for this very layer has to be decided before it is routed;
-  //      copies of an earlier prefetch for it must have landed -------------------
+  // ---- a prefetch for this very layer has to be decided before it is routed ----
   if (h->pending_layer == layer) {
     const int rc = settle_prefetch(h);
     if (rc != SMOE_OK) return rc;
   }
-  // Experts of this layer whose prefetch copy may still be running: they count as
-  // resident for every decision, but the resident pass leaves them out (their slot
-  // is hidden from the kernels) and the second pass computes them after the copy
-  // stream has caught up, so neither the router nor the resident pass ever waits.
-  uint64_t deferred = 0;
-  if (!h->pf_inflight.empty() && h->pf_inflight[layer]) {
-    if (hipEventQuery(h->ev_prefetch[layer]) == hipSuccess) {
-      h->pf_inflight[layer] = 0;
-      h->pf_mask[layer] = 0;
-    } else {
-      (void)hipGetLastError();                       // "not ready" is not an error here
-      deferred = h->pf_mask[layer] & ls.resident;
-    }
-  }
+  const uint64_t deferred = prefetched_in_flight(h, layer);
 
   // ---- router + expert-cache router ------------------------------------------
   RouteArgs ra{};
@@ -635,63 +804,34 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
     ra.x_mirror = h->x_host_dev;
     ra.x_units = (int32_t)((int64_t)B * c.hidden * h->esize / 16);
   }
-  EventPair* pr = prof_begin(h, SMOE_PROF_ROUTE, h->s_compute);
-  launch_route(ra, c.dtype, h->s_compute);
-  prof_end(pr, h->s_compute);
-  HIP_TRY(hipGetLastError());
+  {
+    EventPair* pr = prof_begin(h, SMOE_PROF_ROUTE, h->s_compute);
+    launch_route(ra, c.dtype, h->s_compute);
+    prof_end(pr, h->s_compute);
+    timed[0] = pr != nullptr;
+    HIP_TRY(hipGetLastError());
+  }
   // (no event after the router kernel: an event record costs several microseconds of
   // stream time between the router and the FFN; the host polls the mirror instead)
 
   // ---- FFN over what is already resident (+ shared experts), enqueued before
   //      the host knows the routing result ------------------------------------
   FfnArgs fa{};
-  fa.rec = h->rec_dev;
-  fa.x = x_dev; fa.y = y_dev;
-  fa.slab = static_cast<const char*>(h->buf.cache_slab_dev);
-  fa.shared = c.n_shared ? static_cast<const char*>(h->buf.shared_dev) +
-                               (int64_t)layer * c.n_shared * h->shared_bytes
-                         : nullptr;
-  fa.act = h->act; fa.ysum = h->ysum;
-  fa.expert_bytes = h->expert_bytes; fa.shared_bytes = h->shared_bytes;
-  fa.B = B; fa.H = c.hidden; fa.F = c.ffn; fa.Fs = c.n_shared ? c.shared_ffn : 0;
-  fa.k = k; fa.ns = c.n_shared; fa.Fmax = h->Fmax;
-  fa.slot_base = layer * c.cache_cap;
-  fa.pass = 0;
-  fa.TF = h->TF; fa.tilesR = h->tilesR; fa.tilesS = h->tilesS;
-  fa.R = h->R; fa.htiles = h->htiles;
-  fa.stage_all = h->stage_all; fa.chunk = h->chunk; fa.down_lds_floats = h->down_lds;
-  fa.up_upl = h->up_upl; fa.down_upl = h->down_upl; fa.RB = h->RB;
-  fa.nsegR = h->nsegR; fa.nsegS = h->nsegS;
-  for (int i = 0; i < kMaxTasks; ++i) fa.slot_override[i] = -1;
-  fa.grouped = (B > 1 && h->grouped_ok) ? 1 : 0;
-  fa.maxg = std::min(E, B * k);
-  fa.mfma_down = (fa.grouped && c.dtype == SMOE_DTYPE_BF16 && h->mfma_ok) ? 1 : 0;
-  fa.mfma_up = (fa.mfma_down && h->mfma_ok >= 2) ? 1 : 0;
-  fa.nsegGR = h->nsegGR; fa.nsegGS = h->nsegGS; fa.RBG = h->RBG;
-  fa.act_shared_off = (int64_t)fa.maxg * SMOE_MAX_BATCH * c.ffn;
-  if (fa.grouped && fa.up_upl == 0) {                 // grouped up kernel needs units per lane
-    const int n = c.dtype == SMOE_DTYPE_FP32 ? 4 : 8;
-    const int xu = (c.hidden / n + kWave - 1) / kWave;
-    fa.up_upl = xu <= 1 ? 1 : (xu <= 2 ? 2 : (xu <= 4 ? 4 : 8));
+  fill_ffn_args(h, layer, B, x_dev, y_dev, fa);
+  {
+    const int rc = launch_ffn_pair(h, fa, SMOE_PROF_UP, SMOE_PROF_DOWN, &timed[1], &timed[2]);
+    if (rc != SMOE_OK) return rc;
   }
-  EventPair* pu = prof_begin(h, SMOE_PROF_UP, h->s_compute);
-  launch_ffn_up(fa, c.dtype, h->s_compute);
-  prof_end(pu, h->s_compute);
-  EventPair* pd = prof_begin(h, SMOE_PROF_DOWN, h->s_compute);
-  launch_ffn_down(fa, c.dtype, h->s_compute);
-  prof_end(pd, h->s_compute);
-  HIP_TRY(hipGetLastError());
 
-  // ---- the decision reaches the host -----------------------------------------
-  // Poll the pinned mirror (the router kernel publishes its call number last);
-  // after spin_limit polls fall back to draining the compute stream.
+  // ---- the decision reaches the host: poll the pinned mirror (the router kernel
+  //      publishes its call number last), then fall back to draining the stream ----
   {
     const int rc = await_record(h, h->rec_host, h->seq);
     if (rc != SMOE_OK) return rc;
   }
   const StepRec& rec = *h->rec_host;
 
-  // ---- cache bookkeeping: history, shield, victims, residency, counters -------
+  // ---- cache bookkeeping: history, shield, Algorithm 2, victims, residency, counters ----
   StepDecision dec{};
   dec.B = B;
   for (int t = 0; t < B; ++t) {
@@ -706,94 +846,39 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
     const int rc = ls.plan_step(h->cp, dec, h->expert_bytes, plan, h->c_load_us, h->c_cpu_us);
     if (rc != SMOE_OK) return rc;
   }
-  const uint64_t before = plan.before, shield = plan.shield;
-  const int n_fetch = plan.n_fetch;
-  const int64_t hits = plan.hits;
-  const int* fetched = plan.fetched;
-  const int* victims = plan.victims;
-  int gslot[SMOE_MAX_BATCH * SMOE_MAX_TOPK];
-  bool timed_up2 = false, timed_down2 = false;
+  const uint64_t late = deferred & plan.shield;   // prefetched experts this step computes in the second pass
 
-  const uint64_t late = deferred & shield;   // prefetched experts this step computes in the second pass
-  const int n_cpu = plan.n_cpu;
-  if (n_fetch > 0 || late || n_cpu > 0) {
+  if (plan.n_fetch > 0 || late || plan.n_cpu > 0) {
     // ---- loads on the copy stream; the second FFN pass waits for them ---------
-    const bool time_copies = c.cpu_assist && c.load_cost_us <= 0.f;
-    for (int i = 0; i < n_fetch; ++i) {
-      const int m = fetched[i];
-      gslot[i] = plan.slot[i] >= 0 ? layer * c.cache_cap + plan.slot[i]
-                                   : c.n_layers * c.cache_cap + (-plan.slot[i] - 1);
-      const char* src = h->experts_host[layer] + (int64_t)m * h->expert_bytes;
-      char* dst = static_cast<char*>(h->buf.cache_slab_dev) + (int64_t)gslot[i] * h->expert_bytes;
-      EventPair* pc = prof_begin(h, SMOE_PROF_COPY, h->s_copy);
-      EventPair* cost = nullptr;                     // measured C_load: ring of the last copies
-      if (time_copies && !h->copy_ev_pending[h->copy_ev_next]) {
-        cost = &h->copy_ev[h->copy_ev_next];
-        HIP_TRY(hipEventRecord(cost->a, h->s_copy));
-      }
-      HIP_TRY(hipMemcpyAsync(dst, src, h->expert_bytes, hipMemcpyHostToDevice, h->s_copy));
-      if (cost) {
-        HIP_TRY(hipEventRecord(cost->b, h->s_copy));
-        h->copy_ev_pending[h->copy_ev_next] = true;
-        h->copy_ev_next = (h->copy_ev_next + 1) % moe_handle::kCostWindow;
-      }
-      prof_end(pc, h->s_copy);
-      if (pc) h->prof[SMOE_PROF_COPY].bytes += h->expert_bytes;   // bytes of timed copies only
+    int gslot[SMOE_MAX_BATCH * SMOE_MAX_TOPK];
+    {
+      const int rc = enqueue_loads(h, layer, plan, gslot);
+      if (rc != SMOE_OK) return rc;
     }
-    if (n_fetch > 0) HIP_TRY(hipEventRecord(h->ev_copy, h->s_copy));
-    if (n_cpu > 0) {
+    if (plan.n_cpu > 0) {
       // ---- CPU-assisted scheduling: while the copies run, the host cores compute the
       //      experts Algorithm 2 left to them; a prefetch that is waiting goes onto the
       //      copy stream first so that the link stays busy meanwhile.  The result is added
       //      to the fp32 sums of the resident pass, and the second pass rounds y once.
-      const int prc = settle_prefetch(h);
-      if (prc != SMOE_OK) return prc;
-      compute_on_cpu(h, layer, B, rec, plan.on_cpu, n_cpu);
+      const int rc = settle_prefetch(h);
+      if (rc != SMOE_OK) return rc;
+      compute_on_cpu(h, layer, B, rec, plan.on_cpu, plan.n_cpu);
       launch_add_partial(h->ysum, h->ycpu_host_dev, B * c.hidden, h->s_compute);
       HIP_TRY(hipGetLastError());
     }
-    if (n_fetch > 0) {
+    if (plan.n_fetch > 0) {
       // (this layer's prefetch copies precede its loads on the copy stream)
       HIP_TRY(hipStreamWaitEvent(h->s_compute, h->ev_copy, 0));
     } else if (late) {
       HIP_TRY(hipStreamWaitEvent(h->s_compute, h->ev_prefetch[layer], 0));
     }
-    if (deferred && (n_fetch > 0 || late)) {     // the compute stream is now behind those copies
+    if (deferred && (plan.n_fetch > 0 || late)) {   // the compute stream is now behind those copies
       h->pf_inflight[layer] = 0;
       h->pf_mask[layer] = 0;
     }
-    // second FFN pass: only the slots whose expert has just been loaded
-    fa.pass = 1;
-    if (fa.grouped) {
-      // group index of an expert = its rank among the distinct experts of the step (ascending id)
-      for (int i = 0; i < n_fetch; ++i) {
-        const int gi = __builtin_popcountll(shield & ((1ull << fetched[i]) - 1ull));
-        fa.slot_override[gi] = gslot[i];
-      }
-      for (int e = 0; e < E; ++e)
-        if ((late >> e) & 1ull) {
-          const int gi = __builtin_popcountll(shield & ((1ull << e) - 1ull));
-          fa.slot_override[gi] = layer * c.cache_cap + ls.slot_of[e];
-        }
-    } else {
-      for (int t = 0; t < B; ++t)
-        for (int j = 0; j < k; ++j) {
-          const int e = rec.tok[t].final_[j];
-          if ((late >> e) & 1ull) fa.slot_override[t * nj + j] = layer * c.cache_cap + ls.slot_of[e];
-          if ((before >> e) & 1ull) continue;
-          for (int i = 0; i < n_fetch; ++i)
-            if (fetched[i] == e) fa.slot_override[t * nj + j] = gslot[i];
-        }
-    }
-    EventPair* pu2 = prof_begin(h, SMOE_PROF_UP_LOADED, h->s_compute);
-    launch_ffn_up(fa, c.dtype, h->s_compute);
-    prof_end(pu2, h->s_compute);
-    EventPair* pd2 = prof_begin(h, SMOE_PROF_DOWN_LOADED, h->s_compute);
-    launch_ffn_down(fa, c.dtype, h->s_compute);
-    prof_end(pd2, h->s_compute);
-    timed_up2 = pu2 != nullptr;
-    timed_down2 = pd2 != nullptr;
-    HIP_TRY(hipGetLastError());
+    set_second_pass_slots(h, layer, B, rec, plan, gslot, late, fa);
+    const int rc = launch_ffn_pair(h, fa, SMOE_PROF_UP_LOADED, SMOE_PROF_DOWN_LOADED, &timed[3], &timed[4]);
+    if (rc != SMOE_OK) return rc;
   }
   // ---- a prefetch waiting for its decision (for another layer) is settled now:
   //      its copies queue behind the loads this layer is waiting for --------------
@@ -801,52 +886,8 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
     const int rc = settle_prefetch(h);
     if (rc != SMOE_OK) return rc;
   }
-  if (h->prof_mask) {
-    // algorithmic bytes each timed launch was asked to stream (launches past the end of
-    // the event pool are not timed and add no bytes)
-    int64_t late_slots = 0;                           // slots the second pass took over from the first
-    for (int t = 0; t < B; ++t)
-      for (int j = 0; j < k; ++j) late_slots += (late >> rec.tok[t].final_[j]) & 1ull;
-    int64_t cpu_slots = 0;                            // slots the host cores computed: no GPU bytes
-    for (int t = 0; t < B; ++t)
-      for (int j = 0; j < k; ++j)
-        for (int i = 0; i < n_cpu; ++i) cpu_slots += plan.on_cpu[i] == rec.tok[t].final_[j];
-    int64_t miss_slots = (int64_t)B * k - hits + late_slots - cpu_slots;
-    int64_t res_slots = hits - late_slots, shared_times = B;
-    if (fa.grouped) {                                 // weights are streamed once per distinct expert
-      res_slots = __builtin_popcountll(shield & before & ~late);
-      miss_slots = n_fetch + __builtin_popcountll(late);
-      shared_times = 1;
-    }
-    const int64_t up_r = 2ll * c.hidden * c.ffn * h->esize, up_s = 2ll * c.hidden * c.shared_ffn * h->esize;
-    if (pr) h->prof[SMOE_PROF_ROUTE].bytes += (int64_t)E * c.hidden * h->esize;
-    if (pu) h->prof[SMOE_PROF_UP].bytes += res_slots * up_r + shared_times * c.n_shared * up_s;
-    if (pd) h->prof[SMOE_PROF_DOWN].bytes += (res_slots * up_r + shared_times * c.n_shared * up_s) / 2;
-    if (timed_up2) h->prof[SMOE_PROF_UP_LOADED].bytes += miss_slots * up_r;
-    if (timed_down2) h->prof[SMOE_PROF_DOWN_LOADED].bytes += miss_slots * up_r / 2;
-  }
-
-  if (trace) {
-    for (int t = 0; t < B; ++t)
-      for (int j = 0; j < k; ++j) {
-        const int o = t * k + j;
-        if (trace->topk_idx) trace->topk_idx[o] = rec.tok[t].topk[j];
-        if (trace->final_idx) trace->final_idx[o] = rec.tok[t].final_[j];
-        if (trace->substituted) trace->substituted[o] = (uint8_t)(rec.tok[t].subst[j] != 0);
-        if (trace->hit) trace->hit[o] = (uint8_t)((before >> rec.tok[t].final_[j]) & 1ull);
-        if (trace->weights) trace->weights[o] = rec.tok[t].w[j];
-      }
-    if (trace->scores)
-      for (int t = 0; t < B; ++t)
-        std::memcpy(trace->scores + (size_t)t * E, rec.tok[t].scores, sizeof(float) * E);
-    for (int i = 0; i < B * k; ++i) {
-      if (trace->fetched) trace->fetched[i] = i < n_fetch ? fetched[i] : -1;
-      if (trace->victims) trace->victims[i] = i < n_fetch ? victims[i] : -1;
-      if (trace->on_cpu) trace->on_cpu[i] = i < n_cpu ? plan.on_cpu[i] : -1;
-    }
-    trace->n_fetched = n_fetch;
-    trace->n_on_cpu = n_cpu;
-  }
+  if (h->prof_mask) account_profile_bytes(h, B, rec, plan, late, fa.grouped != 0, timed);
+  if (trace) fill_trace(h, B, rec, plan, trace);
   return SMOE_OK;
 }
 
