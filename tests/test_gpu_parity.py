@@ -209,6 +209,27 @@ def test_c3_full_size_in_the_benchmark_launch_configuration():
         pinned_free_all()
 
 
+def test_c5_full_size_batch8_in_the_benchmark_launch_configuration():
+    """All 28 layers of the Qwen2-57B-A14B-shaped workload at batch 8 (grouped
+    MFMA kernels, staging slots, 14 pinned layer blocks shared by 28 layers, as
+    `bench.py --workload c5 --batch 8` sets it up): every decision of every call,
+    y on sampled calls."""
+    import gc
+    from paper_2508_18983_amd.session import pinned_empty, pinned_free_all
+    wl = make_workload(SHAPES["c5"], device="cuda", tokens=10, batch=8, host_alloc=pinned_empty,
+                       distinct_layers=14)
+    try:
+        r = run_parity(wl, y_every=53, batch=8, session_kw=dict(n_stage=64), label="c5-full-b8")
+        assert r["n_y"] >= 5
+        assert r["stats"]["substitutions"] > 0 and r["stats"]["misses"] > 0
+        assert r["stats"]["hits"] + r["stats"]["misses"] == 10 * 28 * 8 * 8
+    finally:
+        del wl
+        gc.collect()
+        torch.cuda.empty_cache()
+        pinned_free_all()
+
+
 @pytest.mark.parametrize("policy", [1, 2, 3])
 def test_baseline_replacement_policies(policy):
     """LRU / FIFO / LFU victims (the caches the paper's ablation compares its
