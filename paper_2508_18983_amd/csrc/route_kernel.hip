@@ -65,7 +65,7 @@ template <> struct GateUnit<bf16_t> {
 
 // Shared memory the selection stage works in.
 struct SelectSmem {
-  float lg[SMOE_MAX_BATCH][kWave];
+  alignas(16) float lg[SMOE_MAX_BATCH][kWave];   // logits; lanes >= E hold -inf
   float sc[SMOE_MAX_BATCH][kWave];
   int rk[SMOE_MAX_BATCH][kWave];
   int tk[SMOE_MAX_BATCH][SMOE_MAX_TOPK];
@@ -93,14 +93,22 @@ __device__ __forceinline__ unsigned long long select_pass1(const RouteArgs& a, S
     const float m = wave_max(l);
     const float p = in ? expf(l - m) : 0.f;
     const float s = p / wave_sum(p);
-    bool rem = in;
-    int myrank = 127, pivot = -1;
-    const int nsel = has_pivot ? k + 1 : k;
-    for (int r = 0; r < nsel; ++r) {
-      const int idx = wave_argmax(l, rem, lane);
-      if (lane == idx) { rem = false; myrank = r; }
-      if (r < k) { if (lane == 0) tk[t][r] = idx; } else pivot = idx;
+    // Rank of this lane's expert in (logit descending, id ascending) order, by
+    // counting the experts that precede it: E broadcast reads of the logits in
+    // LDS instead of k+1 dependent wave-wide arg-max rounds.
+    int myrank = 0;
+    for (int j = 0; j < E; j += 4) {
+      const float4 q = *reinterpret_cast<const float4*>(&lg[t][j]);    // lanes >= E hold -inf
+      myrank += (q.x > l) || (q.x == l && j < lane);
+      myrank += (q.y > l) || (q.y == l && j + 1 < lane);
+      myrank += (q.z > l) || (q.z == l && j + 2 < lane);
+      myrank += (q.w > l) || (q.w == l && j + 3 < lane);
     }
+    if (!in) myrank = 127;
+    if (lane < k) tk[t][lane] = lane;                 // defined even if the logits are not numbers
+    if (myrank < k) tk[t][myrank] = lane;
+    const unsigned long long pivot_m = __ballot(has_pivot && myrank == k);
+    const int pivot = pivot_m ? (int)__ffsll((long long)pivot_m) - 1 : -1;
     float R = 0.f;
     bool top = myrank < k;
     if (has_pivot) {
@@ -274,7 +282,7 @@ __global__ __launch_bounds__(1024) void route_kernel(const RouteArgs a) {
     float v = 0.f;
     if (lane < E)
       for (int sg = 0; sg < nseg; ++sg) v += part[t][lane][sg];
-    sm.lg[t][lane] = v;
+    sm.lg[t][lane] = lane < E ? v : -INFINITY;
   }
 
   select_and_publish(a, sm, a.sim, lane);
@@ -346,7 +354,7 @@ __global__ __launch_bounds__(1024) void route_b1_kernel(const RouteArgs a) {
     float v = 0.f;
     if (lane < E)
       for (int s2 = 0; s2 < nseg; ++s2) v += part[lane][s2];
-    sm.lg[tok][lane] = v;
+    sm.lg[tok][lane] = lane < E ? v : -INFINITY;
   }
   if (gridDim.x == 1) {
     select_and_publish(a, sm, sim_sh, lane);
@@ -438,7 +446,7 @@ __global__ __launch_bounds__(256) void route_split_kernel(const RouteArgs a) {
     if (lane < E)
       for (int s2 = 0; s2 < nseg; ++s2)
         v += __builtin_nontemporal_load(a.split_part + lane * nseg + s2);
-    sm.lg[0][lane] = v;
+    sm.lg[0][lane] = lane < E ? v : -INFINITY;
   }
   select_and_publish(a, sm, sim_sh, lane);
 }
