@@ -80,3 +80,24 @@ def test_zipf_prior_skews_expert_popularity_and_locality_repeats():
     t2 = torch.topk(l2, shp.top_k, dim=-1).indices[:, 0]
     reuse0 = np.mean([len(set(t2[t].tolist()) & set(t2[t - 1].tolist())) for t in range(1, 200)])
     assert reuse > reuse0 + 1.0
+
+
+def test_predicted_states_are_seeded_audited_and_leave_x_unchanged():
+    from smoe_inputs.generate import logit_margin_ok
+    shp = SHAPES["c4"].with_(n_layers=2, hidden=256, ffn=8, shared_ffn=8, n_shared=0, tokens=12, seed=9)
+    base = make_workload(shp)
+    a = make_workload(shp, pred_noise=0.4)
+    b = make_workload(shp, pred_noise=0.4)
+    assert base.x_pred is None
+    assert torch.equal(base.x, a.x) and torch.equal(base.gate_w, a.gate_w)      # x does not depend on the request
+    assert torch.equal(a.x_pred, b.x_pred)                                       # seeded
+    assert a.x_pred.shape == a.x.shape and a.x_pred.dtype == a.x.dtype
+    diff = (a.x_pred.double() - a.x.double())
+    assert 0.3 < float(diff.std()) < 0.5                                         # sigma = 0.4 plus rounding
+    # every predicted token-layer passes the same logit-margin audit as x
+    wg = a.gate_w.double().numpy()
+    for l in range(shp.n_layers):
+        logits = a.x_pred[:, l, 0].double().numpy() @ wg[l].T
+        assert logit_margin_ok(logits, shp.top_k, shp.alpha).all()
+    zero = make_workload(shp, pred_noise=0.0)
+    assert torch.equal(zero.x_pred, zero.x)
