@@ -423,3 +423,79 @@ def test_cpu_assist_measured_costs_outputs_follow_the_chosen_experts():
                 flat[2 * hf:].reshape(s.hidden, s.ffn), xt)
         l2, mx = rel_errors(y_host[t, l, 0], ref)
         assert l2 <= TOL["bf16"] and mx <= TOL["bf16"], (t, l, l2, mx)
+
+
+# ---------------------------------------------------------------- seeded sweep over small random configurations
+def _oracle_margins(wl, batch, prefetch_max, oracle_kw):
+    """Dry run of the oracle alone (decisions only) in the call order run_parity
+    uses: smallest routing and eviction margins of the whole trace."""
+    from oracle import smoe_oracle as O
+    from smoe_inputs import as_numpy
+    s = wl.shape
+    orc = O.oracle_from_workload(wl, **oracle_kw)
+    route, evict = np.inf, np.inf
+    try:
+        for t in range(s.tokens):
+            for l in range(s.n_layers):
+                tn, ln = divmod(t * s.n_layers + l + 1, s.n_layers)
+                if prefetch_max and tn < s.tokens:
+                    pf = orc.prefetch_layer(ln, as_numpy(wl.x_pred[tn, ln]), prefetch_max)
+                    route, evict = min(route, pf.route_margin), min(evict, pf.evict_margin)
+                r = orc.decode_layer(l, as_numpy(wl.x[t, l]), compute_y=False)
+                route, evict = min(route, r.route_margin), min(evict, r.evict_margin)
+    except AssertionError:
+        return 0.0, 0.0
+    return route, evict
+
+
+def test_seeded_sweep_of_small_random_configurations():
+    """Shapes, batch sizes, policies and optional features drawn from a seeded
+    generator, so that every kernel dispatch path (units per lane, row segments,
+    LDS fallbacks, grouped / MFMA kernels, staging, prefetch, host-computed
+    experts) meets shapes nobody hand-picked.  Configurations whose oracle trace
+    has a decision closer to a tie than the parity margins are skipped (the
+    draw continues), so a failure here is a disagreement, not a coin flip."""
+    from smoe_inputs.shapes import MoEShape
+    rng = np.random.default_rng(20260101)
+    done, tried = 0, 0
+    while done < 20 and tried < 80:
+        tried += 1
+        dtype = "bf16" if rng.random() < 0.7 else "fp32"
+        E = int(rng.choice([2, 3, 5, 8, 12, 16, 24, 33, 48, 64]))
+        k = int(rng.integers(1, min(E, 8) + 1))
+        cap = int(rng.integers(k, E + 1))
+        H = int(rng.choice([64, 136, 256, 520, 1024, 2048, 3080, 4096, 5120]))
+        F = int(rng.choice([8, 72, 256, 520, 1408, 2824]))
+        n_shared = int(rng.choice([0, 0, 1, 2]))
+        Fs = int(rng.choice([64, 392, 2056])) if n_shared else 0
+        B = int(rng.choice([1, 1, 1, 2, 3, 5, 8]))
+        policy = int(rng.choice([0, 0, 1, 2, 3]))
+        alpha = float(rng.choice([0.0, 0.1, 0.25, 0.5]))
+        subst_key = int(rng.integers(0, 2))
+        prefetch_max = int(rng.choice([0, 0, 1, 3]))
+        assist = int(rng.choice([0, 0, 1, 2]))
+        costs = (float(rng.choice([1.0, 2.0, 3.0])), float(rng.choice([1.0, 2.5])))
+        shp = MoEShape(f"sweep{tried}", 2, H, E, F, k, cap, alpha, 6, dtype=dtype, batch=B,
+                       n_shared=n_shared, shared_ffn=Fs, renorm_topk=int(rng.integers(0, 2)),
+                       subst_key=subst_key, evict_window=int(rng.choice([0, 1, 3])), evict_policy=policy,
+                       prior="zipf" if E >= 8 and rng.random() < 0.5 else "normal", zipf_s=1.0,
+                       sim="uniform", seed=1000 + tried)
+        try:
+            wl = make_workload(shp, pred_noise=0.5 if prefetch_max else None)
+        except RuntimeError:
+            continue                                  # the margin audit could not place this shape's logits
+        ses_kw = dict(n_stage=B * k if B > 1 else 0)
+        orc_kw = {}
+        if assist:
+            ses_kw.update(cpu_assist=assist, cpu_threads=3, load_cost_us=costs[0], cpu_cost_us=costs[1])
+            orc_kw.update(cpu_assist=assist, c_load=costs[0], c_cpu=costs[1])
+        route, evict = _oracle_margins(wl, B, prefetch_max, orc_kw)
+        from tests.parity import ROUTE_MARGIN, EVICT_MARGIN
+        if route < 2 * ROUTE_MARGIN or evict < 5 * EVICT_MARGIN:
+            continue
+        label = (f"sweep{tried} {dtype} E{E} k{k} cap{cap} H{H} F{F} sh{n_shared}x{Fs} B{B} pol{policy} "
+                 f"a{alpha} key{subst_key} pf{prefetch_max} cpu{assist}")
+        print(f"[sweep] {label}", flush=True)
+        run_parity(wl, batch=B, session_kw=ses_kw, oracle_kw=orc_kw, label=label, prefetch_max=prefetch_max)
+        done += 1
+    assert done >= 12, (done, tried)
