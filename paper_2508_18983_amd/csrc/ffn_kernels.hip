@@ -928,31 +928,27 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void ffn_down_mfma_kernel(const Ff
   };
 
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  u32x4 wreg[8];
-  Item cur = describe(wave);
-  load_tile(cur, wreg);
-  while (cur.valid) {
-    const int after = next_it + kMfmaWaves;
-    // activations of my token: hi and lo terms, 8 K-steps of 8 columns each
-    u32x4 bhi[8], blo[8];
+  u32x4 bhi[8], blo[8];
+  // activations of my token for item d (hi and lo terms, 8 K-steps of 8 columns each), then
+  // the item's weight tile from registers to LDS (row r at r * kMfmaRowBytes)
+  auto stage_item = [&](const Item& d, const u32x4 (&wreg)[8]) {
 #pragma unroll
     for (int st = 0; st < 8; ++st) {
       const int col = 32 * st + 8 * g4;
-      if (cur.pos >= 0 && col < cur.ncols) {
-        bhi[st] = *reinterpret_cast<const u32x4*>(cur.arow + col);
-        blo[st] = *reinterpret_cast<const u32x4*>(cur.arow + cur.F + col);
+      if (d.pos >= 0 && col < d.ncols) {
+        bhi[st] = *reinterpret_cast<const u32x4*>(d.arow + col);
+        blo[st] = *reinterpret_cast<const u32x4*>(d.arow + d.F + col);
       } else {
         bhi[st] = u32x4{};
         blo[st] = u32x4{};
       }
     }
-    // stage the tile (row r at r * kMfmaRowBytes), then start the next item's loads
 #pragma unroll
     for (int q = 0; q < 8; ++q)
       *reinterpret_cast<u32x4*>(stage + (2 * q + rsub) * kMfmaRowBytes + unit * 16) = wreg[q];
     __builtin_amdgcn_wave_barrier();
-    const Item nxt = describe(after);
-    load_tile(nxt, wreg);
+  };
+  auto multiply_staged = [&]() {
 #pragma unroll
     for (int st = 0; st < 8; ++st) {
       const u32x4 af = *reinterpret_cast<const u32x4*>(stage + i16 * kMfmaRowBytes + (4 * st + g4) * 16);
@@ -962,7 +958,26 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void ffn_down_mfma_kernel(const Ff
       acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, l4), acc, 0, 0, 0);
     }
     __builtin_amdgcn_wave_barrier();
-    cur = nxt;
+  };
+  // Two items ahead: while item i is multiplied, the tiles of items i+1 and i+2 are on
+  // their way (two register sets, used alternately), i.e. 16 KB per wave in flight.
+  u32x4 wa[8], wb[8];
+  Item i0 = describe(wave);
+  load_tile(i0, wa);
+  Item i1 = describe(next_it + kMfmaWaves);
+  load_tile(i1, wb);
+  while (i0.valid) {
+    stage_item(i0, wa);
+    const Item i2 = describe(next_it + kMfmaWaves);
+    load_tile(i2, wa);
+    multiply_staged();
+    if (!i1.valid) break;
+    stage_item(i1, wb);
+    const Item i3 = describe(next_it + kMfmaWaves);
+    load_tile(i3, wb);
+    multiply_staged();
+    i0 = i2;
+    i1 = i3;
   }
 
   // ---- add the eight tiles in wave order; lane holds rows 4*g4 + r, column i16 ----
