@@ -215,8 +215,13 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
  *          sum_j w_j FFN_{final_j}(x) + sum_shared FFN_s(x)
  * Enqueues router + substitution, the FFN over resident experts, and -- when
  * the step has misses -- victim selection, the loads on stream_copy and a
- * second FFN pass over the loaded experts.  y is complete when the compute
- * stream has drained.  With a trace the call also fills it (host data only).
+ * second FFN pass over the loaded experts.  With cfg.cpu_assist the misses are
+ * first split by Algorithm 2 (Section V-A): the tail of the score-ordered list
+ * is computed by the host cores while the head is loaded, and the call returns
+ * when they are done.  y is complete when the compute stream has drained.
+ * With a trace the call also fills it (host data only).  SMOE_ESTATE when a
+ * step needs more staging slots than cfg.n_stage provides (the handle then
+ * needs moe_cache_reset).
  * SMOE_EINVAL for a bad layer / batch or NULL x, y. */
 int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch,
                      const void* x_dev, void* y_dev, moe_trace_t* trace_or_null);
@@ -238,9 +243,8 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch,
  * moe_decode_layer(layer) is called, the prefetched experts count as resident
  * for every decision but are computed in that call's second pass, behind the
  * copy stream; neither the router nor the resident pass waits for them.  A
- * wrong prediction costs the
- * copy and the evicted expert, nothing else: the layer loads what it needs on
- * demand as always.
+ * wrong prediction costs the copy and the evicted expert, nothing else: the
+ * layer loads what it needs on demand as always.
  * SMOE_EINVAL for a bad layer / batch, NULL x_pred or prefetch_max == 0. */
 int moe_prefetch_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* x_pred_dev);
 
