@@ -197,6 +197,15 @@ def main() -> int:
         elapsed, prof, st = timed_run(ses, x_dev, y_dev, args.warmup, args.steps, L, prof_launches,
                                       xp_dev=xp_dev)
         cpu_costs = M.moe_cpu_assist_costs(ses.handle) if args.cpu_assist else None
+        # what an event pair reads with nothing between its two records on the compute stream:
+        # the part of `avg_launch_us` that is not the kernel (reported, not subtracted)
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(64)]
+        ses.sync()
+        for a_ev, b_ev in pairs:
+            a_ev.record(ses.stream_compute)
+            b_ev.record(ses.stream_compute)
+        ses.sync()
+        event_pair_us = sum(a_ev.elapsed_time(b_ev) for a_ev, b_ev in pairs) / len(pairs) * 1e3
     tok_s = args.steps * Bt / elapsed
     up = prof["up"]
     up_avg_s = up["ms"] / max(up["launches"], 1) * 1e-3
@@ -292,6 +301,14 @@ def main() -> int:
                      "traffic": (MEASURED_TRAFFIC_RATIO[s.name] * up_bytes_per_launch
                                  if s.name in MEASURED_TRAFFIC_RATIO else None),
                      "bytes_per_launch": up_bytes_per_launch, "avg_launch_us": up_avg_s * 1e6,
+                     "empty_event_pair_us": event_pair_us,
+                     # the same with the empty-pair reading taken off the interval: what the kernel
+                     # itself takes (agrees with the rocprofv3 kernel duration)
+                     "kernel_only": {"avg_us": up_avg_s * 1e6 - event_pair_us,
+                                     "achieved": (up_bytes_per_launch / (up_avg_s - event_pair_us * 1e-6) / 1e9
+                                                  if up_avg_s * 1e6 > event_pair_us else None),
+                                     "frac": (up_bytes_per_launch / (up_avg_s - event_pair_us * 1e-6) / 1e9
+                                              / HBM_PEAK_GBS if up_avg_s * 1e6 > event_pair_us else None)},
                      "launches": up["launches"]},
         "cpu_baseline": cpu,
         "extra": extra,
