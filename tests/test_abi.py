@@ -33,10 +33,11 @@ def test_header_is_plain_c_and_struct_layouts_match_binding(tmp_path):
     import paper_2508_18983_amd as M
     prog = tmp_path / "sizes.c"
     prog.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "smoe.h"\n'
-                    'int main(void){printf("%zu %zu %zu %zu %zu %zu %zu %zu %zu\\n", sizeof(moe_cfg_t),'
+                    'int main(void){printf("%zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu\\n", sizeof(moe_cfg_t),'
                     'sizeof(moe_buffers_t), sizeof(moe_trace_t), sizeof(moe_stats_t), sizeof(moe_profile_t),'
                     'offsetof(moe_cfg_t, alpha), offsetof(moe_trace_t, n_fetched), sizeof(moe_prefetch_info_t),'
-                    'offsetof(moe_cfg_t, cpu_cost_us));return 0;}\n')
+                    'offsetof(moe_cfg_t, cpu_cost_us), offsetof(moe_stats_t, cpu_computed), offsetof(moe_stats_t, prefetches),'
+                    'offsetof(moe_trace_t, on_cpu), offsetof(moe_prefetch_info_t, victims));return 0;}\n')
     exe = tmp_path / "sizes"
     subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
                     str(prog), "-o", str(exe)], check=True)
@@ -44,7 +45,9 @@ def test_header_is_plain_c_and_struct_layouts_match_binding(tmp_path):
     got = [int(v) for v in out]
     want = [ctypes.sizeof(M.MoeCfg), ctypes.sizeof(M.MoeBuffers), ctypes.sizeof(M.MoeTrace),
             ctypes.sizeof(M.MoeStats), ctypes.sizeof(M.MoeProfile), M.MoeCfg.alpha.offset,
-            M.MoeTrace.n_fetched.offset, ctypes.sizeof(M.MoePrefetchInfo), M.MoeCfg.cpu_cost_us.offset]
+            M.MoeTrace.n_fetched.offset, ctypes.sizeof(M.MoePrefetchInfo), M.MoeCfg.cpu_cost_us.offset,
+            M.MoeStats.cpu_computed.offset, M.MoeStats.prefetches.offset, M.MoeTrace.on_cpu.offset,
+            M.MoePrefetchInfo.victims.offset]
     assert got == want
 
 
