@@ -118,8 +118,9 @@ int env_int(const char* name, int dflt) {
 void plan_geometry(moe_handle* h) {
   const moe_cfg_t& c = h->cfg;
   const long total_f = (long)c.top_k * c.ffn + (long)c.n_shared * c.shared_ffn;
-  // up: TF rows of W1 and W3 per block, enough blocks to fill 256 CUs several times
-  int tf = (int)((total_f + 1023) / 1024 + 3) / 4 * 4;         // ~1024 blocks per token
+  // up: TF rows of W1 and W3 per block, ~2560 blocks per token (ten per compute unit: measured
+  // flat from 1000 to 2400 blocks on the 14336-wide experts, 3-4 % better than 1000 on narrow ones)
+  int tf = (int)((total_f + 2559) / 2560 + 3) / 4 * 4;
   tf = env_int("SMOE_TF", std::max(8, tf));
   if (tf < 4) tf = 4;
   tf = tf / 4 * 4;
