@@ -74,6 +74,11 @@ struct SelectSmem {
   int slot_of[kWave];
   int fin[SMOE_MAX_BATCH][SMOE_MAX_TOPK];     // final expert per (token, slot)
   float wsl[SMOE_MAX_BATCH][SMOE_MAX_TOPK];   // combine weight per (token, slot)
+  // expert groups of a batched step while they are being collected
+  int pair_e[kWave];                          // expert of (token, slot) pair t * k + j
+  int gcnt[kWave];                            // tokens per expert
+  int gtok[kWave][SMOE_MAX_BATCH];            // their tokens, ascending
+  float gw[kWave][SMOE_MAX_BATCH];            // and combine weights
 };
 
 // Runs on wave 0 with all 64 lanes active: logits in sm.lg -> decision record.
@@ -183,22 +188,37 @@ __device__ __forceinline__ void publish(const RouteArgs& a, SelectSmem& sm, int 
   const int k = a.k, B = a.B;
   auto& slot_of = sm.slot_of;
   if (B > 1) {
-    // expert groups for the batched FFN: lane e collects the tokens that compute expert e
+    // Expert groups for the batched FFN.  Lane p first stands for the (token, slot) pair
+    // p = t * k + j: its place in its expert's token list is the number of earlier pairs with
+    // the same expert (pairs are in token order and a token uses an expert once, so the list
+    // comes out ascending).  Then lane e stands for expert e and reads its list back.
+    const int np = B * k;                               // <= 64
+    const bool has = lane < np;
+    const int pt = lane / k, pj = lane - pt * k;
+    const int pe = has ? sm.fin[pt][pj] : -1;
+    sm.pair_e[lane] = pe;
+    sm.gcnt[lane] = 0;
+    int pos = 0, cnt = 0;
+    for (int q = 0; q < np; ++q) {
+      const bool same = sm.pair_e[q] == pe;
+      pos += same && q < lane;
+      cnt += same;
+    }
+    if (has) {
+      sm.gtok[pe][pos] = pt;
+      sm.gw[pe][pos] = sm.wsl[pt][pj];
+      if (pos == 0) sm.gcnt[pe] = cnt;
+    }
     GroupTask g;
     g.expert = lane;
     g.slot = ((a.resident >> lane) & 1ull) ? slot_of[lane] : -1;
-    g.ntok = 0;
+    g.ntok = sm.gcnt[lane];
     g.pad_ = 0;
 #pragma unroll
-    for (int i = 0; i < SMOE_MAX_BATCH; ++i) { g.tok[i] = 0; g.w[i] = 0.f; }
-    for (int t = 0; t < B; ++t)
-      for (int j = 0; j < k; ++j)
-        if (sm.fin[t][j] == lane) {
-#pragma unroll
-          for (int i = 0; i < SMOE_MAX_BATCH; ++i)
-            if (i == g.ntok) { g.tok[i] = t; g.w[i] = sm.wsl[t][j]; }
-          ++g.ntok;
-        }
+    for (int i = 0; i < SMOE_MAX_BATCH; ++i) {
+      g.tok[i] = i < g.ntok ? sm.gtok[lane][i] : 0;
+      g.w[i] = i < g.ntok ? sm.gw[lane][i] : 0.f;
+    }
     const unsigned long long has_m = __ballot(g.ntok > 0);
     const int idx = __popcll(has_m & ((1ull << lane) - 1ull));
     if (g.ntok > 0) a.rec_dev->grp[idx] = g;
