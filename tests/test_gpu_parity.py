@@ -230,6 +230,19 @@ def test_c5_full_size_batch8_in_the_benchmark_launch_configuration():
         pinned_free_all()
 
 
+def test_c4_full_size_with_prefetch_and_cpu_assist():
+    """All 26 layers of the DeepSeek-V2-Lite-shaped workload (64 routed + 2 shared
+    experts, top-6) with every optional stage on: a prefetch before each layer
+    call and Algorithm 2 with fixed costs."""
+    ses_kw, orc_kw = _cpu_kw(3.0, 1.0, threads=8)
+    wl = make_workload(SHAPES["c4"], device="cuda", tokens=24, pred_noise=0.3)
+    r = run_parity(wl, y_every=41, session_kw=ses_kw, oracle_kw=orc_kw, label="c4-full-pre-ba", prefetch_max=2)
+    st = r["stats"]
+    assert r["n_y"] >= 10
+    assert st["prefetches"] > 200 and st["cpu_computed"] > 20 and st["fetches"] > 100
+    assert st["hits"] + st["misses"] == 24 * 26 * 6
+
+
 @pytest.mark.parametrize("policy", [1, 2, 3])
 def test_baseline_replacement_policies(policy):
     """LRU / FIFO / LFU victims (the caches the paper's ablation compares its
