@@ -60,10 +60,20 @@ class DecodeSession:
         torch.cuda.set_device(self.device)
         self.tdtype = torch.float32 if shape.dtype == "fp32" else torch.bfloat16
         esize = 4 if shape.dtype == "fp32" else 2
+        # expert blocks that are not page-locked yet are copied into blocks of exactly their size
+        # from moe_host_alloc, owned by this session and released in close() (PyTorch's pinned
+        # allocator rounds sizes up and keeps what it has handed out for the life of the process)
+        self._owned_pinned = []
         pinned = {}
         for blk in experts:
             if id(blk) not in pinned:
-                pinned[id(blk)] = blk if _is_pinned(blk) else blk.pin_memory()
+                if _is_pinned(blk):
+                    pinned[id(blk)] = blk
+                else:
+                    mine = pinned_empty(blk.numel(), blk.dtype).view(blk.shape)
+                    mine.copy_(blk)
+                    self._owned_pinned.append(mine.data_ptr())
+                    pinned[id(blk)] = mine
         self.experts_host = [pinned[id(blk)] for blk in experts]
         self._expert_ptrs = (C.c_void_p * len(self.experts_host))(
             *[blk.data_ptr() for blk in self.experts_host])
@@ -133,9 +143,14 @@ class DecodeSession:
         B.moe_cache_reset(self.handle)
 
     def close(self) -> None:
-        if self.handle:
+        if getattr(self, "handle", None):
             B.moe_cache_destroy(self.handle)
             self.handle = None
+        for ptr in getattr(self, "_owned_pinned", []):
+            if _PINNED_BLOCKS.pop(ptr, None) is not None:
+                B.moe_host_free(ptr)
+        self._owned_pinned = []
+        self.experts_host = []
 
     def __enter__(self):
         return self
