@@ -452,14 +452,17 @@ __global__ __launch_bounds__(256) void route_split_kernel(const RouteArgs a) {
       if (lane == 0 && it < items) a.split_part[it] = v;     // it = row * nseg + sg
     }
   }
-  // this block's partial sums are visible device-wide before its ticket is drawn
-  __threadfence();
+  // This block's partial sums are visible device-wide before its ticket is drawn.  One thread
+  // fences for the whole block (the barrier orders the other waves' stores before it): every
+  // wave that executes an agent-scope release makes the XCD write back its L2.
   __syncthreads();
-  if (tid == 0) is_last = (atomicAdd(a.split_count, 1u) == gridDim.x - 1) ? 1 : 0;
+  if (tid == 0) {
+    __threadfence();
+    is_last = (atomicAdd(a.split_count, 1u) == gridDim.x - 1) ? 1 : 0;
+  }
   __syncthreads();
-  if (!is_last) return;
-  __threadfence();                                // the other blocks' sums are visible to this one
-  if (wave != 0) return;
+  if (!is_last || wave != 0) return;
+  __threadfence();                                // the other blocks' sums are visible to this wave
   if (lane == 0) *a.split_count = 0u;             // stream order: the next launch starts after this one ends
   {
     float v = 0.f;
