@@ -696,3 +696,41 @@ def test_minmax_split_variant_is_the_brute_force_optimum_and_prefers_loading_on_
     assert O.split_load_cpu_minmax(1, 1.0, 3.0) == (1, 0)
     assert O.split_load_cpu_minmax(2, 1.0, 1.0) == (1, 1)
     assert O.split_load_cpu_minmax(4, 3.0, 1.0) == (1, 3)
+
+
+def test_prefetch_load_is_stamped_between_the_layers_steps_for_recency_policies():
+    """LRU / FIFO with prefetch: a prefetched expert counts as loaded (and last
+    touched) after everything the previous step of its layer did and before
+    anything its next step does.  Hand-built scenario, E = 6, k = 1, cap = 3."""
+    E, H = 6, 8
+    gate = np.eye(E, H, dtype=np.float32)                 # logit of expert e = x[e]
+
+    def x_for(e, second=None):
+        x = np.zeros(H, np.float32)
+        x[e] = 4.0
+        if second is not None:
+            x[second] = 3.0
+        return x
+
+    experts = [np.zeros((E, 3 * H * 8), np.float32)]
+    for policy in (O.EVICT_LRU, O.EVICT_FIFO):
+        orc = O.SMoEOracle(n_layers=1, hidden=H, n_experts=E, ffn=8, top_k=1, cache_cap=3, alpha=0.0,
+                           gate_w=gate[None], experts=experts, sim=np.zeros((1, E, E), np.float32),
+                           evict_policy=policy, elem_bytes=4)
+        # residents 0, 1, 2 (loaded in that order before step 0)
+        orc.decode_layer(0, x_for(1), compute_y=False)            # step 0 uses 1
+        orc.decode_layer(0, x_for(0), compute_y=False)            # step 1 uses 0
+        pf = orc.prefetch_layer(0, x_for(4), 1)                   # predicts 4: not resident
+        if policy == O.EVICT_LRU:
+            assert pf.victims == [2]                              # 2 was never used
+        else:
+            assert pf.victims == [0]                              # 0 is the oldest load
+        res = orc.decode_layer(0, x_for(5), compute_y=False)      # step 2 needs 5: one more victim
+        if policy == O.EVICT_LRU:
+            # remaining residents 0 (used at step 1), 1 (step 0), 4 (prefetched after step 1): 1 is oldest
+            assert res.victims == [1]
+        else:
+            # remaining 1, 2 (initial loads) and 4 (prefetched later): 1 was loaded first
+            assert res.victims == [1]
+        assert 4 in orc.layers[0].slot_expert                     # the prefetched expert outlived an older one
+        assert orc.stats().prefetches == 1 and orc.stats().prefetch_used == 0
