@@ -23,6 +23,8 @@ that depend on a convention alone are "parity unpinned" by the paper:
 * CPU-assisted scheduling (``split_load_cpu``): Algorithm 2 itself is pinned;
   which experts count as its list S at batch > 1 and that a CPU-computed
   expert leaves the cache untouched are conventions            -- parity unpinned
+* ``split_load_cpu_minmax`` is a variant of this build (the stated objective
+  solved outright), not the paper's algorithm; pinned by brute force
 * top-score prefetch (``prefetch_layer``): the predicted hidden state is an
   input; order of the prefetches, their cap, the shield of the predicted
   actives and the stamps of a prefetch load are conventions   -- parity unpinned
