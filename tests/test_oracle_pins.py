@@ -734,3 +734,215 @@ def test_prefetch_load_is_stamped_between_the_layers_steps_for_recency_policies(
             assert res.victims == [1]
         assert 4 in orc.layers[0].slot_expert                     # the prefetched expert outlived an older one
         assert orc.stats().prefetches == 1 and orc.stats().prefetch_used == 0
+
+
+# ---------------------------------------------------------------- batch > 1: the step as a whole
+def _batch_step_from_definitions(scores, G, k, alpha, sim, subst_key):
+    """One batched step rebuilt from the definitions (Table "Definitions",
+    Algorithm 1's thresholds, Section IV-B / VI-B prose) without any oracle
+    routine: per-token ranking by a full sort, the batch top-score set as the
+    union over ALL tokens, substitution by exhaustive search of the greedy
+    order, and the distinct misses in (token, slot) order."""
+    B, E = scores.shape
+    order = [sorted(range(E), key=lambda e: (-scores[t, e], e)) for t in range(B)]
+    topk = [o[:k] for o in order]
+    s_k1 = [scores[t, order[t][k]] for t in range(B)]
+    top = [{e for e in topk[t] if scores[t, e] >= (1 + alpha) * s_k1[t]} for t in range(B)]
+    C = set().union(*top)
+    avail = set(G) | C
+    final = []
+    for t in range(B):
+        f = list(topk[t])
+        lows = [e for e in topk[t] if e not in top[t] and e not in avail]
+        lows.sort(key=lambda e: (scores[t, e], -topk[t].index(e)))        # lowest score first
+        cand = [c for c in range(E) if c not in topk[t] and c in avail
+                and scores[t, c] >= (1 - alpha) * s_k1[t]]
+        for b in lows:
+            if not cand:
+                break
+            key = (lambda c: scores[t, c]) if subst_key == 1 else (lambda c: float(sim[b][c]))
+            pick = max(cand, key=lambda c: (key(c), -c))
+            f[topk[t].index(b)] = pick
+            cand.remove(pick)
+        final.append(f)
+    distinct_misses = []
+    for t in range(B):
+        for e in final[t]:
+            if e not in G and e not in distinct_misses:
+                distinct_misses.append(e)
+    hit = [[e in G for e in final[t]] for t in range(B)]
+    return topk, final, C, distinct_misses, hit
+
+
+@pytest.mark.parametrize("B", [2, 4])
+@pytest.mark.parametrize("subst_key", [0, 1])
+def test_batched_step_matches_the_definitions_bruteforce(B, subst_key):
+    """Batch > 1 (Section IV-B prose "top-score experts of other tokens in the same
+    batch", Section VI-B): every step of a replay is rebuilt from the definitions
+    -- C = union over all tokens (not grown token by token), the history entry of
+    Eq. 3 = the batch mean of the score vectors, distinct misses in (token, slot)
+    order of first appearance, per-slot hits against G before the step."""
+    shp = SHAPES["c4"].with_(hidden=64, ffn=16, shared_ffn=8, n_experts=14, top_k=3, cache_cap=6,
+                             alpha=0.35, subst_key=subst_key, seed=60 + B)
+    wl = make_workload(shp, n_layers=2, tokens=60, batch=B)
+    s = wl.shape
+    n = 2
+    orc = O.oracle_from_workload(wl, evict_window=n)
+    log = {l: [] for l in range(s.n_layers)}
+    totals = dict(slots=0, hits=0, subs=0, fetches=0, staged=0, c_mattered=0, mean_mattered=0)
+    for t in range(s.tokens):
+        for l in range(s.n_layers):
+            G = list(orc.layers[l].slot_expert)
+            res = orc.decode_layer(l, as_numpy(wl.x[t, l]), compute_y=False)
+            wg = wl.gate_w[l].to(torch.float64).numpy()
+            xs = wl.x[t, l].to(torch.float64).numpy()
+            sc = scipy.special.softmax(xs @ wg.T, axis=1)                  # [B, E]
+            topk, final, C, misses, hit = _batch_step_from_definitions(
+                sc, set(G), s.top_k, float(np.float32(s.alpha)), wl.sim[l].numpy(), subst_key)
+            assert res.topk.tolist() == topk
+            assert res.final.tolist() == final, (t, l)
+            assert res.hit.tolist() == hit
+            assert res.substituted.tolist() == [[a != b for a, b in zip(f, k_)] for f, k_ in zip(final, topk)]
+            assert res.fetched == misses
+            # would a C grown in token order have decided differently?  (sensitivity of this pin)
+            grown = []
+            for tt in range(B):
+                tk1, fin1, _, _, _ = _batch_step_from_definitions(
+                    sc[:tt + 1], set(G), s.top_k, float(np.float32(s.alpha)), wl.sim[l].numpy(), subst_key)
+                grown.append(fin1[tt])
+            totals["c_mattered"] += grown != final
+            # Eq. 3 on the complete log, one entry per step = the batch mean
+            log[l].append(sc.mean(axis=0))
+            j = len(log[l])
+            lo = max(1, j - n)
+            avg = sum(log[l][i - 1] for i in range(lo, j + 1)) / (j - lo + 1)
+            resident = list(G)
+            shield = {e for f in final for e in f}
+            for m, v in zip(res.fetched, res.victims):
+                cand = [e for e in resident if e not in shield]
+                if not cand:
+                    assert v == -1
+                    totals["staged"] += 1
+                    continue
+                want = min(cand, key=lambda e: (avg[e], e))
+                assert v == want, (t, l)
+                resident[resident.index(v)] = m
+            assert resident == orc.layers[l].slot_expert
+            totals["slots"] += B * s.top_k
+            totals["hits"] += sum(map(sum, hit))
+            totals["subs"] += int(res.substituted.sum())
+            totals["fetches"] += len(misses)
+    st = orc.stats()
+    assert (st.slots, st.hits, st.substitutions, st.fetches) == (
+        totals["slots"], totals["hits"], totals["subs"], totals["fetches"])
+    assert st.misses == st.slots - st.hits and st.misses >= st.fetches
+    assert totals["subs"] > 10 and totals["fetches"] > 20
+    assert totals["c_mattered"] > 0       # the trace contains steps where the two readings of C differ
+
+
+def test_batch_top_score_set_is_the_union_over_all_tokens_not_a_running_set():
+    """Hand-made step (Algorithm 1 grows C inside the token loop, the prose
+    speaks of the other tokens of the batch; the two-pass union is this build's
+    reading): token 0's low-score expert 2 is not resident but is a top-score
+    expert of token 1, which comes LATER in the batch.  Under the union it is
+    kept; a C grown in token order would have replaced it by resident expert 3."""
+    E, H, k = 6, 8, 2
+    gate = np.zeros((1, E, H), np.float32)
+    for e in range(E):
+        gate[0, e, e] = 1.0
+    x = np.zeros((2, H), np.float32)
+    x[0, :E] = [3.0, -9.0, 1.00, 0.95, -9.0, -9.0]      # actives 0 (top), 2 (low); pivot 3
+    x[1, :E] = [-9.0, -9.0, 4.0, -9.0, 3.0, 0.0]        # actives 2, 4: both top-score
+    experts = [np.zeros((E, 3 * H * 8), np.float32)]
+    orc = O.SMoEOracle(n_layers=1, hidden=H, n_experts=E, ffn=8, top_k=k, cache_cap=3, alpha=0.3,
+                       gate_w=gate, experts=experts, sim=np.tile(np.eye(E, dtype=np.float32), (1, 1, 1)),
+                       subst_key=1, init_resident=np.array([[0, 3, 5]]), elem_bytes=4)
+    res = orc.decode_layer(0, x, compute_y=False)
+    assert res.topk.tolist() == [[0, 2], [2, 4]]
+    assert res.final.tolist() == [[0, 2], [2, 4]] and not res.substituted.any()
+    assert res.fetched == [2, 4]                          # one load of expert 2 serves both tokens
+    assert res.hit.tolist() == [[True, False], [False, False]]
+    st = orc.stats()
+    assert (st.hits, st.misses, st.fetches) == (1, 3, 2)  # hits and misses per slot, loads per distinct expert
+    # the same token alone (batch 1: no C) does get the substitute
+    orc.reset()
+    alone = orc.decode_layer(0, x[:1], compute_y=False)
+    assert alone.final.tolist() == [[0, 3]] and alone.substituted.tolist() == [[False, True]]
+
+
+def test_batch_history_entry_is_the_batch_mean():
+    """Eq. 3 at batch > 1 (the paper defines it per iteration j; one entry per
+    decode step holding the batch mean is this build's reading): two tokens with
+    opposite preferences, so that the victim differs depending on whose scores
+    enter the history."""
+    E, H, k = 5, 8, 1
+    gate = np.zeros((1, E, H), np.float32)
+    for e in range(E):
+        gate[0, e, e] = 1.0
+    # residents 0,1,2; both tokens activate resident 0 in step 1 (no load), then step 2 loads
+    # expert 4 and must evict 1 or 2.  token 0 scores expert 1 high and 2 low; token 1 scores
+    # 2 much higher than token 0 scores 1: batch mean says evict 1, token 0 alone says evict 2.
+    x1 = np.zeros((2, H), np.float32)
+    x1[0, :E] = [5.0, 2.0, 0.0, -5.0, -5.0]
+    x1[1, :E] = [5.0, 0.0, 4.0, -5.0, -5.0]
+    x2 = np.zeros((2, H), np.float32)
+    x2[0, :E] = [-5.0, 2.0, 0.0, -5.0, 6.0]
+    x2[1, :E] = [-5.0, 0.0, 4.0, -5.0, 6.0]
+    experts = [np.zeros((E, 3 * H * 8), np.float32)]
+    orc = O.SMoEOracle(n_layers=1, hidden=H, n_experts=E, ffn=8, top_k=k, cache_cap=3, alpha=0.0,
+                       gate_w=gate, experts=experts, sim=np.eye(E, dtype=np.float32)[None],
+                       init_resident=np.array([[0, 1, 2]]), elem_bytes=4, evict_window=3)
+    r1 = orc.decode_layer(0, x1, compute_y=False)
+    assert r1.fetched == []
+    r2 = orc.decode_layer(0, x2, compute_y=False)
+    assert r2.fetched == [4]
+    s1 = scipy.special.softmax(x1[:, :E].astype(np.float64), axis=1)
+    s2 = scipy.special.softmax(x2[:, :E].astype(np.float64), axis=1)
+    mean = (s1.mean(axis=0) + s2.mean(axis=0)) / 2
+    tok0 = (s1[0] + s2[0]) / 2
+    by_mean = min([0, 1, 2], key=lambda e: mean[e])
+    by_tok0 = min([0, 1, 2], key=lambda e: tok0[e])
+    assert by_mean != by_tok0                     # the case separates the two readings
+    assert r2.victims == [by_mean]
+
+
+def test_batch_recency_stamps_follow_token_slot_order_lru_textbook():
+    """alpha = 0, batch 2, LRU: the step's accesses are the (token, slot) pairs in
+    order; an OrderedDict cache fed with that access sequence (the step's experts
+    pinned while its misses are placed, misses placed in first-appearance order)
+    must evict the same experts."""
+    from collections import OrderedDict
+    shp = SHAPES["c4"].with_(hidden=64, ffn=16, shared_ffn=8, n_experts=12, top_k=2, cache_cap=7,
+                             alpha=0.0, evict_policy=O.EVICT_LRU, seed=77)
+    wl = make_workload(shp, n_layers=1, tokens=80, batch=2)
+    orc = O.oracle_from_workload(wl)
+    cache = OrderedDict((e, None) for e in range(shp.cache_cap))
+    logits = torch.einsum("eh,tbh->tbe", wl.gate_w[0].double(), wl.x[:, 0].double())
+    top = torch.topk(logits, shp.top_k, dim=-1).indices.tolist()            # [T][B][k]
+    evictions = 0
+    for t in range(wl.shape.tokens):
+        res = orc.decode_layer(0, as_numpy(wl.x[t, 0]), compute_y=False)
+        accesses = [e for tok in top[t] for e in tok]
+        pinned = set(accesses)
+        before = set(cache)
+        for e in accesses:                       # recency of everything the step touches
+            if e in cache:
+                cache.move_to_end(e)
+        want_victims, loaded = [], []
+        for e in accesses:
+            if e in before or e in loaded:
+                continue
+            victim = next(c for c in cache if c not in pinned)
+            del cache[victim]
+            want_victims.append(victim)
+            loaded.append(e)
+        # loaded experts enter with the recency of their first access in the step
+        for e in accesses:
+            if e in loaded and e not in cache:
+                cache[e] = None
+        for e in accesses:
+            cache.move_to_end(e)
+        assert res.fetched == loaded and res.victims == want_victims, t
+        assert set(orc.layers[0].slot_expert) == set(cache)
+        evictions += len(loaded)
+    assert evictions > 30
