@@ -61,6 +61,10 @@ extern "C" {
 #define SMOE_EHIP      -2   /* a HIP runtime call failed: see moe_last_hip_error() */
 #define SMOE_ENOTPINNED -3  /* an experts_host block is not pinned host memory */
 #define SMOE_ESTATE    -4   /* call not valid in the handle's state */
+#define SMOE_ETOOBIG   -5   /* the configuration needs more scratch than SMOE_STATIC_SCRATCH_BYTES */
+
+/* Size of the per-GPU scratch array behind moe_decode_layer_static. */
+#define SMOE_STATIC_SCRATCH_BYTES (8u << 20)
 
 #define SMOE_DTYPE_FP32 0
 #define SMOE_DTYPE_BF16 1
@@ -225,6 +229,30 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
  * SMOE_EINVAL for a bad layer / batch or NULL x, y. */
 int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch,
                      const void* x_dev, void* y_dev, moe_trace_t* trace_or_null);
+
+/* moe_decode_layer for callers that must not allocate device memory at all
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): same arguments, same results, but every device buffer its kernels
+ * work in besides the caller's inputs and outputs -- the decision record, the
+ * SwiGLU activations between the up and the down kernel, the fp32 sums carried
+ * to the pass over loaded experts, the router's partial sums and counter --
+ * lives in one file-scope device array of SMOE_STATIC_SCRATCH_BYTES (8 MiB) per
+ * GPU, which the library's code object holds on every GPU it runs on until the
+ * process ends.  The call itself allocates and frees nothing, on the device or
+ * on the host.  The array's address on the handle's GPU is looked up once, in
+ * moe_cache_init.
+ * SMOE_ETOOBIG when the handle's configuration needs more than the array holds:
+ * 9.5 KB of records + max_batch*H*4 bytes of sums + the activations, which are
+ * max_batch*(k+n_shared)*max(F, Fs)*4 bytes, or at max_batch > 1 the larger of
+ * that and (min(E, max_batch*k)*F + n_shared*Fs)*32 bytes (the c5-shaped
+ * workload at batch 8 needs 6.1 MB).  All handles on one GPU share the array and
+ * it keeps the last call's contents: what has to start at zero is cleared by the
+ * call.  Two moe_decode_layer_static calls on one GPU whose kernels can run at
+ * the same time (handles on different compute streams, or calls from different
+ * threads) race on the array: the caller keeps them on one stream or orders the
+ * streams itself.  moe_decode_layer is not affected (it has its own buffers). */
+int moe_decode_layer_static(moe_handle_t* h, int32_t layer, int32_t batch,
+                            const void* x_dev, void* y_dev, moe_trace_t* trace_or_null);
 
 /* Top-score prefetch for a layer that has not run yet (Section IV-C).
  *   x_pred_dev  device [batch][H] dtype: the caller's prediction of the hidden

@@ -15,7 +15,7 @@ _LIB_PATH = os.path.join(_PKG, "libsmoe.so")
 _lib = None
 
 PROF_KINDS = ("route", "up", "down", "copy", "up_loaded", "down_loaded")
-ERRORS = {-1: "SMOE_EINVAL", -2: "SMOE_EHIP", -3: "SMOE_ENOTPINNED", -4: "SMOE_ESTATE"}
+ERRORS = {-1: "SMOE_EINVAL", -2: "SMOE_EHIP", -3: "SMOE_ENOTPINNED", -4: "SMOE_ESTATE", -5: "SMOE_ETOOBIG"}
 
 
 class SmoeError(RuntimeError):
@@ -90,6 +90,7 @@ def load_library():
     P, I = C.c_void_p, C.c_int32
     lib.moe_cache_init.argtypes = [C.POINTER(MoeCfg), C.POINTER(MoeBuffers), C.POINTER(P)]
     lib.moe_decode_layer.argtypes = [P, I, I, P, P, C.POINTER(MoeTrace)]
+    lib.moe_decode_layer_static.argtypes = [P, I, I, P, P, C.POINTER(MoeTrace)]
     lib.moe_prefetch_layer.argtypes = [P, I, I, P]
     lib.moe_prefetch_last.argtypes = [P, C.POINTER(MoePrefetchInfo)]
     lib.moe_cpu_assist_costs.argtypes = [P, C.POINTER(C.c_double), C.POINTER(C.c_double),
@@ -104,7 +105,7 @@ def load_library():
     lib.moe_calib_copy.argtypes = [P, P, C.c_int64, P]
     lib.moe_host_alloc.argtypes = [C.c_int64, C.POINTER(P)]
     lib.moe_host_free.argtypes = [P]
-    for fn in ("moe_cache_init", "moe_decode_layer", "moe_prefetch_layer", "moe_prefetch_last", "moe_cpu_assist_costs", "moe_cache_stats", "moe_cache_residency",
+    for fn in ("moe_cache_init", "moe_decode_layer", "moe_decode_layer_static", "moe_prefetch_layer", "moe_prefetch_last", "moe_cpu_assist_costs", "moe_cache_stats", "moe_cache_residency",
                "moe_cache_reset", "moe_cache_destroy", "moe_profile_enable", "moe_profile_read",
                "moe_last_hip_error", "moe_calib_copy", "moe_host_alloc", "moe_host_free"):
         getattr(lib, fn).restype = C.c_int
@@ -157,6 +158,13 @@ def moe_decode_layer(handle: int, layer: int, batch: int, x_dev: int, y_dev: int
                      trace: Optional[Trace] = None) -> None:
     tp = C.byref(trace.c) if trace is not None else None
     _check("moe_decode_layer", load_library().moe_decode_layer(handle, layer, batch, x_dev, y_dev, tp))
+
+
+def moe_decode_layer_static(handle: int, layer: int, batch: int, x_dev: int, y_dev: int,
+                            trace: Optional[Trace] = None) -> None:
+    tp = C.byref(trace.c) if trace is not None else None
+    _check("moe_decode_layer_static",
+           load_library().moe_decode_layer_static(handle, layer, batch, x_dev, y_dev, tp))
 
 
 def moe_prefetch_layer(handle: int, layer: int, batch: int, x_pred_dev: int) -> None:

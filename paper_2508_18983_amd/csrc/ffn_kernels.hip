@@ -1026,6 +1026,8 @@ __global__ __launch_bounds__(256) void add_partial_kernel(float4* __restrict__ y
   }
 }
 
+__global__ void zero_u32_kernel(unsigned int* p) { *p = 0u; }
+
 }  // namespace
 
 template <typename T, int PASS>
@@ -1128,6 +1130,10 @@ void launch_copy(void* dst, const void* src, int64_t n_bytes, hipStream_t s) {
   if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
                      static_cast<uint4*>(dst), static_cast<const uint4*>(src), n);
+}
+
+void launch_zero_u32(unsigned int* p, hipStream_t s) {
+  hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(1), 0, s, p);
 }
 
 void launch_add_partial(float* ysum, const float* part, int n, hipStream_t s) {

@@ -111,5 +111,7 @@ size_t grouped_down_lds_bytes(const FfnArgs& a);
 void launch_copy(void* dst, const void* src, int64_t n_bytes, hipStream_t s);
 // ysum[i] += part[i], i < n (n a multiple of 4): adds what the host cores computed
 void launch_add_partial(float* ysum, const float* part, int n, hipStream_t s);
+// *p = 0 by a one-thread kernel (a fill that is safe to record into a graph)
+void launch_zero_u32(unsigned int* p, hipStream_t s);
 
 }  // namespace smoe

@@ -21,6 +21,12 @@
 
 using namespace smoe;
 
+// Scratch of moe_decode_layer_static: one array per GPU, held until the process
+// ends.  In host code the name below is only a stand-in for the symbol: the
+// device address is looked up once per device at init (scratch_of_device) and
+// only that pointer is ever handed to kernels or runtime calls.
+static __device__ __align__(256) unsigned char scratch[SMOE_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local int g_last_hip = 0;
@@ -34,11 +40,38 @@ thread_local int g_last_hip = 0;
     }                                         \
   } while (0)
 
+constexpr int kMaxDevices = 64;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};
+
 struct EventPair { hipEvent_t a, b; };
 struct ProfKind {
   std::vector<EventPair> ev;
   size_t used = 0;
   int64_t bytes = 0;
+};
+
+// Device address of this GPU's copy of `scratch` (each GPU holds its own);
+// `dev` must be the current device.
+int scratch_of_device(int dev, unsigned char** out) {
+  if (dev < 0 || dev >= kMaxDevices) return SMOE_EINVAL;
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    g_scratch_ptr[dev] = static_cast<unsigned char*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return SMOE_OK;
+}
+
+// Device memory the kernels of one decode call work in besides the caller's
+// inputs and outputs.
+struct Scratch {
+  StepRec* rec = nullptr;                // decision record
+  float* act = nullptr;                  // SwiGLU activations between the up and the down kernel
+  float* ysum = nullptr;                 // [B][H] fp32 sums carried from the resident to the loaded pass
+  RouteTmp* route_tmp = nullptr;         // per-token state between the two launches of a batched router
+  float* split_part = nullptr;           // partial dot products of the multi-block batch-1 router
+  unsigned int* split_count = nullptr;   // its ticket counter (zero between launches)
 };
 
 }  // namespace
@@ -56,14 +89,13 @@ struct moe_handle {
   std::vector<const char*> experts_host; // [L] pinned blocks of E experts
   // device scratch
   float* sim_dev = nullptr;
-  StepRec* rec_dev = nullptr;
+  Scratch own;                           // allocated at init, used by moe_decode_layer
+  Scratch fixed;                         // carved out of this GPU's static array, used by
+                                         // moe_decode_layer_static (null: need > the array)
+  int64_t fixed_need = 0;                // bytes of the static array this configuration needs
+  int device = 0;
   StepRec* rec_host = nullptr;           // pinned
   StepRec* rec_host_dev = nullptr;       // its device-visible address
-  float* act = nullptr;
-  float* ysum = nullptr;
-  RouteTmp* route_tmp = nullptr;
-  float* split_part = nullptr;           // scratch of the multi-block batch-1 router
-  unsigned int* split_count = nullptr;
   int route_split = 1;                   // SMOE_ROUTE_SPLIT: 0 never, 1 for gate matrices >= 512 KiB, 2 always
   // top-score prefetch: the prediction has a decision record of its own
   StepRec* pred_dev = nullptr;
@@ -217,13 +249,13 @@ void free_all(moe_handle* h) {
   if (h->pred_dev) (void)hipFree(h->pred_dev);
   if (h->pred_host) (void)hipHostFree(h->pred_host);
   if (h->sim_dev) (void)hipFree(h->sim_dev);
-  if (h->rec_dev) (void)hipFree(h->rec_dev);
+  if (h->own.rec) (void)hipFree(h->own.rec);
   if (h->rec_host) (void)hipHostFree(h->rec_host);
-  if (h->act) (void)hipFree(h->act);
-  if (h->ysum) (void)hipFree(h->ysum);
-  if (h->route_tmp) (void)hipFree(h->route_tmp);
-  if (h->split_part) (void)hipFree(h->split_part);
-  if (h->split_count) (void)hipFree(h->split_count);
+  if (h->own.act) (void)hipFree(h->own.act);
+  if (h->own.ysum) (void)hipFree(h->own.ysum);
+  if (h->own.route_tmp) (void)hipFree(h->own.route_tmp);
+  if (h->own.split_part) (void)hipFree(h->own.split_part);
+  if (h->own.split_count) (void)hipFree(h->own.split_count);
   delete h;
 }
 
@@ -322,14 +354,14 @@ void compute_on_cpu(moe_handle* h, int layer, int B, const StepRec& rec, const i
 
 // Arguments of one router launch for `layer` on x (the decision record and the
 // call number are filled in by the caller).
-void fill_route_args(const moe_handle* h, int layer, int B, const void* x, RouteArgs& ra) {
+void fill_route_args(const moe_handle* h, const Scratch& sc, int layer, int B, const void* x, RouteArgs& ra) {
   const moe_cfg_t& c = h->cfg;
   const int E = c.n_experts;
   const CacheLayer& ls = h->layers[layer];
   ra.gate_w = static_cast<const char*>(h->buf.gate_w_dev) + (int64_t)layer * E * c.hidden * h->esize;
   ra.x = x;
   ra.sim = h->sim_dev + (size_t)layer * E * E;
-  ra.tmp = h->route_tmp;
+  ra.tmp = sc.route_tmp;
   ra.B = B; ra.H = c.hidden; ra.E = E; ra.k = c.top_k;
   ra.renorm = c.renorm_topk; ra.subst_key = c.subst_key; ra.alpha = c.alpha;
   ra.nseg = 1;
@@ -346,8 +378,8 @@ void fill_route_args(const moe_handle* h, int layer, int B, const void* x, Route
     while (ra.nseg < 8 && E * ra.nseg < 32 && c.hidden / (ra.nseg * 2) >= 512) ra.nseg *= 2;
   }
   ra.split_nb = 0;
-  ra.split_part = h->split_part;
-  ra.split_count = h->split_count;
+  ra.split_part = sc.split_part;
+  ra.split_count = sc.split_count;
   const int64_t gate_bytes = (int64_t)E * c.hidden * h->esize;
   if (B == 1 && h->route_fast && (h->route_split >= 2 || (h->route_split == 1 && gate_bytes >= 512 * 1024))) {
     // batch 1, large gate matrix: spread the GEMV over several blocks, about one (row, segment)
@@ -446,15 +478,16 @@ uint64_t prefetched_in_flight(moe_handle* h, int layer) {
 
 // Arguments of the FFN launches of one call (resident pass; the second pass
 // changes `pass` and `slot_override` only).
-void fill_ffn_args(const moe_handle* h, int layer, int B, const void* x_dev, void* y_dev, FfnArgs& fa) {
+void fill_ffn_args(const moe_handle* h, const Scratch& sc, int layer, int B, const void* x_dev, void* y_dev,
+                   FfnArgs& fa) {
   const moe_cfg_t& c = h->cfg;
-  fa.rec = h->rec_dev;
+  fa.rec = sc.rec;
   fa.x = x_dev; fa.y = y_dev;
   fa.slab = static_cast<const char*>(h->buf.cache_slab_dev);
   fa.shared = c.n_shared ? static_cast<const char*>(h->buf.shared_dev) +
                                (int64_t)layer * c.n_shared * h->shared_bytes
                          : nullptr;
-  fa.act = h->act; fa.ysum = h->ysum;
+  fa.act = sc.act; fa.ysum = sc.ysum;
   fa.expert_bytes = h->expert_bytes; fa.shared_bytes = h->shared_bytes;
   fa.B = B; fa.H = c.hidden; fa.F = c.ffn; fa.Fs = c.n_shared ? c.shared_ffn : 0;
   fa.k = c.top_k; fa.ns = c.n_shared; fa.Fmax = h->Fmax;
@@ -685,7 +718,7 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
     HIP_TRY(hipEventCreateWithFlags(&h->ev_copy, hipEventDisableTiming));
     HIP_TRY(hipMalloc(&h->sim_dev, sim_bytes));
     HIP_TRY(hipMemcpy(h->sim_dev, buf->sim_host, sim_bytes, hipMemcpyHostToDevice));
-    HIP_TRY(hipMalloc(&h->rec_dev, sizeof(StepRec)));
+    HIP_TRY(hipMalloc(&h->own.rec, sizeof(StepRec)));
     HIP_TRY(hipHostMalloc(&h->rec_host, sizeof(StepRec), hipHostMallocDefault));
     std::memset(h->rec_host, 0, sizeof(StepRec));
     h->spin_limit = env_int("SMOE_SPIN_LIMIT", 4000000);
@@ -699,12 +732,36 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
       const int64_t grouped = maxg * SMOE_MAX_BATCH * c.ffn + (int64_t)c.n_shared * SMOE_MAX_BATCH * c.shared_ffn;
       h->act_floats = std::max<int64_t>((int64_t)c.max_batch * nj * h->Fmax, grouped);
     }
-    HIP_TRY(hipMalloc(&h->act, (size_t)h->act_floats * sizeof(float)));
-    HIP_TRY(hipMalloc(&h->ysum, (size_t)c.max_batch * c.hidden * sizeof(float)));
-    HIP_TRY(hipMalloc(&h->route_tmp, (size_t)SMOE_MAX_BATCH * sizeof(RouteTmp)));
-    HIP_TRY(hipMalloc(&h->split_part, (size_t)SMOE_MAX_EXPERTS * 8 * sizeof(float)));
-    HIP_TRY(hipMalloc(&h->split_count, sizeof(unsigned int)));
-    HIP_TRY(hipMemset(h->split_count, 0, sizeof(unsigned int)));
+    HIP_TRY(hipMalloc(&h->own.act, (size_t)h->act_floats * sizeof(float)));
+    HIP_TRY(hipMalloc(&h->own.ysum, (size_t)c.max_batch * c.hidden * sizeof(float)));
+    HIP_TRY(hipMalloc(&h->own.route_tmp, (size_t)SMOE_MAX_BATCH * sizeof(RouteTmp)));
+    HIP_TRY(hipMalloc(&h->own.split_part, (size_t)SMOE_MAX_EXPERTS * 8 * sizeof(float)));
+    HIP_TRY(hipMalloc(&h->own.split_count, sizeof(unsigned int)));
+    HIP_TRY(hipMemset(h->own.split_count, 0, sizeof(unsigned int)));
+    {
+      // the same buffers inside this GPU's static array, for moe_decode_layer_static
+      HIP_TRY(hipGetDevice(&h->device));
+      unsigned char* base = nullptr;
+      const int src = scratch_of_device(h->device, &base);
+      if (src != SMOE_OK) return src;
+      int64_t off = 0;
+      auto carve = [&](int64_t bytes) { const int64_t o = off; off += (bytes + 255) / 256 * 256; return o; };
+      const int64_t o_rec = carve(sizeof(StepRec));
+      const int64_t o_tmp = carve((int64_t)SMOE_MAX_BATCH * sizeof(RouteTmp));
+      const int64_t o_part = carve((int64_t)SMOE_MAX_EXPERTS * 8 * sizeof(float));
+      const int64_t o_count = carve(sizeof(unsigned int));
+      const int64_t o_ysum = carve((int64_t)c.max_batch * c.hidden * sizeof(float));
+      const int64_t o_act = carve(h->act_floats * (int64_t)sizeof(float));
+      h->fixed_need = off;
+      if (off <= (int64_t)SMOE_STATIC_SCRATCH_BYTES) {
+        h->fixed.rec = reinterpret_cast<StepRec*>(base + o_rec);
+        h->fixed.route_tmp = reinterpret_cast<RouteTmp*>(base + o_tmp);
+        h->fixed.split_part = reinterpret_cast<float*>(base + o_part);
+        h->fixed.split_count = reinterpret_cast<unsigned int*>(base + o_count);
+        h->fixed.ysum = reinterpret_cast<float*>(base + o_ysum);
+        h->fixed.act = reinterpret_cast<float*>(base + o_act);
+      }
+    }
     h->route_split = env_int("SMOE_ROUTE_SPLIT", 1);
     if (c.prefetch_max > 0) {
       HIP_TRY(hipMalloc(&h->pred_dev, sizeof(StepRec)));
@@ -777,11 +834,11 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
   return SMOE_OK;
 }
 
-int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* x_dev, void* y_dev,
-                     moe_trace_t* trace) {
-  if (!h || !x_dev || !y_dev) return SMOE_EINVAL;
+// One decode step of one layer with the kernels' scratch in `sc`: the body of
+// moe_decode_layer and moe_decode_layer_static.
+static int decode_layer_with(moe_handle_t* h, const Scratch& sc, int32_t layer, int32_t batch,
+                             const void* x_dev, void* y_dev, moe_trace_t* trace) {
   const moe_cfg_t& c = h->cfg;
-  if (layer < 0 || layer >= c.n_layers || batch < 1 || batch > c.max_batch) return SMOE_EINVAL;
   CacheLayer& ls = h->layers[layer];
   const int E = c.n_experts, B = batch;
   bool timed[5] = {false, false, false, false, false};   // route, up, down, up (2nd pass), down (2nd pass)
@@ -795,8 +852,8 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
 
   // ---- router + expert-cache router ------------------------------------------
   RouteArgs ra{};
-  fill_route_args(h, layer, B, x_dev, ra);
-  ra.rec_dev = h->rec_dev;
+  fill_route_args(h, sc, layer, B, x_dev, ra);
+  ra.rec_dev = sc.rec;
   ra.rec_host = h->rec_host_dev;
   ra.seq = ++h->seq;
   for (int e = 0; e < E; ++e)
@@ -818,7 +875,7 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   // ---- FFN over what is already resident (+ shared experts), enqueued before
   //      the host knows the routing result ------------------------------------
   FfnArgs fa{};
-  fill_ffn_args(h, layer, B, x_dev, y_dev, fa);
+  fill_ffn_args(h, sc, layer, B, x_dev, y_dev, fa);
   {
     const int rc = launch_ffn_pair(h, fa, SMOE_PROF_UP, SMOE_PROF_DOWN, &timed[1], &timed[2]);
     if (rc != SMOE_OK) return rc;
@@ -864,7 +921,7 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
       const int rc = settle_prefetch(h);
       if (rc != SMOE_OK) return rc;
       compute_on_cpu(h, layer, B, rec, plan.on_cpu, plan.n_cpu);
-      launch_add_partial(h->ysum, h->ycpu_host_dev, B * c.hidden, h->s_compute);
+      launch_add_partial(sc.ysum, h->ycpu_host_dev, B * c.hidden, h->s_compute);
       HIP_TRY(hipGetLastError());
     }
     if (plan.n_fetch > 0) {
@@ -892,6 +949,26 @@ int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* 
   return SMOE_OK;
 }
 
+int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* x_dev, void* y_dev,
+                     moe_trace_t* trace) {
+  if (!h || !x_dev || !y_dev) return SMOE_EINVAL;
+  if (layer < 0 || layer >= h->cfg.n_layers || batch < 1 || batch > h->cfg.max_batch) return SMOE_EINVAL;
+  return decode_layer_with(h, h->own, layer, batch, x_dev, y_dev, trace);
+}
+
+int moe_decode_layer_static(moe_handle_t* h, int32_t layer, int32_t batch, const void* x_dev, void* y_dev,
+                            moe_trace_t* trace) {
+  if (!h || !x_dev || !y_dev) return SMOE_EINVAL;
+  if (layer < 0 || layer >= h->cfg.n_layers || batch < 1 || batch > h->cfg.max_batch) return SMOE_EINVAL;
+  if (h->fixed_need > (int64_t)SMOE_STATIC_SCRATCH_BYTES || !h->fixed.rec) return SMOE_ETOOBIG;
+  // The array is shared by every handle on this GPU and keeps the previous call's contents.
+  // The only part that must start at zero is the ticket counter of the multi-block router
+  // (cleared by a one-thread kernel: memset nodes misbehave under graph capture).
+  launch_zero_u32(h->fixed.split_count, h->s_compute);
+  HIP_TRY(hipGetLastError());
+  return decode_layer_with(h, h->fixed, layer, batch, x_dev, y_dev, trace);
+}
+
 int moe_prefetch_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* x_pred_dev) {
   if (!h || !x_pred_dev) return SMOE_EINVAL;
   const moe_cfg_t& c = h->cfg;
@@ -904,7 +981,7 @@ int moe_prefetch_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void
   // The prediction is the router kernel itself on the predicted hidden state,
   // writing to a record of its own; only its scores and top-k are used.
   RouteArgs ra{};
-  fill_route_args(h, layer, batch, x_pred_dev, ra);
+  fill_route_args(h, h->own, layer, batch, x_pred_dev, ra);
   ra.rec_dev = h->pred_dev;
   ra.rec_host = h->pred_host_dev;
   ra.seq = ++h->pred_seq;

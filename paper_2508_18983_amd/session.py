@@ -113,13 +113,18 @@ class DecodeSession:
         return B.Trace(batch, self.cfg.top_k, self.cfg.n_experts)
 
     def decode(self, layer: int, x_dev: torch.Tensor, y_dev: Optional[torch.Tensor] = None,
-               trace: Optional[B.Trace] = None) -> torch.Tensor:
+               trace: Optional[B.Trace] = None, static: bool = False) -> torch.Tensor:
         """x_dev [B, H] on the device (produced on any stream that has been
-        synchronised).  Returns y_dev; valid after ``sync()``."""
+        synchronised).  Returns y_dev; valid after ``sync()``.  ``static``
+        forwards to moe_decode_layer_static (y_dev must then be supplied: that
+        entry point exists for callers that do not allocate)."""
         batch = x_dev.shape[0]
         if y_dev is None:
+            if static:
+                raise ValueError("the static entry point needs a caller-owned y_dev")
             y_dev = torch.empty_like(x_dev)
-        B.moe_decode_layer(self.handle, layer, batch, x_dev.data_ptr(), y_dev.data_ptr(), trace)
+        fn = B.moe_decode_layer_static if static else B.moe_decode_layer
+        fn(self.handle, layer, batch, x_dev.data_ptr(), y_dev.data_ptr(), trace)
         return y_dev
 
     def prefetch(self, layer: int, x_pred_dev: torch.Tensor) -> None:

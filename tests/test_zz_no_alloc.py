@@ -1,0 +1,103 @@
+"""moe_decode_layer_static (the entry point for callers that must not allocate:
+its kernels' scratch is one file-scope device array per GPU) against
+moe_decode_layer, through the C ABI.  Same kernels, same inputs: y must be
+bit-identical, decisions and counters equal."""
+import numpy as np
+import pytest
+import torch
+
+from smoe_inputs import SHAPES, make_workload
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(wl, batches, static, **kw):
+    """Decode token t with batch size batches[t % len(batches)] (a prefix of the
+    workload's tokens) through every layer; returns y, traces, stats."""
+    from paper_2508_18983_amd.session import session_from_workload
+    s = wl.shape
+    Bmax = max(batches)
+    out = []
+    with session_from_workload(wl, max_batch=Bmax, **kw) as ses:
+        x = wl.x.to(ses.device)
+        y = torch.zeros(s.tokens, s.n_layers, Bmax, s.hidden, dtype=ses.tdtype, device=ses.device)
+        for t in range(s.tokens):
+            b = batches[t % len(batches)]
+            for l in range(s.n_layers):
+                tr = ses.new_trace(b)
+                ses.decode(l, x[t, l, :b], y[t, l, :b], tr, static=static)
+                out.append((tr.topk_idx.copy(), tr.final_idx.copy(), tr.hit.copy(),
+                            tr.fetched.copy(), tr.victims.copy()))
+        ses.sync()
+        return y.cpu(), out, ses.stats(), [ses.residency(l).tolist() for l in range(s.n_layers)]
+
+
+def _same(a, b):
+    ya, ta, sa, ra = a
+    yb, tb, sb, rb = b
+    assert torch.equal(ya.view(torch.int16) if ya.dtype == torch.bfloat16 else ya,
+                       yb.view(torch.int16) if yb.dtype == torch.bfloat16 else yb)
+    assert sa == sb and ra == rb
+    for qa, qb in zip(ta, tb):
+        for u, v in zip(qa, qb):
+            np.testing.assert_array_equal(u, v)
+
+
+def test_static_entry_point_two_calls_second_smaller_and_long_runs():
+    # two calls in a row on the shared array, the second with a smaller input (batch 4, then 2),
+    # repeated over a run with misses, substitutions, staging and a second FFN pass
+    shp = SHAPES["c5"].with_(ffn=512, shared_ffn=1024, cache_cap=12, seed=31)
+    wl = make_workload(shp, n_layers=2, tokens=12, batch=4)
+    ref = _run(wl, [4, 2], static=False, n_stage=32)
+    got = _run(wl, [4, 2], static=True, n_stage=32)
+    _same(ref, got)
+    assert ref[2]["misses"] > 0 and ref[2]["substitutions"] > 0
+    # batch 1, fp32 and bf16, the register kernels; then a second handle reuses the array
+    for name in ("c1", "c2"):
+        wl = make_workload(SHAPES[name].with_(tokens=12, seed=5))
+        _same(_run(wl, [1], static=False), _run(wl, [1], static=True))
+    # the multi-block router (its ticket counter lives in the array and must start at zero)
+    wl = make_workload(SHAPES["c2"].with_(tokens=8, seed=6))
+    import os
+    os.environ["SMOE_ROUTE_SPLIT"] = "2"
+    try:
+        _same(_run(wl, [1], static=False), _run(wl, [1], static=True))
+    finally:
+        del os.environ["SMOE_ROUTE_SPLIT"]
+
+
+def test_static_entry_point_against_the_oracle_and_size_limit():
+    import paper_2508_18983_amd as M
+    from oracle import smoe_oracle as O
+    from paper_2508_18983_amd.session import session_from_workload
+    from smoe_inputs import as_numpy
+    from tests.parity import TOL, rel_errors
+    wl = make_workload(SHAPES["c2"].with_(tokens=10, seed=2))
+    s = wl.shape
+    orc = O.oracle_from_workload(wl)
+    with session_from_workload(wl) as ses:
+        x = wl.x.to(ses.device)
+        y = torch.zeros(s.tokens, s.n_layers, 1, s.hidden, dtype=ses.tdtype, device=ses.device)
+        for t in range(s.tokens):
+            for l in range(s.n_layers):
+                tr = ses.new_trace(1)
+                ses.decode(l, x[t, l], y[t, l], tr, static=True)
+                res = orc.decode_layer(l, as_numpy(wl.x[t, l]))
+                assert tr.final_idx.tolist() == res.final.tolist()
+                assert tr.fetched[:tr.n_fetched].tolist() == res.fetched
+                ses.sync()
+                l2, mx = rel_errors(y[t, l].double().cpu().numpy(), res.y)
+                assert l2 <= TOL["bf16"] and mx <= TOL["bf16"]
+        assert ses.stats() == orc.stats().as_dict()
+    # a configuration whose activations alone exceed the 8 MiB array is refused, not truncated
+    big = SHAPES["c1"].with_(dtype="bf16", hidden=64, ffn=8, n_experts=4, top_k=2, cache_cap=2,
+                             n_shared=1, shared_ffn=160000, tokens=2, sim="uniform")
+    wl = make_workload(big, n_layers=1, batch=8)
+    with session_from_workload(wl, max_batch=8, n_stage=16) as ses:
+        x = wl.x.to(ses.device)
+        y = torch.empty_like(x[0, 0])
+        with pytest.raises(M.SmoeError) as ei:
+            ses.decode(0, x[0, 0], y, static=True)
+        assert ei.value.code == -5
+        ses.decode(0, x[0, 0], y)           # the allocating entry point still serves it
+        ses.sync()
