@@ -1,17 +1,23 @@
 #!/usr/bin/env python3
 """Benchmark of the SMoE offloaded-MoE decode hot path on one MI355X.
 
-A step = one decode token through every MoE layer of the workload: router,
-substitution, cache bookkeeping, on-demand loads of the misses, expert FFNs.
-Inputs (weights in pinned host memory, gate / shared weights and hidden states
-in HBM, initial residents in the HBM cache) are in place before the timed
-region starts.  Prints ONE JSON line.
+A step = one decode token through every MoE layer of the workload: gate GEMV,
+selection + substitution, cache bookkeeping, on-demand loads of the misses,
+expert FFNs.  Inputs (weights in pinned host memory, gate / shared weights and
+hidden states in HBM, initial residents in the HBM cache) are in place before
+the timed region starts.  The timed region is repeated (default 3 times, each
+exactly --steps tokens, continuing the token stream) and the median repeat is
+reported.  Prints ONE JSON line.
+
+Headline workload: c5 (Qwen2-57B-A14B-shaped), the largest of the five by bytes
+per token; c3 and c4 are summarised in `extra.other_workloads`.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -20,9 +26,22 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
-# HBM bytes per launch of the resident-pass up kernel / its algorithmic bytes, from the two
-# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) summarised in profiles/c3_ffn_hbm_traffic_pmc.md
-MEASURED_TRAFFIC_RATIO = {"c3-mixtral8x7b-shaped": 1.0003}
+
+# HBM bytes per launch / algorithmic bytes per launch of the resident-pass FFN kernels, from the
+# two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, scaled by the 1 GiB calibration copy) that
+# profiles/<workload>_ffn_hbm_traffic_pmc.md summarises.  bench.py cannot read counters itself;
+# a workload without a committed summary reports traffic = null.
+MEASURED_TRAFFIC_RATIO = {
+    "c3-mixtral8x7b-shaped": 1.0003,       # profiles/c3_ffn_hbm_traffic_pmc.md
+}
+# Names the profiler prints for the two resident-pass kernels at batch 1 (template arguments:
+# up <type, 128-bit units of x per lane, pass, selection fused>; down <type, units per lane,
+# rows per buffer, waves per block, pass>).
+KERNEL_NAMES = {
+    "c3-mixtral8x7b-shaped": ("ffn_up_reg_kernel<bf16_t, 8, 0, true>", "ffn_down_reg_kernel<bf16_t, 8, 1, 8, 0>"),
+    "c4-dsv2lite-shaped": ("ffn_up_reg_kernel<bf16_t, 4, 0, true>", "ffn_down_reg_kernel<bf16_t, 4, 2, 8, 0>"),
+    "c5-qwen2-57b-a14b-shaped": ("ffn_up_reg_kernel<bf16_t, 8, 0, true>", "ffn_down_reg_kernel<bf16_t, 6, 2, 8, 0>"),
+}
 
 
 def log(msg: str) -> None:
@@ -46,61 +65,266 @@ def run_tokens(ses, x_dev, y_dev, t0: int, t1: int, n_layers: int, xp_dev=None) 
             ses.decode(l, x_dev[t, l], y_dev[l])
 
 
-PROF_UP_AND_COPY = (1 << 1) | (1 << 3)
+PROF_RESIDENT_AND_COPY = (1 << 1) | (1 << 2) | (1 << 3)      # up, down (resident pass), copies
 PROF_ALL = (1 << 6) - 1
 
 
-def timed_run(ses, x_dev, y_dev, warmup: int, steps: int, n_layers: int, prof_launches: int,
-              prof_mask: int = PROF_UP_AND_COPY, xp_dev=None):
+def timed_repeats(ses, x_dev, y_dev, warmup: int, steps: int, repeats: int, n_layers: int,
+                  prof_mask: int = PROF_RESIDENT_AND_COPY, xp_dev=None):
+    """`warmup` untimed tokens, then `repeats` timed regions of exactly `steps`
+    tokens each, every one bracketed by a drain of both streams.  Returns the
+    per-repeat wall times, the event profile and the counter deltas over all
+    repeats."""
     import paper_2508_18983_amd as M
     run_tokens(ses, x_dev, y_dev, 0, warmup, n_layers, xp_dev)
     ses.sync()
     st0 = ses.stats()
-    M.moe_profile_enable(ses.handle, prof_mask, prof_launches)
-    ses.sync()
-    t_begin = time.perf_counter()
-    run_tokens(ses, x_dev, y_dev, warmup, warmup + steps, n_layers, xp_dev)
-    ses.sync()
-    elapsed = time.perf_counter() - t_begin
+    M.moe_profile_enable(ses.handle, prof_mask, repeats * steps * n_layers + 8)
+    times = []
+    for r in range(repeats):
+        ses.sync()
+        t_begin = time.perf_counter()
+        run_tokens(ses, x_dev, y_dev, warmup + r * steps, warmup + (r + 1) * steps, n_layers, xp_dev)
+        ses.sync()
+        times.append(time.perf_counter() - t_begin)
     prof = M.moe_profile_read(ses.handle).as_dict()
     M.moe_profile_enable(ses.handle, 0, 1)
     st1 = ses.stats()
     delta = {k: st1[k] - st0[k] for k in st1}
-    return elapsed, prof, delta
+    return times, prof, delta
+
+
+def host_cores() -> int:
+    try:
+        return len(os.sched_getaffinity(0))
+    except AttributeError:
+        return os.cpu_count() or 1
 
 
 def cpu_baseline(wl, budget_s: float):
-    """Time the CPU oracle, as it stands, on the first token's layers until
-    about ``budget_s`` seconds are spent; scale to tokens/s."""
+    """The CPU oracle as it stands, timed on the first token's layers: once with
+    its numerical library held to one thread, once with the cores this process
+    may use (each for about half of ``budget_s``); scaled to tokens/s."""
     from oracle import smoe_oracle as O
     from smoe_inputs import as_numpy
     try:
-        from threadpoolctl import threadpool_info
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        from threadpoolctl import threadpool_limits
     except Exception:
-        threads = 1
+        threadpool_limits = None
     s = wl.shape
-    orc = O.oracle_from_workload(wl, widen_cache_bytes=0)
-    done = 0
+    cores = host_cores()
+
+    def reading(n_threads, budget):
+        orc = O.oracle_from_workload(wl, widen_cache_bytes=0)
+        done = 0
+        t0 = time.perf_counter()
+        for l in range(s.n_layers):
+            orc.decode_layer(l, as_numpy(wl.x[0, l]), compute_y=True)
+            done += 1
+            if time.perf_counter() - t0 > budget:
+                break
+        dt = time.perf_counter() - t0
+        return 1.0 / (dt / done * s.n_layers), done, dt
+
+    if threadpool_limits is not None:
+        with threadpool_limits(limits=1):
+            v1, n1, d1 = reading(1, budget_s / 2)
+        with threadpool_limits(limits=cores):
+            vall, nall, dall = reading(cores, budget_s / 2)
+        used = cores
+    else:
+        v1 = n1 = d1 = None
+        vall, nall, dall = reading(None, budget_s)
+        used = 1
+    return {"value": vall, "unit": "tokens/s", "cores": int(used), "kind": "oracle",
+            "sample": f"token 0, layers 0..{nall - 1} of {s.n_layers} ({dall:.1f} s of fp64 numpy on "
+                      f"{used} threads), scaled to a whole token",
+            "single_thread": None if v1 is None else {
+                "value": v1, "cores": 1,
+                "sample": f"token 0, layers 0..{n1 - 1} of {s.n_layers} ({d1:.1f} s)"},
+            "host_cores_visible": cores}
+
+
+def kernel_block(prof_kind: dict, name: str, event_pair_us: float) -> dict:
+    n = max(prof_kind["launches"], 1)
+    avg_s = prof_kind["ms"] / n * 1e-3
+    bpl = prof_kind["bytes"] / n
+    ach = bpl / avg_s / 1e9 if avg_s > 0 else 0.0
+    only = avg_s - event_pair_us * 1e-6
+    return {"kernel": name, "launches": prof_kind["launches"], "bytes_per_launch": bpl,
+            "avg_launch_us": avg_s * 1e6, "achieved": ach, "frac": ach / HBM_PEAK_GBS,
+            # the event interval with the reading of an empty event pair taken off: brackets the
+            # rocprofv3 kernel duration from the other side
+            "kernel_only_us": only * 1e6 if only > 0 else None,
+            "kernel_only_frac": (bpl / only / 1e9 / HBM_PEAK_GBS) if only > 0 else None}
+
+
+def empty_event_pair_us(ses) -> float:
+    """What an event pair reads with nothing between its two records on the
+    compute stream: the part of an event interval that is not the kernel."""
+    import torch
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(64)]
+    ses.sync()
+    for a_ev, b_ev in pairs:
+        a_ev.record(ses.stream_compute)
+        b_ev.record(ses.stream_compute)
+    ses.sync()
+    return sum(a_ev.elapsed_time(b_ev) for a_ev, b_ev in pairs) / len(pairs) * 1e3
+
+
+def measure(args, workload: str, steps: int, warmup: int, repeats: int, headline: bool):
+    """One workload: the run with misses served (the `value`), the resident-path
+    roofline from it, and the all-resident reference run.  Returns a dict."""
+    import torch
+    import paper_2508_18983_amd as M
+    from paper_2508_18983_amd.session import session_from_workload, pinned_empty, pinned_free_all
+    from smoe_inputs import shape_by_name, make_workload
+
+    shape = shape_by_name(workload)
+    if headline:
+        if args.cache_cap is not None:
+            shape = shape.with_(cache_cap=args.cache_cap)
+        if args.alpha is not None:
+            shape = shape.with_(alpha=args.alpha)
+        if args.evict_policy is not None:
+            shape = shape.with_(evict_policy=args.evict_policy)
+    Bt = args.batch if headline else 1
+    prefetch = args.prefetch if headline else 0
+    cpu_assist = int(args.cpu_assist) if headline else 0
+    while repeats > 1 and warmup + repeats * steps > shape.tokens:
+        repeats -= 1
+    n_tok = warmup + repeats * steps
+    if n_tok > shape.tokens:
+        raise SystemExit(f"bench.py: warmup+steps must be <= {shape.tokens} tokens of {shape.name}")
+    L = shape.n_layers if (args.layers is None or not headline) else args.layers
     t0 = time.perf_counter()
-    for l in range(s.n_layers):
-        orc.decode_layer(l, as_numpy(wl.x[0, l]), compute_y=True)
-        done += 1
-        if time.perf_counter() - t0 > budget_s:
-            break
-    dt = time.perf_counter() - t0
-    per_token = dt / done * s.n_layers
-    return {"value": 1.0 / per_token, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"token 0, layers 0..{done - 1} of {s.n_layers} ({dt:.1f} s of fp64 numpy), "
-                      f"scaled to a whole token"}
+    log(f"drawing {shape.name}: {L} layers, {n_tok} tokens ...")
+    block_bytes = shape.n_experts * shape.expert_bytes
+    distinct = L
+    while distinct > 1 and distinct * block_bytes > args.pin_budget_gb * 1e9:
+        distinct = (distinct + 1) // 2
+    host_note = "every layer has its own pinned host copy"
+    if distinct < L:
+        host_note = (f"host pins at most ~{args.pin_budget_gb:.0f} GB: {distinct} distinct layer blocks "
+                     f"of expert weights, layer l reads block l mod {distinct} (same bytes copied per "
+                     f"load, separate HBM cache slots, gate weights and inputs per layer)")
+    wl = make_workload(shape, device="cuda", n_layers=L, tokens=n_tok, batch=Bt,
+                       host_alloc=pinned_empty, distinct_layers=distinct,
+                       pred_noise=args.pred_noise if prefetch > 0 else None)
+    s = wl.shape
+    log(f"inputs ready in {time.perf_counter() - t0:.1f} s (margin audit redrew {wl.redraws} token-layers)")
+    out = {"shape": s, "L": L, "Bt": Bt, "host_note": host_note, "repeats": repeats}
+    try:
+        with session_from_workload(wl, max_batch=Bt, n_stage=(Bt * s.top_k if Bt > 1 else 0),
+                                   prefetch_max=prefetch, cpu_assist=cpu_assist,
+                                   cpu_threads=args.cpu_threads) as ses:
+            x_dev = wl.x.to(ses.device).contiguous()
+            xp_dev = wl.x_pred.to(ses.device).contiguous() if prefetch > 0 else None
+            y_dev = torch.empty(L, Bt, s.hidden, dtype=ses.tdtype, device=ses.device)
+            log("timed run ...")
+            times, prof, st = timed_repeats(ses, x_dev, y_dev, warmup, steps, repeats, L, xp_dev=xp_dev)
+            out["cpu_costs"] = M.moe_cpu_assist_costs(ses.handle) if cpu_assist else None
+            out["event_pair_us"] = empty_event_pair_us(ses)
+        out.update(times=times, prof=prof, st=st)
+        extra = {}
+        if not args.no_miss_free:
+            # same tokens with every expert resident: the pure HBM path, no loads
+            log("all-resident reference run ...")
+            full = wl.shape.with_(cache_cap=s.n_experts)
+            wl_full = type(wl)(full, wl.gate_w, wl.experts, wl.shared, wl.sim, wl.x, wl.redraws)
+            try:
+                with session_from_workload(wl_full, max_batch=Bt) as ses2:
+                    x_dev = wl.x.to(ses2.device).contiguous()
+                    y_dev = torch.empty(L, Bt, s.hidden, dtype=ses2.tdtype, device=ses2.device)
+                    t2, _, _ = timed_repeats(ses2, x_dev, y_dev, min(warmup, 4), steps, repeats, L, prof_mask=0)
+                    e2 = statistics.median(t2)
+                    roof = HBM_PEAK_GBS * 1e9 / (s.layer_bytes() * L)
+                    extra["miss_free_tokens_per_s"] = steps * Bt / e2
+                    extra["miss_free_frac_of_hbm_roofline"] = (steps / e2) / roof
+                    extra["miss_free_us_per_layer"] = e2 / (steps * L) * 1e6
+                    # a short pass with an event pair around every launch: per-kernel durations
+                    n_short = min(steps, 16)
+                    _, p3, _ = timed_repeats(ses2, x_dev, y_dev, 0, n_short, 1, L, prof_mask=PROF_ALL)
+                for kind in ("route", "up", "down"):
+                    v = p3[kind]
+                    if v["launches"]:
+                        extra[f"miss_free_{kind}_us"] = v["ms"] * 1e3 / v["launches"]
+                        extra[f"miss_free_{kind}_GBs"] = v["bytes"] / (v["ms"] * 1e-3) / 1e9
+            except Exception as exc:            # e.g. not enough HBM for every expert
+                extra["miss_free_error"] = repr(exc)
+        if headline and not args.no_miss_free and not cpu_assist and prefetch == 0:
+            # the same tokens with the paper's CPU-assisted scheduling switched on (reported beside
+            # the headline, never as `value`): Algorithm 2 as printed, and this build's min-max variant
+            for mode, key in ((1, "cpu_assist_algorithm2"), (2, "cpu_assist_minmax_variant")):
+                log(f"run with cpu_assist = {mode} ...")
+                try:
+                    with session_from_workload(wl, max_batch=Bt, n_stage=(Bt * s.top_k if Bt > 1 else 0),
+                                               cpu_assist=mode, cpu_threads=args.cpu_threads) as ses3:
+                        x_dev = wl.x.to(ses3.device).contiguous()
+                        y_dev = torch.empty(L, Bt, s.hidden, dtype=ses3.tdtype, device=ses3.device)
+                        t3, _, st3 = timed_repeats(ses3, x_dev, y_dev, warmup, steps, 1, L, prof_mask=0)
+                        costs = M.moe_cpu_assist_costs(ses3.handle)
+                    extra[key] = {"tokens_per_s": steps * Bt / t3[0],
+                                  "hit_rate": st3["hits"] / max(st3["slots"], 1),
+                                  "loads_per_step": st3["fetches"] / steps,
+                                  "host_computed_per_step": st3["cpu_computed"] / steps,
+                                  "c_load_us": costs["c_load_us"], "c_cpu_us": costs["c_cpu_us"]}
+                except Exception as exc:
+                    extra[key] = {"error": repr(exc)}
+        out["extra"] = extra
+        if headline and args.cpu_budget > 0:
+            log("timing the CPU oracle ...")
+            out["cpu"] = cpu_baseline(wl, args.cpu_budget)
+    finally:
+        del wl
+        import gc
+        gc.collect()
+        torch.cuda.empty_cache()
+        pinned_free_all()
+    return out
+
+
+def summarise(m: dict, steps: int) -> dict:
+    """Common figures of one measured workload."""
+    s, L, Bt = m["shape"], m["L"], m["Bt"]
+    elapsed = statistics.median(m["times"])
+    st, prof = m["st"], m["prof"]
+    n_steps = steps * len(m["times"])
+    names = KERNEL_NAMES.get(s.name, ("ffn_up kernel (resident pass)", "ffn_down kernel (resident pass)"))
+    up = kernel_block(prof["up"], names[0], m["event_pair_us"])
+    down = kernel_block(prof["down"], names[1], m["event_pair_us"])
+    both_bytes = up["bytes_per_launch"] + down["bytes_per_launch"]
+    both_s = (up["avg_launch_us"] + down["avg_launch_us"]) * 1e-6
+    copy = prof["copy"]
+    res = {
+        "tokens_per_s": steps * Bt / elapsed,
+        "ms_per_step": elapsed / steps * 1e3,
+        "ms_per_step_repeats": [t / steps * 1e3 for t in m["times"]],
+        "hit_rate_raw": st["raw_hits"] / max(st["slots"], 1),
+        "hit_rate": st["hits"] / max(st["slots"], 1),
+        "substitutions_per_token": st["substitutions"] / (n_steps * Bt),
+        "fetches_per_step": st["fetches"] / n_steps,
+        "host_link_GBs": (copy["bytes"] / (copy["ms"] * 1e-3) / 1e9) if copy["ms"] > 0 else None,
+        "layer_bytes": s.layer_bytes(),
+        "hbm_roofline_tokens_per_s": HBM_PEAK_GBS * 1e9 / (s.layer_bytes() * L),
+        "resident_path": {"achieved": both_bytes / both_s / 1e9 if both_s > 0 else 0.0,
+                          "bytes_per_launch_pair": both_bytes, "us_per_launch_pair": both_s * 1e6},
+        "up": up, "down": down,
+    }
+    res["resident_path"]["frac"] = res["resident_path"]["achieved"] / HBM_PEAK_GBS
+    res.update(m.get("extra", {}))
+    return res
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=96)
+    ap.add_argument("--steps", type=int, default=32)
     ap.add_argument("--warmup", type=int, default=16)
-    ap.add_argument("--workload", default="c3", help="c1..c5 (default c3: Mixtral-8x7B-shaped)")
+    ap.add_argument("--repeats", type=int, default=3, help="timed regions of --steps tokens each; the median is reported")
+    ap.add_argument("--workload", default="c5", help="c1..c5 (default c5: Qwen2-57B-A14B-shaped, the largest)")
+    ap.add_argument("--others", default="c3,c4",
+                    help="workloads summarised in extra.other_workloads (comma list, '' = none)")
     ap.add_argument("--layers", type=int, default=None, help="override layer count (diagnostic only)")
     ap.add_argument("--batch", type=int, default=1, help="tokens per decode step (the headline metric is batch 1)")
     ap.add_argument("--cpu-budget", type=float, default=20.0, help="seconds of oracle timing; 0 = skip")
@@ -139,40 +363,7 @@ def main() -> int:
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         return 2
     import paper_2508_18983_amd as M
-    from paper_2508_18983_amd.session import session_from_workload, pinned_empty
-    from smoe_inputs import shape_by_name, make_workload
-
     M.load_library()
-    shape = shape_by_name(args.workload)
-    if args.cache_cap is not None:
-        shape = shape.with_(cache_cap=args.cache_cap)
-    if args.alpha is not None:
-        shape = shape.with_(alpha=args.alpha)
-    if args.evict_policy is not None:
-        shape = shape.with_(evict_policy=args.evict_policy)
-    n_tok = args.warmup + args.steps
-    if n_tok > shape.tokens:
-        print(f"bench.py: warmup+steps must be <= {shape.tokens} tokens of {shape.name}", file=sys.stderr)
-        return 2
-    t0 = time.perf_counter()
-    log(f"drawing {shape.name}: {shape.n_layers if args.layers is None else args.layers} layers, "
-        f"{n_tok} tokens ...")
-    L = shape.n_layers if args.layers is None else args.layers
-    block_bytes = shape.n_experts * shape.expert_bytes
-    distinct = L
-    while distinct > 1 and distinct * block_bytes > args.pin_budget_gb * 1e9:
-        distinct = (distinct + 1) // 2
-    host_note = "every layer has its own pinned host copy"
-    if distinct < L:
-        host_note = (f"host pins at most ~{args.pin_budget_gb:.0f} GB: {distinct} distinct layer blocks "
-                     f"of expert weights, layer l reads block l mod {distinct} (same bytes copied per "
-                     f"load, separate HBM cache slots, gate weights and inputs per layer)")
-    Bt = args.batch
-    wl = make_workload(shape, device="cuda", n_layers=args.layers, tokens=n_tok, batch=Bt,
-                       host_alloc=pinned_empty, distinct_layers=distinct,
-                       pred_noise=args.pred_noise if args.prefetch > 0 else None)
-    s = wl.shape
-    log(f"inputs ready in {time.perf_counter() - t0:.1f} s (margin audit redrew {wl.redraws} token-layers)")
 
     if args.calib_copies > 0:
         # known-size traffic for counter calibration: 1 GiB read + 1 GiB written per launch
@@ -186,131 +377,67 @@ def main() -> int:
         del src, dst
         torch.cuda.empty_cache()
 
-    prof_launches = args.steps * L + 8
-    with session_from_workload(wl, max_batch=Bt, n_stage=(Bt * s.top_k if Bt > 1 else 0),
-                               prefetch_max=args.prefetch, cpu_assist=int(args.cpu_assist),
-                               cpu_threads=args.cpu_threads) as ses:
-        x_dev = wl.x.to(ses.device)[:, :, :, :].contiguous()
-        xp_dev = wl.x_pred.to(ses.device).contiguous() if args.prefetch > 0 else None
-        y_dev = torch.empty(L, Bt, s.hidden, dtype=ses.tdtype, device=ses.device)
-        log("timed run ...")
-        elapsed, prof, st = timed_run(ses, x_dev, y_dev, args.warmup, args.steps, L, prof_launches,
-                                      xp_dev=xp_dev)
-        cpu_costs = M.moe_cpu_assist_costs(ses.handle) if args.cpu_assist else None
-        # what an event pair reads with nothing between its two records on the compute stream:
-        # the part of `avg_launch_us` that is not the kernel (reported, not subtracted)
-        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(64)]
-        ses.sync()
-        for a_ev, b_ev in pairs:
-            a_ev.record(ses.stream_compute)
-            b_ev.record(ses.stream_compute)
-        ses.sync()
-        event_pair_us = sum(a_ev.elapsed_time(b_ev) for a_ev, b_ev in pairs) / len(pairs) * 1e3
-    tok_s = args.steps * Bt / elapsed
-    up = prof["up"]
-    up_avg_s = up["ms"] / max(up["launches"], 1) * 1e-3
-    up_bytes_per_launch = up["bytes"] / max(up["launches"], 1)
-    achieved = up_bytes_per_launch / up_avg_s / 1e9 if up_avg_s > 0 else 0.0
-    copy = prof["copy"]
-    host_link = (copy["bytes"] / (copy["ms"] * 1e-3) / 1e9) if copy["ms"] > 0 else None
-
-    extra = {
-        "hit_rate_raw": st["raw_hits"] / max(st["slots"], 1),
-        "hit_rate": st["hits"] / max(st["slots"], 1),
-        "substitutions_per_token": st["substitutions"] / (args.steps * Bt),
-        "fetches_per_step": st["fetches"] / args.steps,
-        "host_link_GBs": host_link,
-        "layer_bytes": s.layer_bytes(),
-        "hbm_roofline_tokens_per_s": HBM_PEAK_GBS * 1e9 / (s.layer_bytes() * L),
-    }
+    m = measure(args, args.workload, args.steps, args.warmup, max(1, args.repeats), headline=True)
+    s, L, Bt = m["shape"], m["L"], m["Bt"]
+    res = summarise(m, args.steps)
+    up, down = res.pop("up"), res.pop("down")
+    rp = res.pop("resident_path")
+    extra = {k: v for k, v in res.items() if k not in ("tokens_per_s", "ms_per_step")}
     if args.cpu_assist:
-        extra["cpu_computed_per_step"] = st["cpu_computed"] / args.steps
-        extra["cpu_assist_costs"] = cpu_costs
+        extra["cpu_computed_per_step"] = m["st"]["cpu_computed"] / (args.steps * len(m["times"]))
+        extra["cpu_assist_costs"] = m["cpu_costs"]
     if args.prefetch > 0:
+        st = m["st"]
         extra.update({
-            "prefetches_per_step": st["prefetches"] / args.steps,
+            "prefetches_per_step": st["prefetches"] / (args.steps * len(m["times"])),
             "prefetch_used_frac": st["prefetch_used"] / max(st["prefetches"], 1),
             "prefetch_top_frac": st["prefetch_top"] / max(st["prefetches"], 1),
         })
 
-    if not args.no_miss_free:
-        # same tokens with every expert resident: the pure HBM path, no loads
-        log("all-resident reference run ...")
-        full = wl.shape.with_(cache_cap=s.n_experts)
-        wl_full = type(wl)(full, wl.gate_w, wl.experts, wl.shared, wl.sim, wl.x, wl.redraws)
+    others = {}
+    for name in [w for w in args.others.split(",") if w and w != args.workload and Bt == 1]:
         try:
-            with session_from_workload(wl_full, max_batch=Bt) as ses2:
-                x_dev = wl.x.to(ses2.device).contiguous()
-                y_dev = torch.empty(L, Bt, s.hidden, dtype=ses2.tdtype, device=ses2.device)
-                e2, p2, _ = timed_run(ses2, x_dev, y_dev, min(args.warmup, 4), args.steps, L, prof_launches,
-                                      prof_mask=0)
-                extra["miss_free_tokens_per_s"] = args.steps * Bt / e2
-                extra["miss_free_frac_of_hbm_roofline"] = (args.steps / e2) / extra["hbm_roofline_tokens_per_s"]
-                # a short pass with an event pair around every launch: per-kernel durations
-                n_short = min(args.steps, 16)
-                _, p3, _ = timed_run(ses2, x_dev, y_dev, 0, n_short, L, n_short * L + 8, prof_mask=PROF_ALL)
-            for kind in ("route", "up", "down"):
-                v = p3[kind]
-                if v["launches"]:
-                    extra[f"miss_free_{kind}_us"] = v["ms"] * 1e3 / v["launches"]
-                    extra[f"miss_free_{kind}_GBs"] = v["bytes"] / (v["ms"] * 1e-3) / 1e9
-        except Exception as exc:            # e.g. not enough HBM for every expert
-            extra["miss_free_error"] = repr(exc)
+            log(f"---- {name} (summary) ----")
+            mo = measure(args, name, min(args.steps, 24), min(args.warmup, 16), 1, headline=False)
+            so = summarise(mo, min(args.steps, 24))
+            o_up, o_down, o_rp = so.pop("up"), so.pop("down"), so.pop("resident_path")
+            so.update(resident_path_GBs=o_rp["achieved"], resident_path_frac=o_rp["frac"],
+                      up_kernel=o_up["kernel"], up_GBs=o_up["achieved"], up_avg_launch_us=o_up["avg_launch_us"],
+                      down_kernel=o_down["kernel"], down_GBs=o_down["achieved"],
+                      down_avg_launch_us=o_down["avg_launch_us"], host_expert_storage=mo["host_note"])
+            others[mo["shape"].name] = so
+        except Exception as exc:
+            others[name] = {"error": repr(exc)}
+    if others:
+        extra["other_workloads"] = others
 
-    if not args.no_miss_free and not args.cpu_assist and args.prefetch == 0:
-        # the same tokens with the paper's CPU-assisted scheduling switched on (reported beside the
-        # headline, never as `value`): Algorithm 2 as printed, and this build's min-max variant
-        for mode, key in ((1, "cpu_assist_algorithm2"), (2, "cpu_assist_minmax_variant")):
-            log(f"run with cpu_assist = {mode} ...")
-            try:
-                with session_from_workload(wl, max_batch=Bt, n_stage=(Bt * s.top_k if Bt > 1 else 0),
-                                           cpu_assist=mode, cpu_threads=args.cpu_threads) as ses3:
-                    x_dev = wl.x.to(ses3.device).contiguous()
-                    y_dev = torch.empty(L, Bt, s.hidden, dtype=ses3.tdtype, device=ses3.device)
-                    e3, _, st3 = timed_run(ses3, x_dev, y_dev, args.warmup, args.steps, L, 1, prof_mask=0)
-                    costs = M.moe_cpu_assist_costs(ses3.handle)
-                extra[key] = {"tokens_per_s": args.steps * Bt / e3,
-                              "hit_rate": st3["hits"] / max(st3["slots"], 1),
-                              "loads_per_step": st3["fetches"] / args.steps,
-                              "host_computed_per_step": st3["cpu_computed"] / args.steps,
-                              "c_load_us": costs["c_load_us"], "c_cpu_us": costs["c_cpu_us"]}
-            except Exception as exc:
-                extra[key] = {"error": repr(exc)}
-
-    cpu = None
-    if args.cpu_budget > 0:
-        log("timing the CPU oracle ...")
-        cpu = cpu_baseline(wl, args.cpu_budget)
-
+    ratio = MEASURED_TRAFFIC_RATIO.get(s.name)
     out = {
         "metric": f"decode tokens/s at batch {Bt} (full MoE stack)",
-        "value": tok_s, "unit": "tokens/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
+        "value": res["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if s.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": s.name, "layers": L, "hidden": s.hidden, "experts": s.n_experts,
                    "ffn": s.ffn, "top_k": s.top_k, "cache_cap": s.cache_cap, "alpha": s.alpha,
                    "n_shared": s.n_shared, "shared_ffn": s.shared_ffn, "batch": Bt,
-                   "zipf_s": s.zipf_s, "seed": s.seed, "evict_policy": s.evict_policy, "cpu_assist": int(args.cpu_assist), "prefetch_max": args.prefetch,
+                   "zipf_s": s.zipf_s, "seed": s.seed, "evict_policy": s.evict_policy,
+                   "cpu_assist": int(args.cpu_assist), "prefetch_max": args.prefetch,
                    "prefetch_ahead": PREFETCH_AHEAD if args.prefetch > 0 else None,
                    "pred_noise": args.pred_noise if args.prefetch > 0 else None,
-                   "host_expert_storage": host_note},
-        "roofline": {"bound": "hbm", "kernel": "ffn_up_kernel (resident pass)",
-                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": (MEASURED_TRAFFIC_RATIO[s.name] * up_bytes_per_launch
-                                 if s.name in MEASURED_TRAFFIC_RATIO else None),
-                     "bytes_per_launch": up_bytes_per_launch, "avg_launch_us": up_avg_s * 1e6,
-                     "empty_event_pair_us": event_pair_us,
-                     # the same with the empty-pair reading taken off the interval: what the kernel
-                     # itself takes (agrees with the rocprofv3 kernel duration)
-                     "kernel_only": {"avg_us": up_avg_s * 1e6 - event_pair_us,
-                                     "achieved": (up_bytes_per_launch / (up_avg_s - event_pair_us * 1e-6) / 1e9
-                                                  if up_avg_s * 1e6 > event_pair_us else None),
-                                     "frac": (up_bytes_per_launch / (up_avg_s - event_pair_us * 1e-6) / 1e9
-                                              / HBM_PEAK_GBS if up_avg_s * 1e6 > event_pair_us else None)},
-                     "launches": up["launches"]},
-        "cpu_baseline": cpu,
+                   "timed_repeats": len(m["times"]), "reported": "median repeat",
+                   "host_expert_storage": m["host_note"]},
+        # the resident-expert FFN path = the two kernels that stream the resident and shared
+        # experts' weights in every call (up: W1, W3; down: W2); the first is the dominant one
+        "roofline": {"bound": "hbm",
+                     "kernel": f"{up['kernel']} + {down['kernel']} (resident pass)",
+                     "achieved": rp["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": rp["frac"],
+                     "traffic": ratio * rp["bytes_per_launch_pair"] if ratio is not None else None,
+                     "bytes_per_launch": rp["bytes_per_launch_pair"],
+                     "avg_launch_us": rp["us_per_launch_pair"],
+                     "empty_event_pair_us": m["event_pair_us"],
+                     "kernels": [up, down]},
+        "cpu_baseline": m.get("cpu"),
         "extra": extra,
     }
     print(json.dumps(out), flush=True)

@@ -11,6 +11,7 @@
 //          order: no partial buffers, atomics or fences.
 #include "smoe_dev.hpp"
 #include "wave_ops.hpp"
+#include "route_select.hpp"
 
 namespace smoe {
 namespace {
@@ -101,6 +102,19 @@ __device__ __forceinline__ const char* task_weights(const FfnArgs& a, int t, int
   return a.shared + (int64_t)(j - a.k) * a.shared_bytes;
 }
 
+// Up kernels, batch-1 style: block -> (token, task j, tile of TF f-rows).  The
+// shared experts' blocks come first: they need no routing decision, so with the
+// selection fused into the kernel they stream weights while the routed blocks
+// are still deciding.
+__device__ __forceinline__ void up_block_coords(const FfnArgs& a, int& t, int& j, int& tile) {
+  const int n_shared_blocks = a.ns * a.tilesS;
+  const int bpt = n_shared_blocks + a.k * a.tilesR;   // blocks per token
+  t = blockIdx.x / bpt;
+  int r = blockIdx.x - t * bpt;
+  if (r < n_shared_blocks) { j = a.k + r / a.tilesS; tile = r - (j - a.k) * a.tilesS; }
+  else { r -= n_shared_blocks; j = r / a.tilesR; tile = r - j * a.tilesR; }
+}
+
 // acc[r] += sum_u row_r[u] . vec[u] over `units` 128-bit units, ROWS rows at a
 // time, UNR independent steps in flight per row.
 template <typename T, int ROWS, int UNR>
@@ -154,11 +168,8 @@ __global__ __launch_bounds__(256) void ffn_up_kernel(const FfnArgs a) {
   constexpr int N = Unit<T>::N;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
   const int nj = a.k + a.ns;
-  const int bpt = a.k * a.tilesR + a.ns * a.tilesS;   // blocks per token
-  const int t = blockIdx.x / bpt;
-  int r = blockIdx.x - t * bpt, j, tile;
-  if (r < a.k * a.tilesR) { j = r / a.tilesR; tile = r - j * a.tilesR; }
-  else { r -= a.k * a.tilesR; j = a.k + r / a.tilesS; tile = r - (j - a.k) * a.tilesS; }
+  int t, j, tile;
+  up_block_coords(a, t, j, tile);
   const int task = t * nj + j;
   int F; float wgt;
   const char* base = task_weights<PASS>(a, t, j, task, F, wgt);
@@ -290,26 +301,41 @@ __global__ __launch_bounds__(256) void ffn_down_kernel(const FfnArgs a) {
 
 // Up projection with x in registers: one wave owns whole rows (H/N <= 64*UPL
 // units).  Per f it has 2*UPL independent 128-bit loads in flight.
-template <typename T, int UPL, int PASS>
-__global__ __launch_bounds__(256) void ffn_up_reg_kernel(const FfnArgs a) {
+//
+// FUSED (batch 1, resident pass): there is no separate selection launch.  Every
+// routed block repeats the selection for itself in its prologue (one wave,
+// about a microsecond of arithmetic on E <= 64 logits that sit in L2) while its
+// loads of x are in flight; the first routed block also writes the decision
+// record for the down kernel and the host mirror.
+template <typename T, int UPL, int PASS, bool FUSED>
+__global__ __launch_bounds__(256) void ffn_up_reg_kernel(const FfnArgs a, const RouteArgs ra) {
   constexpr int N = Unit<T>::N;
   using raw = typename Unit<T>::raw;
+  __shared__ SelectSmem<FUSED ? 1 : 0> sm;             // (empty when not fused)
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
   const int nj = a.k + a.ns;
-  const int bpt = a.k * a.tilesR + a.ns * a.tilesS;
-  const int t = blockIdx.x / bpt;
-  int r = blockIdx.x - t * bpt, j, tile;
-  if (r < a.k * a.tilesR) { j = r / a.tilesR; tile = r - j * a.tilesR; }
-  else { r -= a.k * a.tilesR; j = a.k + r / a.tilesS; tile = r - (j - a.k) * a.tilesS; }
+  int t, j, tile;
+  up_block_coords(a, t, j, tile);
   const int task = t * nj + j;
-  int F; float wgt;
-  const char* base = task_weights<PASS>(a, t, j, task, F, wgt);
-  if (base == nullptr) return;
   const int H = a.H;
   const int units = H / N;
-  const T* W1 = reinterpret_cast<const T*>(base);
-  const T* W3 = W1 + (size_t)F * H;
 
+  // FUSED: what the selection reads from memory is requested first, together with x, so that
+  // one round trip serves all of it (the scalar arguments of the selection are pinned here for
+  // the same reason: fetched with the other kernel arguments instead of one by one later)
+  int my_slot_of = -1;
+  float my_logit = 0.f;
+  if constexpr (FUSED) {
+    const int e_ = ra.E, k_ = ra.k, ns_ = ra.nseg, rn_ = ra.renorm, sk_ = ra.subst_key;
+    const float al_ = ra.alpha;
+    const unsigned long long res_ = ra.resident;
+    const float* gp_ = ra.gate_part;
+    asm volatile("" ::"s"(e_), "s"(k_), "s"(ns_), "s"(rn_), "s"(sk_), "s"(al_), "s"(res_), "s"(gp_));
+    if (j < a.k && wave == 0) {
+      my_slot_of = ra.slot_of[lane];
+      my_logit = logit_from_parts(ra, lane, 0);
+    }
+  }
   raw xr[UPL];                                          // this lane's slice of x, as stored
   const T* x = static_cast<const T*>(a.x) + (size_t)t * H;
 #pragma unroll
@@ -317,6 +343,25 @@ __global__ __launch_bounds__(256) void ffn_up_reg_kernel(const FfnArgs a) {
     const int u = i * kWave + lane;
     xr[i] = (u < units) ? *reinterpret_cast<const raw*>(x + (size_t)u * N) : raw{};
   }
+
+  int F; float wgt;
+  const char* base = nullptr;
+  bool decided = false;
+  if constexpr (FUSED) {
+    if (j < a.k) {                                      // (uniform over the block)
+      if (wave == 0) select_single(ra, sm, lane, my_slot_of, my_logit, j == 0 && tile == 0);
+      __syncthreads();
+      const int slot = sm.slt[0][j];
+      F = a.F;
+      wgt = sm.wsl[0][j];
+      base = slot < 0 ? nullptr : a.slab + (int64_t)(a.slot_base + slot) * a.expert_bytes;
+      decided = true;
+    }
+  }
+  if (!decided) base = task_weights<PASS>(a, t, j, task, F, wgt);
+  if (base == nullptr) return;
+  const T* W1 = reinterpret_cast<const T*>(base);
+  const T* W3 = W1 + (size_t)F * H;
 
   // FPI f-rows (each = one W1 row + one W3 row) in flight per iteration
   constexpr int FPI = UPL >= 8 ? 1 : 2;
@@ -359,37 +404,43 @@ __global__ __launch_bounds__(256) void ffn_up_reg_kernel(const FfnArgs a) {
   }
 }
 
-// Down projection with the activations in registers.  A block owns RB output
-// rows of one token.  A row of task j is cut into nseg in {1, 2, 4} column
-// segments of <= 64*UPL units; a work item is (task, segment) and the four
-// waves take the items round-robin.  For its item a wave loads its slice of
-// the activations once and streams the RB rows, R at a time.  Every (item,
-// row) partial sum is produced by exactly one wave and parked in LDS; after
-// one barrier the block adds them in item order, so y does not depend on
-// scheduling.
-template <typename T, int UPL, int R, int PASS>
-__global__ __launch_bounds__(256) void ffn_down_reg_kernel(const FfnArgs a) {
+// Down projection with the activations in registers.  A block of NW waves owns
+// RB output rows of one token.  A row of task j is cut into column segments of
+// <= 64*UPL units; a work item is (task, segment) and the waves take the items
+// round-robin (the launch picks NW so that a wave has one or two).  For its
+// item a wave loads its slice of the activations once and streams the RB rows
+// R at a time through two register buffers: the loads of the next R rows are
+// issued before the current R rows are reduced, so 2*R*UPL 128-bit loads per
+// lane are in flight.  Every (item, row) partial sum is produced by exactly
+// one wave and parked in LDS; after one barrier the block adds them in item
+// order, so y does not depend on scheduling.
+template <typename T, int UPL, int R, int NW, int PASS>
+__global__ __launch_bounds__(64 * NW) void ffn_down_reg_kernel(const FfnArgs a) {
   extern __shared__ __align__(16) float part[];       // [items][RB]
   constexpr int N = Unit<T>::N;
   using raw = typename Unit<T>::raw;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
   const int nj = a.k + a.ns;
-  const int RB = a.RB;
+  const int RB = a.RB;                                 // multiple of R
   const int t = blockIdx.x / a.htiles;
   const int ht = blockIdx.x - t * a.htiles;
   const int H = a.H;
   const int hb = ht * RB;
-  const int items_r = a.k * a.nsegR;
-  const int n_items = items_r + a.ns * a.nsegS;
+  // items of the shared experts first: their weights do not depend on the decision record, so
+  // the waves that start with them have loads in flight while the record is still on its way
+  const int items_s = a.ns * a.nsegS;
+  const int n_items = items_s + a.k * a.nsegR;
 
-  bool any_miss = false;
-  for (int q = 0; q < a.k; ++q) any_miss |= (a.rec->tok[t].slot[q] < 0);
-  if (PASS == 1 && !any_miss) return;
+  if (PASS == 1) {
+    bool any_miss = false;
+    for (int q = 0; q < a.k; ++q) any_miss |= (a.rec->tok[t].slot[q] < 0);
+    if (!any_miss) return;                              // y of this token is already final
+  }
 
-  for (int it = wave; it < n_items; it += 4) {
+  for (int it = wave; it < n_items; it += NW) {
     int j, seg, nseg;
-    if (it < items_r) { nseg = a.nsegR; j = it / nseg; seg = it - j * nseg; }
-    else { nseg = a.nsegS; const int q = it - items_r; j = q / nseg; seg = q - j * nseg; j += a.k; }
+    if (it < items_s) { nseg = a.nsegS; j = it / nseg; seg = it - j * nseg; j += a.k; }
+    else { nseg = a.nsegR; const int q = it - items_s; j = q / nseg; seg = q - j * nseg; }
     float* prow = part + (size_t)it * RB;
     int F; float wgt;
     const char* base = task_weights<PASS>(a, t, j, t * nj + j, F, wgt);
@@ -403,6 +454,22 @@ __global__ __launch_bounds__(256) void ffn_down_reg_kernel(const FfnArgs a) {
     const int uend = min(units, ubeg + seg_units);
     const T* W2 = reinterpret_cast<const T*>(base) + 2 * (size_t)F * H;
     const float* act = a.act + (size_t)(t * nj + j) * a.Fmax;
+
+    // rows rr .. rr+R-1 of the block into one register buffer (rows past H repeat the last one)
+    auto load_rows = [&](raw (&q)[R][UPL], int rr) {
+#pragma unroll
+      for (int r2 = 0; r2 < R; ++r2) {
+        const T* row = W2 + (size_t)min(hb + rr + r2, H - 1) * F;
+#pragma unroll
+        for (int s2 = 0; s2 < UPL; ++s2) {
+          const int u = ubeg + s2 * kWave + lane;
+          q[r2][s2] = (u < uend) ? Unit<T>::load(row + (size_t)u * N) : raw{};
+        }
+      }
+    };
+    raw qa[R][UPL], qb[R][UPL];
+    load_rows(qa, 0);
+    if (R < RB) load_rows(qb, R);
 
     float ar[UPL][N];
 #pragma unroll
@@ -419,35 +486,35 @@ __global__ __launch_bounds__(256) void ffn_down_reg_kernel(const FfnArgs a) {
         for (int e = 0; e < N; ++e) ar[i][e] = 0.f;
       }
     }
-
-    for (int rr = 0; rr < RB; rr += R) {
-      raw q[R][UPL];
-#pragma unroll
-      for (int r2 = 0; r2 < R; ++r2) {
-        const T* row = W2 + (size_t)min(hb + rr + r2, H - 1) * F;
-#pragma unroll
-        for (int s = 0; s < UPL; ++s) {
-          const int u = ubeg + s * kWave + lane;
-          q[r2][s] = (u < uend) ? Unit<T>::load(row + (size_t)u * N) : raw{};
-        }
-      }
+    auto reduce_rows = [&](const raw (&q)[R][UPL], int rr) {
 #pragma unroll
       for (int r2 = 0; r2 < R; ++r2) {
         float acc = 0.f;
 #pragma unroll
-        for (int s = 0; s < UPL; ++s) {
+        for (int s2 = 0; s2 < UPL; ++s2) {
           float w[N];
-          Unit<T>::widen(q[r2][s], w);
+          Unit<T>::widen(q[r2][s2], w);
 #pragma unroll
-          for (int e = 0; e < N; ++e) acc = fmaf(w[e], ar[s][e], acc);
+          for (int e = 0; e < N; ++e) acc = fmaf(w[e], ar[s2][e], acc);
         }
         acc = wave_sum(acc);
-        if (lane == 0 && rr + r2 < RB) prow[rr + r2] = acc;
+        if (lane == 0) prow[rr + r2] = acc;
+      }
+    };
+    for (int rr = 0; rr < RB; rr += 2 * R) {
+      reduce_rows(qa, rr);
+      if (rr + 2 * R < RB) load_rows(qa, rr + 2 * R);
+      if (rr + R < RB) {
+        reduce_rows(qb, rr + R);
+        if (rr + 3 * R < RB) load_rows(qb, rr + 3 * R);
       }
     }
   }
   __syncthreads();
-  for (int row = tid; row < RB; row += 256) {
+  bool any_miss = false;
+  if (PASS == 0)
+    for (int q = 0; q < a.k; ++q) any_miss |= (a.rec->tok[t].slot[q] < 0);
+  for (int row = tid; row < RB; row += 64 * NW) {
     const int h = hb + row;
     if (h >= H) break;
     float sum = 0.f;
@@ -1026,12 +1093,10 @@ __global__ __launch_bounds__(256) void add_partial_kernel(float4* __restrict__ y
   }
 }
 
-__global__ void zero_u32_kernel(unsigned int* p) { *p = 0u; }
-
 }  // namespace
 
 template <typename T, int PASS>
-static void launch_up_t(const FfnArgs& a, hipStream_t s) {
+static void launch_up_t(const FfnArgs& a, const RouteArgs& ra, hipStream_t s) {
   if (a.grouped && a.mfma_down && a.mfma_up) {
     static bool lds_opted_in[2] = {false, false};
     if (!lds_opted_in[PASS]) {
@@ -1054,22 +1119,30 @@ static void launch_up_t(const FfnArgs& a, hipStream_t s) {
     }
   }
   const int grid = a.B * (a.k * a.tilesR + a.ns * a.tilesS);
+  if (PASS == 0 && a.fused_select) {
+    switch (a.up_upl) {
+      case 1: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 1, 0, true>), dim3(grid), dim3(256), 0, s, a, ra); return;
+      case 2: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 2, 0, true>), dim3(grid), dim3(256), 0, s, a, ra); return;
+      case 4: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 4, 0, true>), dim3(grid), dim3(256), 0, s, a, ra); return;
+      default: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 8, 0, true>), dim3(grid), dim3(256), 0, s, a, ra); return;
+    }
+  }
   switch (a.up_upl) {
-    case 1: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 1, PASS>), dim3(grid), dim3(256), 0, s, a); return;
-    case 2: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 2, PASS>), dim3(grid), dim3(256), 0, s, a); return;
-    case 4: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 4, PASS>), dim3(grid), dim3(256), 0, s, a); return;
-    case 8: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 8, PASS>), dim3(grid), dim3(256), 0, s, a); return;
+    case 1: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 1, PASS, false>), dim3(grid), dim3(256), 0, s, a, ra); return;
+    case 2: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 2, PASS, false>), dim3(grid), dim3(256), 0, s, a, ra); return;
+    case 4: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 4, PASS, false>), dim3(grid), dim3(256), 0, s, a, ra); return;
+    case 8: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 8, PASS, false>), dim3(grid), dim3(256), 0, s, a, ra); return;
     default: break;
   }
   const size_t lds = (size_t)a.H * sizeof(float);
   hipLaunchKernelGGL((ffn_up_kernel<T, PASS>), dim3(grid), dim3(256), lds, s, a);
 }
 
-void launch_ffn_up(const FfnArgs& a, int dtype, hipStream_t s) {
+void launch_ffn_up(const FfnArgs& a, const RouteArgs& ra, int dtype, hipStream_t s) {
   if (dtype == SMOE_DTYPE_FP32) {
-    if (a.pass == 0) launch_up_t<float, 0>(a, s); else launch_up_t<float, 1>(a, s);
+    if (a.pass == 0) launch_up_t<float, 0>(a, ra, s); else launch_up_t<float, 1>(a, ra, s);
   } else {
-    if (a.pass == 0) launch_up_t<bf16_t, 0>(a, s); else launch_up_t<bf16_t, 1>(a, s);
+    if (a.pass == 0) launch_up_t<bf16_t, 0>(a, ra, s); else launch_up_t<bf16_t, 1>(a, ra, s);
   }
 }
 
@@ -1095,15 +1168,19 @@ static void launch_down_t(const FfnArgs& a, hipStream_t s) {
   const int grid = a.B * a.htiles;
   if (a.down_upl > 0) {
     const size_t lds = (size_t)(a.k * a.nsegR + a.ns * a.nsegS) * a.RB * sizeof(float);
-    switch (a.down_upl) {
-      case 2: hipLaunchKernelGGL((ffn_down_reg_kernel<T, 2, 4, PASS>), dim3(grid), dim3(256), lds, s, a); return;
-      case 4: hipLaunchKernelGGL((ffn_down_reg_kernel<T, 4, 2, PASS>), dim3(grid), dim3(256), lds, s, a); return;
-      case 6: hipLaunchKernelGGL((ffn_down_reg_kernel<T, 6, 2, PASS>), dim3(grid), dim3(256), lds, s, a); return;
-      case 8: hipLaunchKernelGGL((ffn_down_reg_kernel<T, 8, 1, PASS>), dim3(grid), dim3(256), lds, s, a); return;
-      case 10: hipLaunchKernelGGL((ffn_down_reg_kernel<T, 10, 1, PASS>), dim3(grid), dim3(256), lds, s, a); return;
-      case 12: hipLaunchKernelGGL((ffn_down_reg_kernel<T, 12, 1, PASS>), dim3(grid), dim3(256), lds, s, a); return;
-      default: break;
-    }
+#define SMOE_DOWN_CASE(U, RR)                                                                                 \
+  if (a.down_upl == U && a.down_r == RR) {                                                                    \
+    if (a.down_nw >= 8)                                                                                       \
+      hipLaunchKernelGGL((ffn_down_reg_kernel<T, U, RR, 8, PASS>), dim3(grid), dim3(512), lds, s, a);         \
+    else                                                                                                      \
+      hipLaunchKernelGGL((ffn_down_reg_kernel<T, U, RR, 4, PASS>), dim3(grid), dim3(256), lds, s, a);         \
+    return;                                                                                                   \
+  }
+    SMOE_DOWN_CASE(2, 4)
+    SMOE_DOWN_CASE(4, 2)
+    SMOE_DOWN_CASE(6, 2)
+    SMOE_DOWN_CASE(8, 1)
+#undef SMOE_DOWN_CASE
   }
   const size_t lds = (size_t)a.down_lds_floats * sizeof(float);
   if (a.R == 1) hipLaunchKernelGGL((ffn_down_kernel<T, 1, PASS>), dim3(grid), dim3(256), lds, s, a);
@@ -1130,10 +1207,6 @@ void launch_copy(void* dst, const void* src, int64_t n_bytes, hipStream_t s) {
   if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
                      static_cast<uint4*>(dst), static_cast<const uint4*>(src), n);
-}
-
-void launch_zero_u32(unsigned int* p, hipStream_t s) {
-  hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(1), 0, s, p);
 }
 
 void launch_add_partial(float* ysum, const float* part, int n, hipStream_t s) {

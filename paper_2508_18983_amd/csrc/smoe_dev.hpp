@@ -40,15 +40,7 @@ struct StepRec {
   int32_t seq;                     // host mirror only: call number, written last
 };
 
-// Per-token state between the two router launches of a batched step.
-struct RouteTmp {
-  float sc[kWave];
-  int32_t rk[kWave];
-  int32_t tk[SMOE_MAX_TOPK];
-  float thr_r;
-  int32_t pad_;
-  unsigned long long top_m;
-};
+constexpr int kMaxGateSeg = 8;   // a gate row is split into at most this many segments
 
 struct RouteArgs {
   const void* gate_w;   // [E][H] of this layer
@@ -56,17 +48,15 @@ struct RouteArgs {
   const float* sim;     // [E][E] of this layer (device)
   StepRec* rec_dev;
   StepRec* rec_host;    // device-visible address of the pinned mirror
-  RouteTmp* tmp;        // [B] scratch of the batched router
+  float* gate_part;     // [B][E][kMaxGateSeg] partial dot products of the gate GEMV, the first nseg of
+                        // each row in use (device scratch, 32-byte aligned)
   void* x_mirror;       // device-visible pinned host copy of x for the host cores, or null
   int32_t x_units;      // 16-byte units of x ([B][H] dtype) to mirror
-  int32_t split_nb;     // batch 1: blocks the gate GEMV is spread over (0 = single-block kernels)
-  float* split_part;    // [E * 8] partial dot products of the spread GEMV (device scratch)
-  unsigned int* split_count;  // blocks of the spread GEMV that have finished (zero between launches)
   int32_t B, H, E, k;
   int32_t renorm, subst_key;
-  int32_t nseg;         // segments each gate row is split into (power of two, <= 8)
+  int32_t nseg;         // segments each gate row is split into (power of two, <= kMaxGateSeg)
+  int32_t upi;          // 128-bit units of one row segment per lane (1, 2, 4 or 8)
   int32_t seq;          // call number published to the host mirror when the record is complete
-  int32_t fast_upi;     // batch-1 fast path: 128-bit units of one row segment per lane (0 = off)
   float alpha;
   uint64_t resident;                  // bit e = expert e is in the HBM cache
   int8_t slot_of[SMOE_MAX_EXPERTS];   // layer-local slot of each resident expert
@@ -95,23 +85,25 @@ struct FfnArgs {
   int32_t up_upl;                          // up: 128-bit units of x per lane held in registers, 0 = LDS path
   int32_t down_upl, RB, nsegR, nsegS;      // down register path: units per lane (0 = LDS path), rows per
                                            // block, column segments of a routed / shared row
+  int32_t down_nw, down_r;                 // ... waves per block (4 or 8), rows per register buffer
   int32_t grouped;                         // batch > 1: tasks are the record's expert groups (+ shared)
   int32_t maxg;                            // grouped: upper bound of groups = min(E, B*k)
   int32_t mfma_down;                       // grouped, bf16: down projection on the matrix cores
   int32_t mfma_up;                         // ... and the up projection too
   int32_t nsegGR, nsegGS, RBG;             // grouped down kernel: segments per routed / shared row, rows per block
   int64_t act_shared_off;                  // grouped: float offset of the shared experts' activations in act
+  int32_t fused_select;                    // batch 1, pass 0: the up kernel runs the selection itself
   int32_t slot_override[kMaxTasks];        // pass 1: global slot per task (grouped: per group), -1 = not in this pass
 };
 
-void launch_route(const RouteArgs& a, int dtype, hipStream_t s);
-void launch_ffn_up(const FfnArgs& a, int dtype, hipStream_t s);
+void launch_gate_partial(const RouteArgs& a, int dtype, hipStream_t s);
+void launch_route_select(const RouteArgs& a, hipStream_t s);
+// `ra` is read only when a.fused_select is set
+void launch_ffn_up(const FfnArgs& a, const RouteArgs& ra, int dtype, hipStream_t s);
 void launch_ffn_down(const FfnArgs& a, int dtype, hipStream_t s);
 size_t grouped_down_lds_bytes(const FfnArgs& a);
 void launch_copy(void* dst, const void* src, int64_t n_bytes, hipStream_t s);
 // ysum[i] += part[i], i < n (n a multiple of 4): adds what the host cores computed
 void launch_add_partial(float* ysum, const float* part, int n, hipStream_t s);
-// *p = 0 by a one-thread kernel (a fill that is safe to record into a graph)
-void launch_zero_u32(unsigned int* p, hipStream_t s);
 
 }  // namespace smoe

@@ -69,10 +69,9 @@ struct Scratch {
   StepRec* rec = nullptr;                // decision record
   float* act = nullptr;                  // SwiGLU activations between the up and the down kernel
   float* ysum = nullptr;                 // [B][H] fp32 sums carried from the resident to the loaded pass
-  RouteTmp* route_tmp = nullptr;         // per-token state between the two launches of a batched router
-  float* split_part = nullptr;           // partial dot products of the multi-block batch-1 router
-  unsigned int* split_count = nullptr;   // its ticket counter (zero between launches)
+  float* gate_part = nullptr;            // [B][E][kMaxGateSeg] partial dot products of the gate GEMV
 };
+constexpr int64_t kGatePartBytes = (int64_t)SMOE_MAX_BATCH * SMOE_MAX_EXPERTS * kMaxGateSeg * sizeof(float);
 
 }  // namespace
 
@@ -96,7 +95,6 @@ struct moe_handle {
   int device = 0;
   StepRec* rec_host = nullptr;           // pinned
   StepRec* rec_host_dev = nullptr;       // its device-visible address
-  int route_split = 1;                   // SMOE_ROUTE_SPLIT: 0 never, 1 for gate matrices >= 512 KiB, 2 always
   // top-score prefetch: the prediction has a decision record of its own
   StepRec* pred_dev = nullptr;
   StepRec* pred_host = nullptr;          // pinned
@@ -127,13 +125,13 @@ struct moe_handle {
   int copy_ev_next = 0, copy_hist_n = 0;
   // launch geometry
   int TF = 0, tilesR = 0, tilesS = 0, R = 0, htiles = 0, stage_all = 0, chunk = 0, down_lds = 0;
-  int up_upl = 0, down_upl = 0, RB = 0, nsegR = 1, nsegS = 1;
+  int up_upl = 0, down_upl = 0, down_nw = 4, down_r = 1, RB = 0, nsegR = 1, nsegS = 1;
   int grouped_ok = 0, nsegGR = 0, nsegGS = 0, RBG = 0;   // batch > 1: grouped kernels
   int mfma_ok = 1;                                       // SMOE_MFMA=0 keeps the vector-ALU down kernel
   int64_t act_floats = 0;
   // profiling
   int32_t seq = 0;                       // number of the last decode call
-  int route_fast = 1;                    // use the batch-1 router kernel
+  int fused_select = 1;                  // batch 1: the up kernel runs the selection (SMOE_FUSED_SELECT=0: own launch)
   long spin_limit = 4000000;             // polls of the mirror before falling back to the event
   uint32_t prof_mask = 0;                // bit i: record kind i
   ProfKind prof[SMOE_PROF_KINDS];
@@ -198,20 +196,31 @@ void plan_geometry(moe_handle* h) {
   int target = per_lane_of(c.ffn);
   if (c.n_shared) target = std::min(target, per_lane_of(c.shared_ffn));
   target = std::max(4, std::min(8, target));
+  target = std::max(1, std::min(8, env_int("SMOE_DSEG", target)));
   auto seg_plan = [&](int F, int& nseg) -> int {               // -> units per lane
-    nseg = std::max(1, std::min(8, (per_lane_of(F) + target - 1) / target));
+    nseg = std::max(1, std::min(16, (per_lane_of(F) + target - 1) / target));
     return ((F / n + nseg - 1) / nseg + kWave - 1) / kWave;
   };
   int need = seg_plan(c.ffn, h->nsegR);
   if (c.n_shared) need = std::max(need, seg_plan(c.shared_ffn, h->nsegS));
-  if (need <= 12) {
-    const int upl = need <= 2 ? 2 : (need <= 4 ? 4 : (need <= 6 ? 6 : (need <= 8 ? 8 : (need <= 10 ? 10 : 12))));
-    const int rows_at_once = upl <= 2 ? 4 : (upl <= 6 ? 2 : 1);
-    int rb = rows_at_once;
-    while (c.hidden / (rb * 2) >= 512) rb *= 2;       // >= 512 blocks per token
+  if (need <= 8) {
+    const int upl = need <= 2 ? 2 : (need <= 4 ? 4 : (need <= 6 ? 6 : 8));
+    const int rows_at_once = upl <= 2 ? 4 : (upl <= 6 ? 2 : 1);   // R of the kernel (two such buffers
+                                                                  // in flight; deeper did not help)
+    const int items = c.top_k * h->nsegR + c.n_shared * h->nsegS;
+    // waves per block: one or two items per wave
+    int nw = env_int("SMOE_DNW", items >= 8 ? 8 : 4);
+    nw = nw >= 8 ? 8 : 4;
+    // rows per block: about one block per compute unit (measured on the three large shapes:
+    // halving the rows costs 3-8 % through the repeated activation loads, doubling them leaves
+    // half of the chip idle), at least two pipeline steps
+    int rb = (c.hidden + 255) / 256;
+    rb = std::max(2 * rows_at_once, (rb + rows_at_once - 1) / rows_at_once * rows_at_once);
     rb = env_int("SMOE_RB", rb);
     rb = std::max(rows_at_once, std::min(256, rb) / rows_at_once * rows_at_once);
     h->down_upl = upl;
+    h->down_nw = nw;
+    h->down_r = rows_at_once;
     h->RB = rb;
     h->htiles = (c.hidden + rb - 1) / rb;
   }
@@ -253,9 +262,7 @@ void free_all(moe_handle* h) {
   if (h->rec_host) (void)hipHostFree(h->rec_host);
   if (h->own.act) (void)hipFree(h->own.act);
   if (h->own.ysum) (void)hipFree(h->own.ysum);
-  if (h->own.route_tmp) (void)hipFree(h->own.route_tmp);
-  if (h->own.split_part) (void)hipFree(h->own.split_part);
-  if (h->own.split_count) (void)hipFree(h->own.split_count);
+  if (h->own.gate_part) (void)hipFree(h->own.gate_part);
   delete h;
 }
 
@@ -361,43 +368,19 @@ void fill_route_args(const moe_handle* h, const Scratch& sc, int layer, int B, c
   ra.gate_w = static_cast<const char*>(h->buf.gate_w_dev) + (int64_t)layer * E * c.hidden * h->esize;
   ra.x = x;
   ra.sim = h->sim_dev + (size_t)layer * E * E;
-  ra.tmp = sc.route_tmp;
+  ra.gate_part = sc.gate_part;
   ra.B = B; ra.H = c.hidden; ra.E = E; ra.k = c.top_k;
   ra.renorm = c.renorm_topk; ra.subst_key = c.subst_key; ra.alpha = c.alpha;
-  ra.nseg = 1;
-  ra.fast_upi = 0;
+  // gate GEMV: one wave per (row, segment); split the rows until there are >= 128 waves of work
+  // or a segment is down to one unit per lane; a segment is at most 8 units per lane
   const int gate_units = c.hidden / (c.dtype == SMOE_DTYPE_FP32 ? 4 : 8);
-  if (h->route_fast) {
-    // one row segment per wave and pass: 16 waves x 4 rows; keep a segment <= 8 units per lane
-    while (ra.nseg < 8 && (E * ra.nseg * 2 <= 16 || gate_units / ra.nseg > 8 * kWave)) ra.nseg *= 2;
-    const int per_lane = ((gate_units + ra.nseg - 1) / ra.nseg + kWave - 1) / kWave;
-    ra.fast_upi = per_lane <= 1 ? 1 : (per_lane <= 2 ? 2 : (per_lane <= 4 ? 4 : (per_lane <= 8 ? 8 : 0)));
-  }
-  if (ra.fast_upi == 0) {
-    ra.nseg = 1;
-    while (ra.nseg < 8 && E * ra.nseg < 32 && c.hidden / (ra.nseg * 2) >= 512) ra.nseg *= 2;
-  }
-  ra.split_nb = 0;
-  ra.split_part = sc.split_part;
-  ra.split_count = sc.split_count;
-  const int64_t gate_bytes = (int64_t)E * c.hidden * h->esize;
-  if (B == 1 && h->route_fast && (h->route_split >= 2 || (h->route_split == 1 && gate_bytes >= 512 * 1024))) {
-    // batch 1, large gate matrix: spread the GEMV over several blocks, about one (row, segment)
-    // item per wave.  Below ~0.5 MB the fence and the ticket cost more than one compute unit
-    // loses by streaming the matrix alone (measured: 64 x 8192 bf16 24 -> 18 us, 64 x 2048 no gain).
-    int nseg = 1;
-    while (nseg < 8 && (E * nseg < 64 || gate_units / nseg > 8 * kWave) && gate_units / (nseg * 2) >= kWave)
-      nseg *= 2;
-    const int per_lane = ((gate_units + nseg - 1) / nseg + kWave - 1) / kWave;
-    if (per_lane <= 8) {
-      ra.nseg = nseg;
-      ra.fast_upi = per_lane <= 1 ? 1 : (per_lane <= 2 ? 2 : (per_lane <= 4 ? 4 : 8));
-      const int items = E * nseg;
-      int nb = std::min(16, (items + 3) / 4);
-      nb = std::max(2, (nb + 1) / 2 * 2);            // 4 * nb waves: a multiple of nseg <= 8
-      ra.split_nb = nb;
-    }
-  }
+  int nseg = 1;
+  while (nseg < kMaxGateSeg && (gate_units / nseg > 8 * kWave || E * nseg < 128) && gate_units / (nseg * 2) >= kWave)
+    nseg *= 2;
+  while (nseg < kMaxGateSeg && ((gate_units + nseg - 1) / nseg + kWave - 1) / kWave > 8) nseg *= 2;
+  const int per_lane = ((gate_units + nseg - 1) / nseg + kWave - 1) / kWave;
+  ra.nseg = nseg;
+  ra.upi = per_lane <= 1 ? 1 : (per_lane <= 2 ? 2 : (per_lane <= 4 ? 4 : 8));
   ra.resident = ls.resident;
   std::memcpy(ra.slot_of, ls.slot_of, sizeof(ra.slot_of));
   ra.x_mirror = nullptr;
@@ -497,7 +480,7 @@ void fill_ffn_args(const moe_handle* h, const Scratch& sc, int layer, int B, con
   fa.R = h->R; fa.htiles = h->htiles;
   fa.stage_all = h->stage_all; fa.chunk = h->chunk; fa.down_lds_floats = h->down_lds;
   fa.up_upl = h->up_upl; fa.down_upl = h->down_upl; fa.RB = h->RB;
-  fa.nsegR = h->nsegR; fa.nsegS = h->nsegS;
+  fa.nsegR = h->nsegR; fa.nsegS = h->nsegS; fa.down_nw = h->down_nw; fa.down_r = h->down_r;
   for (int i = 0; i < kMaxTasks; ++i) fa.slot_override[i] = -1;
   fa.grouped = (B > 1 && h->grouped_ok) ? 1 : 0;
   fa.maxg = std::min(c.n_experts, B * c.top_k);
@@ -514,10 +497,10 @@ void fill_ffn_args(const moe_handle* h, const Scratch& sc, int layer, int B, con
 
 // One up + down launch pair; *timed_up / *timed_down tell whether the profiler
 // recorded them.
-int launch_ffn_pair(moe_handle* h, const FfnArgs& fa, int kind_up, int kind_down, bool* timed_up,
-                    bool* timed_down) {
+int launch_ffn_pair(moe_handle* h, const FfnArgs& fa, const RouteArgs& ra, int kind_up, int kind_down,
+                    bool* timed_up, bool* timed_down) {
   EventPair* pu = prof_begin(h, kind_up, h->s_compute);
-  launch_ffn_up(fa, h->cfg.dtype, h->s_compute);
+  launch_ffn_up(fa, ra, h->cfg.dtype, h->s_compute);
   prof_end(pu, h->s_compute);
   EventPair* pd = prof_begin(h, kind_down, h->s_compute);
   launch_ffn_down(fa, h->cfg.dtype, h->s_compute);
@@ -722,7 +705,7 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
     HIP_TRY(hipHostMalloc(&h->rec_host, sizeof(StepRec), hipHostMallocDefault));
     std::memset(h->rec_host, 0, sizeof(StepRec));
     h->spin_limit = env_int("SMOE_SPIN_LIMIT", 4000000);
-    h->route_fast = env_int("SMOE_ROUTE_FAST", 1);
+    h->fused_select = env_int("SMOE_FUSED_SELECT", 1);
     h->mfma_ok = env_int("SMOE_MFMA", 2);   // 0: vector ALUs, 1: MFMA down only, 2: MFMA up and down
     void* dp = nullptr;
     HIP_TRY(hipHostGetDevicePointer(&dp, h->rec_host, 0));
@@ -734,10 +717,7 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
     }
     HIP_TRY(hipMalloc(&h->own.act, (size_t)h->act_floats * sizeof(float)));
     HIP_TRY(hipMalloc(&h->own.ysum, (size_t)c.max_batch * c.hidden * sizeof(float)));
-    HIP_TRY(hipMalloc(&h->own.route_tmp, (size_t)SMOE_MAX_BATCH * sizeof(RouteTmp)));
-    HIP_TRY(hipMalloc(&h->own.split_part, (size_t)SMOE_MAX_EXPERTS * 8 * sizeof(float)));
-    HIP_TRY(hipMalloc(&h->own.split_count, sizeof(unsigned int)));
-    HIP_TRY(hipMemset(h->own.split_count, 0, sizeof(unsigned int)));
+    HIP_TRY(hipMalloc(&h->own.gate_part, (size_t)kGatePartBytes));
     {
       // the same buffers inside this GPU's static array, for moe_decode_layer_static
       HIP_TRY(hipGetDevice(&h->device));
@@ -747,22 +727,17 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
       int64_t off = 0;
       auto carve = [&](int64_t bytes) { const int64_t o = off; off += (bytes + 255) / 256 * 256; return o; };
       const int64_t o_rec = carve(sizeof(StepRec));
-      const int64_t o_tmp = carve((int64_t)SMOE_MAX_BATCH * sizeof(RouteTmp));
-      const int64_t o_part = carve((int64_t)SMOE_MAX_EXPERTS * 8 * sizeof(float));
-      const int64_t o_count = carve(sizeof(unsigned int));
+      const int64_t o_part = carve(kGatePartBytes);
       const int64_t o_ysum = carve((int64_t)c.max_batch * c.hidden * sizeof(float));
       const int64_t o_act = carve(h->act_floats * (int64_t)sizeof(float));
       h->fixed_need = off;
       if (off <= (int64_t)SMOE_STATIC_SCRATCH_BYTES) {
         h->fixed.rec = reinterpret_cast<StepRec*>(base + o_rec);
-        h->fixed.route_tmp = reinterpret_cast<RouteTmp*>(base + o_tmp);
-        h->fixed.split_part = reinterpret_cast<float*>(base + o_part);
-        h->fixed.split_count = reinterpret_cast<unsigned int*>(base + o_count);
+        h->fixed.gate_part = reinterpret_cast<float*>(base + o_part);
         h->fixed.ysum = reinterpret_cast<float*>(base + o_ysum);
         h->fixed.act = reinterpret_cast<float*>(base + o_act);
       }
     }
-    h->route_split = env_int("SMOE_ROUTE_SPLIT", 1);
     if (c.prefetch_max > 0) {
       HIP_TRY(hipMalloc(&h->pred_dev, sizeof(StepRec)));
       HIP_TRY(hipHostMalloc(&h->pred_host, sizeof(StepRec), hipHostMallocDefault));
@@ -862,22 +837,25 @@ static int decode_layer_with(moe_handle_t* h, const Scratch& sc, int32_t layer, 
     ra.x_mirror = h->x_host_dev;
     ra.x_units = (int32_t)((int64_t)B * c.hidden * h->esize / 16);
   }
+  FfnArgs fa{};
+  fill_ffn_args(h, sc, layer, B, x_dev, y_dev, fa);
+  // batch 1 on the register up kernel: the selection runs in that kernel's prologue
+  fa.fused_select = (B == 1 && h->fused_select && fa.up_upl > 0 && !fa.grouped) ? 1 : 0;
   {
     EventPair* pr = prof_begin(h, SMOE_PROF_ROUTE, h->s_compute);
-    launch_route(ra, c.dtype, h->s_compute);
+    launch_gate_partial(ra, c.dtype, h->s_compute);
+    if (!fa.fused_select) launch_route_select(ra, h->s_compute);
     prof_end(pr, h->s_compute);
     timed[0] = pr != nullptr;
     HIP_TRY(hipGetLastError());
   }
-  // (no event after the router kernel: an event record costs several microseconds of
+  // (no event after the router kernels: an event record costs several microseconds of
   // stream time between the router and the FFN; the host polls the mirror instead)
 
   // ---- FFN over what is already resident (+ shared experts), enqueued before
   //      the host knows the routing result ------------------------------------
-  FfnArgs fa{};
-  fill_ffn_args(h, sc, layer, B, x_dev, y_dev, fa);
   {
-    const int rc = launch_ffn_pair(h, fa, SMOE_PROF_UP, SMOE_PROF_DOWN, &timed[1], &timed[2]);
+    const int rc = launch_ffn_pair(h, fa, ra, SMOE_PROF_UP, SMOE_PROF_DOWN, &timed[1], &timed[2]);
     if (rc != SMOE_OK) return rc;
   }
 
@@ -935,7 +913,8 @@ static int decode_layer_with(moe_handle_t* h, const Scratch& sc, int32_t layer, 
       h->pf_mask[layer] = 0;
     }
     set_second_pass_slots(h, layer, B, rec, plan, gslot, late, fa);
-    const int rc = launch_ffn_pair(h, fa, SMOE_PROF_UP_LOADED, SMOE_PROF_DOWN_LOADED, &timed[3], &timed[4]);
+    fa.fused_select = 0;
+    const int rc = launch_ffn_pair(h, fa, ra, SMOE_PROF_UP_LOADED, SMOE_PROF_DOWN_LOADED, &timed[3], &timed[4]);
     if (rc != SMOE_OK) return rc;
   }
   // ---- a prefetch waiting for its decision (for another layer) is settled now:
@@ -962,10 +941,8 @@ int moe_decode_layer_static(moe_handle_t* h, int32_t layer, int32_t batch, const
   if (layer < 0 || layer >= h->cfg.n_layers || batch < 1 || batch > h->cfg.max_batch) return SMOE_EINVAL;
   if (h->fixed_need > (int64_t)SMOE_STATIC_SCRATCH_BYTES || !h->fixed.rec) return SMOE_ETOOBIG;
   // The array is shared by every handle on this GPU and keeps the previous call's contents.
-  // The only part that must start at zero is the ticket counter of the multi-block router
-  // (cleared by a one-thread kernel: memset nodes misbehave under graph capture).
-  launch_zero_u32(h->fixed.split_count, h->s_compute);
-  HIP_TRY(hipGetLastError());
+  // Nothing in it has to start at zero: every part is written by this call's kernels (gate
+  // partial sums, decision record, activations, carry-over sums) before it is read.
   return decode_layer_with(h, h->fixed, layer, batch, x_dev, y_dev, trace);
 }
 
@@ -985,7 +962,8 @@ int moe_prefetch_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void
   ra.rec_dev = h->pred_dev;
   ra.rec_host = h->pred_host_dev;
   ra.seq = ++h->pred_seq;
-  launch_route(ra, c.dtype, h->s_compute);
+  launch_gate_partial(ra, c.dtype, h->s_compute);
+  launch_route_select(ra, h->s_compute);
   HIP_TRY(hipGetLastError());
   h->pending_layer = layer;
   h->pending_batch = batch;

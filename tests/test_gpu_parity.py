@@ -124,11 +124,12 @@ def test_error_paths_and_reset():
 
 @pytest.mark.parametrize("env", [dict(SMOE_REGPATH="0"), dict(SMOE_REGPATH="0", SMOE_R="2", SMOE_CHUNK="1024"),
                                  dict(SMOE_RB="16", SMOE_TF="64"), dict(SMOE_SPIN_LIMIT="0"),
-                                 dict(SMOE_ROUTE_FAST="0"), dict(SMOE_ROUTE_SPLIT="2")])
+                                 dict(SMOE_FUSED_SELECT="0")])
 def test_alternative_kernel_paths_and_launch_shapes(env, monkeypatch):
     """The LDS-staged kernels (fallback for very wide layers), other tile
-    shapes, the generic and the multi-block router, and the stream-drain fallback
-    of the host must give the same answers."""
+    shapes, the selection as a launch of its own instead of the up kernel's
+    prologue, and the stream-drain fallback of the host must give the same
+    answers."""
     for k, v in env.items():
         monkeypatch.setenv(k, v)
     wl = make_workload(SHAPES["c2"].with_(seed=4), n_layers=2, tokens=24)
@@ -168,7 +169,6 @@ def test_batched_decode_ragged_shapes_matrix_core_and_vector_down_kernels(env, m
 def test_batched_decode_without_expert_grouping(monkeypatch):
     """The per-(token, slot) task path stays available (SMOE_GROUPED=0)."""
     monkeypatch.setenv("SMOE_GROUPED", "0")
-    monkeypatch.setenv("SMOE_ROUTE_FAST", "0")          # and the single-launch batched router
     shp = SHAPES["c5"].with_(ffn=512, shared_ffn=1024, cache_cap=12, seed=21)
     wl = make_workload(shp, n_layers=2, tokens=12, batch=4)
     run_parity(wl, y_every=2, batch=4, session_kw=dict(n_stage=32), label="c5-b4-ungrouped")

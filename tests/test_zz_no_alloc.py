@@ -56,14 +56,14 @@ def test_static_entry_point_two_calls_second_smaller_and_long_runs():
     for name in ("c1", "c2"):
         wl = make_workload(SHAPES[name].with_(tokens=12, seed=5))
         _same(_run(wl, [1], static=False), _run(wl, [1], static=True))
-    # the multi-block router (its ticket counter lives in the array and must start at zero)
+    # the selection as a launch of its own (reads the gate partial sums from the array)
     wl = make_workload(SHAPES["c2"].with_(tokens=8, seed=6))
     import os
-    os.environ["SMOE_ROUTE_SPLIT"] = "2"
+    os.environ["SMOE_FUSED_SELECT"] = "0"
     try:
         _same(_run(wl, [1], static=False), _run(wl, [1], static=True))
     finally:
-        del os.environ["SMOE_ROUTE_SPLIT"]
+        del os.environ["SMOE_FUSED_SELECT"]
 
 
 def test_static_entry_point_against_the_oracle_and_size_limit():
