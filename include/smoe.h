@@ -206,9 +206,12 @@ typedef struct {
   int64_t bytes[SMOE_PROF_KINDS];
 } moe_profile_t;
 
-/* Create a handle: validates cfg, uploads the similarity tables, copies the
- * initial residents into the slab (on stream_copy, waited for) and zeroes
- * history and statistics.  SMOE_EINVAL for shapes outside the limits above,
+/* Create a handle for one model: the expert scheduler of Section IV works per
+ * layer and online (problem statement of Section IV-A: each layer has its own
+ * router, cache set G and history; nothing is prepared offline), so a handle is
+ * L independent layer caches over one HBM slab.  Validates cfg, uploads the
+ * similarity tables, copies the initial residents into the slab (on
+ * stream_copy, waited for) and zeroes history and statistics.  SMOE_EINVAL for shapes outside the limits above,
  * cap < k, duplicate ids in init_resident, NULL buffers or equal streams;
  * SMOE_ENOTPINNED when a block of experts_host is not pinned; SMOE_EHIP on HIP errors. */
 int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t** out);
@@ -224,8 +227,10 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
  * is computed by the host cores while the head is loaded, and the call returns
  * when they are done.  y is complete when the compute stream has drained.
  * With a trace the call also fills it (host data only).  SMOE_ESTATE when a
- * step needs more staging slots than cfg.n_stage provides (the handle then
- * needs moe_cache_reset).
+ * step needs more staging slots than cfg.n_stage provides: the step is refused
+ * before the cache state changes (history, residency and counters are those of
+ * before the call), but its kernels were already queued, so y of this call is
+ * undefined.
  * SMOE_EINVAL for a bad layer / batch or NULL x, y. */
 int moe_decode_layer(moe_handle_t* h, int32_t layer, int32_t batch,
                      const void* x_dev, void* y_dev, moe_trace_t* trace_or_null);
@@ -287,14 +292,22 @@ int moe_prefetch_last(moe_handle_t* h, moe_prefetch_info_t* out);
 int moe_cpu_assist_costs(const moe_handle_t* h, double* c_load_us, double* c_cpu_us,
                          double* cpu_busy_us, int64_t* cpu_experts);
 
-/* Counters of one layer, or of all layers summed when layer == -1.  (Takes a
- * non-const handle since a pending prefetch is settled first.) */
+/* Counters of one layer, or of all layers summed when layer == -1: the expert
+ * cache hits of Eq. 1 (`hits`: slots served from the cache after substitution;
+ * `raw_hits`: |G n E_a| before it) and what the paper's evaluation derives from
+ * them (cache ratio = hits / slots, Section VI-A), plus loads, evictions and the
+ * prefetch / CPU-assist counters.  (Takes a non-const handle since a pending
+ * prefetch is settled first.) */
 int moe_cache_stats(moe_handle_t* h, int32_t layer, moe_stats_t* out);
 
-/* Expert id held by each cache slot of `layer`: out_slots[cache_cap]. */
+/* The cache set G of `layer` (Table "Definitions"): expert id held by each
+ * cache slot, out_slots[cache_cap]. */
 int moe_cache_residency(moe_handle_t* h, int32_t layer, int32_t* out_slots);
 
-/* Drain both streams, reload the initial residents, zero history and counters. */
+/* Back to the state after moe_cache_init (the start of a new sequence: the
+ * history window of Eq. 3 and the cache contents belong to one decode stream):
+ * drains both streams, reloads the initial residents, zeroes history and
+ * counters. */
 int moe_cache_reset(moe_handle_t* h);
 
 /* Drain both streams and release everything the library owns. */
@@ -308,6 +321,19 @@ int moe_cache_destroy(moe_handle_t* h);
  * recorded since the last enable. */
 int moe_profile_enable(moe_handle_t* h, int32_t enable, int32_t max_launches);
 int moe_profile_read(moe_handle_t* h, moe_profile_t* out);
+
+/* The substitution threshold from a latency budget (Section V-C, Eq. 5: minimise
+ * the accuracy loss subject to T(alpha) <= R).  alphas / tpots: n measured pairs
+ * (host arrays; TPOT in any unit, budget in the same).  A polynomial of `degree`
+ * (0..6, n > degree) is fitted by least squares and the uniform grid of
+ * `resolution` >= 2 points over [min alpha, max alpha] is scanned from its low
+ * end; *out_alpha receives the first point whose predicted TPOT is <= budget
+ * (accuracy loss grows with alpha, so this is the minimiser), out_coef[0..degree]
+ * the coefficients, constant term first.  Host arithmetic only, no handle.
+ * SMOE_OK; SMOE_ESTATE when no grid point meets the budget (out_coef is still
+ * filled); SMOE_EINVAL for bad arguments or a singular fit. */
+int moe_select_alpha(const double* alphas, const double* tpots, int32_t n, double budget,
+                     int32_t degree, int32_t resolution, double* out_alpha, double* out_coef);
 
 /* hipError_t of the most recent failing HIP call in this thread (0 if none). */
 int moe_last_hip_error(void);

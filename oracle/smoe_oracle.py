@@ -25,6 +25,9 @@ that depend on a convention alone are "parity unpinned" by the paper:
   expert leaves the cache untouched are conventions            -- parity unpinned
 * ``split_load_cpu_minmax`` is a variant of this build (the stated objective
   solved outright), not the paper's algorithm; pinned by brute force
+* alpha from a latency budget (``select_alpha``): the rule (smallest alpha whose
+  fitted TPOT meets the budget) is the paper's and pinned by closed forms;
+  polynomial degree and search grid are conventions            -- parity unpinned
 * top-score prefetch (``prefetch_layer``): the predicted hidden state is an
   input; order of the prefetches, their cap, the shield of the predicted
   actives and the stamps of a prefetch load are conventions   -- parity unpinned
@@ -128,7 +131,7 @@ def cache_router(info: RouteInfo, resident: Set[int], batch_top: Set[int],
     be replaced by an inactive expert that is resident (or in C) and whose
     score lies in [R, S_{k+1}].  When substitutes run short, the lowest-scoring
     low-score experts are replaced first, so the ones left for loading are the
-    highest-scoring ("top |B_t|-|A_t| experts from B_t").  With no eligible
+    highest-scoring (Algorithm 1 keeps the best-scoring surplus of B_t).  With no eligible
     substitute the original expert stays and becomes a load (Section III).
 
     Ranking of the eligible substitutes: ``subst_key == 1`` takes the highest
@@ -231,26 +234,20 @@ def pick_victim_baseline(policy: int, evictable: Sequence[int], last_use: Dict[i
 # CPU-assisted task load scheduling (Section V-A, Algorithm 2)
 # --------------------------------------------------------------------------
 def split_load_cpu(n_missing: int, c_load: float, c_cpu: float):
-    """Algorithm 2: the missing experts, sorted by descending score, are handed
-    out from both ends -- the front (highest scores) to the PCIe load queue, the
-    back (lowest scores) to the CPU -- always to the side whose accumulated time
-    is smaller (the load side on equality), adding C_load resp. C_CPU per expert.
-    Returns (n_load, n_CPU): the first n_load experts of the list are loaded,
-    the last n_CPU are computed on the CPU."""
-    t_cpu = 0.0
-    t_load = 0.0
-    n_load = n_cpu = 0
-    l, r = 0, n_missing - 1
-    while l <= r:
-        if t_load <= t_cpu:
-            t_load += c_load
-            n_load += 1
-            l += 1
-        else:
-            t_cpu += c_cpu
-            n_cpu += 1
-            r -= 1
-    return n_load, n_cpu
+    """Algorithm 2, stated as the schedule it produces.  The missing experts are
+    sorted by descending score; the PCIe load queue serves the list from its
+    front (highest scores), the CPU from its back (lowest scores).  Each worker
+    takes its next expert when it has finished the previous one: the load queue
+    at times 0, C_load, 2 C_load, ..., the CPU at 0, C_CPU, 2 C_CPU, ...  The n
+    experts are handed out in the order of these times, the load queue first
+    when both are free at the same moment.  Returns (n_load, n_CPU): the first
+    n_load experts of the list are loaded, the last n_CPU are computed on the
+    CPU."""
+    LOAD, CPU = 0, 1
+    turns = [(i * c_load, LOAD) for i in range(n_missing)] + [(j * c_cpu, CPU) for j in range(n_missing)]
+    turns.sort()                              # by time; LOAD < CPU breaks ties towards loading
+    taken = [side for _, side in turns[:n_missing]]
+    return taken.count(LOAD), taken.count(CPU)
 
 
 def split_load_cpu_minmax(n_missing: int, c_load: float, c_cpu: float):
@@ -265,6 +262,32 @@ def split_load_cpu_minmax(n_missing: int, c_load: float, c_cpu: float):
         if best_t is None or t <= best_t:
             best_i, best_t = i, t
     return best_i, n_missing - best_i
+
+
+# --------------------------------------------------------------------------
+# alpha from a latency budget (Section V-C, Eq. 5)
+# --------------------------------------------------------------------------
+def select_alpha(alphas: Sequence[float], tpots: Sequence[float], budget: float, degree: int = 2,
+                 resolution: int = 2001):
+    """min_alpha A(alpha) s.t. T(alpha) <= R, solved the way Section V-C describes:
+    T is approximated by the least-squares polynomial of low degree through the
+    measured (alpha, TPOT) pairs, and a one-dimensional search over alpha returns
+    the smallest value whose predicted TPOT meets the budget R (the accuracy loss
+    A grows with alpha, so the smallest feasible alpha minimises it).  The search
+    is a scan of ``resolution`` equally spaced points over the sampled range
+    (*convention*: the paper names neither the degree nor the search grid).
+    Returns (alpha or None when no point is feasible, coefficients with the
+    constant term first)."""
+    a = np.asarray(alphas, dtype=np.float64)
+    t = np.asarray(tpots, dtype=np.float64)
+    vander = np.stack([a ** i for i in range(degree + 1)], axis=1)     # [n, degree+1]
+    coef, *_ = np.linalg.lstsq(vander, t, rcond=None)
+    lo, hi = float(a.min()), float(a.max())
+    for i in range(resolution):
+        x = lo + (hi - lo) * i / (resolution - 1)
+        if sum(coef[p] * x ** p for p in range(degree + 1)) <= budget:
+            return x, coef
+    return None, coef
 
 
 # --------------------------------------------------------------------------
@@ -500,7 +523,7 @@ class SMoEOracle:
     # -- the step ---------------------------------------------------------
     def decode_layer(self, layer: int, x: np.ndarray, compute_y: bool = True) -> StepResult:
         """x: [B, H] stored values.  Order of operations (Section V-B,
-        dependency 1: cache update and shield strictly after gating):
+        dependency 1: the cache is updated and shielded only once gating is done):
         gate -> scores -> top-k -> Algorithm 1 -> history push -> shield ->
         evictions for the loads -> expert computation -> combine."""
         x = np.atleast_2d(x)

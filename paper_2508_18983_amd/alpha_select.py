@@ -4,7 +4,8 @@ The paper minimises the accuracy loss subject to T(alpha) <= R (Eq. 5) by
 fitting a low-degree polynomial to measured (alpha, TPOT) pairs and taking,
 by a one-dimensional search, the smallest alpha whose predicted TPOT meets the
 budget (accuracy loss grows with alpha, so the smallest feasible alpha is the
-minimiser).  This module is that offline tuner; measuring TPOT needs a GPU.
+minimiser).  The arithmetic lives in the library (moe_select_alpha); this module
+measures TPOT for a list of alphas (needs a GPU) and forwards the pairs.
 
     python -m paper_2508_18983_amd.alpha_select c3 --budget-frac 0.9
 """
@@ -19,26 +20,12 @@ from typing import Optional, Sequence, Tuple
 import numpy as np
 
 
-def fit_tpot(alphas: Sequence[float], tpots: Sequence[float], degree: int = 2) -> np.ndarray:
-    """Least-squares polynomial T(alpha) of the given degree; coefficients,
-    highest power first."""
-    alphas = np.asarray(alphas, dtype=np.float64)
-    tpots = np.asarray(tpots, dtype=np.float64)
-    if alphas.ndim != 1 or alphas.shape != tpots.shape or alphas.size <= degree:
-        raise ValueError("need more (alpha, TPOT) samples than the polynomial degree")
-    return np.polyfit(alphas, tpots, degree)
-
-
 def select_alpha(alphas: Sequence[float], tpots: Sequence[float], budget: float, degree: int = 2,
                  resolution: int = 2001) -> Tuple[Optional[float], np.ndarray]:
-    """Smallest alpha in [min(alphas), max(alphas)] with fitted T(alpha) <= budget,
-    found by scanning a uniform grid from the low end; None when no grid point
-    meets the budget.  Returns (alpha, polynomial coefficients)."""
-    coef = fit_tpot(alphas, tpots, degree)
-    grid = np.linspace(min(alphas), max(alphas), resolution)
-    pred = np.polyval(coef, grid)
-    ok = np.nonzero(pred <= budget)[0]
-    return (float(grid[ok[0]]) if ok.size else None), coef
+    """Forwards to the library's moe_select_alpha (the fit and the scan are done
+    there).  Returns (alpha or None, polynomial coefficients constant term first)."""
+    from . import binding as B
+    return B.moe_select_alpha(alphas, tpots, budget, degree, resolution)
 
 
 def measure_tpot(name: str, alphas: Sequence[float], steps: int = 32, warmup: int = 16,
@@ -93,7 +80,7 @@ def main(argv) -> int:
     budget = args.budget_frac * tp[0]
     chosen, coef = select_alpha(alphas, tp, budget, args.degree)
     print(json.dumps(dict(workload=args.workload, budget_ms=budget, chosen_alpha=chosen,
-                          poly_coef_high_to_low=[float(c) for c in coef])), flush=True)
+                          poly_coef_low_to_high=[float(c) for c in coef])), flush=True)
     return 0
 
 

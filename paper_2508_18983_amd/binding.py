@@ -105,9 +105,10 @@ def load_library():
     lib.moe_calib_copy.argtypes = [P, P, C.c_int64, P]
     lib.moe_host_alloc.argtypes = [C.c_int64, C.POINTER(P)]
     lib.moe_host_free.argtypes = [P]
+    lib.moe_select_alpha.argtypes = [P, P, I, C.c_double, I, I, C.POINTER(C.c_double), P]
     for fn in ("moe_cache_init", "moe_decode_layer", "moe_decode_layer_static", "moe_prefetch_layer", "moe_prefetch_last", "moe_cpu_assist_costs", "moe_cache_stats", "moe_cache_residency",
                "moe_cache_reset", "moe_cache_destroy", "moe_profile_enable", "moe_profile_read",
-               "moe_last_hip_error", "moe_calib_copy", "moe_host_alloc", "moe_host_free"):
+               "moe_last_hip_error", "moe_calib_copy", "moe_host_alloc", "moe_host_free", "moe_select_alpha"):
         getattr(lib, fn).restype = C.c_int
     _lib = lib
     return lib
@@ -226,3 +227,19 @@ def moe_host_alloc(n_bytes: int) -> int:
 
 def moe_host_free(ptr: int) -> None:
     _check("moe_host_free", load_library().moe_host_free(ptr))
+
+
+def moe_select_alpha(alphas, tpots, budget: float, degree: int = 2, resolution: int = 2001):
+    """-> (alpha or None when no grid point meets the budget, coefficients constant term first)."""
+    a = np.ascontiguousarray(alphas, dtype=np.float64)
+    t = np.ascontiguousarray(tpots, dtype=np.float64)
+    if a.ndim != 1 or a.shape != t.shape:
+        raise ValueError("alphas and tpots must be one-dimensional and of equal length")
+    coef = np.zeros(degree + 1, np.float64)
+    out = C.c_double()
+    rc = load_library().moe_select_alpha(a.ctypes.data, t.ctypes.data, a.size, float(budget), degree,
+                                         resolution, C.byref(out), coef.ctypes.data)
+    if rc == -4:
+        return None, coef
+    _check("moe_select_alpha", rc)
+    return out.value, coef

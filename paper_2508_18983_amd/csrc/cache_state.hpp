@@ -42,16 +42,18 @@ struct StepPlan {
   int64_t raw_hits = 0, hits = 0, subs = 0;
 };
 
-// CPU-assisted task load scheduling (Section V-A, Algorithm 2): n missing experts
-// in descending score are handed out from both ends, the front to the load queue
-// and the back to the CPU, always to the side with the smaller accumulated time
-// (loading on equality).  Returns how many are loaded; the rest is computed.
+// CPU-assisted task load scheduling (Section V-A, Algorithm 2).  The n missing
+// experts of a step, in descending score, are shared out between the load queue
+// (which takes from the front of the list) and the host cores (which take from
+// the back).  Seen from the two workers: the load queue becomes free at times
+// 0, C_load, 2 C_load, ..., the host cores at 0, C_CPU, 2 C_CPU, ...; the next
+// expert always goes to the worker that is free first, the load queue when both
+// are.  Returns how many experts are loaded; the other n - n_load are computed.
 inline int split_load_cpu(int n, double c_load, double c_cpu) {
-  double t_load = 0.0, t_cpu = 0.0;
-  int n_load = 0;
-  for (int l = 0, r = n - 1; l <= r;) {
-    if (t_load <= t_cpu) { t_load += c_load; ++n_load; ++l; }
-    else { t_cpu += c_cpu; --r; }
+  int n_load = 0, n_cpu = 0;
+  while (n_load + n_cpu < n) {
+    if (n_load * c_load <= n_cpu * c_cpu) ++n_load;
+    else ++n_cpu;
   }
   return n_load;
 }
@@ -211,12 +213,47 @@ struct CacheLayer {
 
   // One step: push the scores into the history (before victims are chosen),
   // shield what the step computes, pick a victim for every distinct missing
-  // expert, update residency and counters.  Returns SMOE_OK, SMOE_ESTATE when
-  // the decision is malformed or the step needs more staging slots than exist
-  // (the state is then not usable until the next reset).
+  // expert, update residency and counters.  Returns SMOE_OK; SMOE_ESTATE when
+  // the decision is malformed or the step needs more staging slots than exist.
+  // Both are found out before anything is changed: after a refused step the
+  // layer's state is what it was before the call.
   int plan_step(const CacheParams& p, const StepDecision& d, int64_t expert_bytes, StepPlan& out,
                 double c_load = 1.0, double c_cpu = 1.0) {
     const int E = p.n_experts, k = p.top_k, B = d.B;
+    out = StepPlan{};
+    out.before = resident;
+    // ---- what the step needs, read-only -------------------------------------
+    for (int t = 0; t < B; ++t)
+      for (int j = 0; j < k; ++j) {
+        const int e = d.final_[t][j];
+        const int e0 = d.topk[t][j];
+        if (e < 0 || e >= E || e0 < 0 || e0 >= E) return SMOE_ESTATE;
+        out.shield |= 1ull << e;
+        out.raw_hits += (out.before >> e0) & 1ull;
+        out.subs += d.subst[t][j] != 0;
+        if ((out.before >> e) & 1ull) {
+          ++out.hits;
+        } else {
+          bool dup = false;
+          for (int i = 0; i < out.n_fetch; ++i) dup |= out.fetched[i] == e;
+          if (!dup) out.fetched[out.n_fetch++] = e;
+        }
+      }
+    int n_load = out.n_fetch;
+    if (p.cpu_assist && out.n_fetch > 0) {
+      // the distinct misses are in descending score (batch 1: slot order is rank order;
+      // batch > 1: token by token): the tail goes to the host cores, which neither
+      // load nor cache it
+      n_load = p.cpu_assist == 1 ? split_load_cpu(out.n_fetch, c_load, c_cpu)
+                                 : split_load_cpu_minmax(out.n_fetch, c_load, c_cpu);
+    }
+    {
+      // every load needs an unshielded resident to replace, or a staging slot
+      const int evictable = __builtin_popcountll(resident & ~out.shield);
+      if (n_load - evictable > p.n_stage) return SMOE_ESTATE;
+    }
+
+    // ---- from here on the state changes --------------------------------------
     {
       double* row = &hist[(size_t)hist_head * E];
       for (int e = 0; e < E; ++e) {
@@ -227,39 +264,24 @@ struct CacheLayer {
       hist_head = (hist_head + 1) % (p.evict_window + 1);
       if (hist_count < p.evict_window + 1) ++hist_count;
     }
-    out = StepPlan{};
-    out.before = resident;
-    for (int t = 0; t < B; ++t)
-      for (int j = 0; j < k; ++j) {
-        const int e = d.final_[t][j];
-        const int e0 = d.topk[t][j];
-        if (e < 0 || e >= E || e0 < 0 || e0 >= E) return SMOE_ESTATE;
-        out.shield |= 1ull << e;
-        out.raw_hits += (out.before >> e0) & 1ull;
-        out.subs += d.subst[t][j] != 0;
-        const int64_t stamp = step * 64 + (int64_t)t * k + j;
-        if ((out.before >> e) & 1ull) {
-          ++out.hits;
-        } else {
-          bool dup = false;
-          for (int i = 0; i < out.n_fetch; ++i) dup |= out.fetched[i] == e;
-          if (!dup) {
-            out.fetched[out.n_fetch++] = e;
+    {
+      uint64_t stamped = 0;                             // first appearance of a missing expert = its load
+      for (int t = 0; t < B; ++t)
+        for (int j = 0; j < k; ++j) {
+          const int e = d.final_[t][j];
+          const int64_t stamp = step * 64 + (int64_t)t * k + j;
+          if (!((out.before >> e) & 1ull) && !((stamped >> e) & 1ull)) {
+            stamped |= 1ull << e;
             load_stamp[e] = stamp;
             use_count[e] = 0;
           }
+          last_use[e] = stamp;
+          ++use_count[e];
         }
-        last_use[e] = stamp;
-        ++use_count[e];
-      }
+    }
     ++step;
 
-    if (p.cpu_assist && out.n_fetch > 0) {
-      // the distinct misses are in descending score (batch 1: slot order is rank order;
-      // batch > 1: token by token): the tail goes to the host cores, which neither
-      // load nor cache it
-      const int n_load = p.cpu_assist == 1 ? split_load_cpu(out.n_fetch, c_load, c_cpu)
-                                           : split_load_cpu_minmax(out.n_fetch, c_load, c_cpu);
+    if (n_load < out.n_fetch) {
       for (int i = n_load; i < out.n_fetch; ++i) out.on_cpu[out.n_cpu++] = out.fetched[i];
       out.n_fetch = n_load;
       st.cpu_computed += out.n_cpu;
@@ -286,8 +308,7 @@ struct CacheLayer {
           out.slot[i] = replace(victim, m);
           ++out.n_evict;
         } else {
-          if (out.n_staged >= p.n_stage) return SMOE_ESTATE;   // out of transient slots
-          out.slot[i] = -(1 + out.n_staged++);
+          out.slot[i] = -(1 + out.n_staged++);          // (checked above: a staging slot is left)
         }
       }
     }

@@ -8,6 +8,7 @@
 
 #include "cache_state.hpp"
 #include "cpu_expert.hpp"
+#include "alpha_select.hpp"
 
 using namespace smoe;
 
@@ -127,5 +128,11 @@ void smoe_hl_residency(const hl_handle* h, int layer, int32_t* out_slots) {
 }
 
 void smoe_hl_stats(const hl_handle* h, int layer, moe_stats_t* out) { *out = h->layers[layer].st; }
+
+// alpha from a latency budget (Section V-C): 0 found, 1 no feasible alpha, -1 bad arguments
+int smoe_hl_select_alpha(const double* alphas, const double* tpots, int n, double budget, int degree,
+                         int resolution, double* out_alpha, double* out_coef) {
+  return select_alpha(alphas, tpots, n, budget, degree, resolution, out_alpha, out_coef);
+}
 
 }  // extern "C"

@@ -15,6 +15,7 @@
 #include "smoe_dev.hpp"
 #include "cache_state.hpp"
 #include "cpu_expert.hpp"
+#include "alpha_select.hpp"
 
 #include <chrono>
 #include <thread>
@@ -114,7 +115,7 @@ struct moe_handle {
   float* ycpu_host_dev = nullptr;
   std::vector<float> x_f32;              // [B][H] widened hidden states
   double c_load_us = 0.0, c_cpu_us = 0.0;
-  static constexpr int kCostWindow = 8;  // "past p instances" of both costs
+  static constexpr int kCostWindow = 8;  // both costs are means over this many recent samples
   double cpu_busy_us = 0.0;              // wall time spent in the host FFN so far
   int64_t cpu_experts = 0;
   double cpu_hist[kCostWindow] = {0};
@@ -1077,6 +1078,13 @@ int moe_profile_read(moe_handle_t* h, moe_profile_t* out) {
     out->bytes[kind] = h->prof[kind].bytes;
   }
   return SMOE_OK;
+}
+
+int moe_select_alpha(const double* alphas, const double* tpots, int32_t n, double budget, int32_t degree,
+                     int32_t resolution, double* out_alpha, double* out_coef) {
+  const int rc = smoe::select_alpha(alphas, tpots, n, budget, degree, resolution, out_alpha, out_coef);
+  if (rc < 0) return SMOE_EINVAL;
+  return rc == 0 ? SMOE_OK : SMOE_ESTATE;
 }
 
 int moe_host_alloc(int64_t n_bytes, void** out) {

@@ -7,9 +7,22 @@ from oracle import smoe_oracle as O
 from smoe_inputs import as_numpy
 from paper_2508_18983_amd.session import session_from_workload
 
-TOL = {"fp32": 1e-5, "bf16": 2e-2}      # relative, on ||.||_2 and on max|.|
+TOL = {"fp32": 1e-5, "bf16": 2e-2}      # relative, on ||.||_2 and on max|.| (the stated bar)
+# Second, tighter bound for bf16: y is accumulated in fp32 and rounded once, so its error is one
+# bf16 rounding of the result (2^-9 relative per element: ~1.7e-3 in the L2 norm, up to ~3.9e-3 on
+# the largest element) plus fp32 accumulation noise.  A wrong, stale or dropped low-weight slot
+# (w ~ 0.05 next to shared experts of weight 1 moves y by ~2 %) stays inside 2e-2 but not inside
+# these, which are 2-2.5x the rounding floor.
+TIGHT_BF16 = {"l2": 4e-3, "mx": 8e-3}
 ROUTE_MARGIN = 5e-4                     # log-space slack every routing comparison must have
 EVICT_MARGIN = 2e-5                     # relative slack of every eviction arg-min
+
+
+def within_tolerance(dtype, l2, mx):
+    ok = l2 <= TOL[dtype] and mx <= TOL[dtype]
+    if dtype == "bf16":
+        ok = ok and l2 <= TIGHT_BF16["l2"] and mx <= TIGHT_BF16["mx"]
+    return ok
 
 
 def rel_errors(y, ref):
@@ -21,9 +34,10 @@ def rel_errors(y, ref):
 
 
 def run_parity(wl, *, y_every=1, tokens=None, session_kw=None, oracle_kw=None, batch=None,
-               check_margins=True, label="", prefetch_max=0):
+               check_margins=True, label="", prefetch_max=0, y_tokens=None):
     """Decisions, counters and residency must match exactly on every call; y is
-    compared on every ``y_every``-th (token, layer).  Returns summary dict.
+    compared on every ``y_every``-th (token, layer), or -- with ``y_tokens`` --
+    on every layer of those tokens (whole tokens).  Returns summary dict.
 
     With ``prefetch_max > 0`` every call is preceded by a top-score prefetch for
     the layer that runs next (from ``wl.x_pred``), on both sides; what it wanted,
@@ -36,7 +50,6 @@ def run_parity(wl, *, y_every=1, tokens=None, session_kw=None, oracle_kw=None, b
     if prefetch_max:
         session_kw["prefetch_max"] = prefetch_max
     orc = O.oracle_from_workload(wl, **oracle_kw)
-    tol = TOL[s.dtype]
     worst = dict(l2=0.0, mx=0.0, route_margin=np.inf, evict_margin=np.inf)
     n_y = 0
     with session_from_workload(wl, max_batch=B, **session_kw) as ses:
@@ -57,7 +70,7 @@ def run_parity(wl, *, y_every=1, tokens=None, session_kw=None, oracle_kw=None, b
                     worst["route_margin"] = min(worst["route_margin"], pf.route_margin)
                     worst["evict_margin"] = min(worst["evict_margin"], pf.evict_margin)
                 ses.decode(l, x_dev[t, l], y_dev[t, l], tr)
-                want_y = (call % y_every) == 0
+                want_y = (call % y_every) == 0 if y_tokens is None else t in y_tokens
                 res = orc.decode_layer(l, as_numpy(wl.x[t, l]), compute_y=want_y)
                 call += 1
                 ctx = f"{label} token {t} layer {l}"
@@ -89,7 +102,7 @@ def run_parity(wl, *, y_every=1, tokens=None, session_kw=None, oracle_kw=None, b
         y_host = y_dev.to(torch.float64).cpu().numpy()
         for t, l, ref in pending:
             l2, mx = rel_errors(y_host[t, l], ref)
-            assert l2 <= tol and mx <= tol, f"{label} y token {t} layer {l}: l2 {l2:.3e} max {mx:.3e}"
+            assert within_tolerance(s.dtype, l2, mx), f"{label} y token {t} layer {l}: l2 {l2:.3e} max {mx:.3e}"
             worst["l2"] = max(worst["l2"], l2)
             worst["mx"] = max(worst["mx"], mx)
             n_y += 1

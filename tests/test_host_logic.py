@@ -175,3 +175,42 @@ def test_scheduler_rejects_bad_arguments_and_malformed_decisions(shim):
     assert shim.smoe_hl_step(h, 3, 1, topk.ctypes.data, topk.ctypes.data, sub.ctypes.data, sc.ctypes.data,
                              o.ctypes.data, o.ctypes.data, o.ctypes.data, o.ctypes.data, o.ctypes.data) == -1
     shim.smoe_hl_destroy(h)
+
+
+def test_refused_step_leaves_the_layer_as_it_was(shim):
+    """A step that needs more staging slots than exist is refused before anything
+    changes: counters, residency, history and stamps are those of a scheduler
+    that never saw it, so the following steps still match the oracle."""
+    E, k, cap = 8, 2, 2
+    h = shim.smoe_hl_create(1, E, k, cap, 3, 1, 1, 100, None, 0.0, 0, 0, 1.0, 1.0)     # LRU, one staging slot
+    twin = shim.smoe_hl_create(1, E, k, cap, 3, 1, 1, 100, None, 0.0, 0, 0, 1.0, 1.0)
+    o = [np.zeros(8, np.int32) for _ in range(5)]
+    res = np.zeros(cap, np.int32)
+
+    def step(hh, topk_rows):
+        B = len(topk_rows)
+        topk = np.array(topk_rows, np.int32)
+        sub = np.zeros_like(topk)
+        sc = np.full((B, E), 0.05, np.float32)
+        for t, row in enumerate(topk_rows):
+            sc[t, row] = [0.4, 0.3]
+        return shim.smoe_hl_step(hh, 0, B, topk.ctypes.data, topk.ctypes.data, sub.ctypes.data, sc.ctypes.data,
+                                 *[a.ctypes.data for a in o])
+
+    def state(hh):
+        st = Stats()
+        shim.smoe_hl_stats(hh, 0, C.byref(st))
+        shim.smoe_hl_residency(hh, 0, res.ctypes.data)
+        return {n: getattr(st, n) for n, _ in Stats._fields_}, res.tolist()
+
+    for hh in (h, twin):
+        assert step(hh, [[0, 2]]) == 1                       # one load, evicts expert 1
+    before = state(h)
+    # two tokens, four distinct experts, three of them missing: both residents shielded, 3 loads > 1 slot
+    assert step(h, [[0, 3], [4, 5]]) == -4
+    assert state(h) == before
+    for rows in ([[2, 6]], [[0, 6]], [[7, 2]], [[1, 0]]):
+        assert step(h, rows) == step(twin, rows)
+        assert state(h) == state(twin)
+    shim.smoe_hl_destroy(h)
+    shim.smoe_hl_destroy(twin)

@@ -625,6 +625,29 @@ def test_algorithm2_hand_worked_cases():
     assert O.split_load_cpu(6, 1.0, 3.0) == (4, 2)
 
 
+def test_algorithm2_split_is_the_one_both_workers_would_accept():
+    """Property that singles out Algorithm 2's split among all n+1 candidates
+    without replaying it: the last expert the load queue took, it took while it
+    was not behind the CPU -- (n_load - 1) C_load <= n_CPU C_CPU -- and the last
+    expert the CPU took, it took while the load queue was strictly behind --
+    (n_CPU - 1) C_CPU < n_load C_load.  Exactly one split satisfies both."""
+    rng = np.random.default_rng(11)
+    for trial in range(400):
+        n = int(rng.integers(1, 17))
+        c_load = float(rng.choice([0.5, 1.0, 2.0, 3.0, 6.25])) * float(rng.choice([1.0, 1.0, 0.37]))
+        c_cpu = float(rng.choice([0.5, 1.0, 1.75, 2.0, 9.0]))
+        ok = []
+        for a in range(n + 1):
+            b = n - a
+            load_fine = a == 0 or (a - 1) * c_load <= b * c_cpu
+            cpu_fine = b == 0 or (b - 1) * c_cpu < a * c_load
+            if load_fine and cpu_fine:
+                ok.append((a, b))
+        assert len(ok) == 1, (n, c_load, c_cpu, ok)
+        assert O.split_load_cpu(n, c_load, c_cpu) == ok[0]
+    assert O.split_load_cpu(0, 1.0, 1.0) == (0, 0)
+
+
 def test_algorithm2_balances_both_sides_and_is_near_the_best_split():
     """Section V-A: the goal is min max(n_load C_load, n_CPU C_CPU).  The
     two-pointer walk keeps the two sides within one item of each other and ends

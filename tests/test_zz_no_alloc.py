@@ -71,7 +71,7 @@ def test_static_entry_point_against_the_oracle_and_size_limit():
     from oracle import smoe_oracle as O
     from paper_2508_18983_amd.session import session_from_workload
     from smoe_inputs import as_numpy
-    from tests.parity import TOL, rel_errors
+    from tests.parity import within_tolerance, rel_errors
     wl = make_workload(SHAPES["c2"].with_(tokens=10, seed=2))
     s = wl.shape
     orc = O.oracle_from_workload(wl)
@@ -87,7 +87,7 @@ def test_static_entry_point_against_the_oracle_and_size_limit():
                 assert tr.fetched[:tr.n_fetched].tolist() == res.fetched
                 ses.sync()
                 l2, mx = rel_errors(y[t, l].double().cpu().numpy(), res.y)
-                assert l2 <= TOL["bf16"] and mx <= TOL["bf16"]
+                assert within_tolerance("bf16", l2, mx)
         assert ses.stats() == orc.stats().as_dict()
     # a configuration whose activations alone exceed the 8 MiB array is refused, not truncated
     big = SHAPES["c1"].with_(dtype="bf16", hidden=64, ffn=8, n_experts=4, top_k=2, cache_cap=2,
