@@ -17,7 +17,9 @@
 #include <thread>
 #include <vector>
 
-#if defined(__x86_64__) && defined(__GNUC__) && !defined(__clang__)
+// (SMOE_NO_CLONES: a single baseline version.  ThreadSanitizer builds need it: the clones are
+// dispatched through IFUNC resolvers, which run before that sanitizer's runtime is up.)
+#if defined(__x86_64__) && defined(__GNUC__) && !defined(__clang__) && !defined(SMOE_NO_CLONES)
 #define SMOE_CLONES __attribute__((target_clones("avx512f", "avx2,fma", "default")))
 #else
 #define SMOE_CLONES
