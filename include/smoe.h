@@ -102,8 +102,8 @@ typedef struct {
   int32_t n_stage;       /* transient slots after the L*cap cache slots, used when a
                             missing expert finds no evictable resident (batch > 1)   */
   int32_t evict_policy;  /* SMOE_EVICT_*: which unshielded resident a load replaces   */
-  int32_t prefetch_max;  /* experts one moe_prefetch_layer call may load (0: prefetch
-                            is off and that call is refused)                          */
+  int32_t prefetch_max;  /* prefetched experts a layer may hold at a time (= spare slots
+                            per layer; 0: prefetch is off and the call is refused), < 64 */
   int32_t cpu_assist;    /* 1: CPU-assisted task load scheduling (Section V-A): the
                             missing experts of a step are split by Algorithm 2 between
                             the load queue (highest scores, cached) and the host cores
@@ -132,9 +132,11 @@ typedef struct {
   const void*    shared_dev;      /* device  [L][n_shared]{W1[Fs][H], W3[Fs][H], W2[H][Fs]}
                                      or NULL when n_shared == 0                               */
   const float*   sim_host;        /* host    [L][E][E] fp32 similarity table, copied at init  */
-  void*          cache_slab_dev;  /* device  (L*cache_cap + n_stage) slots of
-                                     3*H*F*sizeof(dtype) bytes; slot l*cap+s belongs to
-                                     layer l; 256-byte aligned; contents overwritten          */
+  void*          cache_slab_dev;  /* device  (L*(cache_cap + prefetch_max) + n_stage) slots of
+                                     3*H*F*sizeof(dtype) bytes: layer l owns the slots from
+                                     l*(cache_cap + prefetch_max) on (its cache plus the spare
+                                     slots prefetched experts are loaded into), the staging
+                                     slots follow; 256-byte aligned; contents overwritten      */
   const int32_t* init_resident;   /* host    [L][cache_cap] distinct expert ids, or NULL for
                                      experts 0..cap-1 in every layer                          */
   void*          stream_compute;  /* hipStream_t all kernels run on                           */
@@ -152,10 +154,21 @@ typedef struct {
   int32_t* fetched;      /* [B*k]   distinct experts loaded by this call, in load order,
                                     -1 padded                                             */
   int32_t* victims;      /* [B*k]   expert evicted for each load, -1 = staged / padding   */
-  int32_t* on_cpu;       /* [B*k]   distinct missing experts computed by the host cores
-                                    (cpu_assist), in list order, -1 padded                */
+  int32_t* on_cpu;       /* [B*k]   experts computed by the host cores (cpu_assist): missing
+                                    ones and prefetched ones still in flight, in list
+                                    order, -1 padded                                      */
+  int32_t* adopted;      /* [B*k]   prefetched experts this call computed and took into the
+                                    cache, in (token, slot) order, -1 padded              */
+  int32_t* adopt_victims;/* [B*k]   expert evicted for each (-1: none evictable, computed
+                                    where it was loaded and not kept)                     */
   int32_t  n_fetched;    /* out: number of loads issued by this call                      */
   int32_t  n_on_cpu;     /* out: number of experts left to the host cores                 */
+  int32_t  n_adopted;    /* out: number of prefetched experts taken into the cache        */
+  int32_t  pad_;
+  uint64_t inflight_mask;/* out: bit e = expert e was prefetched for this call, is computed
+                                    by it, and its copy had not finished when the call was
+                                    decided (a fact of the machine: with cpu_assist it
+                                    decides whether Algorithm 2 considers the expert)     */
 } moe_trace_t;
 
 typedef struct {
@@ -180,11 +193,16 @@ typedef struct {
 typedef struct {
   int32_t layer;                                       /* -1: no prefetch so far           */
   int32_t n_wanted;                                    /* predicted top-score experts that
-                                                          were not resident                */
-  int32_t n_loaded;                                    /* how many of them were loaded     */
+                                                          were neither resident nor already
+                                                          prefetched                       */
+  int32_t n_loaded;                                    /* how many of them were put on the
+                                                          load queue (a prefix of wanted)  */
   int32_t wanted[SMOE_MAX_BATCH * SMOE_MAX_TOPK];      /* in load order                    */
-  int32_t victims[SMOE_MAX_BATCH * SMOE_MAX_TOPK];     /* expert evicted for wanted[i],
-                                                          i < n_loaded                     */
+  int32_t pad_;
+  int64_t bytes_copied;                                /* prefetch bytes handed to the copy
+                                                          stream since init / reset        */
+  int64_t bytes_withdrawn;                             /* bytes of dropped prefetches that
+                                                          were never copied                */
 } moe_prefetch_info_t;
 
 /* In-stream duration of the launches, measured with HIP events recorded on the
@@ -262,22 +280,30 @@ int moe_decode_layer_static(moe_handle_t* h, int32_t layer, int32_t batch,
 /* Top-score prefetch for a layer that has not run yet (Section IV-C).
  *   x_pred_dev  device [batch][H] dtype: the caller's prediction of the hidden
  *               state `layer` will see (read until the compute stream drains)
- * Enqueues the gate of `layer` on x_pred (router kernel, compute stream) and
- * returns at once.  The decision is taken by the next call on the handle:
- * a moe_decode_layer of ANOTHER layer first queues its own loads and then the
- * prefetch loads behind them on stream_copy (so a prefetch never delays a load
- * the running layer waits for); any other call (a decode of `layer` itself,
- * stats, residency, another prefetch, reset) settles it first.  Loaded are the
+ * Enqueues the gate of `layer` on x_pred (GEMV + selection kernels, compute
+ * stream) and returns at once.  The decision is taken by the next call on the
+ * handle: a moe_decode_layer of ANOTHER layer first queues its own loads and
+ * then takes the prefetch decision; any other call (a decode of `layer` itself,
+ * stats, residency, another prefetch, reset) takes it first.  Wanted are the
  * experts the predicted scores rank in the top-k with score >= T = (1+alpha)
- * S_{k+1} and that are not resident, in rank order (token by token), at most
- * cfg.prefetch_max; each replaces the victim the eviction policy picks among
- * the residents outside the predicted top-k; loading stops when none is left.
- * The score history is not touched.  If the copies are still running when
- * moe_decode_layer(layer) is called, the prefetched experts count as resident
- * for every decision but are computed in that call's second pass, behind the
- * copy stream; neither the router nor the resident pass waits for them.  A
- * wrong prediction costs the copy and the evicted expert, nothing else: the
- * layer loads what it needs on demand as always.
+ * S_{k+1} that are neither resident nor already prefetched for the layer, in
+ * rank order (token by token); as many of them as the layer has spare slots
+ * left go onto the library's load queue (at most cfg.prefetch_max wait per
+ * layer).
+ * The load queue (Section IV-C: the paper's queue can be cleared of mispredicted
+ * experts; Section V-B "Prefetching Experts from Layer i+1": prefetches must not
+ * delay the running layer's loads).  A prefetched expert is copied into a spare
+ * slot of its layer and does NOT enter the cache set until the layer's next
+ * moe_decode_layer: nobody is evicted for it, the score history is not touched.
+ * Its copy is fed to stream_copy in chunks, a bounded number outstanding, from
+ * inside later calls on the handle (there is no background thread), so an
+ * on-demand load never waits behind more than that.  At the layer's next decode
+ * the waiting experts count as resident for every decision (hits, substitutes).
+ * Those the step computes are finished first (the rest of their copy is handed
+ * over at once), computed in the call's second pass, and enter the cache there,
+ * each replacing a victim like any load; the others leave the queue and what
+ * was not yet handed to the copy stream is never copied.  A wrong prediction
+ * therefore costs at most the chunks already under way.
  * SMOE_EINVAL for a bad layer / batch, NULL x_pred or prefetch_max == 0. */
 int moe_prefetch_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void* x_pred_dev);
 

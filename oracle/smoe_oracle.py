@@ -29,8 +29,10 @@ that depend on a convention alone are "parity unpinned" by the paper:
   fitted TPOT meets the budget) is the paper's and pinned by closed forms;
   polynomial degree and search grid are conventions            -- parity unpinned
 * top-score prefetch (``prefetch_layer``): the predicted hidden state is an
-  input; order of the prefetches, their cap, the shield of the predicted
-  actives and the stamps of a prefetch load are conventions   -- parity unpinned
+  input (or, ``predict_state``, the partial layer output); order and cap of the
+  prefetches, and that a prefetched expert waits outside the cache set until
+  its layer confirms it (the load queue drops the others), are conventions
+                                                               -- parity unpinned
 
 Inputs are the stored fp32 / bf16 values (bf16 arrives as raw uint16); all
 arithmetic is fp64 with no intermediate rounding.
@@ -318,7 +320,8 @@ class LayerCache:
     last_use: Dict[int, int] = field(default_factory=dict)
     load_stamp: Dict[int, int] = field(default_factory=dict)
     use_count: Dict[int, int] = field(default_factory=dict)
-    prefetched: Set[int] = field(default_factory=set)   # prefetched since the layer's last step
+    landed: List[int] = field(default_factory=list)     # prefetched for the layer's next step, in load
+                                                        # order; not part of the cache set G yet
 
     @property
     def resident(self) -> Set[int]:
@@ -360,20 +363,23 @@ class StepResult:
     fetched: List[int]            # distinct missing experts that were loaded, in load order
     victims: List[int]            # evicted expert per fetch, -1 when staged
     on_cpu: List[int]             # distinct missing experts computed on the CPU (Algorithm 2)
+    adopted: List[int]            # prefetched experts this step used and took into the cache, in order
+    adopt_victims: List[int]      # expert evicted for each, -1 when nothing was evictable
+    dropped: List[int]            # prefetched experts this step did not use (removed from the load queue)
     y: Optional[np.ndarray]       # [B, H] fp64 or None
     route_margin: float
     evict_margin: float
+    y_partial: Optional[np.ndarray] = None   # [B, H] fp64: experts resident in G + shared experts only
 
 
 @dataclass
 class PrefetchResult:
     scores: np.ndarray            # [B, E] fp64 scores of the predicted hidden states
     topk: np.ndarray              # [B, k] predicted active experts
-    wanted: List[int]             # predicted top-score experts that were not resident, in load order
-    prefetched: List[int]         # the ones that were loaded
-    victims: List[int]            # expert evicted for each
+    wanted: List[int]             # predicted top-score experts that were neither resident nor already
+                                  # prefetched, in load order
+    prefetched: List[int]         # the ones that were put on the load queue (a prefix of wanted)
     route_margin: float
-    evict_margin: float
 
 
 class SMoEOracle:
@@ -455,18 +461,19 @@ class SMoEOracle:
         that has not run yet is applied to a *predicted* hidden state, the
         experts it ranks in the top-k are classified with the same threshold
         T = (1+alpha) S_{k+1}, and only the top-score ones are loaded ahead of
-        time; low-score ones are left to the substitution of Algorithm 1.  How
-        the prediction is made (partial layer output -> next layer's attention)
-        lies outside this step: ``x_pred`` [B, H] is an input.
+        time; low-score ones are left to the substitution of Algorithm 1.
+        ``x_pred`` [B, H] is the predicted state (see ``predict_state`` for the
+        one the paper's Fig. "prefetch" derives from the partial layer output).
 
-        *Conventions*: loads go in descending predicted score (batch > 1: token
-        by token, skipping repeats), at most ``max_experts`` of them; every
-        predicted active expert is shielded while victims are chosen with the
-        layer's eviction policy over its current history (an empty history
-        counts as mean 0 for everyone); when nothing is evictable the rest is
-        dropped; a prefetch load is stamped just before the layer's next step.
-        A wrong prediction is simply a resident expert nobody asked for: the
-        step itself then loads what it needs as usual."""
+        The paper's load queue can be cleared of mispredicted experts and a
+        misprediction costs nothing but the baseline behaviour.  Reading taken
+        here (*convention*): a prefetched expert is loaded into a spare slot and
+        stays OUTSIDE the cache set G until the layer's next step.  That step
+        treats it as resident (a hit, a possible substitute); if the step
+        computes it, it enters G there, replacing a victim like any load; if
+        not, it is dropped from the queue and G was never touched.  Loads go in
+        descending predicted score (batch > 1: token by token, skipping
+        repeats); a layer holds at most ``max_experts`` prefetched experts."""
         x_pred = np.atleast_2d(x_pred)
         B = x_pred.shape[0]
         k, E = self.k, self.E
@@ -477,7 +484,6 @@ class SMoEOracle:
                  for t in range(B)]
         route_margin = np.inf
         wanted: List[int] = []
-        shield: Set[int] = set()
         for info in infos:
             ls = np.log(info.scores[info.order[:min(E, k + 1)]])
             if len(ls) > 1:
@@ -485,53 +491,51 @@ class SMoEOracle:
             if info.T is not None:
                 for e in info.topk:
                     route_margin = min(route_margin, abs(float(np.log(info.scores[e] / info.T))))
-            shield |= set(info.topk)
             for e in info.topk:                       # rank order = descending score
-                if e in info.top_score and e not in G and e not in wanted:
+                if e in info.top_score and e not in G and e not in cache.landed and e not in wanted:
                     wanted.append(e)
-        if cache.history:
-            means = mean_window_scores(cache.history)
-        else:
-            means = np.zeros(E)
-        stamp = cache.step * 64 - 1
-        prefetched: List[int] = []
-        victims: List[int] = []
-        evict_margin = np.inf
-        for m in wanted[:max(0, max_experts)]:
-            evictable = [e for e in cache.slot_expert if e not in shield]
-            if not evictable:
-                break
-            if self.evict_policy == EVICT_SCORE:
-                v, gap = pick_victim(means, evictable)
-                if cache.history:
-                    evict_margin = min(evict_margin, gap)
-            else:
-                v = pick_victim_baseline(self.evict_policy, evictable, cache.last_use,
-                                         cache.load_stamp, cache.use_count)
-            cache.slot_expert[cache.slot_expert.index(v)] = m
-            cache.load_stamp[m] = cache.last_use[m] = stamp
-            cache.use_count[m] = 0
-            cache.prefetched.add(m)
-            prefetched.append(m)
-            victims.append(v)
-            st.evictions += 1
-            st.prefetches += 1
+        room = max(0, max_experts - len(cache.landed))
+        prefetched = wanted[:room]
+        cache.landed.extend(prefetched)
+        st.prefetches += len(prefetched)
         return PrefetchResult(np.stack([i.scores for i in infos]),
                               np.array([i.topk for i in infos], dtype=np.int64),
-                              wanted, prefetched, victims, float(route_margin), float(evict_margin))
+                              wanted, prefetched, float(route_margin))
+
+    def predict_state(self, x: np.ndarray, y_partial: np.ndarray) -> np.ndarray:
+        """Predicted input of the next layer from the running layer's partial
+        output (Section IV-C, Fig. "prefetch": the prediction starts from the
+        output of the experts that are already on the GPU, before the loaded
+        ones are done).  With the attention block outside this path, the next
+        MoE layer's input is modelled as the RMS-normalised residual sum
+        (*convention*, the same rule the chained test inputs use):
+        x' = (x + y_partial) / rms(x + y_partial), fp64; the caller rounds it to
+        the storage type.  x: [B, H] stored values, y_partial: [B, H] fp64."""
+        z = widen(np.atleast_2d(x)) + np.atleast_2d(y_partial)
+        return z / np.sqrt(np.mean(z * z, axis=1, keepdims=True))
 
     # -- the step ---------------------------------------------------------
-    def decode_layer(self, layer: int, x: np.ndarray, compute_y: bool = True) -> StepResult:
+    def decode_layer(self, layer: int, x: np.ndarray, compute_y: bool = True,
+                     inflight: Optional[Set[int]] = None) -> StepResult:
         """x: [B, H] stored values.  Order of operations (Section V-B,
         dependency 1: the cache is updated and shielded only once gating is done):
         gate -> scores -> top-k -> Algorithm 1 -> history push -> shield ->
-        evictions for the loads -> expert computation -> combine."""
+        evictions for the loads -> expert computation -> combine.
+
+        Experts prefetched for this layer (``prefetch_layer``) count as resident
+        for Algorithm 1 and for the hit count.  ``inflight``: the prefetched
+        experts whose copy had not finished when the step was decided -- a fact
+        of the machine, not of the method, hence an input; it only matters with
+        CPU-assisted scheduling, which may compute such an expert on the CPU
+        instead of waiting for it (Section V-B dependency 2)."""
         x = np.atleast_2d(x)
         B = x.shape[0]
         k, E = self.k, self.E
         cache = self.layers[layer]
         st = self.stats_per_layer[layer]
         G_before = cache.resident
+        landed = list(cache.landed)
+        on_gpu = G_before | set(landed)           # what Algorithm 1 may count on
 
         infos = [route(softmax_scores(gate_logits(self.gate_w[layer], x[t])), k, self.alpha)
                  for t in range(B)]
@@ -547,13 +551,13 @@ class SMoEOracle:
         results = []
         for t, info in enumerate(infos):
             extra = C if B > 1 else set()
-            r = cache_router(info, G_before, extra, self.sim[layer], self.subst_key)
+            r = cache_router(info, on_gpu, extra, self.sim[layer], self.subst_key)
             route_margin = min(route_margin, r.margin)
             results.append(r)
             if B == 1:
                 # Eq. 1 holds per token-layer at batch 1
-                served = sum(1 for e in r.final if e in G_before)
-                assert served == hit_count_eq1(G_before, info, len(r.cand))
+                served = sum(1 for e in r.final if e in on_gpu)
+                assert served == hit_count_eq1(on_gpu, info, len(r.cand))
 
         topk = np.array([info.topk for info in infos], dtype=np.int64)
         final = np.array([r.final for r in results], dtype=np.int64)
@@ -562,7 +566,7 @@ class SMoEOracle:
         weights = np.array([[info.scores[e] for e in info.topk] for info in infos])
         if self.renorm:
             weights = weights / weights.sum(axis=1, keepdims=True)
-        hit = np.array([[e in G_before for e in r.final] for r in results], dtype=bool)
+        hit = np.array([[e in on_gpu for e in r.final] for r in results], dtype=bool)
 
         # history: one entry per decode step, the batch mean of the score vectors
         cache.history.append(scores.mean(axis=0))
@@ -572,36 +576,47 @@ class SMoEOracle:
 
         shield = set(int(e) for e in final.reshape(-1))
         # prefetch accuracy: a prefetched expert counts as used when the layer's
-        # next step computes it (Section VI reports this as prediction accuracy)
-        st.prefetch_used += len(cache.prefetched & shield)
-        st.prefetch_top += len(cache.prefetched & C)
-        cache.prefetched = set()
-        fetched: List[int] = []
-        for pos, e in enumerate(final.reshape(-1)):          # (token, slot) order
+        # next step computes it (Section VI reports this as prediction accuracy);
+        # the others are dropped from the load queue and never enter the cache
+        st.prefetch_used += len(set(landed) & shield)
+        st.prefetch_top += len(set(landed) & C)
+        dropped = [e for e in landed if e not in shield]
+        cache.landed = []
+        incoming: List[int] = []                 # experts that are not in G, in (token, slot) order
+        for pos, e in enumerate(final.reshape(-1)):
             e = int(e)
             stamp = cache.step * 64 + pos
-            if e not in G_before and e not in fetched:
-                fetched.append(e)
+            if e not in G_before and e not in incoming:
+                incoming.append(e)
                 cache.load_stamp[e] = stamp
                 cache.use_count[e] = 0
             cache.last_use[e] = stamp
             cache.use_count[e] = cache.use_count.get(e, 0) + 1
         cache.step += 1
-        # CPU-assisted scheduling (Section V-A): the distinct missing experts, in
-        # descending score (batch 1: slot order is rank order; batch > 1: token by
-        # token, *convention*), are split by Algorithm 2.  The tail is computed on
-        # the CPU from the host copy of the weights: it is neither loaded nor
-        # cached, evicts nobody and needs no slot.
+        # CPU-assisted scheduling (Section V-A): the experts the step would have to wait
+        # for -- the missing ones and the prefetched ones still in flight -- in descending
+        # score (batch 1: slot order is rank order; batch > 1: token by token,
+        # *convention*), are split by Algorithm 2.  The tail is computed on the CPU from
+        # the host copy of the weights: it is neither loaded nor cached, evicts nobody
+        # and needs no slot (a prefetch in flight for such an expert is abandoned).
         on_cpu: List[int] = []
-        if self.cpu_assist and fetched:
-            split = split_load_cpu if self.cpu_assist == 1 else split_load_cpu_minmax
-            n_load, n_cpu = split(len(fetched), self.c_load, self.c_cpu)
-            fetched, on_cpu = fetched[:n_load], fetched[n_load:]
-            st.cpu_computed += n_cpu
+        if self.cpu_assist:
+            waiting = [e for e in incoming if e not in landed or (inflight is not None and e in inflight)]
+            if waiting:
+                split = split_load_cpu if self.cpu_assist == 1 else split_load_cpu_minmax
+                n_load, n_cpu = split(len(waiting), self.c_load, self.c_cpu)
+                on_cpu = waiting[n_load:]
+                st.cpu_computed += n_cpu
+        fetched: List[int] = []
         victims: List[int] = []
+        adopted: List[int] = []
+        adopt_victims: List[int] = []
         evict_margin = np.inf
-        for m in fetched:
+        for m in incoming:
+            if m in on_cpu:
+                continue
             evictable = [e for e in cache.slot_expert if e not in shield]
+            v = -1
             if evictable:
                 if self.evict_policy == EVICT_SCORE:
                     v, gap = pick_victim(means, evictable)
@@ -610,11 +625,15 @@ class SMoEOracle:
                     v = pick_victim_baseline(self.evict_policy, evictable, cache.last_use,
                                              cache.load_stamp, cache.use_count)
                 cache.slot_expert[cache.slot_expert.index(v)] = m
-                victims.append(v)
                 st.evictions += 1
+            if m in landed:
+                adopted.append(m)               # already loaded (or on its way): no fetch
+                adopt_victims.append(v)         # -1: computed where it landed, not kept
             else:
-                victims.append(-1)          # computed from a transient slot, not inserted
-                st.staged += 1
+                fetched.append(m)
+                victims.append(v)               # -1: computed from a transient slot, not inserted
+                if v < 0:
+                    st.staged += 1
         st.tokens += B
         st.slots += B * k
         st.raw_hits += sum(len(set(info.topk) & G_before) for info in infos)
@@ -624,19 +643,26 @@ class SMoEOracle:
         st.fetches += len(fetched)
         st.bytes_fetched += len(fetched) * self.expert_bytes
 
-        y = None
+        y = y_partial = None
         if compute_y:
             y = np.zeros((B, self.H))
+            y_partial = np.zeros((B, self.H))    # what the experts resident in G and the shared ones give
             for t in range(B):
                 xt = widen(x[t])
                 for j in range(k):
                     w1, w3, w2 = self._mats(layer, int(final[t, j]))
-                    y[t] += weights[t, j] * swiglu_expert(w1, w3, w2, xt)
+                    contrib = weights[t, j] * swiglu_expert(w1, w3, w2, xt)
+                    y[t] += contrib
+                    if int(final[t, j]) in G_before:
+                        y_partial[t] += contrib
                 for sidx in range(self.n_shared):
                     w1, w3, w2 = self._mats(layer, sidx, shared=True)
-                    y[t] += swiglu_expert(w1, w3, w2, xt)
-        return StepResult(scores, topk, final, substituted, hit, weights, fetched, victims, on_cpu, y,
-                          float(route_margin), float(evict_margin))
+                    contrib = swiglu_expert(w1, w3, w2, xt)
+                    y[t] += contrib
+                    y_partial[t] += contrib
+        return StepResult(scores, topk, final, substituted, hit, weights, fetched, victims, on_cpu,
+                          adopted, adopt_victims, dropped, y, float(route_margin), float(evict_margin),
+                          y_partial)
 
 
 def oracle_from_workload(wl, **override) -> SMoEOracle:

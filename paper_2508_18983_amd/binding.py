@@ -43,7 +43,9 @@ class MoeTrace(C.Structure):
     _fields_ = [("topk_idx", C.c_void_p), ("final_idx", C.c_void_p), ("substituted", C.c_void_p),
                 ("hit", C.c_void_p), ("scores", C.c_void_p), ("weights", C.c_void_p),
                 ("fetched", C.c_void_p), ("victims", C.c_void_p), ("on_cpu", C.c_void_p),
-                ("n_fetched", C.c_int32), ("n_on_cpu", C.c_int32)]
+                ("adopted", C.c_void_p), ("adopt_victims", C.c_void_p),
+                ("n_fetched", C.c_int32), ("n_on_cpu", C.c_int32), ("n_adopted", C.c_int32), ("pad_", C.c_int32),
+                ("inflight_mask", C.c_uint64)]
 
 
 class MoeStats(C.Structure):
@@ -57,12 +59,12 @@ class MoeStats(C.Structure):
 
 class MoePrefetchInfo(C.Structure):
     _fields_ = [("layer", C.c_int32), ("n_wanted", C.c_int32), ("n_loaded", C.c_int32),
-                ("wanted", C.c_int32 * 64), ("victims", C.c_int32 * 64)]
+                ("wanted", C.c_int32 * 64), ("pad_", C.c_int32),
+                ("bytes_copied", C.c_int64), ("bytes_withdrawn", C.c_int64)]
 
     def as_dict(self):
         return dict(layer=int(self.layer), wanted=[int(v) for v in self.wanted[:self.n_wanted]],
-                    loaded=[int(v) for v in self.wanted[:self.n_loaded]],
-                    victims=[int(v) for v in self.victims[:self.n_loaded]])
+                    loaded=[int(v) for v in self.wanted[:self.n_loaded]])
 
 
 class MoeProfile(C.Structure):
@@ -132,9 +134,11 @@ class Trace:
         self.fetched = np.full(batch * k, -1, np.int32)
         self.victims = np.full(batch * k, -1, np.int32)
         self.on_cpu = np.full(batch * k, -1, np.int32)
+        self.adopted = np.full(batch * k, -1, np.int32)
+        self.adopt_victims = np.full(batch * k, -1, np.int32)
         self.c = MoeTrace(*(a.ctypes.data for a in (
             self.topk_idx, self.final_idx, self.substituted, self.hit, self.scores, self.weights,
-            self.fetched, self.victims, self.on_cpu)), 0, 0)
+            self.fetched, self.victims, self.on_cpu, self.adopted, self.adopt_victims)), 0, 0, 0, 0, 0)
 
     @property
     def n_fetched(self) -> int:
@@ -143,6 +147,15 @@ class Trace:
     @property
     def n_on_cpu(self) -> int:
         return int(self.c.n_on_cpu)
+
+    @property
+    def n_adopted(self) -> int:
+        return int(self.c.n_adopted)
+
+    @property
+    def inflight(self) -> set:
+        m = int(self.c.inflight_mask)
+        return {e for e in range(64) if (m >> e) & 1}
 
 
 def moe_last_hip_error() -> int:

@@ -49,12 +49,16 @@ hl_handle* smoe_hl_create(int n_layers, int n_experts, int top_k, int cache_cap,
 
 void smoe_hl_destroy(hl_handle* h) { delete h; }
 
-// topk / final_ / subst: [B][k] int32; scores: [B][E] fp32.  Outputs (each sized B*k):
-// fetched experts, victims (-1 = staged), slots (>= 0 cache slot, < 0 staging), experts left
-// to the host cores (count in *n_cpu).  Returns the number of loads, or a negative SMOE_E* code.
+// topk / final_ / subst: [B][k] int32; scores: [B][E] fp32; inflight: bit mask of prefetched
+// experts whose copy is taken to be unfinished.  Outputs (each sized B*k): fetched experts,
+// victims (-1 = staged), slots (>= 0 physical slot, < 0 staging), experts left to the host
+// cores (count in *n_cpu), prefetched experts taken into the cache with their victims
+// (count in *n_adopted), prefetched experts dropped (count in *n_dropped).  Returns the
+// number of loads, or a negative SMOE_E* code.
 int smoe_hl_step(hl_handle* h, int layer, int B, const int32_t* topk, const int32_t* final_,
-                 const int32_t* subst, const float* scores, int32_t* fetched, int32_t* victims,
-                 int32_t* slots, int32_t* on_cpu, int32_t* n_cpu) {
+                 const int32_t* subst, const float* scores, uint64_t inflight, int32_t* fetched,
+                 int32_t* victims, int32_t* slots, int32_t* on_cpu, int32_t* n_cpu, int32_t* adopted,
+                 int32_t* adopt_victims, int32_t* n_adopted, int32_t* dropped, int32_t* n_dropped) {
   if (!h || layer < 0 || layer >= h->n_layers || B < 1 || B > SMOE_MAX_BATCH) return SMOE_EINVAL;
   StepDecision d{};
   d.B = B;
@@ -65,7 +69,7 @@ int smoe_hl_step(hl_handle* h, int layer, int B, const int32_t* topk, const int3
     d.scores[t] = scores + (size_t)t * h->p.n_experts;
   }
   StepPlan plan;
-  const int rc = h->layers[layer].plan_step(h->p, d, h->expert_bytes, plan, h->c_load, h->c_cpu);
+  const int rc = h->layers[layer].plan_step(h->p, d, h->expert_bytes, plan, h->c_load, h->c_cpu, inflight);
   if (rc != SMOE_OK) return rc;
   for (int i = 0; i < plan.n_cpu; ++i) on_cpu[i] = plan.on_cpu[i];
   *n_cpu = plan.n_cpu;
@@ -74,14 +78,39 @@ int smoe_hl_step(hl_handle* h, int layer, int B, const int32_t* topk, const int3
     victims[i] = plan.victims[i];
     slots[i] = plan.slot[i];
   }
+  for (int i = 0; i < plan.n_adopted; ++i) {
+    adopted[i] = plan.adopted[i];
+    adopt_victims[i] = plan.adopt_victims[i];
+  }
+  *n_adopted = plan.n_adopted;
+  for (int i = 0; i < plan.n_dropped; ++i) dropped[i] = plan.dropped[i];
+  *n_dropped = plan.n_dropped;
+  // every physical slot of the layer is in exactly one place: G, waiting, or spare
+  {
+    const CacheLayer& ls = h->layers[layer];
+    uint64_t seen_lo = 0, seen_hi = 0;
+    auto mark = [&](int phys) {
+      uint64_t& w = phys < 64 ? seen_lo : seen_hi;
+      const uint64_t bit = 1ull << (phys & 63);
+      if (w & bit) return false;
+      w |= bit;
+      return true;
+    };
+    bool ok = true;
+    for (int s = 0; s < h->p.cache_cap; ++s) ok &= mark(ls.phys_of_slot[s]);
+    for (int i = 0; i < ls.n_landed; ++i) ok &= mark(ls.landed_slot[i]);
+    for (int phys : ls.spare) ok &= mark(phys);
+    if (!ok || __builtin_popcountll(seen_lo) + __builtin_popcountll(seen_hi) != h->p.cache_cap + h->p.prefetch_max)
+      return SMOE_ESTATE;
+  }
   return plan.n_fetch;
 }
 
 // Top-score prefetch on predicted scores / top-k ([B][E], [B][k]).  Outputs sized B*k:
-// wanted experts, and for the loaded prefix the victims and slots.  Returns the number
-// loaded; *n_wanted gets the number of wanted experts.
+// wanted experts and the physical slots of the loaded prefix.  Returns the number put on
+// the load queue; *n_wanted gets the number of wanted experts.
 int smoe_hl_prefetch(hl_handle* h, int layer, int B, const int32_t* topk, const float* scores,
-                     int32_t* wanted, int32_t* n_wanted, int32_t* victims, int32_t* slots) {
+                     int32_t* wanted, int32_t* n_wanted, int32_t* slots) {
   if (!h || layer < 0 || layer >= h->n_layers || B < 1 || B > SMOE_MAX_BATCH) return SMOE_EINVAL;
   StepDecision d{};
   d.B = B;
@@ -92,10 +121,7 @@ int smoe_hl_prefetch(hl_handle* h, int layer, int B, const int32_t* topk, const 
   PrefetchPlan pp;
   h->layers[layer].plan_prefetch(h->p, d, pp);
   for (int i = 0; i < pp.n_wanted; ++i) wanted[i] = pp.wanted[i];
-  for (int i = 0; i < pp.n; ++i) {
-    victims[i] = pp.victims[i];
-    slots[i] = pp.slot[i];
-  }
+  for (int i = 0; i < pp.n; ++i) slots[i] = pp.slot[i];
   *n_wanted = pp.n_wanted;
   return pp.n;
 }

@@ -102,9 +102,27 @@ struct moe_handle {
   StepRec* pred_host_dev = nullptr;
   int32_t pred_seq = 0;                  // number of the last prediction launched
   int pending_layer = -1, pending_batch = 0;   // prediction launched, loads not queued yet
-  std::vector<hipEvent_t> ev_prefetch;   // [L] recorded behind a layer's prefetch copies
-  std::vector<uint8_t> pf_inflight;      // [L] 1 until that event has completed or been waited for
-  std::vector<uint64_t> pf_mask;         // [L] experts whose prefetch copy may still be in flight
+  // Load queue of the prefetcher (Section IV-C): prefetch copies are not handed to the copy
+  // stream whole.  They wait here and are fed to it in chunks, a bounded number outstanding,
+  // so that an on-demand load of the running layer never queues behind more than that, and a
+  // prefetch whose layer has run without it is withdrawn before the rest of it is copied.
+  struct PfEntry {
+    int layer = -1, expert = -1, slot = -1;   // physical slot of the layer
+    int64_t next_off = 0;                      // bytes handed to the copy stream so far
+    hipEvent_t done = nullptr;                 // recorded behind the last chunk
+    bool all_submitted = false;
+  };
+  std::vector<PfEntry> pf_entries;       // live entries (waiting for their layer's step), oldest first
+  std::vector<hipEvent_t> pf_event_pool; // spare events for entries
+  static constexpr int kMaxChunksOut = 8;
+  hipEvent_t chunk_ev[kMaxChunksOut] = {};
+  bool chunk_busy[kMaxChunksOut] = {false};
+  int chunks_out_limit = 4;              // SMOE_PF_OUTSTANDING
+  int64_t chunk_bytes = 64ll << 20;      // SMOE_PF_CHUNK_MB (smaller chunks cost more in submission
+                                         // overhead than they gain: measured 16 MB -> 64 MB +3-5 %)
+  int64_t pf_bytes_submitted = 0, pf_bytes_withdrawn = 0;
+  std::vector<int32_t> slot_guard;       // per global slot: number of the decode call whose kernels may
+                                         // still read a slot that has been given up since (-1: none)
   moe_prefetch_info_t pf_last{};
   // CPU-assisted scheduling (Section V-A): host-core FFN, the hidden states and the
   // partial outputs it exchanges with the GPU, and the two costs of Algorithm 2
@@ -227,6 +245,16 @@ void plan_geometry(moe_handle* h) {
   }
 }
 
+// Global slot numbers: layer l owns the physical slots [l * (cap + prefetch_max), ...); the
+// staging slots follow the last layer.
+inline int64_t layer_slot_base(const moe_handle* h, int layer) {
+  return (int64_t)layer * (h->cfg.cache_cap + h->cfg.prefetch_max);
+}
+inline int64_t staging_slot_base(const moe_handle* h) { return layer_slot_base(h, h->cfg.n_layers); }
+inline char* slot_ptr(const moe_handle* h, int64_t gslot) {
+  return static_cast<char*>(h->buf.cache_slab_dev) + gslot * h->expert_bytes;
+}
+
 int upload_initial(moe_handle* h) {
   const moe_cfg_t& c = h->cfg;
   for (int l = 0; l < c.n_layers; ++l) {
@@ -234,8 +262,7 @@ int upload_initial(moe_handle* h) {
     for (int s = 0; s < c.cache_cap; ++s) {
       const int e = h->init_resident[(size_t)l * c.cache_cap + s];
       const char* src = h->experts_host[l] + (int64_t)e * h->expert_bytes;
-      char* dst = static_cast<char*>(h->buf.cache_slab_dev) +
-                  ((int64_t)l * c.cache_cap + s) * h->expert_bytes;
+      char* dst = slot_ptr(h, layer_slot_base(h, l) + s);
       HIP_TRY(hipMemcpyAsync(dst, src, h->expert_bytes, hipMemcpyHostToDevice, h->s_copy));
     }
   }
@@ -248,7 +275,9 @@ void free_all(moe_handle* h) {
   for (auto& k : h->prof)
     for (auto& p : k.ev) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
   if (h->ev_copy) (void)hipEventDestroy(h->ev_copy);
-  for (hipEvent_t e : h->ev_prefetch) (void)hipEventDestroy(e);
+  for (auto& e : h->pf_entries) if (e.done) (void)hipEventDestroy(e.done);
+  for (hipEvent_t e : h->pf_event_pool) (void)hipEventDestroy(e);
+  for (hipEvent_t e : h->chunk_ev) if (e) (void)hipEventDestroy(e);
   delete h->cpu;
   for (auto& p : h->copy_ev) {
     if (p.a) (void)hipEventDestroy(p.a);
@@ -382,8 +411,12 @@ void fill_route_args(const moe_handle* h, const Scratch& sc, int layer, int B, c
   const int per_lane = ((gate_units + nseg - 1) / nseg + kWave - 1) / kWave;
   ra.nseg = nseg;
   ra.upi = per_lane <= 1 ? 1 : (per_lane <= 2 ? 2 : (per_lane <= 4 ? 4 : 8));
-  ra.resident = ls.resident;
-  std::memcpy(ra.slot_of, ls.slot_of, sizeof(ra.slot_of));
+  // experts prefetched for this layer count as resident for every decision, but the resident
+  // pass cannot use them (their copy may still be running): they have no slot here and are
+  // computed in the second pass
+  ra.resident = ls.resident | ls.landed_mask();
+  for (int e = 0; e < SMOE_MAX_EXPERTS; ++e)
+    ra.slot_of[e] = ((ls.resident >> e) & 1ull) ? (int8_t)ls.phys_of_expert(e) : (int8_t)-1;
   ra.x_mirror = nullptr;
   ra.x_units = 0;
 }
@@ -399,17 +432,112 @@ int await_record(moe_handle* h, const StepRec* mirror, int32_t want) {
   return *seq == want ? SMOE_OK : SMOE_ESTATE;
 }
 
+// ---- load queue of the prefetcher --------------------------------------------
+// Chunks of queued prefetches go to the copy stream while fewer than
+// chunks_out_limit of them are outstanding there.  Entries of `first_layer` (the
+// layer that is about to need them) go first, then the oldest entry.  Called
+// only at points where the host has just seen a record of a kernel that was
+// launched after every kernel that could still read a slot given up earlier.
+int pump_prefetch_queue(moe_handle* h, int first_layer) {
+  int out = 0;
+  for (int i = 0; i < moe_handle::kMaxChunksOut; ++i) {
+    if (!h->chunk_busy[i]) continue;
+    if (hipEventQuery(h->chunk_ev[i]) == hipSuccess) h->chunk_busy[i] = false;
+    else { (void)hipGetLastError(); ++out; }           // "not ready" is not an error here
+  }
+  while (out < h->chunks_out_limit) {
+    // (an entry whose slot was read by the kernels of the call that is still running waits)
+    auto ready = [&](const moe_handle::PfEntry& c) {
+      return !c.all_submitted && h->slot_guard[layer_slot_base(h, c.layer) + c.slot] < h->seq;
+    };
+    moe_handle::PfEntry* e = nullptr;
+    for (auto& c : h->pf_entries)
+      if (c.layer == first_layer && ready(c)) { e = &c; break; }
+    if (!e)
+      for (auto& c : h->pf_entries)
+        if (ready(c)) { e = &c; break; }
+    if (!e) break;
+    int slot_i = 0;
+    while (h->chunk_busy[slot_i]) ++slot_i;             // out < limit <= kMaxChunksOut: one is free
+    const int64_t n = std::min(h->chunk_bytes, h->expert_bytes - e->next_off);
+    const char* src = h->experts_host[e->layer] + (int64_t)e->expert * h->expert_bytes + e->next_off;
+    char* dst = slot_ptr(h, layer_slot_base(h, e->layer) + e->slot) + e->next_off;
+    EventPair* pc = prof_begin(h, SMOE_PROF_COPY, h->s_copy);
+    HIP_TRY(hipMemcpyAsync(dst, src, (size_t)n, hipMemcpyHostToDevice, h->s_copy));
+    prof_end(pc, h->s_copy);
+    if (pc) h->prof[SMOE_PROF_COPY].bytes += n;
+    e->next_off += n;
+    h->pf_bytes_submitted += n;
+    if (e->next_off >= h->expert_bytes) {
+      e->all_submitted = true;
+      HIP_TRY(hipEventRecord(e->done, h->s_copy));
+    }
+    HIP_TRY(hipEventRecord(h->chunk_ev[slot_i], h->s_copy));
+    h->chunk_busy[slot_i] = true;
+    ++out;
+  }
+  return SMOE_OK;
+}
+
+moe_handle::PfEntry* find_prefetch_entry(moe_handle* h, int layer, int expert) {
+  for (auto& e : h->pf_entries)
+    if (e.layer == layer && e.expert == expert) return &e;
+  return nullptr;
+}
+
+// Hand the rest of an entry to the copy stream at once (its layer computes the expert now).
+int finish_prefetch_entry(moe_handle* h, moe_handle::PfEntry* e) {
+  if (e->all_submitted) return SMOE_OK;
+  const int64_t n = h->expert_bytes - e->next_off;
+  const char* src = h->experts_host[e->layer] + (int64_t)e->expert * h->expert_bytes + e->next_off;
+  char* dst = slot_ptr(h, layer_slot_base(h, e->layer) + e->slot) + e->next_off;
+  EventPair* pc = prof_begin(h, SMOE_PROF_COPY, h->s_copy);
+  HIP_TRY(hipMemcpyAsync(dst, src, (size_t)n, hipMemcpyHostToDevice, h->s_copy));
+  prof_end(pc, h->s_copy);
+  if (pc) h->prof[SMOE_PROF_COPY].bytes += n;
+  e->next_off = h->expert_bytes;
+  e->all_submitted = true;
+  h->pf_bytes_submitted += n;
+  HIP_TRY(hipEventRecord(e->done, h->s_copy));
+  return SMOE_OK;
+}
+
+// Remove an entry from the queue; what has not been handed to the copy stream is never copied.
+void retire_prefetch_entry(moe_handle* h, int layer, int expert, bool withdrawn) {
+  for (size_t i = 0; i < h->pf_entries.size(); ++i) {
+    moe_handle::PfEntry& e = h->pf_entries[i];
+    if (e.layer != layer || e.expert != expert) continue;
+    if (withdrawn) h->pf_bytes_withdrawn += h->expert_bytes - e.next_off;
+    h->pf_event_pool.push_back(e.done);
+    h->pf_entries.erase(h->pf_entries.begin() + (long)i);
+    return;
+  }
+}
+
+// Prefetched experts of `layer` whose copy has not finished (queued, or on the copy stream).
+uint64_t prefetches_in_flight(moe_handle* h, int layer) {
+  uint64_t m = 0;
+  for (auto& e : h->pf_entries) {
+    if (e.layer != layer) continue;
+    bool done = false;
+    if (e.all_submitted) {
+      if (hipEventQuery(e.done) == hipSuccess) done = true;
+      else (void)hipGetLastError();
+    }
+    if (!done) m |= 1ull << e.expert;
+  }
+  return m;
+}
+
 // Take the decision of a pending prefetch (Section IV-C): read the predicted
-// scores, pick what to load and whom to evict, queue the copies on the copy
-// stream.  The prediction kernel precedes every kernel launched since the
-// prefetch call on the compute stream, so once its record is visible the only
-// kernels that can still be running belong to the current call, which works on
-// another layer's slots.
+// scores, pick what to load, put it on the load queue.  The prediction kernels
+// precede every kernel launched since the prefetch call on the compute stream,
+// so once their record is visible the only kernels that can still be running
+// belong to the current call.
 int settle_prefetch(moe_handle* h) {
   if (h->pending_layer < 0) return SMOE_OK;
   const int layer = h->pending_layer, B = h->pending_batch;
   h->pending_layer = -1;
-  const moe_cfg_t& c = h->cfg;
   {
     const int rc = await_record(h, h->pred_host, h->pred_seq);
     if (rc != SMOE_OK) return rc;
@@ -425,39 +553,21 @@ int settle_prefetch(moe_handle* h) {
   h->pf_last.layer = layer;
   h->pf_last.n_wanted = pp.n_wanted;
   h->pf_last.n_loaded = pp.n;
-  for (int i = 0; i < SMOE_MAX_BATCH * SMOE_MAX_TOPK; ++i) {
-    h->pf_last.wanted[i] = i < pp.n_wanted ? pp.wanted[i] : -1;
-    h->pf_last.victims[i] = i < pp.n ? pp.victims[i] : -1;
-  }
+  for (int i = 0; i < SMOE_MAX_BATCH * SMOE_MAX_TOPK; ++i) h->pf_last.wanted[i] = i < pp.n_wanted ? pp.wanted[i] : -1;
   for (int i = 0; i < pp.n; ++i) {
-    const char* src = h->experts_host[layer] + (int64_t)pp.experts[i] * h->expert_bytes;
-    char* dst = static_cast<char*>(h->buf.cache_slab_dev) +
-                ((int64_t)layer * c.cache_cap + pp.slot[i]) * h->expert_bytes;
-    EventPair* pc = prof_begin(h, SMOE_PROF_COPY, h->s_copy);
-    HIP_TRY(hipMemcpyAsync(dst, src, h->expert_bytes, hipMemcpyHostToDevice, h->s_copy));
-    prof_end(pc, h->s_copy);
-    if (pc) h->prof[SMOE_PROF_COPY].bytes += h->expert_bytes;
+    moe_handle::PfEntry e;
+    e.layer = layer;
+    e.expert = pp.experts[i];
+    e.slot = pp.slot[i];
+    if (h->pf_event_pool.empty()) {
+      HIP_TRY(hipEventCreateWithFlags(&e.done, hipEventDisableTiming));
+    } else {
+      e.done = h->pf_event_pool.back();
+      h->pf_event_pool.pop_back();
+    }
+    h->pf_entries.push_back(e);
   }
-  if (pp.n > 0) {
-    HIP_TRY(hipEventRecord(h->ev_prefetch[layer], h->s_copy));
-    h->pf_inflight[layer] = 1;
-    for (int i = 0; i < pp.n; ++i) h->pf_mask[layer] |= 1ull << pp.experts[i];
-  }
-  return SMOE_OK;
-}
-// Experts of `layer` whose prefetch copy may still be running.  They count as
-// resident for every decision, but the resident pass leaves them out (their slot
-// is hidden from the kernels) and the second pass computes them after the copy
-// stream has caught up, so neither the router nor the resident pass ever waits.
-uint64_t prefetched_in_flight(moe_handle* h, int layer) {
-  if (h->pf_inflight.empty() || !h->pf_inflight[layer]) return 0;
-  if (hipEventQuery(h->ev_prefetch[layer]) == hipSuccess) {
-    h->pf_inflight[layer] = 0;
-    h->pf_mask[layer] = 0;
-    return 0;
-  }
-  (void)hipGetLastError();                           // "not ready" is not an error here
-  return h->pf_mask[layer] & h->layers[layer].resident;
+  return pump_prefetch_queue(h, -1);
 }
 
 // Arguments of the FFN launches of one call (resident pass; the second pass
@@ -475,7 +585,7 @@ void fill_ffn_args(const moe_handle* h, const Scratch& sc, int layer, int B, con
   fa.expert_bytes = h->expert_bytes; fa.shared_bytes = h->shared_bytes;
   fa.B = B; fa.H = c.hidden; fa.F = c.ffn; fa.Fs = c.n_shared ? c.shared_ffn : 0;
   fa.k = c.top_k; fa.ns = c.n_shared; fa.Fmax = h->Fmax;
-  fa.slot_base = layer * c.cache_cap;
+  fa.slot_base = (int32_t)layer_slot_base(h, layer);
   fa.pass = 0;
   fa.TF = h->TF; fa.tilesR = h->tilesR; fa.tilesS = h->tilesS;
   fa.R = h->R; fa.htiles = h->htiles;
@@ -521,8 +631,8 @@ int enqueue_loads(moe_handle* h, int layer, const StepPlan& plan, int* gslot) {
   const bool time_copies = c.cpu_assist && c.load_cost_us <= 0.f;
   for (int i = 0; i < plan.n_fetch; ++i) {
     const int m = plan.fetched[i];
-    gslot[i] = plan.slot[i] >= 0 ? layer * c.cache_cap + plan.slot[i]
-                                 : c.n_layers * c.cache_cap + (-plan.slot[i] - 1);
+    gslot[i] = plan.slot[i] >= 0 ? (int)(layer_slot_base(h, layer) + plan.slot[i])
+                                 : (int)(staging_slot_base(h) + (-plan.slot[i] - 1));
     const char* src = h->experts_host[layer] + (int64_t)m * h->expert_bytes;
     char* dst = static_cast<char*>(h->buf.cache_slab_dev) + (int64_t)gslot[i] * h->expert_bytes;
     EventPair* pc = prof_begin(h, SMOE_PROF_COPY, h->s_copy);
@@ -545,55 +655,56 @@ int enqueue_loads(moe_handle* h, int layer, const StepPlan& plan, int* gslot) {
 }
 
 // Second pass: which task computes from which global slot -- the experts this
-// call has loaded, and prefetched experts (`late`) whose copy was in flight when
-// the call began.
+// call has loaded (gslot[i] for plan.fetched[i]) and the prefetched experts it
+// computes (from the physical slot they were loaded into).
 void set_second_pass_slots(const moe_handle* h, int layer, int B, const StepRec& rec, const StepPlan& plan,
-                           const int* gslot, uint64_t late, FfnArgs& fa) {
+                           const int* gslot, FfnArgs& fa) {
   const moe_cfg_t& c = h->cfg;
-  const CacheLayer& ls = h->layers[layer];
   const int k = c.top_k, nj = k + c.n_shared;
+  const int base = (int)layer_slot_base(h, layer);
   fa.pass = 1;
+  auto slot_for = [&](int e) -> int {
+    for (int i = 0; i < plan.n_fetch; ++i)
+      if (plan.fetched[i] == e) return gslot[i];
+    for (int i = 0; i < plan.n_adopted; ++i)
+      if (plan.adopted[i] == e) return base + plan.adopt_slot[i];
+    return -1;
+  };
   if (fa.grouped) {
     // group index of an expert = its rank among the distinct experts of the step (ascending id)
-    for (int i = 0; i < plan.n_fetch; ++i) {
-      const int gi = __builtin_popcountll(plan.shield & ((1ull << plan.fetched[i]) - 1ull));
-      fa.slot_override[gi] = gslot[i];
+    for (int e = 0; e < c.n_experts; ++e) {
+      if (!((plan.shield >> e) & 1ull) || ((plan.before >> e) & 1ull)) continue;
+      const int gi = __builtin_popcountll(plan.shield & ((1ull << e) - 1ull));
+      fa.slot_override[gi] = slot_for(e);
     }
-    for (int e = 0; e < c.n_experts; ++e)
-      if ((late >> e) & 1ull) {
-        const int gi = __builtin_popcountll(plan.shield & ((1ull << e) - 1ull));
-        fa.slot_override[gi] = layer * c.cache_cap + ls.slot_of[e];
-      }
     return;
   }
   for (int t = 0; t < B; ++t)
     for (int j = 0; j < k; ++j) {
       const int e = rec.tok[t].final_[j];
-      if ((late >> e) & 1ull) fa.slot_override[t * nj + j] = layer * c.cache_cap + ls.slot_of[e];
       if ((plan.before >> e) & 1ull) continue;
-      for (int i = 0; i < plan.n_fetch; ++i)
-        if (plan.fetched[i] == e) fa.slot_override[t * nj + j] = gslot[i];
+      fa.slot_override[t * nj + j] = slot_for(e);
     }
 }
 
 // Algorithmic bytes the timed launches of this call were asked to stream
 // (launches past the end of the event pool are not timed and add no bytes).
-void account_profile_bytes(moe_handle* h, int B, const StepRec& rec, const StepPlan& plan, uint64_t late,
-                           bool grouped, const bool (&timed)[5]) {
+void account_profile_bytes(moe_handle* h, int B, const StepRec& rec, const StepPlan& plan, bool grouped,
+                           const bool (&timed)[5]) {
   const moe_cfg_t& c = h->cfg;
   const int k = c.top_k;
-  int64_t late_slots = 0, cpu_slots = 0;   // slots moved to the second pass / computed by the host cores
+  // slots computed by the resident pass (expert in G), by the second pass, by the host cores
+  int64_t res_slots = 0, cpu_slots = 0;
   for (int t = 0; t < B; ++t)
     for (int j = 0; j < k; ++j) {
       const int e = rec.tok[t].final_[j];
-      late_slots += (late >> e) & 1ull;
+      res_slots += (plan.before >> e) & 1ull;
       for (int i = 0; i < plan.n_cpu; ++i) cpu_slots += plan.on_cpu[i] == e;
     }
-  int64_t miss_slots = (int64_t)B * k - plan.hits + late_slots - cpu_slots;
-  int64_t res_slots = plan.hits - late_slots, shared_times = B;
+  int64_t late_slots = (int64_t)B * k - res_slots - cpu_slots, shared_times = B;
   if (grouped) {                                      // weights are streamed once per distinct expert
-    res_slots = __builtin_popcountll(plan.shield & plan.before & ~late);
-    miss_slots = plan.n_fetch + __builtin_popcountll(late);
+    res_slots = __builtin_popcountll(plan.shield & plan.before);
+    late_slots = plan.n_fetch + plan.n_adopted;
     shared_times = 1;
   }
   const int64_t up_r = 2ll * c.hidden * c.ffn * h->esize, up_s = 2ll * c.hidden * c.shared_ffn * h->esize;
@@ -601,8 +712,8 @@ void account_profile_bytes(moe_handle* h, int B, const StepRec& rec, const StepP
   if (timed[0]) h->prof[SMOE_PROF_ROUTE].bytes += (int64_t)c.n_experts * c.hidden * h->esize;
   if (timed[1]) h->prof[SMOE_PROF_UP].bytes += resident_up;
   if (timed[2]) h->prof[SMOE_PROF_DOWN].bytes += resident_up / 2;
-  if (timed[3]) h->prof[SMOE_PROF_UP_LOADED].bytes += miss_slots * up_r;
-  if (timed[4]) h->prof[SMOE_PROF_DOWN_LOADED].bytes += miss_slots * up_r / 2;
+  if (timed[3]) h->prof[SMOE_PROF_UP_LOADED].bytes += late_slots * up_r;
+  if (timed[4]) h->prof[SMOE_PROF_DOWN_LOADED].bytes += late_slots * up_r / 2;
 }
 
 void fill_trace(const moe_handle* h, int B, const StepRec& rec, const StepPlan& plan, moe_trace_t* trace) {
@@ -613,7 +724,7 @@ void fill_trace(const moe_handle* h, int B, const StepRec& rec, const StepPlan& 
       if (trace->topk_idx) trace->topk_idx[o] = rec.tok[t].topk[j];
       if (trace->final_idx) trace->final_idx[o] = rec.tok[t].final_[j];
       if (trace->substituted) trace->substituted[o] = (uint8_t)(rec.tok[t].subst[j] != 0);
-      if (trace->hit) trace->hit[o] = (uint8_t)((plan.before >> rec.tok[t].final_[j]) & 1ull);
+      if (trace->hit) trace->hit[o] = (uint8_t)((plan.on_gpu >> rec.tok[t].final_[j]) & 1ull);
       if (trace->weights) trace->weights[o] = rec.tok[t].w[j];
     }
   if (trace->scores)
@@ -623,9 +734,12 @@ void fill_trace(const moe_handle* h, int B, const StepRec& rec, const StepPlan& 
     if (trace->fetched) trace->fetched[i] = i < plan.n_fetch ? plan.fetched[i] : -1;
     if (trace->victims) trace->victims[i] = i < plan.n_fetch ? plan.victims[i] : -1;
     if (trace->on_cpu) trace->on_cpu[i] = i < plan.n_cpu ? plan.on_cpu[i] : -1;
+    if (trace->adopted) trace->adopted[i] = i < plan.n_adopted ? plan.adopted[i] : -1;
+    if (trace->adopt_victims) trace->adopt_victims[i] = i < plan.n_adopted ? plan.adopt_victims[i] : -1;
   }
   trace->n_fetched = plan.n_fetch;
   trace->n_on_cpu = plan.n_cpu;
+  trace->n_adopted = plan.n_adopted;
 }
 
 }  // namespace
@@ -651,7 +765,7 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
   if (c.subst_key != 0 && c.subst_key != 1) return SMOE_EINVAL;
   if (c.evict_window < 0 || c.evict_window > 1024 || c.n_stage < 0) return SMOE_EINVAL;
   if (c.evict_policy < SMOE_EVICT_SCORE || c.evict_policy > SMOE_EVICT_LFU) return SMOE_EINVAL;
-  if (c.prefetch_max < 0 || c.prefetch_max > SMOE_MAX_BATCH * SMOE_MAX_TOPK) return SMOE_EINVAL;
+  if (c.prefetch_max < 0 || c.prefetch_max > SMOE_MAX_BATCH * SMOE_MAX_TOPK - 1) return SMOE_EINVAL;
   if (c.cpu_assist < 0 || c.cpu_assist > 2 || c.cpu_threads < 0 || c.cpu_threads > 256) return SMOE_EINVAL;
   if (!buf->gate_w_dev || !buf->experts_host || !buf->sim_host || !buf->cache_slab_dev) return SMOE_EINVAL;
   if (c.n_shared > 0 && !buf->shared_dev) return SMOE_EINVAL;
@@ -745,13 +859,10 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
       std::memset(h->pred_host, 0, sizeof(StepRec));
       HIP_TRY(hipHostGetDevicePointer(&dp, h->pred_host, 0));
       h->pred_host_dev = static_cast<StepRec*>(dp);
-      h->pf_inflight.assign(c.n_layers, 0);
-      h->pf_mask.assign(c.n_layers, 0);
-      for (int l = 0; l < c.n_layers; ++l) {
-        hipEvent_t e = nullptr;
-        HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
-        h->ev_prefetch.push_back(e);
-      }
+      h->slot_guard.assign((size_t)staging_slot_base(h), -1);
+      h->chunks_out_limit = std::max(1, std::min((int)moe_handle::kMaxChunksOut, env_int("SMOE_PF_OUTSTANDING", 4)));
+      h->chunk_bytes = (int64_t)std::max(1, env_int("SMOE_PF_CHUNK_MB", 64)) << 20;
+      for (auto& e : h->chunk_ev) HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
     }
     if (c.cpu_assist) {
       int nt = c.cpu_threads;
@@ -816,15 +927,18 @@ static int decode_layer_with(moe_handle_t* h, const Scratch& sc, int32_t layer, 
                              const void* x_dev, void* y_dev, moe_trace_t* trace) {
   const moe_cfg_t& c = h->cfg;
   CacheLayer& ls = h->layers[layer];
-  const int E = c.n_experts, B = batch;
+  const int B = batch;
   bool timed[5] = {false, false, false, false, false};   // route, up, down, up (2nd pass), down (2nd pass)
 
   // ---- a prefetch for this very layer has to be decided before it is routed ----
   if (h->pending_layer == layer) {
     const int rc = settle_prefetch(h);
     if (rc != SMOE_OK) return rc;
+  } else if (!h->pf_entries.empty()) {
+    // keep the link fed (slots that the previous call's kernels may still read are guarded)
+    const int rc = pump_prefetch_queue(h, layer);
+    if (rc != SMOE_OK) return rc;
   }
-  const uint64_t deferred = prefetched_in_flight(h, layer);
 
   // ---- router + expert-cache router ------------------------------------------
   RouteArgs ra{};
@@ -832,8 +946,6 @@ static int decode_layer_with(moe_handle_t* h, const Scratch& sc, int32_t layer, 
   ra.rec_dev = sc.rec;
   ra.rec_host = h->rec_host_dev;
   ra.seq = ++h->seq;
-  for (int e = 0; e < E; ++e)
-    if ((deferred >> e) & 1ull) ra.slot_of[e] = -1;
   if (c.cpu_assist) {                    // the host cores may need x: the router kernel mirrors it
     ra.x_mirror = h->x_host_dev;
     ra.x_units = (int32_t)((int64_t)B * c.hidden * h->esize / 16);
@@ -878,15 +990,35 @@ static int decode_layer_with(moe_handle_t* h, const Scratch& sc, int32_t layer, 
     dec.scores[t] = rec.tok[t].scores;
   }
   StepPlan plan;
+  // prefetched experts of this layer whose copy is not complete: with CPU-assisted scheduling
+  // Algorithm 2 may give them to the host cores instead of waiting (Section V-B, dependency 2)
+  const uint64_t inflight = (ls.n_landed > 0) ? prefetches_in_flight(h, layer) : 0;
   {
     if (c.cpu_assist) refresh_load_cost(h);
-    const int rc = ls.plan_step(h->cp, dec, h->expert_bytes, plan, h->c_load_us, h->c_cpu_us);
+    const int rc = ls.plan_step(h->cp, dec, h->expert_bytes, plan, h->c_load_us, h->c_cpu_us, inflight);
     if (rc != SMOE_OK) return rc;
   }
-  const uint64_t late = deferred & plan.shield;   // prefetched experts this step computes in the second pass
+  // prefetched experts the step does not wait for leave the load queue; what was not yet
+  // handed to the copy stream is never copied
+  for (int i = 0; i < plan.n_dropped; ++i) retire_prefetch_entry(h, layer, plan.dropped[i], true);
+  // a prefetched expert that found no victim is computed where it landed and its slot is
+  // spare again at once: nothing may be copied into it while this call's kernels run
+  for (int i = 0; i < plan.n_adopted; ++i)
+    if (plan.adopt_victims[i] < 0) h->slot_guard[layer_slot_base(h, layer) + plan.adopt_slot[i]] = h->seq;
 
-  if (plan.n_fetch > 0 || late || plan.n_cpu > 0) {
-    // ---- loads on the copy stream; the second FFN pass waits for them ---------
+  if (plan.n_fetch > 0 || plan.n_adopted > 0 || plan.n_cpu > 0) {
+    // ---- copies the second FFN pass waits for: first the rest of the prefetched experts
+    //      this step computes (requested earlier), then the on-demand loads ------------
+    bool adopted_needs_copy_event = false;
+    hipEvent_t adopted_done[SMOE_MAX_BATCH * SMOE_MAX_TOPK];
+    for (int i = 0; i < plan.n_adopted; ++i) {
+      moe_handle::PfEntry* e = find_prefetch_entry(h, layer, plan.adopted[i]);
+      if (!e) return SMOE_ESTATE;
+      if (!e->all_submitted) adopted_needs_copy_event = true;
+      const int rc = finish_prefetch_entry(h, e);
+      if (rc != SMOE_OK) return rc;
+      adopted_done[i] = e->done;
+    }
     int gslot[SMOE_MAX_BATCH * SMOE_MAX_TOPK];
     {
       const int rc = enqueue_loads(h, layer, plan, gslot);
@@ -894,9 +1026,9 @@ static int decode_layer_with(moe_handle_t* h, const Scratch& sc, int32_t layer, 
     }
     if (plan.n_cpu > 0) {
       // ---- CPU-assisted scheduling: while the copies run, the host cores compute the
-      //      experts Algorithm 2 left to them; a prefetch that is waiting goes onto the
-      //      copy stream first so that the link stays busy meanwhile.  The result is added
-      //      to the fp32 sums of the resident pass, and the second pass rounds y once.
+      //      experts Algorithm 2 left to them; a prefetch that is waiting for its decision
+      //      joins the load queue first so that the link stays busy meanwhile.  The result is
+      //      added to the fp32 sums of the resident pass, and the second pass rounds y once.
       const int rc = settle_prefetch(h);
       if (rc != SMOE_OK) return rc;
       compute_on_cpu(h, layer, B, rec, plan.on_cpu, plan.n_cpu);
@@ -904,28 +1036,32 @@ static int decode_layer_with(moe_handle_t* h, const Scratch& sc, int32_t layer, 
       HIP_TRY(hipGetLastError());
     }
     if (plan.n_fetch > 0) {
-      // (this layer's prefetch copies precede its loads on the copy stream)
+      // (recorded behind the loads, which are behind everything handed over before)
       HIP_TRY(hipStreamWaitEvent(h->s_compute, h->ev_copy, 0));
-    } else if (late) {
-      HIP_TRY(hipStreamWaitEvent(h->s_compute, h->ev_prefetch[layer], 0));
+    } else {
+      for (int i = 0; i < plan.n_adopted; ++i) HIP_TRY(hipStreamWaitEvent(h->s_compute, adopted_done[i], 0));
     }
-    if (deferred && (plan.n_fetch > 0 || late)) {   // the compute stream is now behind those copies
-      h->pf_inflight[layer] = 0;
-      h->pf_mask[layer] = 0;
-    }
-    set_second_pass_slots(h, layer, B, rec, plan, gslot, late, fa);
+    (void)adopted_needs_copy_event;
+    set_second_pass_slots(h, layer, B, rec, plan, gslot, fa);
     fa.fused_select = 0;
     const int rc = launch_ffn_pair(h, fa, ra, SMOE_PROF_UP_LOADED, SMOE_PROF_DOWN_LOADED, &timed[3], &timed[4]);
     if (rc != SMOE_OK) return rc;
+    // the adopted experts' queue entries are done with (their events stay valid: a recorded
+    // event may be re-recorded only after the wait above has been enqueued, which it has)
+    for (int i = 0; i < plan.n_adopted; ++i) retire_prefetch_entry(h, layer, plan.adopted[i], false);
   }
-  // ---- a prefetch waiting for its decision (for another layer) is settled now:
-  //      its copies queue behind the loads this layer is waiting for --------------
+  // ---- a prefetch waiting for its decision (for another layer) joins the load queue now,
+  //      and the queue is fed: behind the loads this layer is waiting for --------------
   {
-    const int rc = settle_prefetch(h);
+    int rc = settle_prefetch(h);
+    if (rc == SMOE_OK) rc = pump_prefetch_queue(h, layer + 1 < c.n_layers ? layer + 1 : 0);
     if (rc != SMOE_OK) return rc;
   }
-  if (h->prof_mask) account_profile_bytes(h, B, rec, plan, late, fa.grouped != 0, timed);
-  if (trace) fill_trace(h, B, rec, plan, trace);
+  if (h->prof_mask) account_profile_bytes(h, B, rec, plan, fa.grouped != 0, timed);
+  if (trace) {
+    fill_trace(h, B, rec, plan, trace);
+    trace->inflight_mask = inflight & plan.shield;
+  }
   return SMOE_OK;
 }
 
@@ -987,6 +1123,8 @@ int moe_prefetch_last(moe_handle_t* h, moe_prefetch_info_t* out) {
   const int rc = settle_prefetch(h);
   if (rc != SMOE_OK) return rc;
   *out = h->pf_last;
+  out->bytes_copied = h->pf_bytes_submitted;
+  out->bytes_withdrawn = h->pf_bytes_withdrawn;
   return SMOE_OK;
 }
 
@@ -1028,8 +1166,11 @@ int moe_cache_reset(moe_handle_t* h) {
   h->pending_layer = -1;                     // a prediction that was not acted on is dropped
   h->pf_last.layer = -1;
   h->pf_last.n_wanted = h->pf_last.n_loaded = 0;
-  std::fill(h->pf_inflight.begin(), h->pf_inflight.end(), (uint8_t)0);
-  std::fill(h->pf_mask.begin(), h->pf_mask.end(), (uint64_t)0);
+  for (auto& e : h->pf_entries) h->pf_event_pool.push_back(e.done);
+  h->pf_entries.clear();
+  for (bool& b : h->chunk_busy) b = false;
+  h->pf_bytes_submitted = h->pf_bytes_withdrawn = 0;
+  std::fill(h->slot_guard.begin(), h->slot_guard.end(), -1);
   return upload_initial(h);
 }
 

@@ -93,7 +93,7 @@ class DecodeSession:
         cfg.update(cfg_override)
         self.cfg = B.MoeCfg(**cfg)
         self.expert_bytes = 3 * cfg["hidden"] * cfg["ffn"] * esize
-        n_slots = cfg["n_layers"] * cfg["cache_cap"] + n_stage
+        n_slots = cfg["n_layers"] * (cfg["cache_cap"] + cfg["prefetch_max"]) + n_stage
         self.slab = torch.empty(n_slots * self.expert_bytes, dtype=torch.uint8, device=self.device)
         self._init_res = None
         if init_resident is not None:
@@ -133,6 +133,11 @@ class DecodeSession:
 
     def prefetch_last(self) -> dict:
         return B.moe_prefetch_last(self.handle).as_dict()
+
+    def prefetch_bytes(self) -> dict:
+        """Bytes of prefetch copies handed to the copy stream / withdrawn before they were copied."""
+        info = B.moe_prefetch_last(self.handle)
+        return dict(copied=int(info.bytes_copied), withdrawn=int(info.bytes_withdrawn))
 
     def sync(self) -> None:
         self.stream_compute.synchronize()

@@ -50,7 +50,7 @@ def run_parity(wl, *, y_every=1, tokens=None, session_kw=None, oracle_kw=None, b
     if prefetch_max:
         session_kw["prefetch_max"] = prefetch_max
     orc = O.oracle_from_workload(wl, **oracle_kw)
-    worst = dict(l2=0.0, mx=0.0, route_margin=np.inf, evict_margin=np.inf)
+    worst = dict(l2=0.0, mx=0.0, route_margin=np.inf, evict_margin=np.inf, n_inflight=0, n_inflight_on_cpu=0)
     n_y = 0
     with session_from_workload(wl, max_batch=B, **session_kw) as ses:
         x_dev = wl.x[:T].to(ses.device)
@@ -68,10 +68,10 @@ def run_parity(wl, *, y_every=1, tokens=None, session_kw=None, oracle_kw=None, b
                     ses.prefetch(ln, xp_dev[tn, ln])
                     pf = orc.prefetch_layer(ln, as_numpy(wl.x_pred[tn, ln]), prefetch_max)
                     worst["route_margin"] = min(worst["route_margin"], pf.route_margin)
-                    worst["evict_margin"] = min(worst["evict_margin"], pf.evict_margin)
                 ses.decode(l, x_dev[t, l], y_dev[t, l], tr)
                 want_y = (call % y_every) == 0 if y_tokens is None else t in y_tokens
-                res = orc.decode_layer(l, as_numpy(wl.x[t, l]), compute_y=want_y)
+                # (which prefetched experts were still in flight is a fact of the run: an input of the oracle)
+                res = orc.decode_layer(l, as_numpy(wl.x[t, l]), compute_y=want_y, inflight=tr.inflight)
                 call += 1
                 ctx = f"{label} token {t} layer {l}"
                 np.testing.assert_array_equal(tr.topk_idx, res.topk, err_msg=f"topk {ctx}")
@@ -83,6 +83,11 @@ def run_parity(wl, *, y_every=1, tokens=None, session_kw=None, oracle_kw=None, b
                 assert tr.fetched[:tr.n_fetched].tolist() == res.fetched, ctx
                 assert tr.victims[:tr.n_fetched].tolist() == res.victims, ctx
                 assert tr.on_cpu[:tr.n_on_cpu].tolist() == res.on_cpu, ctx
+                assert tr.adopted[:tr.n_adopted].tolist() == res.adopted, ctx
+                assert tr.adopt_victims[:tr.n_adopted].tolist() == res.adopt_victims, ctx
+                assert tr.inflight <= set(res.adopted) | set(res.on_cpu), ctx
+                worst["n_inflight"] += len(tr.inflight)
+                worst["n_inflight_on_cpu"] += len(tr.inflight & set(res.on_cpu))
                 np.testing.assert_allclose(tr.scores, res.scores, rtol=2e-5, atol=1e-9,
                                            err_msg=f"scores {ctx}")
                 np.testing.assert_allclose(tr.weights, res.weights, rtol=2e-5, atol=1e-9,
@@ -90,8 +95,8 @@ def run_parity(wl, *, y_every=1, tokens=None, session_kw=None, oracle_kw=None, b
                 assert ses.residency(l).tolist() == orc.layers[l].slot_expert, ctx
                 if pf is not None:
                     got_pf = ses.prefetch_last()
-                    assert got_pf == dict(layer=ln, wanted=pf.wanted, loaded=pf.prefetched,
-                                          victims=pf.victims), f"prefetch {ctx}: {got_pf} vs {pf}"
+                    assert got_pf == dict(layer=ln, wanted=pf.wanted, loaded=pf.prefetched), \
+                        f"prefetch {ctx}: {got_pf} vs {pf}"
                     if ln != l:
                         assert ses.residency(ln).tolist() == orc.layers[ln].slot_expert, ctx
                 worst["route_margin"] = min(worst["route_margin"], res.route_margin)
@@ -106,6 +111,8 @@ def run_parity(wl, *, y_every=1, tokens=None, session_kw=None, oracle_kw=None, b
             worst["l2"] = max(worst["l2"], l2)
             worst["mx"] = max(worst["mx"], mx)
             n_y += 1
+        if prefetch_max:
+            worst["prefetch_bytes"] = ses.prefetch_bytes()
         got = ses.stats()
         want = orc.stats().as_dict()
         assert got == want, f"{label} stats {got} != {want}"

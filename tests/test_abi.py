@@ -37,7 +37,7 @@ def test_header_is_plain_c_and_struct_layouts_match_binding(tmp_path):
                     'sizeof(moe_buffers_t), sizeof(moe_trace_t), sizeof(moe_stats_t), sizeof(moe_profile_t),'
                     'offsetof(moe_cfg_t, alpha), offsetof(moe_trace_t, n_fetched), sizeof(moe_prefetch_info_t),'
                     'offsetof(moe_cfg_t, cpu_cost_us), offsetof(moe_stats_t, cpu_computed), offsetof(moe_stats_t, prefetches),'
-                    'offsetof(moe_trace_t, on_cpu), offsetof(moe_prefetch_info_t, victims));return 0;}\n')
+                    'offsetof(moe_trace_t, on_cpu), offsetof(moe_trace_t, inflight_mask) + 1000 * offsetof(moe_prefetch_info_t, bytes_withdrawn));return 0;}\n')
     exe = tmp_path / "sizes"
     subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
                     str(prog), "-o", str(exe)], check=True)
@@ -47,7 +47,7 @@ def test_header_is_plain_c_and_struct_layouts_match_binding(tmp_path):
             ctypes.sizeof(M.MoeStats), ctypes.sizeof(M.MoeProfile), M.MoeCfg.alpha.offset,
             M.MoeTrace.n_fetched.offset, ctypes.sizeof(M.MoePrefetchInfo), M.MoeCfg.cpu_cost_us.offset,
             M.MoeStats.cpu_computed.offset, M.MoeStats.prefetches.offset, M.MoeTrace.on_cpu.offset,
-            M.MoePrefetchInfo.victims.offset]
+            M.MoeTrace.inflight_mask.offset + 1000 * M.MoePrefetchInfo.bytes_withdrawn.offset]
     assert got == want
 
 

@@ -263,7 +263,7 @@ def test_prefetch_parity_small_and_shared_shapes():
     """Every call is preceded by a prefetch for the layer that runs next: what
     it wanted, loaded and evicted, the residency of both layers, the following
     routing decisions, the accuracy counters and y all match the oracle."""
-    wl = make_workload(SHAPES["c2"].with_(tokens=48), pred_noise=0.5)
+    wl = make_workload(SHAPES["c2"].with_(tokens=48, seed=3), pred_noise=0.5)
     r = run_parity(wl, label="c2-prefetch", prefetch_max=2)
     st = r["stats"]
     assert st["prefetches"] > 20 and 0 < st["prefetch_used"] <= st["prefetches"]
@@ -456,7 +456,7 @@ def _oracle_margins(wl, batch, prefetch_max, oracle_kw):
                 tn, ln = divmod(t * s.n_layers + l + 1, s.n_layers)
                 if prefetch_max and tn < s.tokens:
                     pf = orc.prefetch_layer(ln, as_numpy(wl.x_pred[tn, ln]), prefetch_max)
-                    route, evict = min(route, pf.route_margin), min(evict, pf.evict_margin)
+                    route = min(route, pf.route_margin)
                 r = orc.decode_layer(l, as_numpy(wl.x[t, l]), compute_y=False)
                 route, evict = min(route, r.route_margin), min(evict, r.evict_margin)
     except AssertionError:
@@ -544,3 +544,36 @@ def test_alpha_selection_on_measured_tpot_matches_the_oracle():
     # a budget the measurements already meet asks for no substitution at all
     assert M.moe_select_alpha(alphas, tp, tp[0] * 1.5, degree=1)[0] == 0.0
     assert M.moe_select_alpha(alphas, tp, tp[2] * 0.5, degree=1)[0] is None
+
+
+# ---------------------------------------------------------------- the prefetcher's load queue (Section IV-C)
+def test_load_queue_withdraws_mispredicted_prefetches_and_leaves_the_cache_alone(monkeypatch):
+    """A predictor that is wrong most of the time: the experts it asks for wait in
+    spare slots, outside the cache set; the layer's step drops the unused ones
+    and what had not been handed to the copy stream is never copied.  Parity with
+    the oracle on every call; with small chunks and only one outstanding, part of
+    the mispredicted bytes is withdrawn."""
+    monkeypatch.setenv("SMOE_PF_CHUNK_MB", "1")
+    monkeypatch.setenv("SMOE_PF_OUTSTANDING", "1")
+    shp = SHAPES["c4"].with_(seed=44)
+    wl = make_workload(shp, n_layers=3, tokens=40, pred_noise=3.0)        # mostly wrong predictions
+    r = run_parity(wl, y_every=3, label="c4-mispredict", prefetch_max=3)
+    st, pb = r["stats"], r["prefetch_bytes"]
+    assert st["prefetches"] > 100 and st["prefetch_used"] < 0.5 * st["prefetches"]
+    assert pb["withdrawn"] > 0 and pb["copied"] + pb["withdrawn"] == st["prefetches"] * shp.expert_bytes
+    print(f"[load queue] {st['prefetches']} prefetches, {st['prefetch_used']} used, "
+          f"{pb['copied'] / 1e6:.0f} MB copied, {pb['withdrawn'] / 1e6:.0f} MB withdrawn", flush=True)
+
+
+def test_in_flight_prefetches_can_be_taken_over_by_the_host_cores():
+    """CPU-assisted scheduling with prefetch (Section V-A with Section V-B's second
+    dependency): a prefetched expert whose copy has not finished when its layer is
+    decided joins the list Algorithm 2 splits; with the host cores cheaper than a
+    load the min-max variant computes it on the CPU and abandons the copy.  Which
+    experts were in flight is reported by the call and given to the oracle."""
+    ses_kw, orc_kw = _cpu_kw(3.0, 1.0, threads=8, mode=2)
+    shp = SHAPES["c4"].with_(seed=45)
+    wl = make_workload(shp, n_layers=4, tokens=30, pred_noise=0.3)
+    r = run_parity(wl, y_every=2, session_kw=ses_kw, oracle_kw=orc_kw, label="c4-inflight-cpu", prefetch_max=3)
+    assert r["stats"]["prefetches"] > 50 and r["stats"]["cpu_computed"] > 20
+    assert r["n_inflight"] > 0 and r["n_inflight_on_cpu"] > 0, r

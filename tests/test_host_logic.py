@@ -29,15 +29,41 @@ def shim():
     lib.smoe_hl_create.restype = C.c_void_p
     lib.smoe_hl_create.argtypes = [C.c_int] * 7 + [C.c_int64, C.c_void_p, C.c_float, C.c_int, C.c_int,
                                    C.c_double, C.c_double]
-    lib.smoe_hl_prefetch.argtypes = [C.c_void_p, C.c_int, C.c_int] + [C.c_void_p] * 6
+    lib.smoe_hl_prefetch.argtypes = [C.c_void_p, C.c_int, C.c_int] + [C.c_void_p] * 5
     lib.smoe_hl_destroy.argtypes = [C.c_void_p]
-    lib.smoe_hl_step.argtypes = [C.c_void_p, C.c_int, C.c_int] + [C.c_void_p] * 9
+    lib.smoe_hl_step.argtypes = [C.c_void_p, C.c_int, C.c_int] + [C.c_void_p] * 4 + [C.c_uint64] + [C.c_void_p] * 10
     lib.smoe_hl_residency.argtypes = [C.c_void_p, C.c_int, C.c_void_p]
     lib.smoe_hl_stats.argtypes = [C.c_void_p, C.c_int, C.POINTER(Stats)]
     return lib
 
 
-def replay(lib, wl, batch=1, n_stage=0, prefetch_max=0, **oracle_kw):
+class StepOut:
+    """Output arrays of one smoe_hl_step call."""
+
+    def __init__(self, nk):
+        self.fetched, self.victims, self.slots, self.on_cpu, self.adopted, self.adopt_victims, self.dropped = (
+            np.zeros(nk, np.int32) for _ in range(7))
+        self.n_cpu, self.n_adopted, self.n_dropped = (np.zeros(1, np.int32) for _ in range(3))
+
+    def args(self):
+        return [a.ctypes.data for a in (self.fetched, self.victims, self.slots, self.on_cpu, self.n_cpu,
+                                        self.adopted, self.adopt_victims, self.n_adopted, self.dropped,
+                                        self.n_dropped)]
+
+
+def hl_step(lib, h, layer, batch, r, out, inflight=0):
+    """Feed the oracle's routing decision `r` to the scheduler; returns the number of loads."""
+    topk = np.ascontiguousarray(r.topk, np.int32)
+    fin = np.ascontiguousarray(r.final, np.int32)
+    sub = np.ascontiguousarray(r.substituted, np.int32)
+    sc = np.ascontiguousarray(r.scores, np.float32)
+    return lib.smoe_hl_step(h, layer, batch, topk.ctypes.data, fin.ctypes.data, sub.ctypes.data, sc.ctypes.data,
+                            inflight, *out.args())
+
+
+def replay(lib, wl, batch=1, n_stage=0, prefetch_max=0, inflight_all=False, **oracle_kw):
+    """`inflight_all`: every prefetched expert is taken to be still in flight at its
+    layer's step (on both sides), so that CPU-assisted scheduling may take it over."""
     s = wl.shape
     orc = O.oracle_from_workload(wl, **oracle_kw)
     h = lib.smoe_hl_create(s.n_layers, s.n_experts, s.top_k, orc.cap, orc.window, orc.evict_policy,
@@ -45,37 +71,37 @@ def replay(lib, wl, batch=1, n_stage=0, prefetch_max=0, **oracle_kw):
                            int(orc.cpu_assist), orc.c_load, orc.c_cpu)
     assert h
     nk = batch * s.top_k
-    fetched = np.zeros(nk, np.int32); victims = np.zeros(nk, np.int32); slots = np.zeros(nk, np.int32)
-    wanted = np.zeros(nk, np.int32); n_wanted = np.zeros(1, np.int32)
-    on_cpu = np.zeros(nk, np.int32); n_cpu = np.zeros(1, np.int32)
+    out = StepOut(nk)
+    wanted = np.zeros(nk, np.int32); n_wanted = np.zeros(1, np.int32); pslots = np.zeros(nk, np.int32)
     res_slots = np.zeros(orc.cap, np.int32)
     loads = 0
     try:
         for t in range(s.tokens):
             for l in range(s.n_layers):
+                inflight = set()
                 if prefetch_max:
                     pf = orc.prefetch_layer(l, as_numpy(wl.x_pred[t, l]), prefetch_max)
                     p_topk = np.ascontiguousarray(pf.topk, np.int32)
                     p_sc = np.ascontiguousarray(pf.scores, np.float32)
                     n = lib.smoe_hl_prefetch(h, l, batch, p_topk.ctypes.data, p_sc.ctypes.data,
-                                             wanted.ctypes.data, n_wanted.ctypes.data,
-                                             victims.ctypes.data, slots.ctypes.data)
+                                             wanted.ctypes.data, n_wanted.ctypes.data, pslots.ctypes.data)
                     assert wanted[:n_wanted[0]].tolist() == pf.wanted, (t, l)
-                    assert n == len(pf.prefetched) and victims[:n].tolist() == pf.victims, (t, l)
+                    assert n == len(pf.prefetched), (t, l)
+                    assert all(orc.cap <= v < orc.cap + prefetch_max or v < orc.cap for v in pslots[:n])
                     lib.smoe_hl_residency(h, l, res_slots.ctypes.data)
-                    assert res_slots.tolist() == orc.layers[l].slot_expert, (t, l)
-                r = orc.decode_layer(l, as_numpy(wl.x[t, l]), compute_y=False)
-                topk = np.ascontiguousarray(r.topk, np.int32)
-                fin = np.ascontiguousarray(r.final, np.int32)
-                sub = np.ascontiguousarray(r.substituted, np.int32)
-                sc = np.ascontiguousarray(r.scores, np.float32)
-                n = lib.smoe_hl_step(h, l, batch, topk.ctypes.data, fin.ctypes.data, sub.ctypes.data,
-                                     sc.ctypes.data, fetched.ctypes.data, victims.ctypes.data, slots.ctypes.data,
-                                     on_cpu.ctypes.data, n_cpu.ctypes.data)
+                    assert res_slots.tolist() == orc.layers[l].slot_expert, (t, l)      # G untouched
+                    if inflight_all:
+                        inflight = set(orc.layers[l].landed)
+                r = orc.decode_layer(l, as_numpy(wl.x[t, l]), compute_y=False, inflight=inflight)
+                n = hl_step(lib, h, l, batch, r, out, sum(1 << e for e in inflight))
                 assert n == len(r.fetched), (t, l, n)
-                assert on_cpu[:n_cpu[0]].tolist() == r.on_cpu, (t, l)
-                assert fetched[:n].tolist() == r.fetched and victims[:n].tolist() == r.victims, (t, l)
-                assert [v >= 0 for v in victims[:n]] == [sl >= 0 for sl in slots[:n]]
+                assert out.on_cpu[:out.n_cpu[0]].tolist() == r.on_cpu, (t, l)
+                assert out.fetched[:n].tolist() == r.fetched and out.victims[:n].tolist() == r.victims, (t, l)
+                assert [v >= 0 for v in out.victims[:n]] == [sl >= 0 for sl in out.slots[:n]]
+                na = out.n_adopted[0]
+                assert out.adopted[:na].tolist() == r.adopted and out.adopt_victims[:na].tolist() == r.adopt_victims
+                want_dropped = r.dropped + [e for e in r.on_cpu if e in inflight]
+                assert sorted(out.dropped[:out.n_dropped[0]].tolist()) == sorted(want_dropped), (t, l)
                 lib.smoe_hl_residency(h, l, res_slots.ctypes.data)
                 assert res_slots.tolist() == orc.layers[l].slot_expert, (t, l)
                 loads += n
@@ -116,17 +142,11 @@ def test_scheduler_batch_and_staging(shim):
     h = shim.smoe_hl_create(s.n_layers, s.n_experts, s.top_k, s.cache_cap, 3, 0, 0, s.expert_bytes, None,
                             0.25, 0, 0, 1.0, 1.0)
     rc = 0
-    buf = np.zeros(64, np.int32)
+    out = StepOut(64)
     for t in range(s.tokens):
         for l in range(s.n_layers):
             r = orc.decode_layer(l, as_numpy(wl.x[t, l]), compute_y=False)
-            a_topk = np.ascontiguousarray(r.topk, np.int32)       # keep the arrays alive over the call
-            a_fin = np.ascontiguousarray(r.final, np.int32)
-            a_sub = np.ascontiguousarray(r.substituted, np.int32)
-            a_sc = np.ascontiguousarray(r.scores, np.float32)
-            rc = shim.smoe_hl_step(h, l, 4, a_topk.ctypes.data, a_fin.ctypes.data, a_sub.ctypes.data,
-                                   a_sc.ctypes.data, buf.ctypes.data, buf.ctypes.data, buf.ctypes.data,
-                                   buf.ctypes.data, buf.ctypes.data)
+            rc = hl_step(shim, h, l, 4, r, out)
             if rc < 0 or -1 in r.victims:
                 break
         if rc < 0 or -1 in r.victims:
@@ -143,6 +163,11 @@ def test_prefetch_replay_matches_oracle(shim, policy, batch):
     wl = make_workload(shp, n_layers=2, tokens=50, batch=batch, pred_noise=0.6)
     loads, st = replay(shim, wl, batch=batch, n_stage=batch * shp.top_k, prefetch_max=3, evict_policy=policy)
     assert st.prefetches > 30 and 0 < st.prefetch_top <= st.prefetch_used < st.prefetches
+    # the same with every prefetch taken to be in flight and Algorithm 2 on: some prefetched
+    # experts are handed to the host cores instead of being waited for
+    loads, st = replay(shim, wl, batch=batch, n_stage=batch * shp.top_k, prefetch_max=3, evict_policy=policy,
+                       inflight_all=True, cpu_assist=1, c_load=3.0, c_cpu=1.0)
+    assert st.prefetches > 30 and st.cpu_computed > 5
 
 
 @pytest.mark.parametrize("mode", [1, 2])
@@ -169,11 +194,11 @@ def test_scheduler_rejects_bad_arguments_and_malformed_decisions(shim):
     assert not shim.smoe_hl_create(1, 8, 2, 4, 3, 9, 0, 100, None, *tail)       # unknown policy
     h = shim.smoe_hl_create(1, 8, 2, 4, 3, 0, 0, 100, None, *tail)
     topk = np.array([[0, 1]], np.int32); bad = np.array([[0, 9]], np.int32); sub = np.zeros((1, 2), np.int32)
-    sc = np.full((1, 8), 0.125, np.float32); o = np.zeros(2, np.int32)
+    sc = np.full((1, 8), 0.125, np.float32); o = StepOut(2)
     assert shim.smoe_hl_step(h, 0, 1, topk.ctypes.data, bad.ctypes.data, sub.ctypes.data, sc.ctypes.data,
-                             o.ctypes.data, o.ctypes.data, o.ctypes.data, o.ctypes.data, o.ctypes.data) == -4
+                             0, *o.args()) == -4
     assert shim.smoe_hl_step(h, 3, 1, topk.ctypes.data, topk.ctypes.data, sub.ctypes.data, sc.ctypes.data,
-                             o.ctypes.data, o.ctypes.data, o.ctypes.data, o.ctypes.data, o.ctypes.data) == -1
+                             0, *o.args()) == -1
     shim.smoe_hl_destroy(h)
 
 
@@ -184,7 +209,7 @@ def test_refused_step_leaves_the_layer_as_it_was(shim):
     E, k, cap = 8, 2, 2
     h = shim.smoe_hl_create(1, E, k, cap, 3, 1, 1, 100, None, 0.0, 0, 0, 1.0, 1.0)     # LRU, one staging slot
     twin = shim.smoe_hl_create(1, E, k, cap, 3, 1, 1, 100, None, 0.0, 0, 0, 1.0, 1.0)
-    o = [np.zeros(8, np.int32) for _ in range(5)]
+    o = StepOut(8)
     res = np.zeros(cap, np.int32)
 
     def step(hh, topk_rows):
@@ -195,7 +220,7 @@ def test_refused_step_leaves_the_layer_as_it_was(shim):
         for t, row in enumerate(topk_rows):
             sc[t, row] = [0.4, 0.3]
         return shim.smoe_hl_step(hh, 0, B, topk.ctypes.data, topk.ctypes.data, sub.ctypes.data, sc.ctypes.data,
-                                 *[a.ctypes.data for a in o])
+                                 0, *o.args())
 
     def state(hh):
         st = Stats()
