@@ -120,6 +120,15 @@ typedef struct {
                             duration of the last 8 expert copies)                     */
   float   cpu_cost_us;   /* C_CPU of Algorithm 2; <= 0: measured (mean wall time of the
                             last 8 host-computed experts)                             */
+  int32_t auto_prefetch; /* 1 (needs prefetch_max > 0): every moe_decode_layer of a layer
+                            l < L-1 predicts the input of layer l+1 from its own partial
+                            output -- the resident and shared experts' result, before
+                            the loaded experts are done (Section IV-C, Fig. "prefetch")
+                            -- as (x + partial) / rms(x + partial), runs layer l+1's gate
+                            on it and prefetches for layer l+1 exactly as a
+                            moe_prefetch_layer call with that state would; the decision
+                            is taken when layer l+1 is decoded.  0: predictions come
+                            from the caller through moe_prefetch_layer only           */
 } moe_cfg_t;
 
 typedef struct {

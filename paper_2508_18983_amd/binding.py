@@ -30,7 +30,8 @@ class MoeCfg(C.Structure):
         "n_layers", "hidden", "n_experts", "ffn", "top_k", "cache_cap", "n_shared",
         "shared_ffn", "dtype", "max_batch")] + [("alpha", C.c_float)] + [(n, C.c_int32) for n in (
         "subst_key", "renorm_topk", "evict_window", "n_stage", "evict_policy", "prefetch_max",
-        "cpu_assist", "cpu_threads")] + [("load_cost_us", C.c_float), ("cpu_cost_us", C.c_float)]
+        "cpu_assist", "cpu_threads")] + [("load_cost_us", C.c_float), ("cpu_cost_us", C.c_float),
+                                            ("auto_prefetch", C.c_int32)]
 
 
 class MoeBuffers(C.Structure):

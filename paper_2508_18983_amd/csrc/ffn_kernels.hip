@@ -1073,6 +1073,41 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void ffn_down_mfma_kernel(const Ff
   }
 }
 
+// Predicted input of the next MoE layer from this layer's partial output (top-
+// score prefetch, Section IV-C, Fig. "prefetch": the prediction starts from what
+// the experts already on the GPU have produced, before the loaded ones are
+// done).  With the attention block outside this path the next layer's input is
+// modelled as the RMS-normalised residual sum: xp = (x + p) / rms(x + p), where
+// p is the resident pass's result -- its fp32 sums for a token that still waits
+// for experts, its finished output otherwise.  One block per token.
+template <typename T>
+__global__ __launch_bounds__(256) void predict_state_kernel(const StepRec* rec, const T* __restrict__ x,
+                                                            const T* __restrict__ y,
+                                                            const float* __restrict__ ysum, T* __restrict__ xp,
+                                                            int H, int k) {
+  __shared__ float red[4];
+  const int t = blockIdx.x, tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+  bool any_miss = false;
+  for (int q = 0; q < k; ++q) any_miss |= (rec->tok[t].slot[q] < 0);
+  const T* xt = x + (size_t)t * H;
+  const T* yt = y + (size_t)t * H;
+  const float* st = ysum + (size_t)t * H;
+  float acc = 0.f;
+  for (int h = tid; h < H; h += 256) {
+    const float z = Unit<T>::widen1(xt[h]) + (any_miss ? st[h] : Unit<T>::widen1(yt[h]));
+    acc = fmaf(z, z, acc);
+  }
+  acc = wave_sum(acc);
+  if (lane == 0) red[wave] = acc;
+  __syncthreads();
+  const float ms = ((red[0] + red[1]) + (red[2] + red[3])) / (float)H;
+  const float inv = 1.0f / sqrtf(ms);
+  for (int h = tid; h < H; h += 256) {
+    const float z = Unit<T>::widen1(xt[h]) + (any_miss ? st[h] : Unit<T>::widen1(yt[h]));
+    xp[(size_t)t * H + h] = Unit<T>::narrow(z * inv);
+  }
+}
+
 __global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst,
                                                    const uint4* __restrict__ src, int64_t n) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -1207,6 +1242,17 @@ void launch_copy(void* dst, const void* src, int64_t n_bytes, hipStream_t s) {
   if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
                      static_cast<uint4*>(dst), static_cast<const uint4*>(src), n);
+}
+
+void launch_predict_state(const StepRec* rec, const void* x, const void* y, const float* ysum, void* xp, int B,
+                          int H, int k, int dtype, hipStream_t s) {
+  if (dtype == SMOE_DTYPE_FP32)
+    hipLaunchKernelGGL(predict_state_kernel<float>, dim3(B), dim3(256), 0, s, rec, static_cast<const float*>(x),
+                       static_cast<const float*>(y), ysum, static_cast<float*>(xp), H, k);
+  else
+    hipLaunchKernelGGL(predict_state_kernel<bf16_t>, dim3(B), dim3(256), 0, s, rec,
+                       static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(y), ysum,
+                       static_cast<bf16_t*>(xp), H, k);
 }
 
 void launch_add_partial(float* ysum, const float* part, int n, hipStream_t s) {

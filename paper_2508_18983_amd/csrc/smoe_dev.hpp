@@ -103,6 +103,9 @@ void launch_ffn_up(const FfnArgs& a, const RouteArgs& ra, int dtype, hipStream_t
 void launch_ffn_down(const FfnArgs& a, int dtype, hipStream_t s);
 size_t grouped_down_lds_bytes(const FfnArgs& a);
 void launch_copy(void* dst, const void* src, int64_t n_bytes, hipStream_t s);
+// xp[t] = (x[t] + partial[t]) / rms(x[t] + partial[t]) for t < B: the predicted input of the next layer
+void launch_predict_state(const StepRec* rec, const void* x, const void* y, const float* ysum, void* xp, int B,
+                          int H, int k, int dtype, hipStream_t s);
 // ysum[i] += part[i], i < n (n a multiple of 4): adds what the host cores computed
 void launch_add_partial(float* ysum, const float* part, int n, hipStream_t s);
 

@@ -71,6 +71,7 @@ struct Scratch {
   float* act = nullptr;                  // SwiGLU activations between the up and the down kernel
   float* ysum = nullptr;                 // [B][H] fp32 sums carried from the resident to the loaded pass
   float* gate_part = nullptr;            // [B][E][kMaxGateSeg] partial dot products of the gate GEMV
+  void* x_pred = nullptr;                // [B][H] dtype: predicted input of the next layer (auto_prefetch)
 };
 constexpr int64_t kGatePartBytes = (int64_t)SMOE_MAX_BATCH * SMOE_MAX_EXPERTS * kMaxGateSeg * sizeof(float);
 
@@ -293,6 +294,7 @@ void free_all(moe_handle* h) {
   if (h->own.act) (void)hipFree(h->own.act);
   if (h->own.ysum) (void)hipFree(h->own.ysum);
   if (h->own.gate_part) (void)hipFree(h->own.gate_part);
+  if (h->own.x_pred) (void)hipFree(h->own.x_pred);
   delete h;
 }
 
@@ -767,6 +769,7 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
   if (c.evict_policy < SMOE_EVICT_SCORE || c.evict_policy > SMOE_EVICT_LFU) return SMOE_EINVAL;
   if (c.prefetch_max < 0 || c.prefetch_max > SMOE_MAX_BATCH * SMOE_MAX_TOPK - 1) return SMOE_EINVAL;
   if (c.cpu_assist < 0 || c.cpu_assist > 2 || c.cpu_threads < 0 || c.cpu_threads > 256) return SMOE_EINVAL;
+  if (c.auto_prefetch < 0 || c.auto_prefetch > 1 || (c.auto_prefetch && c.prefetch_max < 1)) return SMOE_EINVAL;
   if (!buf->gate_w_dev || !buf->experts_host || !buf->sim_host || !buf->cache_slab_dev) return SMOE_EINVAL;
   if (c.n_shared > 0 && !buf->shared_dev) return SMOE_EINVAL;
   if (buf->stream_compute == buf->stream_copy) return SMOE_EINVAL;
@@ -833,6 +836,7 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
     HIP_TRY(hipMalloc(&h->own.act, (size_t)h->act_floats * sizeof(float)));
     HIP_TRY(hipMalloc(&h->own.ysum, (size_t)c.max_batch * c.hidden * sizeof(float)));
     HIP_TRY(hipMalloc(&h->own.gate_part, (size_t)kGatePartBytes));
+    HIP_TRY(hipMalloc(&h->own.x_pred, (size_t)c.max_batch * c.hidden * h->esize));
     {
       // the same buffers inside this GPU's static array, for moe_decode_layer_static
       HIP_TRY(hipGetDevice(&h->device));
@@ -843,12 +847,14 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
       auto carve = [&](int64_t bytes) { const int64_t o = off; off += (bytes + 255) / 256 * 256; return o; };
       const int64_t o_rec = carve(sizeof(StepRec));
       const int64_t o_part = carve(kGatePartBytes);
+      const int64_t o_xp = carve((int64_t)c.max_batch * c.hidden * h->esize);
       const int64_t o_ysum = carve((int64_t)c.max_batch * c.hidden * sizeof(float));
       const int64_t o_act = carve(h->act_floats * (int64_t)sizeof(float));
       h->fixed_need = off;
       if (off <= (int64_t)SMOE_STATIC_SCRATCH_BYTES) {
         h->fixed.rec = reinterpret_cast<StepRec*>(base + o_rec);
         h->fixed.gate_part = reinterpret_cast<float*>(base + o_part);
+        h->fixed.x_pred = base + o_xp;
         h->fixed.ysum = reinterpret_cast<float*>(base + o_ysum);
         h->fixed.act = reinterpret_cast<float*>(base + o_act);
       }
@@ -972,6 +978,28 @@ static int decode_layer_with(moe_handle_t* h, const Scratch& sc, int32_t layer, 
     if (rc != SMOE_OK) return rc;
   }
 
+  // ---- top-score prefetch from the partial output (Section IV-C): the input of the next
+  //      layer is predicted from what the resident pass has produced and that layer's gate
+  //      runs on it, queued right behind the resident pass; its decision is taken when the
+  //      next layer is decoded ----------------------------------------------------------
+  if (c.auto_prefetch && layer + 1 < c.n_layers) {
+    {
+      const int rc = settle_prefetch(h);                // one prediction may wait at a time
+      if (rc != SMOE_OK) return rc;
+    }
+    launch_predict_state(sc.rec, x_dev, y_dev, sc.ysum, sc.x_pred, B, c.hidden, c.top_k, c.dtype, h->s_compute);
+    RouteArgs pa{};
+    fill_route_args(h, sc, layer + 1, B, sc.x_pred, pa);
+    pa.rec_dev = h->pred_dev;
+    pa.rec_host = h->pred_host_dev;
+    pa.seq = ++h->pred_seq;
+    launch_gate_partial(pa, c.dtype, h->s_compute);
+    launch_route_select(pa, h->s_compute);
+    HIP_TRY(hipGetLastError());
+    h->pending_layer = layer + 1;
+    h->pending_batch = B;
+  }
+
   // ---- the decision reaches the host: poll the pinned mirror (the router kernel
   //      publishes its call number last), then fall back to draining the stream ----
   {
@@ -1029,7 +1057,8 @@ static int decode_layer_with(moe_handle_t* h, const Scratch& sc, int32_t layer, 
       //      experts Algorithm 2 left to them; a prefetch that is waiting for its decision
       //      joins the load queue first so that the link stays busy meanwhile.  The result is
       //      added to the fp32 sums of the resident pass, and the second pass rounds y once.
-      const int rc = settle_prefetch(h);
+      const bool own_prediction = c.auto_prefetch && h->pending_layer == layer + 1;
+      const int rc = own_prediction ? SMOE_OK : settle_prefetch(h);
       if (rc != SMOE_OK) return rc;
       compute_on_cpu(h, layer, B, rec, plan.on_cpu, plan.n_cpu);
       launch_add_partial(sc.ysum, h->ycpu_host_dev, B * c.hidden, h->s_compute);
@@ -1053,7 +1082,10 @@ static int decode_layer_with(moe_handle_t* h, const Scratch& sc, int32_t layer, 
   // ---- a prefetch waiting for its decision (for another layer) joins the load queue now,
   //      and the queue is fed: behind the loads this layer is waiting for --------------
   {
-    int rc = settle_prefetch(h);
+    // (a prediction this call has launched itself is left for the next call: it is queued
+    // behind the resident pass, waiting for it here would stall the host)
+    const bool own_prediction = c.auto_prefetch && h->pending_layer == layer + 1;
+    int rc = own_prediction ? SMOE_OK : settle_prefetch(h);
     if (rc == SMOE_OK) rc = pump_prefetch_queue(h, layer + 1 < c.n_layers ? layer + 1 : 0);
     if (rc != SMOE_OK) return rc;
   }

@@ -89,7 +89,7 @@ class DecodeSession:
                    alpha=float(shape.alpha), subst_key=shape.subst_key,
                    renorm_topk=shape.renorm_topk, evict_window=shape.evict_window, n_stage=n_stage,
                    evict_policy=getattr(shape, "evict_policy", 0), prefetch_max=0,
-                   cpu_assist=0, cpu_threads=0, load_cost_us=0.0, cpu_cost_us=0.0)
+                   cpu_assist=0, cpu_threads=0, load_cost_us=0.0, cpu_cost_us=0.0, auto_prefetch=0)
         cfg.update(cfg_override)
         self.cfg = B.MoeCfg(**cfg)
         self.expert_bytes = 3 * cfg["hidden"] * cfg["ffn"] * esize

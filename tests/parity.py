@@ -125,3 +125,71 @@ def run_parity(wl, *, y_every=1, tokens=None, session_kw=None, oracle_kw=None, b
     worst.update(n_y=n_y, stats=want)
     print(f"[parity {label}] ok: {worst}", flush=True)
     return worst
+
+
+def rms_chain(x_rows, y_rows):
+    """Input of the next MoE layer in the chained mode: the RMS-normalised residual
+    sum, per token (a stand-in for the blocks between two MoE layers)."""
+    z = np.asarray(x_rows, np.float64) + np.asarray(y_rows, np.float64)
+    return z / np.sqrt(np.mean(z * z, axis=1, keepdims=True))
+
+
+def run_chained_with_predictor(wl, *, prefetch_max, tokens=None, batch=None, session_kw=None, label=""):
+    """Chained decode with the library's own predictor (cfg.auto_prefetch): only
+    layer 0 of a token takes its input from the workload, layer l+1 gets
+    x = rms_chain(x_l, y_l) computed from the ORACLE's fp64 output (rounded to the
+    storage type), and both sides predict layer l+1's input from layer l's partial
+    output and prefetch for it.  Decisions, prefetch lists, counters exact; y and
+    the chained state within tolerance."""
+    import torch
+    s = wl.shape
+    T = s.tokens if tokens is None else tokens
+    B = s.batch if batch is None else batch
+    tdt = torch.float32 if s.dtype == "fp32" else torch.bfloat16
+    orc = O.oracle_from_workload(wl)
+    worst = dict(l2=0.0, mx=0.0, route_margin=np.inf, evict_margin=np.inf, n_calls=0)
+
+    def stored(a64):                                     # fp64 -> storage type, as numpy view
+        return torch.from_numpy(np.ascontiguousarray(a64)).to(tdt)
+
+    with session_from_workload(wl, max_batch=B, prefetch_max=prefetch_max, auto_prefetch=1,
+                               **(session_kw or {})) as ses:
+        for t in range(T):
+            x_t = wl.x[t, 0].clone()                     # [B, H] storage type, host
+            for l in range(s.n_layers):
+                x_dev = x_t.to(ses.device)
+                y_dev = torch.zeros(B, s.hidden, dtype=tdt, device=ses.device)
+                tr = ses.new_trace(B)
+                ses.decode(l, x_dev, y_dev, tr)
+                res = orc.decode_layer(l, as_numpy(x_t), compute_y=True, inflight=tr.inflight)
+                ctx = f"{label} token {t} layer {l}"
+                np.testing.assert_array_equal(tr.topk_idx, res.topk, err_msg=f"topk {ctx}")
+                np.testing.assert_array_equal(tr.final_idx, res.final, err_msg=f"final {ctx}")
+                np.testing.assert_array_equal(tr.hit.astype(bool), res.hit, err_msg=f"hit {ctx}")
+                assert tr.fetched[:tr.n_fetched].tolist() == res.fetched, ctx
+                assert tr.victims[:tr.n_fetched].tolist() == res.victims, ctx
+                assert tr.adopted[:tr.n_adopted].tolist() == res.adopted, ctx
+                assert tr.adopt_victims[:tr.n_adopted].tolist() == res.adopt_victims, ctx
+                assert ses.residency(l).tolist() == orc.layers[l].slot_expert, ctx
+                worst["route_margin"] = min(worst["route_margin"], res.route_margin)
+                worst["evict_margin"] = min(worst["evict_margin"], res.evict_margin)
+                ses.sync()
+                l2, mx = rel_errors(y_dev.double().cpu().numpy(), res.y)
+                assert within_tolerance(s.dtype, l2, mx), f"y {ctx}: l2 {l2:.3e} max {mx:.3e}"
+                worst["l2"], worst["mx"] = max(worst["l2"], l2), max(worst["mx"], mx)
+                if l + 1 < s.n_layers:
+                    # both sides predict layer l+1's input from the partial output and prefetch
+                    xp = stored(orc.predict_state(as_numpy(x_t), res.y_partial))
+                    pf = orc.prefetch_layer(l + 1, as_numpy(xp), prefetch_max)
+                    worst["route_margin"] = min(worst["route_margin"], pf.route_margin)
+                    got_pf = ses.prefetch_last()         # settles the library's own prediction
+                    assert got_pf == dict(layer=l + 1, wanted=pf.wanted, loaded=pf.prefetched), \
+                        f"prefetch {ctx}: {got_pf} vs {pf.wanted} / {pf.prefetched}"
+                    x_t = stored(rms_chain(O.widen(as_numpy(x_t)), res.y))
+                worst["n_calls"] += 1
+        got, want = ses.stats(), orc.stats().as_dict()
+        assert got == want, f"{label} stats {got} != {want}"
+    assert worst["route_margin"] >= ROUTE_MARGIN and worst["evict_margin"] >= EVICT_MARGIN, worst
+    worst["stats"] = want
+    print(f"[chained {label}] ok: {worst}", flush=True)
+    return worst

@@ -577,3 +577,57 @@ def test_in_flight_prefetches_can_be_taken_over_by_the_host_cores():
     r = run_parity(wl, y_every=2, session_kw=ses_kw, oracle_kw=orc_kw, label="c4-inflight-cpu", prefetch_max=3)
     assert r["stats"]["prefetches"] > 50 and r["stats"]["cpu_computed"] > 20
     assert r["n_inflight"] > 0 and r["n_inflight_on_cpu"] > 0, r
+
+
+# ---------------------------------------------------------------- the predictor of Section IV-C on the GPU
+@pytest.mark.parametrize("case", ["c1x4-seed0", "c1x4-seed4", "c4ish-shared"])
+def test_chained_decode_with_the_librarys_own_predictor(case):
+    """cfg.auto_prefetch: each layer call predicts the next layer's input from its
+    partial output (resident + shared experts, before the loaded ones are done),
+    runs the next layer's gate on it and prefetches.  Chained inputs (layer l+1
+    sees the RMS-normalised x_l + y_l, taken from the oracle), fp32 so that the
+    predicted state agrees to rounding: prefetch lists, adoption, victims,
+    residency and counters must equal the oracle's, y within tolerance."""
+    from tests.parity import run_chained_with_predictor
+    if case.startswith("c1x4"):
+        shp = SHAPES["c1"].with_(n_layers=4, tokens=12, seed=int(case[-1]))
+        pfmax = 2
+    else:
+        shp = SHAPES["c4"].with_(dtype="fp32", hidden=256, ffn=64, shared_ffn=64, n_experts=16, top_k=3,
+                                 cache_cap=6, n_layers=4, tokens=10, seed=1, prior="normal", sim="uniform")
+        pfmax = 3
+    wl = make_workload(shp)
+    r = run_chained_with_predictor(wl, prefetch_max=pfmax, label=case)
+    st = r["stats"]
+    assert st["prefetches"] >= 8 and st["prefetch_used"] > 0 and r["n_calls"] == shp.tokens * 4
+
+
+def test_own_predictor_bf16_is_deterministic_and_consistent():
+    """bf16: the predicted state is rounded to bf16 on both sides from slightly
+    different partial sums, so its top-score set can differ from the oracle's at
+    a near-tie; what must hold regardless: two runs agree bit for bit, counters
+    are consistent, and every prefetched expert the step used entered the cache."""
+    from paper_2508_18983_amd.session import session_from_workload
+    shp = SHAPES["c4"].with_(seed=47)
+    wl = make_workload(shp, n_layers=4, tokens=16)
+    s = wl.shape
+    outs = []
+    for rep in range(2):
+        with session_from_workload(wl, prefetch_max=3, auto_prefetch=1) as ses:
+            x = wl.x.to(ses.device)
+            y = torch.zeros(s.tokens, s.n_layers, 1, s.hidden, dtype=ses.tdtype, device=ses.device)
+            log = []
+            for t in range(s.tokens):
+                for l in range(s.n_layers):
+                    tr = ses.new_trace(1)
+                    ses.decode(l, x[t, l], y[t, l], tr)
+                    log.append((tr.final_idx.tolist(), tr.adopted[:tr.n_adopted].tolist(),
+                                tr.fetched[:tr.n_fetched].tolist()))
+                    assert set(tr.adopted[:tr.n_adopted].tolist()) <= set(tr.final_idx[0].tolist())
+            ses.sync()
+            st = ses.stats()
+            outs.append((y.cpu().view(torch.int16), log, st))
+    assert torch.equal(outs[0][0], outs[1][0]) and outs[0][1] == outs[1][1] and outs[0][2] == outs[1][2]
+    st = outs[0][2]
+    assert st["prefetches"] > 20 and 0 < st["prefetch_used"] <= st["prefetches"]
+    assert st["hits"] + st["misses"] == st["slots"] and torch.isfinite(outs[0][0].view(torch.bfloat16).float()).all()

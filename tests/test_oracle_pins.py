@@ -1028,3 +1028,58 @@ def test_batch_recency_stamps_follow_token_slot_order_lru_textbook():
         assert set(orc.layers[0].slot_expert) == set(cache)
         evictions += len(loaded)
     assert evictions > 30
+
+
+# ---------------------------------------------------------------- the predictor's state (Section IV-C)
+def test_partial_output_is_the_output_minus_the_experts_that_had_to_be_loaded(c1_workload):
+    """y_partial (what the prediction starts from) = shared experts + the slots
+    whose expert was in G before the step; recomputed here from the dense
+    expert outputs and the returned weights.  With nothing to load it is y."""
+    wl = c1_workload
+    s = wl.shape
+    orc = O.oracle_from_workload(wl)
+    saw_loaded = saw_equal = 0
+    for t in range(s.tokens):
+        for l in range(s.n_layers):
+            G = set(orc.layers[l].resident)
+            x = as_numpy(wl.x[t, l])
+            res = orc.decode_layer(l, x)
+            xt = torch.from_numpy(O.widen(x[0]))
+            want = np.zeros(s.hidden)
+            for j, e in enumerate(res.final[0]):
+                if int(e) in G:
+                    w1, w3, w2 = (m.to(torch.float64) for m in wl.expert_mats(l, int(e)))
+                    want += res.weights[0, j] * (w2 @ (torch.nn.functional.silu(w1 @ xt) * (w3 @ xt))).numpy()
+            np.testing.assert_allclose(res.y_partial[0], want, rtol=1e-10, atol=1e-14)
+            if res.fetched:
+                saw_loaded += 1
+                assert not np.allclose(res.y_partial, res.y, rtol=1e-6, atol=0)
+            else:
+                saw_equal += 1
+                np.testing.assert_array_equal(res.y_partial, res.y)
+    assert saw_loaded > 3 and saw_equal > 3
+    # shared experts are always on the GPU: with every routed expert resident too, the partial
+    # output is the whole output (which the dense-library pin above fixes, shared experts included)
+    shp = SHAPES["c4"].with_(hidden=128, ffn=96, shared_ffn=64, n_experts=16, cache_cap=16, top_k=4, sim="uniform")
+    wl = make_workload(shp, n_layers=1, tokens=2)
+    res = O.oracle_from_workload(wl).decode_layer(0, as_numpy(wl.x[0, 0]))
+    np.testing.assert_array_equal(res.y_partial, res.y)
+    assert np.abs(res.y).max() > 0
+
+
+def test_predicted_state_is_the_unit_rms_residual_sum():
+    rng = np.random.default_rng(2)
+    orc = O.oracle_from_workload(make_workload(SHAPES["c1"].with_(tokens=1)))
+    x = rng.normal(size=(3, 64)).astype(np.float32)
+    yp = rng.normal(size=(3, 64)) * 0.3
+    xp = orc.predict_state(x, yp)
+    np.testing.assert_allclose(np.sqrt((xp ** 2).mean(axis=1)), 1.0, rtol=1e-13)           # unit RMS
+    z = x.astype(np.float64) + yp
+    cos = (xp * z).sum(axis=1) / np.linalg.norm(xp, axis=1) / np.linalg.norm(z, axis=1)
+    np.testing.assert_allclose(cos, 1.0, rtol=1e-13)                                       # direction of x + y
+    np.testing.assert_allclose(orc.predict_state(4.0 * x, 4.0 * yp), xp, rtol=1e-13)       # scale-free
+    unit = x / np.sqrt((x.astype(np.float64) ** 2).mean(axis=1, keepdims=True))
+    np.testing.assert_allclose(orc.predict_state(unit, np.zeros_like(yp)), unit, rtol=1e-6)  # fixed point
+    # hand case: x + y = (3, 4, 0, 0): rms = sqrt(25/4) = 2.5
+    np.testing.assert_allclose(orc.predict_state(np.array([[1.0, 4.0, 0.0, -1.0]], np.float32),
+                                                 np.array([[2.0, 0.0, 0.0, 1.0]])), [[1.2, 1.6, 0.0, 0.0]])

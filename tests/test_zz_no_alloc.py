@@ -56,6 +56,11 @@ def test_static_entry_point_two_calls_second_smaller_and_long_runs():
     for name in ("c1", "c2"):
         wl = make_workload(SHAPES[name].with_(tokens=12, seed=5))
         _same(_run(wl, [1], static=False), _run(wl, [1], static=True))
+    # the library's own predictor (its predicted state lives in the array too)
+    wl = make_workload(SHAPES["c2"].with_(tokens=10, seed=8))
+    ref = _run(wl, [1], static=False, prefetch_max=2, auto_prefetch=1)
+    _same(ref, _run(wl, [1], static=True, prefetch_max=2, auto_prefetch=1))
+    assert ref[2]["prefetches"] > 0
     # the selection as a launch of its own (reads the gate partial sums from the array)
     wl = make_workload(SHAPES["c2"].with_(tokens=8, seed=6))
     import os
