@@ -67,6 +67,55 @@ def run_tokens(ses, x_dev, y_dev, t0: int, t1: int, n_layers: int, xp_dev=None) 
             ses.decode(l, x_dev[t, l], y_dev[l])
 
 
+def run_tokens_chained(ses, x_dev, y_dev, t0: int, t1: int, n_layers: int) -> None:
+    """Chained input mode: layer 0 of a token takes the workload's input, layer
+    l+1 the RMS-normalised x_l + y_l (the stand-in for the blocks between two
+    MoE layers, a few torch kernels on the library's compute stream).  With
+    cfg.auto_prefetch the library predicts that state itself, from the partial
+    output, while the layer's loads are still in flight (Section IV-C)."""
+    import torch
+    from smoe_inputs import chain_next_input
+    with torch.cuda.stream(ses.stream_compute):
+        for t in range(t0, t1):
+            x = x_dev[t, 0]
+            for l in range(n_layers):
+                ses.decode(l, x, y_dev[l])
+                x = chain_next_input(x, y_dev[l]).to(x_dev.dtype)
+
+
+def predictor_reading(wl, Bt: int, L: int, warmup: int, steps: int, prefetch_max: int) -> dict:
+    """Chained inputs, once without prefetch and once with the library's own
+    predictor; the prefetch counters over the timed tokens next to the accuracy
+    the paper reports for its predictor (Section VI-C)."""
+    import torch
+    from paper_2508_18983_amd.session import session_from_workload
+    s = wl.shape
+    out = {"inputs": "chained (layer l+1 input = RMS-normalised x_l + y_l)", "prefetch_max": prefetch_max,
+           "paper_top_score_accuracy": 0.82, "paper_active_accuracy": 0.95}
+    for key, auto in (("off", 0), ("own_predictor", 1)):
+        with session_from_workload(wl, max_batch=Bt, n_stage=(Bt * s.top_k if Bt > 1 else 0),
+                                   prefetch_max=prefetch_max if auto else 0, auto_prefetch=auto) as ses:
+            x_dev = wl.x.to(ses.device).contiguous()
+            y_dev = torch.empty(L, Bt, s.hidden, dtype=ses.tdtype, device=ses.device)
+            run_tokens_chained(ses, x_dev, y_dev, 0, warmup, L)
+            ses.sync()
+            st0 = ses.stats()
+            t_begin = time.perf_counter()
+            run_tokens_chained(ses, x_dev, y_dev, warmup, warmup + steps, L)
+            ses.sync()
+            dt = time.perf_counter() - t_begin
+            st1 = ses.stats()
+        st = {k: st1[k] - st0[k] for k in st1}
+        r = {"tokens_per_s": steps * Bt / dt, "hit_rate": st["hits"] / max(st["slots"], 1),
+             "loads_per_step": st["fetches"] / steps}
+        if auto:
+            r.update(prefetches_per_step=st["prefetches"] / steps,
+                     prefetched_and_computed_frac=st["prefetch_used"] / max(st["prefetches"], 1),
+                     prefetched_and_top_score_frac=st["prefetch_top"] / max(st["prefetches"], 1))
+        out[key] = r
+    return out
+
+
 PROF_RESIDENT_AND_COPY = (1 << 1) | (1 << 2) | (1 << 3)      # up, down (resident pass), copies
 PROF_ALL = (1 << 6) - 1
 
@@ -273,6 +322,14 @@ def measure(args, workload: str, steps: int, warmup: int, repeats: int, headline
                                   "c_load_us": costs["c_load_us"], "c_cpu_us": costs["c_cpu_us"]}
                 except Exception as exc:
                     extra[key] = {"error": repr(exc)}
+        if headline and args.predictor > 0 and not cpu_assist and prefetch == 0:
+            log("chained inputs, the library's own predictor ...")
+            try:
+                torch.cuda.empty_cache()
+                extra["predictor_chained_inputs"] = predictor_reading(wl, Bt, L, min(warmup, 16), min(steps, 32),
+                                                                      args.predictor)
+            except Exception as exc:
+                extra["predictor_chained_inputs"] = {"error": repr(exc)}
         out["extra"] = extra
         if headline and args.cpu_budget > 0:
             log("timing the CPU oracle ...")
@@ -341,6 +398,9 @@ def main() -> int:
                     help="override the workload's HBM cache capacity per layer (diagnostic only)")
     ap.add_argument("--prefetch", type=int, default=0,
                     help="experts a top-score prefetch may load per layer (0 = off, the headline setting)")
+    ap.add_argument("--predictor", type=int, default=2,
+                    help="experts per layer the library's own predictor may prefetch in the extra chained-input "
+                         "reading (extra.predictor_chained_inputs; 0 = skip that reading)")
     ap.add_argument("--cpu-assist", type=int, nargs="?", const=1, default=0,
                     help="CPU-assisted task load scheduling with measured costs: part of the misses is computed "
                          "by the host cores instead of being loaded.  1 = Algorithm 2, 2 = min-max split "

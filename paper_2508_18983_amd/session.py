@@ -161,6 +161,9 @@ class DecodeSession:
                 B.moe_host_free(ptr)
         self._owned_pinned = []
         self.experts_host = []
+        # the HBM cache slab goes back to the allocator with the handle (a closed session
+        # that is still referenced must not keep tens of GB of device memory)
+        self.slab = None
 
     def __enter__(self):
         return self

@@ -52,6 +52,17 @@ def _to_f64(t: torch.Tensor) -> np.ndarray:
     return t.to(torch.float64).numpy()
 
 
+def chain_next_input(x: torch.Tensor, y: torch.Tensor) -> torch.Tensor:
+    """Chained input mode: the next MoE layer's input from this layer's input x
+    and output y, both [B, H].  The blocks between two MoE layers (attention,
+    norms) are outside this path; their stand-in is the RMS-normalised residual
+    sum z / rms(z), z = x + y, per token.  Computed in fp64 when y is fp64 (the
+    tests' checking side), else in fp32; the caller rounds to the storage type."""
+    acc = torch.float64 if y.dtype == torch.float64 else torch.float32
+    z = x.to(acc) + y.to(acc)
+    return z * torch.rsqrt(z.square().mean(dim=-1, keepdim=True))
+
+
 def logit_margin_ok(logits: np.ndarray, k: int, alpha: float,
                     delta: float = LOGIT_DELTA) -> np.ndarray:
     """Row-wise audit of gate logits [N, E]: True where every comparison the

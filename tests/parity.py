@@ -128,10 +128,12 @@ def run_parity(wl, *, y_every=1, tokens=None, session_kw=None, oracle_kw=None, b
 
 
 def rms_chain(x_rows, y_rows):
-    """Input of the next MoE layer in the chained mode: the RMS-normalised residual
-    sum, per token (a stand-in for the blocks between two MoE layers)."""
-    z = np.asarray(x_rows, np.float64) + np.asarray(y_rows, np.float64)
-    return z / np.sqrt(np.mean(z * z, axis=1, keepdims=True))
+    """Input of the next MoE layer in the chained mode (smoe_inputs.chain_next_input
+    on fp64 rows): the RMS-normalised residual sum, per token."""
+    import torch
+    from smoe_inputs import chain_next_input
+    return chain_next_input(torch.from_numpy(np.asarray(x_rows, np.float64)),
+                            torch.from_numpy(np.asarray(y_rows, np.float64))).numpy()
 
 
 def run_chained_with_predictor(wl, *, prefetch_max, tokens=None, batch=None, session_kw=None, label=""):
