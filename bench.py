@@ -350,6 +350,9 @@ def summarise(m: dict, steps: int) -> dict:
     st, prof = m["st"], m["prof"]
     n_steps = steps * len(m["times"])
     names = KERNEL_NAMES.get(s.name, ("ffn_up kernel (resident pass)", "ffn_down kernel (resident pass)"))
+    if Bt > 1:      # batched steps run the grouped kernels (bf16: on the matrix cores)
+        names = (("ffn_up_mfma_kernel<0>", "ffn_down_mfma_kernel<0>") if s.dtype == "bf16"
+                 else ("ffn_up_grp_kernel<float, 0>", "ffn_down_grp_kernel<float, 0>"))
     up = kernel_block(prof["up"], names[0], m["event_pair_us"])
     down = kernel_block(prof["down"], names[1], m["event_pair_us"])
     both_bytes = up["bytes_per_launch"] + down["bytes_per_launch"]
@@ -473,7 +476,7 @@ def main() -> int:
     if others:
         extra["other_workloads"] = others
 
-    ratio = MEASURED_TRAFFIC_RATIO.get(s.name)
+    ratio = MEASURED_TRAFFIC_RATIO.get(s.name) if Bt == 1 else None      # counters were read at batch 1
     out = {
         "metric": f"decode tokens/s at batch {Bt} (full MoE stack)",
         "value": res["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1,

@@ -804,13 +804,19 @@ __global__ __launch_bounds__(256) void ffn_down_grp_kernel(const FfnArgs a) {
 // tokens per expert the product W2[rows, cols] x act[cols, tokens] is a real
 // contraction; on the vector ALUs it costs one cross-lane reduction per (row,
 // token), on MFMA none.  A block owns 16 output rows (the M of the 16x16x32
-// tile), the 16 tile columns are the step's tokens (column j = token j), K runs
-// over an item = (task, 256-column segment).  The eight waves take items
-// round-robin; each stages its 16 x 256 weight tile through a private, padded
-// LDS region (coalesced 128-bit global loads in, MFMA operand order out), takes
-// the activations as two bf16 terms (hi + lo) written by the up kernel, and
-// accumulates ONE 16 x 16 fp32 tile over all of its items.  The eight tiles are
-// then added in wave order.
+// tile), K runs over an item = (task, 256-column segment).  The activations
+// come as two bf16 terms (hi + lo) written by the up kernel; with at most 8
+// tokens per step both fit the 16 tile columns: column j holds the hi terms of
+// token j, column 8 + j its lo terms, so ONE MFMA per K-step multiplies both and
+// the two halves of the result tile are added in the epilogue.  The eight waves
+// take items round-robin; each stages its 16 x 256 weight tile through a
+// private, padded LDS region (coalesced 128-bit global loads in, MFMA operand
+// order out) and accumulates one 16 x 16 fp32 tile over all of its items.  The
+// activations of the next item and the weight tiles of the next two are in
+// flight while an item is multiplied (loads retire in order, so an activation
+// load that is waited for must be older than the tiles meant to stay in flight).
+// The eight tiles are then added in wave order.
+static_assert(SMOE_MAX_BATCH <= 8, "hi and lo terms of every token share the 16 tile columns");
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 constexpr int kMfmaCols = 256;                  // columns per item
 constexpr int kMfmaRowBytes = 2 * kMfmaCols + 16;   // staged row + pad against bank conflicts
@@ -914,7 +920,8 @@ __global__ __launch_bounds__(64 * kMfmaUpWaves) void ffn_up_mfma_kernel(const Ff
 template <int PASS>
 __global__ __launch_bounds__(64 * kMfmaWaves) void ffn_down_mfma_kernel(const FfnArgs a) {
   extern __shared__ __align__(16) unsigned char lds[];
-  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // item bookkeeping stays on the scalar unit
   const int i16 = lane & 15, g4 = lane >> 4;     // tile row / column index, K sub-block
   const int H = a.H;
   const int hb = blockIdx.x * 16;
@@ -957,26 +964,32 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void ffn_down_mfma_kernel(const Ff
   // One item: where its 16 x 256 weight tile and this lane's activation row live.
   struct Item {
     const bf16_t* w2;        // W2 + c0 of row 0 of the matrix
-    const uint16_t* arow;    // hi terms of my token's activation row (lo terms F further), at c0
-    int F, ncols, pos;
+    const uint16_t* arow;    // my tile column's terms of the activation row (hi, or lo F further), at c0;
+                             // null when my column's token is not in the task's list
+    int F, ncols;
     bool valid;
   };
   auto describe = [&](int it) -> Item {
-    Item d{nullptr, nullptr, 0, 0, -1, false};
+    Item d{nullptr, nullptr, 0, 0, false};
     // skip forward over items whose task is not part of this pass
     for (; it < n_items; it += kMfmaWaves) {
       int task, seg;
       if (it < items_r) { task = it / nsegR; seg = it - task * nsegR; }
       else { const int q = it - items_r; const int sidx = q / nsegS; seg = q - sidx * nsegS; task = a.maxg + sidx; }
       const TaskEnt& e = ttab[task];
-      if (e.w2 == nullptr) continue;
+      // the entry is the same for the whole wave: pointer and width go to scalar registers
+      const unsigned long long w2_bits = reinterpret_cast<unsigned long long>(e.w2);
+      const unsigned w2_lo = __builtin_amdgcn_readfirstlane((unsigned)w2_bits);
+      const unsigned w2_hi = __builtin_amdgcn_readfirstlane((unsigned)(w2_bits >> 32));
+      if ((w2_lo | w2_hi) == 0u) continue;
+      const int eF = __builtin_amdgcn_readfirstlane(e.F);
       const int c0 = seg * kMfmaCols;
-      const int pos = e.pos_of_tok[i16];
-      d.F = e.F;
-      d.ncols = min(kMfmaCols, e.F - c0);
-      d.w2 = reinterpret_cast<const bf16_t*>(e.w2) + c0;
-      d.arow = reinterpret_cast<const uint16_t*>(e.act + (size_t)max(pos, 0) * e.F) + c0;
-      d.pos = pos;
+      const int pos = e.pos_of_tok[i16 & 7];
+      d.F = eF;
+      d.ncols = min(kMfmaCols, eF - c0);
+      d.w2 = reinterpret_cast<const bf16_t*>(((unsigned long long)w2_hi << 32) | w2_lo) + c0;
+      d.arow = pos >= 0 ? reinterpret_cast<const uint16_t*>(e.act + (size_t)pos * eF) + (i16 >> 3) * eF + c0
+                        : nullptr;
       d.valid = true;
       break;
     }
@@ -993,61 +1006,60 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void ffn_down_mfma_kernel(const Ff
                     : u32x4{};
     }
   };
-
-  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  u32x4 bhi[8], blo[8];
-  // activations of my token for item d (hi and lo terms, 8 K-steps of 8 columns each), then
-  // the item's weight tile from registers to LDS (row r at r * kMfmaRowBytes)
-  auto stage_item = [&](const Item& d, const u32x4 (&wreg)[8]) {
+  // B operand of item d for this lane: 8 K-steps of 8 columns of my token's hi (tile
+  // columns 0..7) or lo (columns 8..15) terms
+  auto load_act = [&](const Item& d, u32x4 (&areg)[8]) {
 #pragma unroll
     for (int st = 0; st < 8; ++st) {
       const int col = 32 * st + 8 * g4;
-      if (d.pos >= 0 && col < d.ncols) {
-        bhi[st] = *reinterpret_cast<const u32x4*>(d.arow + col);
-        blo[st] = *reinterpret_cast<const u32x4*>(d.arow + d.F + col);
-      } else {
-        bhi[st] = u32x4{};
-        blo[st] = u32x4{};
-      }
+      areg[st] = (d.arow != nullptr && col < d.ncols) ? *reinterpret_cast<const u32x4*>(d.arow + col)
+                                                          : u32x4{};
     }
+  };
+  // the item's weight tile from registers to LDS (row r at r * kMfmaRowBytes)
+  auto stage_tile = [&](const u32x4 (&wreg)[8]) {
 #pragma unroll
     for (int q = 0; q < 8; ++q)
       *reinterpret_cast<u32x4*>(stage + (2 * q + rsub) * kMfmaRowBytes + unit * 16) = wreg[q];
     __builtin_amdgcn_wave_barrier();
   };
-  auto multiply_staged = [&]() {
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  auto multiply_staged = [&](const u32x4 (&areg)[8]) {
 #pragma unroll
     for (int st = 0; st < 8; ++st) {
       const u32x4 af = *reinterpret_cast<const u32x4*>(stage + i16 * kMfmaRowBytes + (4 * st + g4) * 16);
-      const bf16x8 av = __builtin_bit_cast(bf16x8, af);
-      const u32x4 h4 = bhi[st], l4 = blo[st];
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, h4), acc, 0, 0, 0);
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, l4), acc, 0, 0, 0);
+      const u32x4 b4 = areg[st];
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af), __builtin_bit_cast(bf16x8, b4),
+                                                    acc, 0, 0, 0);
     }
     __builtin_amdgcn_wave_barrier();
   };
-  // Two items ahead: while item i is multiplied, the tiles of items i+1 and i+2 are on
-  // their way (two register sets, used alternately), i.e. 16 KB per wave in flight.
-  u32x4 wa[8], wb[8];
+  // Issue order per item: activations of the next item, then the tile two items ahead; the
+  // multiply then waits for activations issued a whole item earlier and leaves both tiles
+  // (16 KB per wave) in flight.
+  u32x4 wa[8], wb[8], aa[8], ab[8];
   Item i0 = describe(wave);
   load_tile(i0, wa);
+  load_act(i0, aa);
   Item i1 = describe(next_it + kMfmaWaves);
   load_tile(i1, wb);
   while (i0.valid) {
-    stage_item(i0, wa);
+    stage_tile(wa);
+    load_act(i1, ab);
     const Item i2 = describe(next_it + kMfmaWaves);
     load_tile(i2, wa);
-    multiply_staged();
+    multiply_staged(aa);
     if (!i1.valid) break;
-    stage_item(i1, wb);
+    stage_tile(wb);
+    load_act(i2, aa);
     const Item i3 = describe(next_it + kMfmaWaves);
     load_tile(i3, wb);
-    multiply_staged();
+    multiply_staged(ab);
     i0 = i2;
     i1 = i3;
   }
 
-  // ---- add the eight tiles in wave order; lane holds rows 4*g4 + r, column i16 ----
+  // ---- add the eight tiles in wave order (hi half, then lo half); lane holds rows 4*g4 + r, column i16 ----
   __syncthreads();
   float* red = reinterpret_cast<float*>(lds);           // [wave][16 rows][16 cols]
 #pragma unroll
@@ -1061,7 +1073,7 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void ffn_down_mfma_kernel(const Ff
     for (int q = 0; q < a.k; ++q) any_miss |= (a.rec->tok[t].slot[q] < 0);
     if (PASS == 1 && !any_miss) continue;
     float sum = 0.f;
-    for (int w = 0; w < kMfmaWaves; ++w) sum += red[(w * 16 + row) * 16 + t];
+    for (int w = 0; w < kMfmaWaves; ++w) sum += red[(w * 16 + row) * 16 + t] + red[(w * 16 + row) * 16 + 8 + t];
     bf16_t* y = static_cast<bf16_t*>(a.y) + (size_t)t * H;
     float* ysum = a.ysum + (size_t)t * H;
     if (PASS == 0) {
