@@ -92,9 +92,10 @@ def predictor_reading(wl, Bt: int, L: int, warmup: int, steps: int, prefetch_max
     s = wl.shape
     out = {"inputs": "chained (layer l+1 input = RMS-normalised x_l + y_l)", "prefetch_max": prefetch_max,
            "paper_top_score_accuracy": 0.82, "paper_active_accuracy": 0.95}
-    for key, auto in (("off", 0), ("own_predictor", 1)):
+    for key, auto, yld in (("off", 0, 0), ("own_predictor", 1, 0), ("own_predictor_yielding_to_a_busy_link", 1, 1)):
         with session_from_workload(wl, max_batch=Bt, n_stage=(Bt * s.top_k if Bt > 1 else 0),
-                                   prefetch_max=prefetch_max if auto else 0, auto_prefetch=auto) as ses:
+                                   prefetch_max=prefetch_max if auto else 0, auto_prefetch=auto,
+                                   prefetch_yield=yld) as ses:
             x_dev = wl.x.to(ses.device).contiguous()
             y_dev = torch.empty(L, Bt, s.hidden, dtype=ses.tdtype, device=ses.device)
             run_tokens_chained(ses, x_dev, y_dev, 0, warmup, L)
@@ -268,6 +269,7 @@ def measure(args, workload: str, steps: int, warmup: int, repeats: int, headline
     try:
         with session_from_workload(wl, max_batch=Bt, n_stage=(Bt * s.top_k if Bt > 1 else 0),
                                    prefetch_max=prefetch, cpu_assist=cpu_assist,
+                                   prefetch_yield=int(args.prefetch_yield and prefetch > 0),
                                    cpu_threads=args.cpu_threads) as ses:
             x_dev = wl.x.to(ses.device).contiguous()
             xp_dev = wl.x_pred.to(ses.device).contiguous() if prefetch > 0 else None
@@ -404,6 +406,8 @@ def main() -> int:
     ap.add_argument("--predictor", type=int, default=2,
                     help="experts per layer the library's own predictor may prefetch in the extra chained-input "
                          "reading (extra.predictor_chained_inputs; 0 = skip that reading)")
+    ap.add_argument("--prefetch-yield", type=int, default=0,
+                    help="1: predictions are skipped while earlier copies are still on the host link")
     ap.add_argument("--cpu-assist", type=int, nargs="?", const=1, default=0,
                     help="CPU-assisted task load scheduling with measured costs: part of the misses is computed "
                          "by the host cores instead of being loaded.  1 = Algorithm 2, 2 = min-max split "
@@ -489,6 +493,7 @@ def main() -> int:
                    "zipf_s": s.zipf_s, "seed": s.seed, "evict_policy": s.evict_policy,
                    "cpu_assist": int(args.cpu_assist), "prefetch_max": args.prefetch,
                    "prefetch_ahead": PREFETCH_AHEAD if args.prefetch > 0 else None,
+                   "prefetch_yield": args.prefetch_yield if args.prefetch > 0 else None,
                    "pred_noise": args.pred_noise if args.prefetch > 0 else None,
                    "timed_repeats": len(m["times"]), "reported": "median repeat",
                    "host_expert_storage": m["host_note"]},

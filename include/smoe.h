@@ -129,6 +129,13 @@ typedef struct {
                             moe_prefetch_layer call with that state would; the decision
                             is taken when layer l+1 is decoded.  0: predictions come
                             from the caller through moe_prefetch_layer only           */
+  int32_t prefetch_yield;/* 1: a prediction is skipped when, at the moment it would be
+                            launched, copies of earlier calls (on-demand loads or
+                            prefetches) are still on the host link: with the link as
+                            the bottleneck a prefetch cannot arrive early and every
+                            misprediction costs link time.  Such a call is reported by
+                            moe_prefetch_last with yielded = 1 and prefetches nothing.
+                            0: every prediction is taken (the paper's behaviour)       */
 } moe_cfg_t;
 
 typedef struct {
@@ -207,7 +214,8 @@ typedef struct {
   int32_t n_loaded;                                    /* how many of them were put on the
                                                           load queue (a prefix of wanted)  */
   int32_t wanted[SMOE_MAX_BATCH * SMOE_MAX_TOPK];      /* in load order                    */
-  int32_t pad_;
+  int32_t yielded;                                     /* 1: skipped because the link was busy
+                                                          (cfg.prefetch_yield)             */
   int64_t bytes_copied;                                /* prefetch bytes handed to the copy
                                                           stream since init / reset        */
   int64_t bytes_withdrawn;                             /* bytes of dropped prefetches that

@@ -31,7 +31,7 @@ class MoeCfg(C.Structure):
         "shared_ffn", "dtype", "max_batch")] + [("alpha", C.c_float)] + [(n, C.c_int32) for n in (
         "subst_key", "renorm_topk", "evict_window", "n_stage", "evict_policy", "prefetch_max",
         "cpu_assist", "cpu_threads")] + [("load_cost_us", C.c_float), ("cpu_cost_us", C.c_float),
-                                            ("auto_prefetch", C.c_int32)]
+                                            ("auto_prefetch", C.c_int32), ("prefetch_yield", C.c_int32)]
 
 
 class MoeBuffers(C.Structure):
@@ -60,7 +60,7 @@ class MoeStats(C.Structure):
 
 class MoePrefetchInfo(C.Structure):
     _fields_ = [("layer", C.c_int32), ("n_wanted", C.c_int32), ("n_loaded", C.c_int32),
-                ("wanted", C.c_int32 * 64), ("pad_", C.c_int32),
+                ("wanted", C.c_int32 * 64), ("yielded", C.c_int32),
                 ("bytes_copied", C.c_int64), ("bytes_withdrawn", C.c_int64)]
 
     def as_dict(self):

@@ -122,6 +122,7 @@ struct moe_handle {
   int64_t chunk_bytes = 64ll << 20;      // SMOE_PF_CHUNK_MB (smaller chunks cost more in submission
                                          // overhead than they gain: measured 16 MB -> 64 MB +3-5 %)
   int64_t pf_bytes_submitted = 0, pf_bytes_withdrawn = 0;
+  int64_t pf_yielded = 0;                // predictions skipped because the link was busy
   std::vector<int32_t> slot_guard;       // per global slot: number of the decode call whose kernels may
                                          // still read a slot that has been given up since (-1: none)
   moe_prefetch_info_t pf_last{};
@@ -531,6 +532,31 @@ uint64_t prefetches_in_flight(moe_handle* h, int layer) {
   return m;
 }
 
+// Are copies of earlier calls still on the host link (on-demand loads, chunks of queued
+// prefetches, or prefetches not yet handed over)?  With cfg.prefetch_yield a prediction that
+// would be launched now is skipped then.
+bool link_busy(moe_handle* h) {
+  for (auto& e : h->pf_entries) {
+    if (!e.all_submitted) return true;
+    if (hipEventQuery(e.done) != hipSuccess) { (void)hipGetLastError(); return true; }
+  }
+  for (int i = 0; i < moe_handle::kMaxChunksOut; ++i) {
+    if (!h->chunk_busy[i]) continue;
+    if (hipEventQuery(h->chunk_ev[i]) != hipSuccess) { (void)hipGetLastError(); return true; }
+  }
+  if (hipEventQuery(h->ev_copy) != hipSuccess) { (void)hipGetLastError(); return true; }   // (never recorded: ready)
+  return false;
+}
+
+// A prediction for `layer` that is not made because the link is busy.
+void note_yielded_prefetch(moe_handle* h, int layer) {
+  h->pf_last = moe_prefetch_info_t{};
+  h->pf_last.layer = layer;
+  h->pf_last.yielded = 1;
+  for (int i = 0; i < SMOE_MAX_BATCH * SMOE_MAX_TOPK; ++i) h->pf_last.wanted[i] = -1;
+  ++h->pf_yielded;
+}
+
 // Take the decision of a pending prefetch (Section IV-C): read the predicted
 // scores, pick what to load, put it on the load queue.  The prediction kernels
 // precede every kernel launched since the prefetch call on the compute stream,
@@ -553,6 +579,7 @@ int settle_prefetch(moe_handle* h) {
   PrefetchPlan pp;
   h->layers[layer].plan_prefetch(h->cp, dec, pp);
   h->pf_last.layer = layer;
+  h->pf_last.yielded = 0;
   h->pf_last.n_wanted = pp.n_wanted;
   h->pf_last.n_loaded = pp.n;
   for (int i = 0; i < SMOE_MAX_BATCH * SMOE_MAX_TOPK; ++i) h->pf_last.wanted[i] = i < pp.n_wanted ? pp.wanted[i] : -1;
@@ -770,6 +797,7 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
   if (c.prefetch_max < 0 || c.prefetch_max > SMOE_MAX_BATCH * SMOE_MAX_TOPK - 1) return SMOE_EINVAL;
   if (c.cpu_assist < 0 || c.cpu_assist > 2 || c.cpu_threads < 0 || c.cpu_threads > 256) return SMOE_EINVAL;
   if (c.auto_prefetch < 0 || c.auto_prefetch > 1 || (c.auto_prefetch && c.prefetch_max < 1)) return SMOE_EINVAL;
+  if (c.prefetch_yield < 0 || c.prefetch_yield > 1) return SMOE_EINVAL;
   if (!buf->gate_w_dev || !buf->experts_host || !buf->sim_host || !buf->cache_slab_dev) return SMOE_EINVAL;
   if (c.n_shared > 0 && !buf->shared_dev) return SMOE_EINVAL;
   if (buf->stream_compute == buf->stream_copy) return SMOE_EINVAL;
@@ -987,6 +1015,9 @@ static int decode_layer_with(moe_handle_t* h, const Scratch& sc, int32_t layer, 
       const int rc = settle_prefetch(h);                // one prediction may wait at a time
       if (rc != SMOE_OK) return rc;
     }
+    if (c.prefetch_yield && link_busy(h)) {
+      note_yielded_prefetch(h, layer + 1);
+    } else {
     launch_predict_state(sc.rec, x_dev, y_dev, sc.ysum, sc.x_pred, B, c.hidden, c.top_k, c.dtype, h->s_compute);
     RouteArgs pa{};
     fill_route_args(h, sc, layer + 1, B, sc.x_pred, pa);
@@ -998,6 +1029,7 @@ static int decode_layer_with(moe_handle_t* h, const Scratch& sc, int32_t layer, 
     HIP_TRY(hipGetLastError());
     h->pending_layer = layer + 1;
     h->pending_batch = B;
+    }
   }
 
   // ---- the decision reaches the host: poll the pinned mirror (the router kernel
@@ -1124,6 +1156,10 @@ int moe_prefetch_layer(moe_handle_t* h, int32_t layer, int32_t batch, const void
     const int rc = settle_prefetch(h);      // one prediction may wait at a time
     if (rc != SMOE_OK) return rc;
   }
+  if (c.prefetch_yield && link_busy(h)) {
+    note_yielded_prefetch(h, layer);
+    return SMOE_OK;
+  }
   // The prediction is the router kernel itself on the predicted hidden state,
   // writing to a record of its own; only its scores and top-k are used.
   RouteArgs ra{};
@@ -1202,6 +1238,7 @@ int moe_cache_reset(moe_handle_t* h) {
   h->pf_entries.clear();
   for (bool& b : h->chunk_busy) b = false;
   h->pf_bytes_submitted = h->pf_bytes_withdrawn = 0;
+  h->pf_yielded = 0;
   std::fill(h->slot_guard.begin(), h->slot_guard.end(), -1);
   return upload_initial(h);
 }

@@ -89,7 +89,8 @@ class DecodeSession:
                    alpha=float(shape.alpha), subst_key=shape.subst_key,
                    renorm_topk=shape.renorm_topk, evict_window=shape.evict_window, n_stage=n_stage,
                    evict_policy=getattr(shape, "evict_policy", 0), prefetch_max=0,
-                   cpu_assist=0, cpu_threads=0, load_cost_us=0.0, cpu_cost_us=0.0, auto_prefetch=0)
+                   cpu_assist=0, cpu_threads=0, load_cost_us=0.0, cpu_cost_us=0.0, auto_prefetch=0,
+                   prefetch_yield=0)
         cfg.update(cfg_override)
         self.cfg = B.MoeCfg(**cfg)
         self.expert_bytes = 3 * cfg["hidden"] * cfg["ffn"] * esize
@@ -133,6 +134,11 @@ class DecodeSession:
 
     def prefetch_last(self) -> dict:
         return B.moe_prefetch_last(self.handle).as_dict()
+
+    def prefetch_yielded(self) -> bool:
+        """Was the last prediction skipped because the link was busy (cfg.prefetch_yield)?
+        Like prefetch_last, this takes the decision of a prediction that is still pending."""
+        return bool(B.moe_prefetch_last(self.handle).yielded)
 
     def prefetch_bytes(self) -> dict:
         """Bytes of prefetch copies handed to the copy stream / withdrawn before they were copied."""

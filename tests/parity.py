@@ -50,7 +50,8 @@ def run_parity(wl, *, y_every=1, tokens=None, session_kw=None, oracle_kw=None, b
     if prefetch_max:
         session_kw["prefetch_max"] = prefetch_max
     orc = O.oracle_from_workload(wl, **oracle_kw)
-    worst = dict(l2=0.0, mx=0.0, route_margin=np.inf, evict_margin=np.inf, n_inflight=0, n_inflight_on_cpu=0)
+    worst = dict(l2=0.0, mx=0.0, route_margin=np.inf, evict_margin=np.inf, n_inflight=0, n_inflight_on_cpu=0,
+                 n_yielded=0)
     n_y = 0
     with session_from_workload(wl, max_batch=B, **session_kw) as ses:
         x_dev = wl.x[:T].to(ses.device)
@@ -66,8 +67,13 @@ def run_parity(wl, *, y_every=1, tokens=None, session_kw=None, oracle_kw=None, b
                 tn, ln = divmod(t * s.n_layers + l + 1, s.n_layers)
                 if prefetch_max and tn < T:
                     ses.prefetch(ln, xp_dev[tn, ln])
-                    pf = orc.prefetch_layer(ln, as_numpy(wl.x_pred[tn, ln]), prefetch_max)
-                    worst["route_margin"] = min(worst["route_margin"], pf.route_margin)
+                    # cfg.prefetch_yield: whether the link was busy is a fact of the run; a prediction the
+                    # library skipped for that reason is skipped on the oracle's side too
+                    if session_kw.get("prefetch_yield") and ses.prefetch_yielded():
+                        worst["n_yielded"] += 1
+                    else:
+                        pf = orc.prefetch_layer(ln, as_numpy(wl.x_pred[tn, ln]), prefetch_max)
+                        worst["route_margin"] = min(worst["route_margin"], pf.route_margin)
                 ses.decode(l, x_dev[t, l], y_dev[t, l], tr)
                 want_y = (call % y_every) == 0 if y_tokens is None else t in y_tokens
                 # (which prefetched experts were still in flight is a fact of the run: an input of the oracle)

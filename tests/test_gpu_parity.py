@@ -631,3 +631,39 @@ def test_own_predictor_bf16_is_deterministic_and_consistent():
     st = outs[0][2]
     assert st["prefetches"] > 20 and 0 < st["prefetch_used"] <= st["prefetches"]
     assert st["hits"] + st["misses"] == st["slots"] and torch.isfinite(outs[0][0].view(torch.bfloat16).float()).all()
+
+
+def test_prefetch_that_yields_to_a_busy_link():
+    """cfg.prefetch_yield: a prediction is skipped when copies of earlier calls are
+    still on the link.  Which calls yield depends on timing, so that is fed to the
+    oracle; everything else (lists, adoption, residency, counters, y) must match,
+    and with a link that is never idle at the calls (every call followed at once
+    by the next prefetch) the throttle has to engage."""
+    wl = make_workload(SHAPES["c2"].with_(tokens=24, seed=3), pred_noise=0.3)
+    r = run_parity(wl, prefetch_max=2, session_kw=dict(prefetch_yield=1), label="c2-prefetch-yield")
+    st = r["stats"]
+    print("yielded", r["n_yielded"], "prefetches", st["prefetches"], flush=True)
+    assert r["n_yielded"] + st["prefetches"] > 0
+    import paper_2508_18983_amd as M
+    from paper_2508_18983_amd.session import session_from_workload
+    # free-running (no checking between the calls): a call with misses leaves its loads on the link
+    # when the next prediction is due, so some predictions must be skipped, and none of the others lost
+    s = wl.shape
+    with session_from_workload(wl, prefetch_max=2, prefetch_yield=1) as ses:
+        x = wl.x.to(ses.device); xp = wl.x_pred.to(ses.device)
+        y = torch.empty(s.n_layers, 1, s.hidden, dtype=ses.tdtype, device=ses.device)
+        yielded = made = 0
+        for t in range(s.tokens):
+            for l in range(s.n_layers):
+                tn, ln = divmod(t * s.n_layers + l + 1, s.n_layers)
+                if tn < s.tokens:
+                    ses.prefetch(ln, xp[tn, ln])
+                    made += 1
+                    yielded += int(M.moe_prefetch_last(ses.handle).yielded)
+                ses.decode(l, x[t, l], y[l])
+        ses.sync()
+        free = ses.stats()
+    print("free-running: predictions", made, "yielded", yielded, "misses", free["misses"], flush=True)
+    assert 0 < yielded < made and free["hits"] + free["misses"] == free["slots"]
+    with pytest.raises(M.SmoeError):
+        session_from_workload(wl, prefetch_max=2, prefetch_yield=2)
