@@ -803,8 +803,12 @@ __global__ __launch_bounds__(256) void ffn_down_grp_kernel(const FfnArgs a) {
 // Batch > 1, bf16: down projection + combine on the matrix cores.  With several
 // tokens per expert the product W2[rows, cols] x act[cols, tokens] is a real
 // contraction; on the vector ALUs it costs one cross-lane reduction per (row,
-// token), on MFMA none.  A block owns 16 output rows (the M of the 16x16x32
-// tile), K runs over an item = (task, 256-column segment).  The activations
+// token), on MFMA none.  A block owns RT <= 16 output rows (the M of the
+// 16x16x32 tile is 16: with RT < 16 the last tile rows are neither loaded nor
+// written, their LDS rows hold whatever was there and their results are dropped;
+// RT is chosen so that the grid has at least one block per compute unit, which
+// is what this kernel's rate scales with).  K runs over an item = (task,
+// 256-column segment).  The activations
 // come as two bf16 terms (hi + lo) written by the up kernel; with at most 8
 // tokens per step both fit the 16 tile columns: column j holds the hi terms of
 // token j, column 8 + j its lo terms, so ONE MFMA per K-step multiplies both and
@@ -817,6 +821,17 @@ __global__ __launch_bounds__(256) void ffn_down_grp_kernel(const FfnArgs a) {
 // load that is waited for must be older than the tiles meant to stay in flight).
 // The eight tiles are then added in wave order.
 static_assert(SMOE_MAX_BATCH <= 8, "hi and lo terms of every token share the 16 tile columns");
+
+// 128-bit loads through pointers that are known to point to device memory.  A pointer that went
+// through LDS (the down kernel's task table) has lost its address space; loading through it is a
+// generic ("flat") load, which counts on the vector-memory AND the LDS counter, and the compiler
+// then waits for every outstanding load before the next LDS access: no load stays in flight
+// across an item.  The explicit address space brings back global loads.
+typedef const u32x4 __attribute__((address_space(1)))* global_u32x4_ptr;
+__device__ __forceinline__ u32x4 load_global_stream(const void* p) {
+  return __builtin_nontemporal_load((global_u32x4_ptr)p);
+}
+__device__ __forceinline__ u32x4 load_global(const void* p) { return *(global_u32x4_ptr)p; }
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 constexpr int kMfmaCols = 256;                  // columns per item
 constexpr int kMfmaRowBytes = 2 * kMfmaCols + 16;   // staged row + pad against bank conflicts
@@ -917,14 +932,15 @@ __global__ __launch_bounds__(64 * kMfmaUpWaves) void ffn_up_mfma_kernel(const Ff
   }
 }
 
-template <int PASS>
+template <int PASS, int RT>
 __global__ __launch_bounds__(64 * kMfmaWaves) void ffn_down_mfma_kernel(const FfnArgs a) {
+  static_assert(RT % 2 == 0 && RT >= 2 && RT <= 16, "a block owns RT of the tile's 16 rows, loaded two per instruction");
   extern __shared__ __align__(16) unsigned char lds[];
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // item bookkeeping stays on the scalar unit
   const int i16 = lane & 15, g4 = lane >> 4;     // tile row / column index, K sub-block
   const int H = a.H;
-  const int hb = blockIdx.x * 16;
+  const int hb = blockIdx.x * RT;
   const int n_groups = min(a.rec->n_groups, a.maxg);
   const int nsegR = (a.F + kMfmaCols - 1) / kMfmaCols;
   const int nsegS = a.ns ? (a.Fs + kMfmaCols - 1) / kMfmaCols : 0;
@@ -961,16 +977,21 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void ffn_down_mfma_kernel(const Ff
   }
   __syncthreads();
 
-  // One item: where its 16 x 256 weight tile and this lane's activation row live.
+  // One item: where its 16 x 256 weight tile and this lane's activation row live.  Every load
+  // of the pipeline is issued unconditionally (a load inside a branch makes the number of loads
+  // in flight unknown to the compiler, which then waits for all of them): columns past the end
+  // of a short segment are clamped into it and multiplied by zero activations, an item past the
+  // end of the list reads 16 bytes of the decision record and is never multiplied.
   struct Item {
     const bf16_t* w2;        // W2 + c0 of row 0 of the matrix
-    const uint16_t* arow;    // my tile column's terms of the activation row (hi, or lo F further), at c0;
-                             // null when my column's token is not in the task's list
+    const uint16_t* arow;    // my tile column's terms of the activation row (hi, or lo F further), at c0
     int F, ncols;
+    bool has_tok;            // my column's token is in the task's list
     bool valid;
   };
+  const bf16_t* const dummy_w = reinterpret_cast<const bf16_t*>(a.rec);
   auto describe = [&](int it) -> Item {
-    Item d{nullptr, nullptr, 0, 0, false};
+    Item d{dummy_w, reinterpret_cast<const uint16_t*>(a.rec), 0, 8, false, false};
     // skip forward over items whose task is not part of this pass
     for (; it < n_items; it += kMfmaWaves) {
       int task, seg;
@@ -988,8 +1009,8 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void ffn_down_mfma_kernel(const Ff
       d.F = eF;
       d.ncols = min(kMfmaCols, eF - c0);
       d.w2 = reinterpret_cast<const bf16_t*>(((unsigned long long)w2_hi << 32) | w2_lo) + c0;
-      d.arow = pos >= 0 ? reinterpret_cast<const uint16_t*>(e.act + (size_t)pos * eF) + (i16 >> 3) * eF + c0
-                        : nullptr;
+      d.arow = reinterpret_cast<const uint16_t*>(e.act + (size_t)max(pos, 0) * eF) + (i16 >> 3) * eF + c0;
+      d.has_tok = pos >= 0;
       d.valid = true;
       break;
     }
@@ -997,13 +1018,12 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void ffn_down_mfma_kernel(const Ff
     return d;
   };
   const int unit = lane & 31, rsub = lane >> 5;
-  auto load_tile = [&](const Item& d, u32x4 (&wreg)[8]) {   // 8 coalesced loads, two 512-byte rows each
+  auto load_tile = [&](const Item& d, u32x4 (&wreg)[8]) {   // RT/2 coalesced loads, two 512-byte rows each
+    const int cu = min(unit * 8, d.ncols - 8);
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
+    for (int q = 0; q < RT / 2; ++q) {
       const int r = 2 * q + rsub;
-      wreg[q] = (d.valid && unit * 8 < d.ncols)
-                    ? Unit<bf16_t>::load(d.w2 + (size_t)min(hb + r, H - 1) * d.F + unit * 8)
-                    : u32x4{};
+      wreg[q] = load_global_stream(d.w2 + (size_t)min(hb + r, H - 1) * d.F + cu);
     }
   };
   // B operand of item d for this lane: 8 K-steps of 8 columns of my token's hi (tile
@@ -1012,51 +1032,61 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void ffn_down_mfma_kernel(const Ff
 #pragma unroll
     for (int st = 0; st < 8; ++st) {
       const int col = 32 * st + 8 * g4;
-      areg[st] = (d.arow != nullptr && col < d.ncols) ? *reinterpret_cast<const u32x4*>(d.arow + col)
-                                                          : u32x4{};
+      areg[st] = load_global(d.arow + min(col, d.ncols - 8));
     }
   };
   // the item's weight tile from registers to LDS (row r at r * kMfmaRowBytes)
   auto stage_tile = [&](const u32x4 (&wreg)[8]) {
 #pragma unroll
-    for (int q = 0; q < 8; ++q)
+    for (int q = 0; q < RT / 2; ++q)
       *reinterpret_cast<u32x4*>(stage + (2 * q + rsub) * kMfmaRowBytes + unit * 16) = wreg[q];
     __builtin_amdgcn_wave_barrier();
   };
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  auto multiply_staged = [&](const u32x4 (&areg)[8]) {
+  // (what was loaded for a token outside the task's list or past the end of a short segment is
+  // replaced by zeros here, next to its use: a select right behind the load would wait for it)
+  auto multiply_staged = [&](const u32x4 (&areg)[8], bool has_tok, int ncols) {
 #pragma unroll
     for (int st = 0; st < 8; ++st) {
       const u32x4 af = *reinterpret_cast<const u32x4*>(stage + i16 * kMfmaRowBytes + (4 * st + g4) * 16);
-      const u32x4 b4 = areg[st];
+      const u32x4 b4 = (has_tok && 32 * st + 8 * g4 < ncols) ? areg[st] : u32x4{};
       acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af), __builtin_bit_cast(bf16x8, b4),
                                                     acc, 0, 0, 0);
     }
     __builtin_amdgcn_wave_barrier();
   };
-  // Issue order per item: activations of the next item, then the tile two items ahead; the
-  // multiply then waits for activations issued a whole item earlier and leaves both tiles
-  // (16 KB per wave) in flight.
-  u32x4 wa[8], wb[8], aa[8], ab[8];
-  Item i0 = describe(wave);
-  load_tile(i0, wa);
-  load_act(i0, aa);
-  Item i1 = describe(next_it + kMfmaWaves);
-  load_tile(i1, wb);
-  while (i0.valid) {
-    stage_tile(wa);
-    load_act(i1, ab);
-    const Item i2 = describe(next_it + kMfmaWaves);
-    load_tile(i2, wa);
-    multiply_staged(aa);
-    if (!i1.valid) break;
-    stage_tile(wb);
-    load_act(i2, aa);
-    const Item i3 = describe(next_it + kMfmaWaves);
-    load_tile(i3, wb);
-    multiply_staged(ab);
-    i0 = i2;
-    i1 = i3;
+  // Issue order per item n: activations of item n+1, then the tile of item n+3.  Loads retire in
+  // order, so the multiply's wait for the activations of item n (issued one item earlier) lets the
+  // tiles of items n+2 and n+3 stay in flight: 16 KB per wave during the multiply, and a tile has
+  // two items' time to arrive.  Three tile buffers, two activation buffers, three descriptors,
+  // all indexed at compile time (the loop body is six items).
+  u32x4 wt[3][8], av[2][8];
+  bool av_tok[2];
+  int av_cols[2];
+  Item q[3];
+  q[0] = describe(wave);
+  load_tile(q[0], wt[0]);
+  load_act(q[0], av[0]);
+  av_tok[0] = q[0].has_tok;
+  av_cols[0] = q[0].ncols;
+  q[1] = describe(next_it + kMfmaWaves);
+  load_tile(q[1], wt[1]);
+  q[2] = describe(next_it + kMfmaWaves);
+  load_tile(q[2], wt[2]);
+  bool more = q[0].valid;
+  while (more) {
+#pragma unroll
+    for (int s6 = 0; s6 < 6; ++s6) {
+      const int t3 = s6 % 3, a2 = s6 & 1;
+      stage_tile(wt[t3]);                         // item n (buffer n % 3)
+      load_act(q[(s6 + 1) % 3], av[a2 ^ 1]);      // item n + 1
+      av_tok[a2 ^ 1] = q[(s6 + 1) % 3].has_tok;
+      av_cols[a2 ^ 1] = q[(s6 + 1) % 3].ncols;
+      q[t3] = describe(next_it + kMfmaWaves);     // item n + 3 takes over item n's buffer and descriptor
+      load_tile(q[t3], wt[t3]);
+      multiply_staged(av[a2], av_tok[a2], av_cols[a2]);
+      if (!q[(s6 + 1) % 3].valid) { more = false; break; }
+    }
   }
 
   // ---- add the eight tiles in wave order (hi half, then lo half); lane holds rows 4*g4 + r, column i16 ----
@@ -1065,8 +1095,8 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void ffn_down_mfma_kernel(const Ff
 #pragma unroll
   for (int r = 0; r < 4; ++r) red[(wave * 16 + 4 * g4 + r) * 16 + i16] = acc[r];
   __syncthreads();
-  for (int idx = tid; idx < 16 * a.B; idx += 64 * kMfmaWaves) {
-    const int t = idx >> 4, row = idx & 15;
+  for (int idx = tid; idx < RT * a.B; idx += 64 * kMfmaWaves) {
+    const int t = idx / RT, row = idx - t * RT;
     const int h = hb + row;
     if (h >= H) continue;
     bool any_miss = false;
@@ -1197,15 +1227,24 @@ template <typename T, int PASS>
 static void launch_down_t(const FfnArgs& a, hipStream_t s) {
   if (a.grouped) {
     if (a.mfma_down) {
-      static bool lds_opted_in[2] = {false, false};   // the staging area is larger than the 64 KB default
-      if (!lds_opted_in[PASS]) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_down_mfma_kernel<PASS>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  kMfmaLdsBytes + kMfmaTaskTabBytes);
-        lds_opted_in[PASS] = true;
-      }
-      hipLaunchKernelGGL((ffn_down_mfma_kernel<PASS>), dim3((a.H + 15) / 16), dim3(64 * kMfmaWaves),
-                         kMfmaLdsBytes + kMfmaTaskTabBytes, s, a);
+      // the staging area is larger than the 64 KB default: opt in once per instance
+#define SMOE_MFMA_DOWN_CASE(RT)                                                                              \
+  if (a.mfma_rt == RT) {                                                                                     \
+    static bool opted_in = false;                                                                            \
+    if (!opted_in) {                                                                                         \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_down_mfma_kernel<PASS, RT>),              \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kMfmaLdsBytes + kMfmaTaskTabBytes); \
+      opted_in = true;                                                                                       \
+    }                                                                                                        \
+    hipLaunchKernelGGL((ffn_down_mfma_kernel<PASS, RT>), dim3((a.H + RT - 1) / RT), dim3(64 * kMfmaWaves),   \
+                       kMfmaLdsBytes + kMfmaTaskTabBytes, s, a);                                             \
+    return;                                                                                                  \
+  }
+      SMOE_MFMA_DOWN_CASE(8)
+      SMOE_MFMA_DOWN_CASE(12)
+      SMOE_MFMA_DOWN_CASE(14)
+      SMOE_MFMA_DOWN_CASE(16)
+#undef SMOE_MFMA_DOWN_CASE
       return;
     }
     const int grid = (a.H + a.RBG - 1) / a.RBG;

@@ -122,6 +122,7 @@ struct moe_handle {
   int64_t chunk_bytes = 64ll << 20;      // SMOE_PF_CHUNK_MB (smaller chunks cost more in submission
                                          // overhead than they gain: measured 16 MB -> 64 MB +3-5 %)
   int64_t pf_bytes_submitted = 0, pf_bytes_withdrawn = 0;
+  int mfma_rt = 16;                      // output rows per block of the MFMA down kernel
   int64_t pf_yielded = 0;                // predictions skipped because the link was busy
   std::vector<int32_t> slot_guard;       // per global slot: number of the decode call whose kernels may
                                          // still read a slot that has been given up since (-1: none)
@@ -203,6 +204,16 @@ void plan_geometry(moe_handle* h) {
     const bool lds_ok = items * SMOE_MAX_BATCH * rbg * 4 <= 60 * 1024 && 4L * c.hidden * esz <= 60 * 1024;
     const int xu0 = (c.hidden / n + kWave - 1) / kWave;
     if (lds_ok && xu0 <= 8) { h->grouped_ok = 1; h->RBG = rbg; }
+  }
+
+  // MFMA down kernel: output rows per block.  Its rate scales with the number of compute
+  // units that have a block (measured: 224 blocks of 16 rows at H = 3584 ran at 7/8 of the rate
+  // of 256 blocks at H = 4096), so take the largest row count that still gives every unit one.
+  {
+    const int per_cu = c.hidden / 256;
+    int rt = per_cu >= 16 ? 16 : (per_cu >= 14 ? 14 : (per_cu >= 12 ? 12 : 8));
+    rt = env_int("SMOE_MFMA_RT", rt);
+    h->mfma_rt = (rt == 8 || rt == 12 || rt == 14) ? rt : 16;
   }
 
   // register-resident fast paths (SMOE_REGPATH=0 forces the LDS kernels)
@@ -626,6 +637,7 @@ void fill_ffn_args(const moe_handle* h, const Scratch& sc, int layer, int B, con
   fa.maxg = std::min(c.n_experts, B * c.top_k);
   fa.mfma_down = (fa.grouped && c.dtype == SMOE_DTYPE_BF16 && h->mfma_ok) ? 1 : 0;
   fa.mfma_up = (fa.mfma_down && h->mfma_ok >= 2) ? 1 : 0;
+  fa.mfma_rt = h->mfma_rt;
   fa.nsegGR = h->nsegGR; fa.nsegGS = h->nsegGS; fa.RBG = h->RBG;
   fa.act_shared_off = (int64_t)fa.maxg * SMOE_MAX_BATCH * c.ffn;
   if (fa.grouped && fa.up_upl == 0) {                 // grouped up kernel needs units per lane
