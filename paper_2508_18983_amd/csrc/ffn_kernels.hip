@@ -2,8 +2,9 @@
 // (Section V-B, GPU operations "Direct expert computation" and "New Expert
 // Computation"; shared experts per Section II-A).  Pure weight streaming: every
 // weight element is read once from HBM with non-temporal 128-bit loads, the
-// activation vector sits in LDS, one wavefront owns whole rows and reduces
-// with cross-lane shuffles, accumulation is fp32.
+// activation vector sits in registers (LDS in the fallback kernels), one
+// wavefront owns whole rows and reduces with cross-lane permutes, accumulation
+// is fp32.
 //
 //   up   : act[task][f] = w_task * silu(W1[f].x) * (W3[f].x)
 //   down : y[h] = sum_task sum_f W2[h][f] * act[task][f]
