@@ -20,9 +20,13 @@
  *   scheduling        to the host cores, which compute them from the host copy while
  *                     the others are loaded (Section V-A; Section V-B CPU operations 2, 3)
  *   top-score         optional: the gate of a layer that has not run yet is applied
- *   prefetch          to a predicted hidden state and its top-score experts are
- *                     loaded behind the current layer's own loads (Section IV-C;
+ *   prefetch          to a predicted hidden state (the caller's, or the library's own
+ *                     from the running layer's partial output) and its top-score
+ *                     experts go through a load queue behind the current layer's
+ *                     own loads; mispredicted ones are withdrawn (Section IV-C;
  *                     Section V-B, "Prefetching Experts from Layer i+1")
+ *   alpha selection   the substitution threshold from a latency budget: polynomial
+ *                     fit of measured TPOT, smallest feasible alpha (Section V-C, Eq. 5)
  *
  * All entry points return 0 on success or a negative SMOE_E* code; nothing
  * throws across this boundary.  "device" pointers are HIP device pointers on

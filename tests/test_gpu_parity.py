@@ -152,10 +152,12 @@ def test_batched_decode_cross_token_substitution_and_staging(batch):
         assert r["stats"]["staged"] > 0
 
 
-@pytest.mark.parametrize("env", [dict(), dict(SMOE_MFMA="1"), dict(SMOE_MFMA="0")])
+@pytest.mark.parametrize("env", [dict(), dict(SMOE_MFMA="1"), dict(SMOE_MFMA="0"), dict(SMOE_MFMA_RT="16"),
+                                 dict(SMOE_MFMA_RT="14"), dict(SMOE_MFMA_RT="12")])
 def test_batched_decode_ragged_shapes_matrix_core_and_vector_down_kernels(env, monkeypatch):
-    """bf16 batch with rows and columns that do not fill the 16 x 256 MFMA tiles,
-    and the vector-ALU grouped down kernel it replaces."""
+    """bf16 batch with rows and columns that do not fill the 16 x 256 MFMA tiles
+    (every rows-per-block variant of the MFMA down kernel, with a ragged last
+    block), and the vector-ALU grouped down kernel it replaces."""
     for k_, v in env.items():
         monkeypatch.setenv(k_, v)
     shp = SHAPES["c4"].with_(hidden=264, ffn=520, shared_ffn=72, n_experts=12, top_k=3, cache_cap=5, seed=17)

@@ -101,3 +101,20 @@ def test_predicted_states_are_seeded_audited_and_leave_x_unchanged():
         assert logit_margin_ok(logits, shp.top_k, shp.alpha).all()
     zero = make_workload(shp, pred_noise=0.0)
     assert torch.equal(zero.x_pred, zero.x)
+
+
+def test_chained_input_is_the_unit_rms_residual_sum_in_the_checking_and_the_running_precision():
+    import torch
+    from smoe_inputs import chain_next_input
+    g = torch.Generator().manual_seed(5)
+    x = torch.randn(3, 96, generator=g).to(torch.bfloat16)
+    y64 = torch.randn(3, 96, generator=g, dtype=torch.float64) * 0.1
+    z = x.double() + y64
+    want = z / z.pow(2).mean(dim=1, keepdim=True).sqrt()
+    got64 = chain_next_input(x, y64)
+    assert got64.dtype == torch.float64 and torch.allclose(got64, want, rtol=1e-13, atol=0)
+    got32 = chain_next_input(x, y64.to(torch.bfloat16))          # what a run on the device computes
+    assert got32.dtype == torch.float32
+    z32 = x.double() + y64.to(torch.bfloat16).double()
+    assert torch.allclose(got32.double(), z32 / z32.pow(2).mean(dim=1, keepdim=True).sqrt(), rtol=1e-5)
+    assert torch.allclose(got64.pow(2).mean(dim=1), torch.ones(3, dtype=torch.float64), rtol=1e-13)
