@@ -33,6 +33,10 @@ that depend on a convention alone are "parity unpinned" by the paper:
   prefetches, and that a prefetched expert waits outside the cache set until
   its layer confirms it (the load queue drops the others), are conventions
                                                                -- parity unpinned
+* ``predict_state``: with attention outside this path the predicted input of the
+  next layer is the RMS-normalised sum of the layer's input and its partial
+  output; which prefetched experts are still in flight (and may therefore be
+  handed to the host cores by Algorithm 2) is an input       -- parity unpinned
 
 Inputs are the stored fp32 / bf16 values (bf16 arrives as raw uint16); all
 arithmetic is fp64 with no intermediate rounding.

@@ -234,6 +234,26 @@ def test_c5_full_size_batch8_in_the_benchmark_launch_configuration():
         pinned_free_all()
 
 
+def test_c5_full_size_batch1_in_the_benchmark_launch_configuration():
+    """The configuration the default `bench.py` run times: all 28 layers of the
+    Qwen2-57B-A14B-shaped workload at batch 1 (gate kernel, selection inside the
+    up kernel, register down kernel; 14 pinned layer blocks shared by 28
+    layers): every decision of every call, y on every layer of two whole tokens."""
+    import gc
+    from paper_2508_18983_amd.session import pinned_empty, pinned_free_all
+    wl = make_workload(SHAPES["c5"], device="cuda", tokens=12, host_alloc=pinned_empty, distinct_layers=14)
+    try:
+        r = run_parity(wl, y_tokens={1, 9}, label="c5-full-b1")
+        assert r["n_y"] == 2 * 28
+        assert r["stats"]["substitutions"] > 0 and r["stats"]["misses"] > 0
+        assert r["stats"]["hits"] + r["stats"]["misses"] == 12 * 28 * 8
+    finally:
+        del wl
+        gc.collect()
+        torch.cuda.empty_cache()
+        pinned_free_all()
+
+
 def test_c4_full_size_with_prefetch_and_cpu_assist():
     """All 26 layers of the DeepSeek-V2-Lite-shaped workload (64 routed + 2 shared
     experts, top-6) with every optional stage on: a prefetch before each layer
