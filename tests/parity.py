@@ -142,7 +142,8 @@ def rms_chain(x_rows, y_rows):
                             torch.from_numpy(np.asarray(y_rows, np.float64))).numpy()
 
 
-def run_chained_with_predictor(wl, *, prefetch_max, tokens=None, batch=None, session_kw=None, label=""):
+def run_chained_with_predictor(wl, *, prefetch_max, tokens=None, batch=None, session_kw=None, oracle_kw=None,
+                               label=""):
     """Chained decode with the library's own predictor (cfg.auto_prefetch): only
     layer 0 of a token takes its input from the workload, layer l+1 gets
     x = rms_chain(x_l, y_l) computed from the ORACLE's fp64 output (rounded to the
@@ -154,7 +155,7 @@ def run_chained_with_predictor(wl, *, prefetch_max, tokens=None, batch=None, ses
     T = s.tokens if tokens is None else tokens
     B = s.batch if batch is None else batch
     tdt = torch.float32 if s.dtype == "fp32" else torch.bfloat16
-    orc = O.oracle_from_workload(wl)
+    orc = O.oracle_from_workload(wl, **(oracle_kw or {}))
     worst = dict(l2=0.0, mx=0.0, route_margin=np.inf, evict_margin=np.inf, n_calls=0)
 
     def stored(a64):                                     # fp64 -> storage type, as numpy view
@@ -178,6 +179,7 @@ def run_chained_with_predictor(wl, *, prefetch_max, tokens=None, batch=None, ses
                 assert tr.victims[:tr.n_fetched].tolist() == res.victims, ctx
                 assert tr.adopted[:tr.n_adopted].tolist() == res.adopted, ctx
                 assert tr.adopt_victims[:tr.n_adopted].tolist() == res.adopt_victims, ctx
+                assert tr.on_cpu[:tr.n_on_cpu].tolist() == res.on_cpu, ctx
                 assert ses.residency(l).tolist() == orc.layers[l].slot_expert, ctx
                 worst["route_margin"] = min(worst["route_margin"], res.route_margin)
                 worst["evict_margin"] = min(worst["evict_margin"], res.evict_margin)

@@ -602,7 +602,7 @@ def test_in_flight_prefetches_can_be_taken_over_by_the_host_cores():
 
 
 # ---------------------------------------------------------------- the predictor of Section IV-C on the GPU
-@pytest.mark.parametrize("case", ["c1x4-seed0", "c1x4-seed4", "c4ish-shared"])
+@pytest.mark.parametrize("case", ["c1x4-seed0", "c1x4-seed4", "c4ish-shared", "c1x4-batch3", "c1x4-cpu-assist"])
 def test_chained_decode_with_the_librarys_own_predictor(case):
     """cfg.auto_prefetch: each layer call predicts the next layer's input from its
     partial output (resident + shared experts, before the loaded ones are done),
@@ -611,7 +611,17 @@ def test_chained_decode_with_the_librarys_own_predictor(case):
     predicted state agrees to rounding: prefetch lists, adoption, victims,
     residency and counters must equal the oracle's, y within tolerance."""
     from tests.parity import run_chained_with_predictor
-    if case.startswith("c1x4"):
+    kw = {}
+    if case == "c1x4-batch3":          # grouped kernels, staging, the predicted state of every token
+        shp = SHAPES["c1"].with_(n_layers=4, tokens=8, seed=11, batch=3)
+        pfmax = 2
+        kw = dict(batch=3, session_kw=dict(n_stage=6))
+    elif case == "c1x4-cpu-assist":    # Algorithm 2 with fixed costs: the partial output excludes the host cores' experts
+        shp = SHAPES["c1"].with_(n_layers=4, tokens=10, seed=9, cache_cap=2)
+        pfmax = 2
+        ses_kw, orc_kw = _cpu_kw(2.0, 1.0)
+        kw = dict(session_kw=ses_kw, oracle_kw=orc_kw)
+    elif case.startswith("c1x4"):
         shp = SHAPES["c1"].with_(n_layers=4, tokens=12, seed=int(case[-1]))
         pfmax = 2
     else:
@@ -619,9 +629,11 @@ def test_chained_decode_with_the_librarys_own_predictor(case):
                                  cache_cap=6, n_layers=4, tokens=10, seed=1, prior="normal", sim="uniform")
         pfmax = 3
     wl = make_workload(shp)
-    r = run_chained_with_predictor(wl, prefetch_max=pfmax, label=case)
+    r = run_chained_with_predictor(wl, prefetch_max=pfmax, label=case, **kw)
     st = r["stats"]
     assert st["prefetches"] >= 8 and st["prefetch_used"] > 0 and r["n_calls"] == shp.tokens * 4
+    if case == "c1x4-cpu-assist":
+        assert st["cpu_computed"] > 0
 
 
 def test_own_predictor_bf16_is_deterministic_and_consistent():
