@@ -76,6 +76,14 @@ template <> struct Unit<bf16_t> {
   }
 };
 
+// Keeps the loads written above this point above it in the instruction stream.  Without it the
+// compiler may sink each load next to its first use to save registers, which turns "all loads
+// of a row in flight, then the arithmetic" into one load at a time.
+__device__ __forceinline__ void loads_issued_before_here() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
+}
+
 // Weights of task (t, j): null when the task is not part of this pass.
 // PASS 0: routed slots whose expert is resident + shared experts; PASS 1: the
 // slots whose expert has just been loaded (slot_override >= 0).  The pass is a
@@ -378,18 +386,18 @@ __global__ __launch_bounds__(256) void ffn_up_reg_kernel(const FfnArgs a, const 
       const bool live = (i + p < per_wave) && (f + p < F);
       const T* g = W1 + (size_t)(live ? f + p : f) * H;
       const T* up = W3 + (size_t)(live ? f + p : f) * H;
+      // (loads are issued unconditionally: a load inside a branch costs the branch and makes the
+      // number of loads in flight unknown to the compiler.  Columns past the end of the row are
+      // clamped into it and meet zeros in x; a row past the end of the tile repeats row f and
+      // its result is not stored)
 #pragma unroll
       for (int s = 0; s < UPL; ++s) {
-        const int u = s * kWave + lane;
-        if (live && u < units) {
-          qg[p][s] = Unit<T>::load(g + (size_t)u * N);
-          qu[p][s] = Unit<T>::load(up + (size_t)u * N);
-        } else {
-          qg[p][s] = raw{};
-          qu[p][s] = raw{};
-        }
+        const int u = min(s * kWave + lane, units - 1);
+        qg[p][s] = Unit<T>::load(g + (size_t)u * N);
+        qu[p][s] = Unit<T>::load(up + (size_t)u * N);
       }
     }
+    loads_issued_before_here();
 #pragma unroll
     for (int p = 0; p < FPI; ++p) {
       float ag = 0.f, au = 0.f;
@@ -456,37 +464,35 @@ __global__ __launch_bounds__(64 * NW) void ffn_down_reg_kernel(const FfnArgs a) 
     const T* W2 = reinterpret_cast<const T*>(base) + 2 * (size_t)F * H;
     const float* act = a.act + (size_t)(t * nj + j) * a.Fmax;
 
-    // rows rr .. rr+R-1 of the block into one register buffer (rows past H repeat the last one)
+    // Every load below is issued unconditionally (a load inside a branch makes the number of
+    // loads in flight unknown to the compiler, which then waits for all of them and the two
+    // buffers stop overlapping): columns past the end of the segment are clamped into the row
+    // and meet zero activations, rows past H repeat the last one and are not written.
+    float ar[UPL][N];                                   // my slice of the activations, loaded first:
+#pragma unroll                                          // waiting for it must not wait for weight rows
+    for (int i = 0; i < UPL; ++i) {
+      const int u = ubeg + i * kWave + lane;
+      const int uc = min(u, units - 1);
+#pragma unroll
+      for (int e = 0; e < N; e += 4) {
+        const float4 v = *reinterpret_cast<const float4*>(act + (size_t)uc * N + e);
+        const bool in = u < uend;
+        ar[i][e] = in ? v.x : 0.f; ar[i][e + 1] = in ? v.y : 0.f;
+        ar[i][e + 2] = in ? v.z : 0.f; ar[i][e + 3] = in ? v.w : 0.f;
+      }
+    }
+    // rows rr .. rr+R-1 of the block into one register buffer
     auto load_rows = [&](raw (&q)[R][UPL], int rr) {
 #pragma unroll
       for (int r2 = 0; r2 < R; ++r2) {
         const T* row = W2 + (size_t)min(hb + rr + r2, H - 1) * F;
 #pragma unroll
         for (int s2 = 0; s2 < UPL; ++s2) {
-          const int u = ubeg + s2 * kWave + lane;
-          q[r2][s2] = (u < uend) ? Unit<T>::load(row + (size_t)u * N) : raw{};
+          const int u = min(ubeg + s2 * kWave + lane, units - 1);
+          q[r2][s2] = Unit<T>::load(row + (size_t)u * N);
         }
       }
     };
-    raw qa[R][UPL], qb[R][UPL];
-    load_rows(qa, 0);
-    if (R < RB) load_rows(qb, R);
-
-    float ar[UPL][N];
-#pragma unroll
-    for (int i = 0; i < UPL; ++i) {
-      const int u = ubeg + i * kWave + lane;
-      if (u < uend) {
-#pragma unroll
-        for (int e = 0; e < N; e += 4) {
-          const float4 v = *reinterpret_cast<const float4*>(act + (size_t)u * N + e);
-          ar[i][e] = v.x; ar[i][e + 1] = v.y; ar[i][e + 2] = v.z; ar[i][e + 3] = v.w;
-        }
-      } else {
-#pragma unroll
-        for (int e = 0; e < N; ++e) ar[i][e] = 0.f;
-      }
-    }
     auto reduce_rows = [&](const raw (&q)[R][UPL], int rr) {
 #pragma unroll
       for (int r2 = 0; r2 < R; ++r2) {
@@ -502,13 +508,25 @@ __global__ __launch_bounds__(64 * NW) void ffn_down_reg_kernel(const FfnArgs a) 
         if (lane == 0) prow[rr + r2] = acc;
       }
     };
-    for (int rr = 0; rr < RB; rr += 2 * R) {
+    // two buffers, RB / R >= 2 steps: in the steady loop both reloads are unconditional, the last
+    // two or three steps are peeled
+    raw qa[R][UPL], qb[R][UPL];
+    load_rows(qa, 0);
+    load_rows(qb, R);
+    int rr = 0;
+    for (; rr + 3 * R < RB; rr += 2 * R) {
       reduce_rows(qa, rr);
-      if (rr + 2 * R < RB) load_rows(qa, rr + 2 * R);
-      if (rr + R < RB) {
-        reduce_rows(qb, rr + R);
-        if (rr + 3 * R < RB) load_rows(qb, rr + 3 * R);
-      }
+      load_rows(qa, rr + 2 * R);
+      reduce_rows(qb, rr + R);
+      load_rows(qb, rr + 3 * R);
+    }
+    reduce_rows(qa, rr);
+    if (rr + 2 * R < RB) {                              // three steps left
+      load_rows(qa, rr + 2 * R);
+      reduce_rows(qb, rr + R);
+      reduce_rows(qa, rr + 2 * R);
+    } else {
+      reduce_rows(qb, rr + R);
     }
   }
   __syncthreads();

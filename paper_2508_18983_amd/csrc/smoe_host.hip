@@ -249,7 +249,8 @@ void plan_geometry(moe_handle* h) {
     int rb = (c.hidden + 255) / 256;
     rb = std::max(2 * rows_at_once, (rb + rows_at_once - 1) / rows_at_once * rows_at_once);
     rb = env_int("SMOE_RB", rb);
-    rb = std::max(rows_at_once, std::min(256, rb) / rows_at_once * rows_at_once);
+    rb = std::max(2 * rows_at_once, std::min(256, rb) / rows_at_once * rows_at_once);   // the kernel's pipeline
+                                                                                        // needs two steps
     h->down_upl = upl;
     h->down_nw = nw;
     h->down_r = rows_at_once;
@@ -1030,17 +1031,17 @@ static int decode_layer_with(moe_handle_t* h, const Scratch& sc, int32_t layer, 
     if (c.prefetch_yield && link_busy(h)) {
       note_yielded_prefetch(h, layer + 1);
     } else {
-    launch_predict_state(sc.rec, x_dev, y_dev, sc.ysum, sc.x_pred, B, c.hidden, c.top_k, c.dtype, h->s_compute);
-    RouteArgs pa{};
-    fill_route_args(h, sc, layer + 1, B, sc.x_pred, pa);
-    pa.rec_dev = h->pred_dev;
-    pa.rec_host = h->pred_host_dev;
-    pa.seq = ++h->pred_seq;
-    launch_gate_partial(pa, c.dtype, h->s_compute);
-    launch_route_select(pa, h->s_compute);
-    HIP_TRY(hipGetLastError());
-    h->pending_layer = layer + 1;
-    h->pending_batch = B;
+      launch_predict_state(sc.rec, x_dev, y_dev, sc.ysum, sc.x_pred, B, c.hidden, c.top_k, c.dtype, h->s_compute);
+      RouteArgs pa{};
+      fill_route_args(h, sc, layer + 1, B, sc.x_pred, pa);
+      pa.rec_dev = h->pred_dev;
+      pa.rec_host = h->pred_host_dev;
+      pa.seq = ++h->pred_seq;
+      launch_gate_partial(pa, c.dtype, h->s_compute);
+      launch_route_select(pa, h->s_compute);
+      HIP_TRY(hipGetLastError());
+      h->pending_layer = layer + 1;
+      h->pending_batch = B;
     }
   }
 
@@ -1081,12 +1082,10 @@ static int decode_layer_with(moe_handle_t* h, const Scratch& sc, int32_t layer, 
   if (plan.n_fetch > 0 || plan.n_adopted > 0 || plan.n_cpu > 0) {
     // ---- copies the second FFN pass waits for: first the rest of the prefetched experts
     //      this step computes (requested earlier), then the on-demand loads ------------
-    bool adopted_needs_copy_event = false;
     hipEvent_t adopted_done[SMOE_MAX_BATCH * SMOE_MAX_TOPK];
     for (int i = 0; i < plan.n_adopted; ++i) {
       moe_handle::PfEntry* e = find_prefetch_entry(h, layer, plan.adopted[i]);
       if (!e) return SMOE_ESTATE;
-      if (!e->all_submitted) adopted_needs_copy_event = true;
       const int rc = finish_prefetch_entry(h, e);
       if (rc != SMOE_OK) return rc;
       adopted_done[i] = e->done;
@@ -1114,7 +1113,6 @@ static int decode_layer_with(moe_handle_t* h, const Scratch& sc, int32_t layer, 
     } else {
       for (int i = 0; i < plan.n_adopted; ++i) HIP_TRY(hipStreamWaitEvent(h->s_compute, adopted_done[i], 0));
     }
-    (void)adopted_needs_copy_event;
     set_second_pass_slots(h, layer, B, rec, plan, gslot, fa);
     fa.fused_select = 0;
     const int rc = launch_ffn_pair(h, fa, ra, SMOE_PROF_UP_LOADED, SMOE_PROF_DOWN_LOADED, &timed[3], &timed[4]);
