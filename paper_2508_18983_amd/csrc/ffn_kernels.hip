@@ -386,15 +386,19 @@ __global__ __launch_bounds__(256) void ffn_up_reg_kernel(const FfnArgs a, const 
       const bool live = (i + p < per_wave) && (f + p < F);
       const T* g = W1 + (size_t)(live ? f + p : f) * H;
       const T* up = W3 + (size_t)(live ? f + p : f) * H;
-      // (loads are issued unconditionally: a load inside a branch costs the branch and makes the
-      // number of loads in flight unknown to the compiler.  Columns past the end of the row are
-      // clamped into it and meet zeros in x; a row past the end of the tile repeats row f and
-      // its result is not stored)
+      // (no per-lane branches around the loads: columns past the end of the row are clamped into
+      // it and meet zeros in x; a row past the end of the tile repeats row f and its result is
+      // not stored)
 #pragma unroll
       for (int s = 0; s < UPL; ++s) {
-        const int u = min(s * kWave + lane, units - 1);
-        qg[p][s] = Unit<T>::load(g + (size_t)u * N);
-        qu[p][s] = Unit<T>::load(up + (size_t)u * N);
+        if (s * kWave < units) {                       // (the same for the whole wave: a unit slot
+          const int u = min(s * kWave + lane, units - 1);   // no lane needs is not loaded at all)
+          qg[p][s] = Unit<T>::load(g + (size_t)u * N);
+          qu[p][s] = Unit<T>::load(up + (size_t)u * N);
+        } else {
+          qg[p][s] = raw{};
+          qu[p][s] = raw{};
+        }
       }
     }
     loads_issued_before_here();
@@ -464,18 +468,19 @@ __global__ __launch_bounds__(64 * NW) void ffn_down_reg_kernel(const FfnArgs a) 
     const T* W2 = reinterpret_cast<const T*>(base) + 2 * (size_t)F * H;
     const float* act = a.act + (size_t)(t * nj + j) * a.Fmax;
 
-    // Every load below is issued unconditionally (a load inside a branch makes the number of
-    // loads in flight unknown to the compiler, which then waits for all of them and the two
-    // buffers stop overlapping): columns past the end of the segment are clamped into the row
-    // and meet zero activations, rows past H repeat the last one and are not written.
+    // No per-lane branches around the loads: columns past the end of the segment are clamped into
+    // it and meet zero activations, rows past H repeat the last one and are not written.  Only
+    // whole unit slots that no lane needs are skipped, by a branch the whole wave takes together.
     float ar[UPL][N];                                   // my slice of the activations, loaded first:
 #pragma unroll                                          // waiting for it must not wait for weight rows
     for (int i = 0; i < UPL; ++i) {
       const int u = ubeg + i * kWave + lane;
-      const int uc = min(u, units - 1);
+      const int uc = min(u, uend - 1);
+      const bool slot_live = ubeg + i * kWave < uend;   // the same for the whole wave
 #pragma unroll
       for (int e = 0; e < N; e += 4) {
-        const float4 v = *reinterpret_cast<const float4*>(act + (size_t)uc * N + e);
+        float4 v = {0.f, 0.f, 0.f, 0.f};
+        if (slot_live) v = *reinterpret_cast<const float4*>(act + (size_t)uc * N + e);
         const bool in = u < uend;
         ar[i][e] = in ? v.x : 0.f; ar[i][e + 1] = in ? v.y : 0.f;
         ar[i][e + 2] = in ? v.z : 0.f; ar[i][e + 3] = in ? v.w : 0.f;
@@ -488,8 +493,14 @@ __global__ __launch_bounds__(64 * NW) void ffn_down_reg_kernel(const FfnArgs a) 
         const T* row = W2 + (size_t)min(hb + rr + r2, H - 1) * F;
 #pragma unroll
         for (int s2 = 0; s2 < UPL; ++s2) {
-          const int u = min(ubeg + s2 * kWave + lane, units - 1);
-          q[r2][s2] = Unit<T>::load(row + (size_t)u * N);
+          // (a unit slot past the end of the segment is skipped by the whole wave; single lanes
+          // past it re-read the segment's last unit)
+          if (ubeg + s2 * kWave < uend) {
+            const int u = min(ubeg + s2 * kWave + lane, uend - 1);
+            q[r2][s2] = Unit<T>::load(row + (size_t)u * N);
+          } else {
+            q[r2][s2] = raw{};
+          }
         }
       }
     };
@@ -508,8 +519,8 @@ __global__ __launch_bounds__(64 * NW) void ffn_down_reg_kernel(const FfnArgs a) 
         if (lane == 0) prow[rr + r2] = acc;
       }
     };
-    // two buffers, RB / R >= 2 steps: in the steady loop both reloads are unconditional, the last
-    // two or three steps are peeled
+    // two buffers, RB / R >= 2 steps: the steady loop reloads both, the last two or three steps
+    // are peeled
     raw qa[R][UPL], qb[R][UPL];
     load_rows(qa, 0);
     load_rows(qb, R);
