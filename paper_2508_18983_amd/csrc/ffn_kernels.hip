@@ -383,16 +383,15 @@ __global__ __launch_bounds__(256) void ffn_up_reg_kernel(const FfnArgs a, const 
     raw qg[FPI][UPL], qu[FPI][UPL];
 #pragma unroll
     for (int p = 0; p < FPI; ++p) {
-      const bool live = (i + p < per_wave) && (f + p < F);
-      const T* g = W1 + (size_t)(live ? f + p : f) * H;
-      const T* up = W3 + (size_t)(live ? f + p : f) * H;
+      const bool live = (i + p < per_wave) && (f + p < F);   // (the same for the whole wave)
+      const T* g = W1 + (size_t)(f + p) * H;
+      const T* up = W3 + (size_t)(f + p) * H;
       // (no per-lane branches around the loads: columns past the end of the row are clamped into
-      // it and meet zeros in x; a row past the end of the tile repeats row f and its result is
-      // not stored)
+      // it and meet zeros in x; a row or a unit slot that nobody needs is skipped by the whole wave)
 #pragma unroll
       for (int s = 0; s < UPL; ++s) {
-        if (s * kWave < units) {                       // (the same for the whole wave: a unit slot
-          const int u = min(s * kWave + lane, units - 1);   // no lane needs is not loaded at all)
+        if (live && s * kWave < units) {
+          const int u = min(s * kWave + lane, units - 1);
           qg[p][s] = Unit<T>::load(g + (size_t)u * N);
           qu[p][s] = Unit<T>::load(up + (size_t)u * N);
         } else {

@@ -173,7 +173,23 @@ void plan_geometry(moe_handle* h) {
   // up: TF rows of W1 and W3 per block, ~2560 blocks per token (ten per compute unit: measured
   // flat from 1000 to 2400 blocks on the 14336-wide experts, 3-4 % better than 1000 on narrow ones)
   int tf = (int)((total_f + 2559) / 2560 + 3) / 4 * 4;
-  tf = env_int("SMOE_TF", std::max(8, tf));
+  tf = std::max(8, tf);
+  {
+    // A small layer whose blocks do not all fit on the chip at once, but almost do, runs as one
+    // full round of blocks plus a short second one that pays the whole start-up chain (kernel
+    // arguments, gate sums, selection, first weights) again: take rows per block so that one
+    // round holds them all.  Blocks the chip holds at once: 4 waves each, 8 / 8 / 4 / 3 waves per
+    // SIMD for 1 / 2 / 4 / 8 units of x per lane (register use of the kernel instances).
+    const int nx = c.dtype == SMOE_DTYPE_FP32 ? 4 : 8;
+    const int xu = (c.hidden / nx + kWave - 1) / kWave;
+    const long at_once = 256L * (xu <= 2 ? 8 : (xu <= 4 ? 4 : 3));
+    auto blocks_of = [&](int t) {
+      return (long)c.top_k * ((c.ffn + t - 1) / t) + (c.n_shared ? (long)c.n_shared * ((c.shared_ffn + t - 1) / t) : 0);
+    };
+    if (blocks_of(tf) > at_once && blocks_of(tf) <= 2 * at_once)
+      while (blocks_of(tf) > at_once && tf < 64) tf += 4;
+  }
+  tf = env_int("SMOE_TF", tf);
   if (tf < 4) tf = 4;
   tf = tf / 4 * 4;
   h->TF = tf;
