@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # a workload without a committed summary reports traffic = null.
 MEASURED_TRAFFIC_RATIO = {
     "c3-mixtral8x7b-shaped": 1.0020,       # profiles/c3_ffn_hbm_traffic_pmc.md
-    "c4-dsv2lite-shaped": 1.0054,          # profiles/c4_ffn_hbm_traffic_pmc.md
+    "c4-dsv2lite-shaped": 1.0055,          # profiles/c4_ffn_hbm_traffic_pmc.md
     "c5-qwen2-57b-a14b-shaped": 1.0022,    # profiles/c5_ffn_hbm_traffic_pmc.md
 }
 # Names the profiler prints for the two resident-pass kernels at batch 1 (template arguments:

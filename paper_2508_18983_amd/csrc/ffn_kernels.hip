@@ -198,15 +198,19 @@ __global__ __launch_bounds__(256) void ffn_up_kernel(const FfnArgs a) {
   for (int i = 0; i < per_wave; i += 2) {
     const int f = f_begin + i;
     if (f >= F) break;
+    // two f-rows at a time; when the wave's share or the matrix ends on an odd row the second
+    // one repeats the first and is not stored
+    const bool two = (i + 1 < per_wave) && (f + 1 < F);
+    const int f2 = two ? f + 1 : f;
     const T* const rows[4] = {W1 + (size_t)f * H, W3 + (size_t)f * H,
-                              W1 + (size_t)(f + 1) * H, W3 + (size_t)(f + 1) * H};
+                              W1 + (size_t)f2 * H, W3 + (size_t)f2 * H};
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
     dot_rows<T, 4, 2>(rows, xs, units, lane, acc);
 #pragma unroll
     for (int q = 0; q < 4; ++q) acc[q] = wave_sum(acc[q]);
     if (lane == 0) {
       act[f] = wgt * (acc[0] / (1.0f + expf(-acc[0]))) * acc[1];
-      act[f + 1] = wgt * (acc[2] / (1.0f + expf(-acc[2]))) * acc[3];
+      if (two) act[f + 1] = wgt * (acc[2] / (1.0f + expf(-acc[2]))) * acc[3];
     }
   }
 }

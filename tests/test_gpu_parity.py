@@ -123,6 +123,7 @@ def test_error_paths_and_reset():
 
 
 @pytest.mark.parametrize("env", [dict(SMOE_REGPATH="0"), dict(SMOE_REGPATH="0", SMOE_R="2", SMOE_CHUNK="1024"),
+                                 dict(SMOE_REGPATH="0", SMOE_TF="12"), dict(SMOE_TF="12"),
                                  dict(SMOE_RB="16", SMOE_TF="64"), dict(SMOE_SPIN_LIMIT="0"),
                                  dict(SMOE_FUSED_SELECT="0")])
 def test_alternative_kernel_paths_and_launch_shapes(env, monkeypatch):
