@@ -1083,3 +1083,86 @@ def test_predicted_state_is_the_unit_rms_residual_sum():
     # hand case: x + y = (3, 4, 0, 0): rms = sqrt(25/4) = 2.5
     np.testing.assert_allclose(orc.predict_state(np.array([[1.0, 4.0, 0.0, -1.0]], np.float32),
                                                  np.array([[2.0, 0.0, 0.0, 1.0]])), [[1.2, 1.6, 0.0, 0.0]])
+
+
+# ---------------------------------------------------------------- Algorithm 2 and prefetches in flight
+def _identity_gate_oracle(E, k, cap, **kw):
+    """Gate = identity on the first E coordinates: the logits are x[:E], so a test
+    chooses the score order directly."""
+    H = max(8, E)
+    gate = np.zeros((1, E, H), np.float32)
+    for e in range(E):
+        gate[0, e, e] = 1.0
+    rng = np.random.default_rng(3)
+    experts = [rng.normal(0, 0.05, size=(E, 3 * H * 8)).astype(np.float32)]
+    return O.SMoEOracle(n_layers=1, hidden=H, n_experts=E, ffn=8, top_k=k, cache_cap=cap, alpha=0.0,
+                        gate_w=gate, experts=experts, sim=np.eye(E, dtype=np.float32)[None],
+                        init_resident=np.array([list(range(cap))]), elem_bytes=4, **kw), H
+
+
+def _x_with_order(H, order):
+    x = np.zeros((1, H), np.float32)
+    for r, e in enumerate(order):
+        x[0, e] = 6.0 - 0.5 * r                    # order[0] scores highest
+    return x
+
+
+def test_in_flight_prefetches_join_algorithm_2_hand_case():
+    """Section V-A with Section V-B dependency 2.  E = 8, top-4, G = {0, 1, 2, 3}.  The step
+    computes 5, 4, 0, 6 (descending score); 5 and 6 were prefetched, 4 is missing.
+    With equal costs the two workers of Algorithm 2 alternate, the loader first:
+      * both prefetches complete: only 4 waits -> it is loaded; 5 and 6 are adopted;
+      * both still in flight: the step waits for 5, 4, 6 -> 5 stays on the link and is
+        adopted, 6 (tail of the list) goes to the host cores and its prefetch is
+        dropped -- never adopted, never cached -- and 4 is loaded;
+      * only 6 in flight: the step waits for 4, 6 -> 4 is loaded, 6 goes to the host cores."""
+    E, k, cap = 8, 4, 4
+    order = [5, 4, 0, 6]
+    for inflight, want_cpu, want_fetched, want_adopted in (
+            (set(), [], [4], [5, 6]),
+            ({5, 6}, [6], [4], [5]),
+            ({6}, [6], [4], [5])):
+        orc, H = _identity_gate_oracle(E, k, cap, cpu_assist=1, c_load=1.0, c_cpu=1.0)
+        pf = orc.prefetch_layer(0, _x_with_order(H, [5, 6, 0, 1]), 2)
+        assert pf.prefetched == [5, 6]
+        r = orc.decode_layer(0, _x_with_order(H, order), inflight=inflight)
+        assert r.final[0].tolist() == order
+        assert r.hit[0].tolist() == [True, False, True, True]      # prefetched experts count as on the GPU
+        assert (r.on_cpu, r.fetched, r.adopted) == (want_cpu, want_fetched, want_adopted)
+        G = set(orc.layers[0].slot_expert)
+        assert len(G) == cap and set(want_fetched + want_adopted + [0]) <= G and not (set(want_cpu) & G)
+        assert orc.layers[0].landed == [] and all(v in (1, 2, 3) for v in r.victims + r.adopt_victims)
+        st = orc.stats()
+        assert (st.cpu_computed, st.fetches, st.prefetch_used) == (len(want_cpu), 1, 2)
+
+
+def test_in_flight_takeover_rebuilt_from_the_definitions_bruteforce():
+    """Random steps: the waiting list is, in descending score, every expert the step
+    computes that is neither in G nor a prefetch whose copy has finished; Algorithm 2
+    splits it head / tail; the head is loaded or adopted, the tail computed on the
+    host cores; prefetched experts the step does not compute, or that went to the
+    host cores, leave the queue."""
+    rng = np.random.default_rng(12)
+    E, k, cap = 12, 5, 6
+    seen_takeover = 0
+    for trial in range(200):
+        cl, cc = float(rng.uniform(0.5, 4)), float(rng.uniform(0.5, 4))
+        orc, H = _identity_gate_oracle(E, k, cap, cpu_assist=1, c_load=cl, c_cpu=cc)
+        pred = list(rng.permutation(E)[:k])
+        pf = orc.prefetch_layer(0, _x_with_order(H, pred), 3)
+        landed = list(pf.prefetched)
+        order = [int(e) for e in rng.permutation(E)[:k]]
+        inflight = set(e for e in landed if rng.random() < 0.5)
+        G0 = set(orc.layers[0].slot_expert)
+        r = orc.decode_layer(0, _x_with_order(H, order), inflight=inflight)
+        assert r.final[0].tolist() == order                          # alpha = 0: no substitution
+        waiting = [e for e in order if e not in G0 and (e not in landed or e in inflight)]
+        n_load, n_cpu = O.split_load_cpu(len(waiting), cl, cc)
+        head, tail = waiting[:n_load], waiting[n_load:]
+        assert r.on_cpu == tail
+        assert r.fetched == [e for e in order if e not in G0 and e not in landed and e not in tail]
+        assert r.adopted == [e for e in order if e in landed and e not in tail]
+        assert sorted(r.dropped) == sorted(e for e in landed if e not in order)
+        assert not (set(tail) & set(orc.layers[0].slot_expert))
+        seen_takeover += len(set(tail) & inflight)
+    assert seen_takeover > 20
