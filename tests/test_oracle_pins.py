@@ -1166,3 +1166,26 @@ def test_in_flight_takeover_rebuilt_from_the_definitions_bruteforce():
         assert not (set(tail) & set(orc.layers[0].slot_expert))
         seen_takeover += len(set(tail) & inflight)
     assert seen_takeover > 20
+
+
+def test_batched_prefetch_list_is_token_by_token_without_repeats_and_capped_by_the_spare_slots():
+    """Hand case, batch 3, G = {0, 1, 2, 3}, alpha = 0 (every predicted top-k expert is
+    top-score).  Predicted top-3 per token: (5, 0, 6), (6, 7, 1), (8, 5, 9).  Wanted, in
+    load order: 5, 6 from token 0 (0 is resident), then 7 (6 is a repeat, 1 resident),
+    then 8, 9 (5 a repeat).  Three spare slots take 5, 6, 7; a second prediction for the
+    same layer wants only what is not waiting yet and finds no room."""
+    orc, H = _identity_gate_oracle(10, 3, 4)
+    xp = np.concatenate([_x_with_order(H, o) for o in ([5, 0, 6], [6, 7, 1], [8, 5, 9])])
+    pf = orc.prefetch_layer(0, xp, 3)
+    assert pf.wanted == [5, 6, 7, 8, 9] and pf.prefetched == [5, 6, 7]
+    assert pf.topk.tolist() == [[5, 0, 6], [6, 7, 1], [8, 5, 9]]
+    again = orc.prefetch_layer(0, xp, 3)
+    assert again.wanted == [8, 9] and again.prefetched == []
+    assert orc.layers[0].landed == [5, 6, 7] and orc.layers[0].slot_expert == [0, 1, 2, 3]
+    assert orc.stats().prefetches == 3
+    # the batched step then adopts what it computes, in (token, slot) order, and drops the rest
+    x = np.concatenate([_x_with_order(H, o) for o in ([6, 0, 1], [2, 5, 0], [0, 1, 2])])
+    r = orc.decode_layer(0, x)
+    assert r.adopted == [6, 5] and r.dropped == [7] and r.fetched == []
+    assert r.adopt_victims == [3, -1]            # shield {6,0,1,2,5}: only 3 is evictable, 5 is not kept
+    assert orc.layers[0].slot_expert == [0, 1, 2, 6]
