@@ -115,11 +115,11 @@ __device__ __forceinline__ const char* task_weights(const FfnArgs& a, int t, int
 // shared experts' blocks come first: they need no routing decision, so with the
 // selection fused into the kernel they stream weights while the routed blocks
 // are still deciding.
-__device__ __forceinline__ void up_block_coords(const FfnArgs& a, int& t, int& j, int& tile) {
+__device__ __forceinline__ void up_block_coords(const FfnArgs& a, int bid, int& t, int& j, int& tile) {
   const int n_shared_blocks = a.ns * a.tilesS;
   const int bpt = n_shared_blocks + a.k * a.tilesR;   // blocks per token
-  t = blockIdx.x / bpt;
-  int r = blockIdx.x - t * bpt;
+  t = bid / bpt;
+  int r = bid - t * bpt;
   if (r < n_shared_blocks) { j = a.k + r / a.tilesS; tile = r - (j - a.k) * a.tilesS; }
   else { r -= n_shared_blocks; j = r / a.tilesR; tile = r - j * a.tilesR; }
 }
@@ -178,7 +178,7 @@ __global__ __launch_bounds__(256) void ffn_up_kernel(const FfnArgs a) {
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
   const int nj = a.k + a.ns;
   int t, j, tile;
-  up_block_coords(a, t, j, tile);
+  up_block_coords(a, (int)blockIdx.x, t, j, tile);
   const int task = t * nj + j;
   int F; float wgt;
   const char* base = task_weights<PASS>(a, t, j, task, F, wgt);
@@ -327,8 +327,12 @@ __global__ __launch_bounds__(256) void ffn_up_reg_kernel(const FfnArgs a, const 
   __shared__ SelectSmem<FUSED ? 1 : 0> sm;             // (empty when not fused)
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
   const int nj = a.k + a.ns;
-  int t, j, tile;
-  up_block_coords(a, t, j, tile);
+  // FUSED with ra.gate_blocks > 0: the launch starts with the blocks of the gate GEMV
+  int ng = 0;
+  if constexpr (FUSED) ng = ra.gate_blocks;
+  const bool gate_block = (int)blockIdx.x < ng;
+  int t = 0, j = 0, tile = 0;
+  if (!gate_block) up_block_coords(a, (int)blockIdx.x - ng, t, j, tile);
   const int task = t * nj + j;
   const int H = a.H;
   const int units = H / N;
@@ -344,9 +348,9 @@ __global__ __launch_bounds__(256) void ffn_up_reg_kernel(const FfnArgs a, const 
     const unsigned long long res_ = ra.resident;
     const float* gp_ = ra.gate_part;
     asm volatile("" ::"s"(e_), "s"(k_), "s"(ns_), "s"(rn_), "s"(sk_), "s"(al_), "s"(res_), "s"(gp_));
-    if (j < a.k && wave == 0) {
+    if (!gate_block && j < a.k && wave == 0) {
       my_slot_of = ra.slot_of[lane];
-      my_logit = logit_from_parts(ra, lane, 0);
+      if (ng == 0) my_logit = logit_from_parts(ra, lane, 0);
     }
   }
   raw xr[UPL];                                          // this lane's slice of x, as stored
@@ -355,6 +359,62 @@ __global__ __launch_bounds__(256) void ffn_up_reg_kernel(const FfnArgs a, const 
   for (int i = 0; i < UPL; ++i) {
     const int u = i * kWave + lane;
     xr[i] = (u < units) ? *reinterpret_cast<const raw*>(x + (size_t)u * N) : raw{};
+  }
+
+  if constexpr (FUSED) {
+    // logit of expert e: one wave, the row against the slice of x every lane already holds
+    auto gate_logit = [&](int e) -> float {
+      const T* row = static_cast<const T*>(ra.gate_w) + (size_t)e * H;
+      raw q[UPL];
+#pragma unroll
+      for (int s = 0; s < UPL; ++s) {
+        if (s * kWave < units) q[s] = Unit<T>::load(row + (size_t)min(s * kWave + lane, units - 1) * N);
+        else q[s] = raw{};
+      }
+      float acc = 0.f;
+#pragma unroll
+      for (int s = 0; s < UPL; ++s) acc = Unit<T>::dot(q[s], xr[s], acc);
+      return wave_sum(acc);
+    };
+    if (gate_block) {
+      // Gate GEMV (Section II-A): wave w of gate block b owns expert row 4 b + w and publishes
+      // its logit with this call's epoch in one 64-bit word (one store: no fence, no counter).
+      const int e = (int)blockIdx.x * 4 + wave;
+      if (e < ra.E) {
+        const float l = gate_logit(e);
+        if (lane == 0)
+          __hip_atomic_store(&ra.gate_word[e], ((unsigned long long)ra.epoch << 32) | __float_as_uint(l),
+                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      return;
+    }
+    if (ng > 0 && j < a.k && wave == 0) {
+      // The selecting wave reads the E words until all of them carry this call's epoch.  The
+      // gate blocks are the first blocks of this launch, so they are running or done by the
+      // time any other block exists; the wait is bounded all the same, and a wave that gives
+      // up computes the logits itself (slower, same values).
+      unsigned long long v = 0;
+      bool all_here = false;
+      // (hundreds of blocks read the same few cache lines past the L2: the first read is put off
+      // until the logits can be there, and the reads are spaced out)
+      if (ra.gate_spin > 0) __builtin_amdgcn_s_sleep(64);
+      for (int spin = 0; spin < ra.gate_spin; ++spin) {
+        v = lane < ra.E ? __hip_atomic_load(&ra.gate_word[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                        : ((unsigned long long)ra.epoch << 32);
+        all_here = __all((unsigned)(v >> 32) == ra.epoch);
+        if (all_here) break;
+        __builtin_amdgcn_s_sleep(32);
+      }
+      if (all_here) {
+        my_logit = lane < ra.E ? __uint_as_float((unsigned)v) : -INFINITY;
+      } else {
+        my_logit = -INFINITY;
+        for (int e = 0; e < ra.E; ++e) {
+          const float l = gate_logit(e);
+          if (lane == e) my_logit = l;
+        }
+      }
+    }
   }
 
   int F; float wgt;
@@ -1230,11 +1290,12 @@ static void launch_up_t(const FfnArgs& a, const RouteArgs& ra, hipStream_t s) {
   }
   const int grid = a.B * (a.k * a.tilesR + a.ns * a.tilesS);
   if (PASS == 0 && a.fused_select) {
+    const int fgrid = grid + ra.gate_blocks;            // (the gate GEMV's blocks come first)
     switch (a.up_upl) {
-      case 1: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 1, 0, true>), dim3(grid), dim3(256), 0, s, a, ra); return;
-      case 2: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 2, 0, true>), dim3(grid), dim3(256), 0, s, a, ra); return;
-      case 4: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 4, 0, true>), dim3(grid), dim3(256), 0, s, a, ra); return;
-      default: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 8, 0, true>), dim3(grid), dim3(256), 0, s, a, ra); return;
+      case 1: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 1, 0, true>), dim3(fgrid), dim3(256), 0, s, a, ra); return;
+      case 2: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 2, 0, true>), dim3(fgrid), dim3(256), 0, s, a, ra); return;
+      case 4: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 4, 0, true>), dim3(fgrid), dim3(256), 0, s, a, ra); return;
+      default: hipLaunchKernelGGL((ffn_up_reg_kernel<T, 8, 0, true>), dim3(fgrid), dim3(256), 0, s, a, ra); return;
     }
   }
   switch (a.up_upl) {

@@ -58,6 +58,14 @@ struct RouteArgs {
   int32_t upi;          // 128-bit units of one row segment per lane (1, 2, 4 or 8)
   int32_t seq;          // call number published to the host mirror when the record is complete
   float alpha;
+  // Gate GEMV inside the up kernel (batch 1, selection fused): the first gate_blocks blocks of
+  // that launch compute the logits, one wave per expert row, and publish each as one 64-bit
+  // word {epoch, logit bits} in gate_word[e]; the routed blocks read the words until all carry
+  // this call's epoch (at most gate_spin times, then they compute the logits themselves).
+  unsigned long long* gate_word;   // [E], device scratch
+  uint32_t epoch;                  // unique per (handle, call); never 0
+  int32_t gate_blocks;             // 0: the logits come from gate_part (separate gate launch)
+  int32_t gate_spin;
   uint64_t resident;                  // bit e = expert e is in the HBM cache
   int8_t slot_of[SMOE_MAX_EXPERTS];   // layer-local slot of each resident expert
 };

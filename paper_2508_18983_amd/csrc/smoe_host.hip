@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -74,6 +75,8 @@ struct Scratch {
   void* x_pred = nullptr;                // [B][H] dtype: predicted input of the next layer (auto_prefetch)
 };
 constexpr int64_t kGatePartBytes = (int64_t)SMOE_MAX_BATCH * SMOE_MAX_EXPERTS * kMaxGateSeg * sizeof(float);
+// (the 64-bit {epoch, logit} words of the in-kernel gate GEMV follow the partial sums)
+constexpr int64_t kGateWordBytes = (int64_t)SMOE_MAX_EXPERTS * sizeof(unsigned long long);
 
 }  // namespace
 
@@ -123,6 +126,9 @@ struct moe_handle {
                                          // overhead than they gain: measured 16 MB -> 64 MB +3-5 %)
   int64_t pf_bytes_submitted = 0, pf_bytes_withdrawn = 0;
   int mfma_rt = 16;                      // output rows per block of the MFMA down kernel
+  int fused_gate = 1;                    // batch 1: gate GEMV in the first blocks of the up kernel
+  int gate_spin = 8192;                  // reads of the logit words before a block computes them itself
+  int uid = 0;                           // 1..255, distinguishes the epochs of handles that share scratch
   int64_t pf_yielded = 0;                // predictions skipped because the link was busy
   std::vector<int32_t> slot_guard;       // per global slot: number of the decode call whose kernels may
                                          // still read a slot that has been given up since (-1: none)
@@ -430,6 +436,10 @@ void fill_route_args(const moe_handle* h, const Scratch& sc, int layer, int B, c
   ra.x = x;
   ra.sim = h->sim_dev + (size_t)layer * E * E;
   ra.gate_part = sc.gate_part;
+  ra.gate_word = reinterpret_cast<unsigned long long*>(reinterpret_cast<char*>(sc.gate_part) + kGatePartBytes);
+  ra.epoch = 0;
+  ra.gate_blocks = 0;
+  ra.gate_spin = h->gate_spin;
   ra.B = B; ra.H = c.hidden; ra.E = E; ra.k = c.top_k;
   ra.renorm = c.renorm_topk; ra.subst_key = c.subst_key; ra.alpha = c.alpha;
   // gate GEMV: one wave per (row, segment); split the rows until there are >= 128 waves of work
@@ -881,6 +891,12 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
     std::memset(h->rec_host, 0, sizeof(StepRec));
     h->spin_limit = env_int("SMOE_SPIN_LIMIT", 4000000);
     h->fused_select = env_int("SMOE_FUSED_SELECT", 1);
+    h->fused_gate = env_int("SMOE_FUSED_GATE", 1);
+    h->gate_spin = std::max(0, env_int("SMOE_GATE_SPIN", 8192));
+    {
+      static std::atomic<int> next_uid{0};
+      h->uid = next_uid.fetch_add(1) % 255 + 1;
+    }
     h->mfma_ok = env_int("SMOE_MFMA", 2);   // 0: vector ALUs, 1: MFMA down only, 2: MFMA up and down
     void* dp = nullptr;
     HIP_TRY(hipHostGetDevicePointer(&dp, h->rec_host, 0));
@@ -892,7 +908,8 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
     }
     HIP_TRY(hipMalloc(&h->own.act, (size_t)h->act_floats * sizeof(float)));
     HIP_TRY(hipMalloc(&h->own.ysum, (size_t)c.max_batch * c.hidden * sizeof(float)));
-    HIP_TRY(hipMalloc(&h->own.gate_part, (size_t)kGatePartBytes));
+    HIP_TRY(hipMalloc(&h->own.gate_part, (size_t)(kGatePartBytes + kGateWordBytes)));
+    HIP_TRY(hipMemset(h->own.gate_part, 0, (size_t)(kGatePartBytes + kGateWordBytes)));   // epoch 0 = never written
     HIP_TRY(hipMalloc(&h->own.x_pred, (size_t)c.max_batch * c.hidden * h->esize));
     {
       // the same buffers inside this GPU's static array, for moe_decode_layer_static
@@ -903,7 +920,7 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
       int64_t off = 0;
       auto carve = [&](int64_t bytes) { const int64_t o = off; off += (bytes + 255) / 256 * 256; return o; };
       const int64_t o_rec = carve(sizeof(StepRec));
-      const int64_t o_part = carve(kGatePartBytes);
+      const int64_t o_part = carve(kGatePartBytes + kGateWordBytes);
       const int64_t o_xp = carve((int64_t)c.max_batch * c.hidden * h->esize);
       const int64_t o_ysum = carve((int64_t)c.max_batch * c.hidden * sizeof(float));
       const int64_t o_act = carve(h->act_floats * (int64_t)sizeof(float));
@@ -1017,7 +1034,11 @@ static int decode_layer_with(moe_handle_t* h, const Scratch& sc, int32_t layer, 
   fill_ffn_args(h, sc, layer, B, x_dev, y_dev, fa);
   // batch 1 on the register up kernel: the selection runs in that kernel's prologue
   fa.fused_select = (B == 1 && h->fused_select && fa.up_upl > 0 && !fa.grouped) ? 1 : 0;
-  {
+  if (fa.fused_select && h->fused_gate) {
+    // the gate GEMV runs in the first blocks of the up kernel: two launches per layer
+    ra.gate_blocks = (c.n_experts + 3) / 4;
+    ra.epoch = ((uint32_t)h->uid << 24) | ((uint32_t)h->seq & 0xFFFFFFu);
+  } else {
     EventPair* pr = prof_begin(h, SMOE_PROF_ROUTE, h->s_compute);
     launch_gate_partial(ra, c.dtype, h->s_compute);
     if (!fa.fused_select) launch_route_select(ra, h->s_compute);

@@ -125,12 +125,14 @@ def test_error_paths_and_reset():
 @pytest.mark.parametrize("env", [dict(SMOE_REGPATH="0"), dict(SMOE_REGPATH="0", SMOE_R="2", SMOE_CHUNK="1024"),
                                  dict(SMOE_REGPATH="0", SMOE_TF="12"), dict(SMOE_TF="12"),
                                  dict(SMOE_RB="16", SMOE_TF="64"), dict(SMOE_SPIN_LIMIT="0"),
-                                 dict(SMOE_FUSED_SELECT="0")])
+                                 dict(SMOE_FUSED_SELECT="0"), dict(SMOE_FUSED_GATE="0"), dict(SMOE_GATE_SPIN="0")])
 def test_alternative_kernel_paths_and_launch_shapes(env, monkeypatch):
     """The LDS-staged kernels (fallback for very wide layers), other tile
     shapes, the selection as a launch of its own instead of the up kernel's
-    prologue, and the stream-drain fallback of the host must give the same
-    answers."""
+    prologue, the gate GEMV as a launch of its own instead of the up kernel's
+    first blocks, a selecting wave that does not wait for those blocks at all
+    (it then computes the logits itself), and the stream-drain fallback of the
+    host must give the same answers."""
     for k, v in env.items():
         monkeypatch.setenv(k, v)
     wl = make_workload(SHAPES["c2"].with_(seed=4), n_layers=2, tokens=24)
