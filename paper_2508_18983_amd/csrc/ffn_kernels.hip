@@ -336,6 +336,11 @@ __global__ __launch_bounds__(256) void ffn_up_reg_kernel(const FfnArgs a, const 
   const int task = t * nj + j;
   const int H = a.H;
   const int units = H / N;
+  // The wave that runs the selection.  A block's wave w sits on SIMD w of its compute unit, and
+  // the blocks that share a compute unit at the start of a launch are 256 apart in the grid: with
+  // wave 0 selecting in all of them the selections queue up on one SIMD while three idle
+  // (2.2 us per selection instead of under one).
+  const int sel_wave = ((int)blockIdx.x >> 8) & 3;
 
   // FUSED: what the selection reads from memory is requested first, together with x, so that
   // one round trip serves all of it (the scalar arguments of the selection are pinned here for
@@ -348,7 +353,7 @@ __global__ __launch_bounds__(256) void ffn_up_reg_kernel(const FfnArgs a, const 
     const unsigned long long res_ = ra.resident;
     const float* gp_ = ra.gate_part;
     asm volatile("" ::"s"(e_), "s"(k_), "s"(ns_), "s"(rn_), "s"(sk_), "s"(al_), "s"(res_), "s"(gp_));
-    if (!gate_block && j < a.k && wave == 0) {
+    if (!gate_block && j < a.k && wave == sel_wave) {
       my_slot_of = ra.slot_of[lane];
       if (ng == 0) my_logit = logit_from_parts(ra, lane, 0);
     }
@@ -388,22 +393,23 @@ __global__ __launch_bounds__(256) void ffn_up_reg_kernel(const FfnArgs a, const 
       }
       return;
     }
-    if (ng > 0 && j < a.k && wave == 0) {
+    if (ng > 0 && j < a.k && wave == sel_wave) {
       // The selecting wave reads the E words until all of them carry this call's epoch.  The
       // gate blocks are the first blocks of this launch, so they are running or done by the
       // time any other block exists; the wait is bounded all the same, and a wave that gives
       // up computes the logits itself (slower, same values).
       unsigned long long v = 0;
       bool all_here = false;
-      // (hundreds of blocks read the same few cache lines past the L2: the first read is put off
-      // until the logits can be there, and the reads are spaced out)
-      if (ra.gate_spin > 0) __builtin_amdgcn_s_sleep(64);
+      // (hundreds of blocks read the same few cache lines past the L2.  A block that starts when
+      // the logits are long there must not wait at all, so the first read comes at once; after a
+      // miss the wave stays away for about the time the gate blocks need, then reads at intervals)
       for (int spin = 0; spin < ra.gate_spin; ++spin) {
         v = lane < ra.E ? __hip_atomic_load(&ra.gate_word[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
                         : ((unsigned long long)ra.epoch << 32);
         all_here = __all((unsigned)(v >> 32) == ra.epoch);
         if (all_here) break;
-        __builtin_amdgcn_s_sleep(32);
+        if (spin == 0) __builtin_amdgcn_s_sleep(64);
+        else __builtin_amdgcn_s_sleep(32);
       }
       if (all_here) {
         my_logit = lane < ra.E ? __uint_as_float((unsigned)v) : -INFINITY;
@@ -422,7 +428,16 @@ __global__ __launch_bounds__(256) void ffn_up_reg_kernel(const FfnArgs a, const 
   bool decided = false;
   if constexpr (FUSED) {
     if (j < a.k) {                                      // (uniform over the block)
-      if (wave == 0) select_single(ra, sm, lane, my_slot_of, my_logit, j == 0 && tile == 0);
+      if (wave == sel_wave) {
+        if (j == 0 && tile == 0) {
+          select_single(ra, sm, lane, my_slot_of, my_logit, true);     // also writes the decision record
+        } else {
+          int e_sel, slot_sel;
+          float w_sel;
+          select_slot_in_registers(ra, lane, my_slot_of, my_logit, j, e_sel, slot_sel, w_sel);
+          if (lane == 0) { sm.slt[0][j] = slot_sel; sm.wsl[0][j] = w_sel; }
+        }
+      }
       __syncthreads();
       const int slot = sm.slt[0][j];
       F = a.F;

@@ -70,6 +70,29 @@ __device__ __forceinline__ float logit_from_parts(const RouteArgs& a, int lane, 
   return v;
 }
 
+// Rank of this lane's expert in (logit descending, id ascending) order = the number of
+// experts that precede it.  Every lane gets a unique 64-bit key (the logit as an order-
+// preserving integer, then 63 - id so that the lower id wins a tie) and counts the larger
+// keys, which arrive by lane broadcast: 64 x (two v_readlane, one 64-bit compare, one add),
+// no memory access.  (E reads of the logits from LDS, one per loop trip, took 2.0 us of the
+// 2.9 us the selection took in the up kernel's prologue; k+1 dependent wave-wide arg-max
+// rounds are slower still.)  Lanes >= E hold -inf and precede nobody.
+__device__ __forceinline__ int rank_by_logit(float l, int lane) {
+  const float lz = l + 0.0f;                                     // -0 and +0 tie
+  unsigned ub = __float_as_uint(lz);
+  ub = (ub & 0x80000000u) ? ~ub : (ub | 0x80000000u);
+  const unsigned key_hi = ub >> 26, key_lo = (ub << 6) | (unsigned)(63 - lane);
+  const unsigned long long key = ((unsigned long long)key_hi << 32) | key_lo;
+  int myrank = 0;
+#pragma unroll
+  for (int j = 0; j < kWave; ++j) {
+    const unsigned long long kj = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)key_hi, j) << 32) |
+                                  (unsigned)__builtin_amdgcn_readlane((int)key_lo, j);
+    myrank += kj > key;
+  }
+  return myrank;
+}
+
 // Scores, top-(k+1), alpha classes of one token.
 template <int NB>
 __device__ __forceinline__ TokenClasses select_pass1(const RouteArgs& a, SelectSmem<NB>& sm, int lane, int row) {
@@ -80,17 +103,7 @@ __device__ __forceinline__ TokenClasses select_pass1(const RouteArgs& a, SelectS
   const float m = wave_max(l);
   const float p = in ? expf(l - m) : 0.f;
   const float s = p / wave_sum(p);
-  // Rank of this lane's expert in (logit descending, id ascending) order, by
-  // counting the experts that precede it: E broadcast reads of the logits in
-  // LDS instead of k+1 dependent wave-wide arg-max rounds.
-  int myrank = 0;
-  for (int j = 0; j < E; j += 4) {
-    const float4 q = *reinterpret_cast<const float4*>(&sm.lg[row][j]);    // lanes >= E hold -inf
-    myrank += (q.x > l) || (q.x == l && j < lane);
-    myrank += (q.y > l) || (q.y == l && j + 1 < lane);
-    myrank += (q.z > l) || (q.z == l && j + 2 < lane);
-    myrank += (q.w > l) || (q.w == l && j + 3 < lane);
-  }
+  int myrank = rank_by_logit(l, lane);
   if (!in) myrank = 127;
   if (lane < k) sm.tk[row][lane] = lane;               // defined even if the logits are not numbers
   wave_lds_handoff();
@@ -192,6 +205,80 @@ __device__ __forceinline__ void select_single(const RouteArgs& a, SelectSmem<1>&
   const TokenClasses cls = select_pass1(a, sm, lane, 0);
   select_pass2(a, sm, cls, cls.top_m, lane, 0, 0, emit);
   if (emit) publish_seq(a, lane);
+}
+
+// What one routed slot of a batch-1 call computes -- final expert of slot j, its cache slot (-1:
+// to be loaded) and its combine weight -- by one wave, in registers only: the same steps as
+// select_pass1 / select_pass2 (same arithmetic, same order of the weight sum, hence the same
+// bits), with the hand-offs through LDS replaced by ballots and lane broadcasts.  The blocks
+// of the up kernel that do not have to write the decision record use this; results are uniform
+// over the wave.
+__device__ __forceinline__ void select_slot_in_registers(const RouteArgs& a, int lane, int slot_of_lane, float l,
+                                                         int j, int& expert, int& slot, float& wgt) {
+  const int E = a.E, k = a.k;
+  const bool has_pivot = E > k;
+  const bool in = lane < E;
+  const float m = wave_max(l);
+  const float p = in ? expf(l - m) : 0.f;
+  const float s = p / wave_sum(p);
+  int myrank = rank_by_logit(l, lane);
+  if (!in) myrank = 127;
+  int t[SMOE_MAX_TOPK];                                 // E_a by rank (uniform values)
+#pragma unroll
+  for (int r = 0; r < SMOE_MAX_TOPK; ++r) {
+    const unsigned long long mr = __ballot(myrank == r);
+    t[r] = (r < k && mr) ? (int)__ffsll((long long)mr) - 1 : r;
+  }
+  float R = 0.f;
+  bool top = myrank < k;
+  if (has_pivot) {
+    const unsigned long long pivot_m = __ballot(myrank == k);
+    const int pivot = pivot_m ? (int)__ffsll((long long)pivot_m) - 1 : 0;
+    const float s_k1 = lane_f(s, pivot);
+    const float T_hi = (1.0f + a.alpha) * s_k1;
+    R = (1.0f - a.alpha) * s_k1;
+    top = top && (s >= T_hi);
+  }
+  const unsigned long long top_m = __ballot(top);
+  const unsigned long long avail = a.resident | top_m;
+  const bool active = myrank < k;
+  const bool is_avail = (avail >> lane) & 1ull;
+  const unsigned long long need_m = __ballot(active && !((top_m >> lane) & 1ull) && !is_avail);
+  unsigned long long cand_m = has_pivot ? __ballot(in && !active && is_avail && s >= R) : 0ull;
+  int fin[SMOE_MAX_TOPK];
+#pragma unroll
+  for (int r = 0; r < SMOE_MAX_TOPK; ++r) fin[r] = t[r];
+  if (need_m && cand_m) {
+#pragma unroll
+    for (int r = SMOE_MAX_TOPK - 1; r >= 0; --r) {      // lowest-scoring active first
+      if (r >= k) continue;
+      const int b = t[r];
+      if (!((need_m >> b) & 1ull)) continue;
+      if (!cand_m) continue;
+      const bool is_cand = (cand_m >> lane) & 1ull;
+      float key = s;
+      if (a.subst_key == 0) key = is_cand ? a.sim[(size_t)b * E + lane] : 0.f;
+      const int c = wave_argmax(key, is_cand, lane);
+      fin[r] = c;
+      cand_m &= ~(1ull << c);
+    }
+  }
+  // lane r < k holds the score of the expert ranked r: the same operands, in the same lanes, as
+  // the weight sum of select_pass2
+  float w = 0.f;
+#pragma unroll
+  for (int r = 0; r < SMOE_MAX_TOPK; ++r) {
+    const float sr = lane_f(s, t[r]);
+    if (r < k && lane == r) w = sr;
+  }
+  const float wsum = wave_sum(w);
+  if (a.renorm) w = w / wsum;
+  expert = 0;
+#pragma unroll
+  for (int r = 0; r < SMOE_MAX_TOPK; ++r)
+    if (r == j) expert = fin[r];
+  wgt = lane_f(w, j);
+  slot = ((a.resident >> expert) & 1ull) ? __builtin_amdgcn_readlane(slot_of_lane, expert) : -1;
 }
 
 }  // namespace smoe
