@@ -32,7 +32,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # profiles/<workload>_ffn_hbm_traffic_pmc.md summarises.  bench.py cannot read counters itself;
 # a workload without a committed summary reports traffic = null.
 MEASURED_TRAFFIC_RATIO = {
-    "c3-mixtral8x7b-shaped": 1.0023,       # profiles/c3_ffn_hbm_traffic_pmc.md
+    "c3-mixtral8x7b-shaped": 1.0022,       # profiles/c3_ffn_hbm_traffic_pmc.md
     "c4-dsv2lite-shaped": 1.0080,          # profiles/c4_ffn_hbm_traffic_pmc.md
     "c5-qwen2-57b-a14b-shaped": 1.0028,    # profiles/c5_ffn_hbm_traffic_pmc.md
 }

@@ -891,7 +891,10 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
     std::memset(h->rec_host, 0, sizeof(StepRec));
     h->spin_limit = env_int("SMOE_SPIN_LIMIT", 4000000);
     h->fused_select = env_int("SMOE_FUSED_SELECT", 1);
-    h->fused_gate = env_int("SMOE_FUSED_GATE", 1);
+    // (worth it where blocks exist that can stream while the logits are on their way: the shared
+    // experts'.  Without them every block of the launch waits for the gate blocks and the kernel
+    // boundary it replaces was no slower: measured on the Mixtral-shaped workload)
+    h->fused_gate = env_int("SMOE_FUSED_GATE", c.n_shared > 0 ? 1 : 0);
     h->gate_spin = std::max(0, env_int("SMOE_GATE_SPIN", 8192));
     {
       static std::atomic<int> next_uid{0};

@@ -125,7 +125,8 @@ def test_error_paths_and_reset():
 @pytest.mark.parametrize("env", [dict(SMOE_REGPATH="0"), dict(SMOE_REGPATH="0", SMOE_R="2", SMOE_CHUNK="1024"),
                                  dict(SMOE_REGPATH="0", SMOE_TF="12"), dict(SMOE_TF="12"),
                                  dict(SMOE_RB="16", SMOE_TF="64"), dict(SMOE_SPIN_LIMIT="0"),
-                                 dict(SMOE_FUSED_SELECT="0"), dict(SMOE_FUSED_GATE="0"), dict(SMOE_GATE_SPIN="0")])
+                                 dict(SMOE_FUSED_SELECT="0"), dict(SMOE_FUSED_GATE="0"), dict(SMOE_FUSED_GATE="1"),
+                                 dict(SMOE_FUSED_GATE="1", SMOE_GATE_SPIN="0")])
 def test_alternative_kernel_paths_and_launch_shapes(env, monkeypatch):
     """The LDS-staged kernels (fallback for very wide layers), other tile
     shapes, the selection as a launch of its own instead of the up kernel's
