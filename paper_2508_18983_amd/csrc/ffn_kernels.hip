@@ -402,13 +402,13 @@ __global__ __launch_bounds__(256) void ffn_up_reg_kernel(const FfnArgs a, const 
       bool all_here = false;
       // (hundreds of blocks read the same few cache lines past the L2.  A block that starts when
       // the logits are long there must not wait at all, so the first read comes at once; after a
-      // miss the wave stays away for about the time the gate blocks need, then reads at intervals)
+      // miss the wave stays away for a while, then reads at intervals)
       for (int spin = 0; spin < ra.gate_spin; ++spin) {
         v = lane < ra.E ? __hip_atomic_load(&ra.gate_word[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
                         : ((unsigned long long)ra.epoch << 32);
         all_here = __all((unsigned)(v >> 32) == ra.epoch);
         if (all_here) break;
-        if (spin == 0) __builtin_amdgcn_s_sleep(64);
+        if (spin == 0) __builtin_amdgcn_s_sleep(24);
         else __builtin_amdgcn_s_sleep(32);
       }
       if (all_here) {

@@ -71,24 +71,31 @@ __device__ __forceinline__ float logit_from_parts(const RouteArgs& a, int lane, 
 }
 
 // Rank of this lane's expert in (logit descending, id ascending) order = the number of
-// experts that precede it.  Every lane gets a unique 64-bit key (the logit as an order-
-// preserving integer, then 63 - id so that the lower id wins a tie) and counts the larger
-// keys, which arrive by lane broadcast: 64 x (two v_readlane, one 64-bit compare, one add),
-// no memory access.  (E reads of the logits from LDS, one per loop trip, took 2.0 us of the
-// 2.9 us the selection took in the up kernel's prologue; k+1 dependent wave-wide arg-max
-// rounds are slower still.)  Lanes >= E hold -inf and precede nobody.
-__device__ __forceinline__ int rank_by_logit(float l, int lane) {
+// experts that precede it.  The logit becomes an order-preserving 32-bit integer and every lane
+// counts the larger ones, which arrive by lane broadcast: 64 x (v_readlane, compare, add), no
+// memory access.  (E reads of the logits from LDS, one per loop trip, took 2.0 us of the 2.9 us
+// the selection took in the up kernel's prologue; k+1 dependent wave-wide arg-max rounds are
+// slower still.)  Equal logits leave equal counts, and then the counts of the E real experts no
+// longer add up to 0 + 1 + ... + (E-1): only then the count is redone with 64-bit keys that
+// carry 63 - id in their low bits, so that the lower id wins the tie.  Lanes >= E hold -inf and
+// precede nobody.
+__device__ __forceinline__ int rank_by_logit(float l, int lane, int E) {
   const float lz = l + 0.0f;                                     // -0 and +0 tie
   unsigned ub = __float_as_uint(lz);
   ub = (ub & 0x80000000u) ? ~ub : (ub | 0x80000000u);
-  const unsigned key_hi = ub >> 26, key_lo = (ub << 6) | (unsigned)(63 - lane);
-  const unsigned long long key = ((unsigned long long)key_hi << 32) | key_lo;
   int myrank = 0;
 #pragma unroll
-  for (int j = 0; j < kWave; ++j) {
-    const unsigned long long kj = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)key_hi, j) << 32) |
-                                  (unsigned)__builtin_amdgcn_readlane((int)key_lo, j);
-    myrank += kj > key;
+  for (int j = 0; j < kWave; ++j) myrank += (unsigned)__builtin_amdgcn_readlane((int)ub, j) > ub;
+  const float total = wave_sum(lane < E ? (float)myrank : 0.f);  // (exact: at most 2016)
+  if (total != (float)(E * (E - 1) / 2)) {                       // ties among the real experts: rare
+    const unsigned key_hi = ub >> 26, key_lo = (ub << 6) | (unsigned)(63 - lane);
+    const unsigned long long key = ((unsigned long long)key_hi << 32) | key_lo;
+    myrank = 0;
+    for (int j = 0; j < kWave; ++j) {
+      const unsigned long long kj = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)key_hi, j) << 32) |
+                                    (unsigned)__builtin_amdgcn_readlane((int)key_lo, j);
+      myrank += kj > key;
+    }
   }
   return myrank;
 }
@@ -103,7 +110,7 @@ __device__ __forceinline__ TokenClasses select_pass1(const RouteArgs& a, SelectS
   const float m = wave_max(l);
   const float p = in ? expf(l - m) : 0.f;
   const float s = p / wave_sum(p);
-  int myrank = rank_by_logit(l, lane);
+  int myrank = rank_by_logit(l, lane, E);
   if (!in) myrank = 127;
   if (lane < k) sm.tk[row][lane] = lane;               // defined even if the logits are not numbers
   wave_lds_handoff();
@@ -221,7 +228,7 @@ __device__ __forceinline__ void select_slot_in_registers(const RouteArgs& a, int
   const float m = wave_max(l);
   const float p = in ? expf(l - m) : 0.f;
   const float s = p / wave_sum(p);
-  int myrank = rank_by_logit(l, lane);
+  int myrank = rank_by_logit(l, lane, E);
   if (!in) myrank = 127;
   int t[SMOE_MAX_TOPK];                                 // E_a by rank (uniform values)
 #pragma unroll

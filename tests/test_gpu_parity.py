@@ -705,3 +705,27 @@ def test_prefetch_that_yields_to_a_busy_link():
     assert 0 < yielded < made and free["hits"] + free["misses"] == free["slots"]
     with pytest.raises(M.SmoeError):
         session_from_workload(wl, prefetch_max=2, prefetch_yield=2)
+
+
+@pytest.mark.parametrize("case", ["fp32-separate-gate", "bf16-gate-in-up-kernel", "bf16-batch3"])
+def test_exactly_equal_logits_are_ranked_by_expert_id(case):
+    """Duplicate gate rows give bitwise equal logits (and scores, and Eq. 3 means):
+    ranking, top-k membership, substitution order and eviction then hinge on the
+    tie rules (lower id first), on the GPU's fast 32-bit ranking as well as on its
+    64-bit fallback.  Every other comparison keeps the margin the inputs were
+    drawn with, so the decisions must still match the oracle exactly."""
+    if case == "fp32-separate-gate":
+        shp, B, dup = SHAPES["c1"].with_(tokens=24, seed=21), 1, [(2, 3), (5, 6), (0, 7)]
+    else:
+        B = 3 if case.endswith("batch3") else 1
+        shp = SHAPES["c4"].with_(hidden=256, ffn=64, shared_ffn=64, n_experts=24, top_k=4, cache_cap=9,
+                                 n_layers=2, tokens=24, seed=22, sim="uniform", batch=B)
+        dup = [(1, 2), (2, 3), (10, 17), (5, 23), (8, 9)]
+    wl = make_workload(shp)
+    for l in range(wl.shape.n_layers):
+        for a, b in dup:                                  # (chains make triples)
+            wl.gate_w[l, b] = wl.gate_w[l, a]
+    kw = dict(session_kw=dict(n_stage=B * shp.top_k)) if B > 1 else {}
+    r = run_parity(wl, batch=B, check_margins=False, label=f"ties-{case}", **kw)
+    assert r["route_margin"] == 0.0                       # the ties did reach the compared ranks
+    assert r["stats"]["substitutions"] > 0 and r["stats"]["misses"] > 0
