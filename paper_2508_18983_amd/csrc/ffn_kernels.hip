@@ -920,8 +920,10 @@ __global__ __launch_bounds__(256) void ffn_down_grp_kernel(const FfnArgs a) {
 // come as two bf16 terms (hi + lo) written by the up kernel; with at most 8
 // tokens per step both fit the 16 tile columns: column j holds the hi terms of
 // token j, column 8 + j its lo terms, so ONE MFMA per K-step multiplies both and
-// the two halves of the result tile are added in the epilogue.  The eight waves
-// take items round-robin; each stages its 16 x 256 weight tile through a
+// the two halves of the result tile are added in the epilogue.  Each of the
+// eight waves takes a contiguous range of the items (it walks along the rows of
+// one expert, segment after segment; measured 3 % faster than every eighth item,
+// which a.mfma_contig = 0 keeps) and stages its 16 x 256 weight tile through a
 // private, padded LDS region (coalesced 128-bit global loads in, MFMA operand
 // order out) and accumulates one 16 x 16 fp32 tile over all of its items.  The
 // activations of the next item and the weight tiles of the next two are in
@@ -1056,6 +1058,12 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void ffn_down_mfma_kernel(const Ff
   const int n_items = items_r + a.ns * nsegS;
   unsigned char* stage = lds + (size_t)wave * 16 * kMfmaRowBytes;
   int next_it = 0;                          // item index at which describe() last stopped
+  // Items of a wave: a contiguous range (a.mfma_contig), so that the wave walks along the rows of one
+  // task segment after segment, or every eighth item.
+  const int ipw = (n_items + kMfmaWaves - 1) / kMfmaWaves;
+  const int it_step = a.mfma_contig ? 1 : kMfmaWaves;
+  const int it_first = a.mfma_contig ? wave * ipw : wave;
+  const int it_end = a.mfma_contig ? min(n_items, (wave + 1) * ipw) : n_items;
 
   // Task table in LDS (built once per block): decoding an item must not cost a
   // round trip to the decision record in the middle of the pipeline.
@@ -1101,7 +1109,7 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void ffn_down_mfma_kernel(const Ff
   auto describe = [&](int it) -> Item {
     Item d{dummy_w, reinterpret_cast<const uint16_t*>(a.rec), 0, 8, false, false};
     // skip forward over items whose task is not part of this pass
-    for (; it < n_items; it += kMfmaWaves) {
+    for (; it < it_end; it += it_step) {
       int task, seg;
       if (it < items_r) { task = it / nsegR; seg = it - task * nsegR; }
       else { const int q = it - items_r; const int sidx = q / nsegS; seg = q - sidx * nsegS; task = a.maxg + sidx; }
@@ -1172,14 +1180,14 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void ffn_down_mfma_kernel(const Ff
   bool av_tok[2];
   int av_cols[2];
   Item q[3];
-  q[0] = describe(wave);
+  q[0] = describe(it_first);
   load_tile(q[0], wt[0]);
   load_act(q[0], av[0]);
   av_tok[0] = q[0].has_tok;
   av_cols[0] = q[0].ncols;
-  q[1] = describe(next_it + kMfmaWaves);
+  q[1] = describe(next_it + it_step);
   load_tile(q[1], wt[1]);
-  q[2] = describe(next_it + kMfmaWaves);
+  q[2] = describe(next_it + it_step);
   load_tile(q[2], wt[2]);
   bool more = q[0].valid;
   while (more) {
@@ -1190,7 +1198,7 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void ffn_down_mfma_kernel(const Ff
       load_act(q[(s6 + 1) % 3], av[a2 ^ 1]);      // item n + 1
       av_tok[a2 ^ 1] = q[(s6 + 1) % 3].has_tok;
       av_cols[a2 ^ 1] = q[(s6 + 1) % 3].ncols;
-      q[t3] = describe(next_it + kMfmaWaves);     // item n + 3 takes over item n's buffer and descriptor
+      q[t3] = describe(next_it + it_step);     // item n + 3 takes over item n's buffer and descriptor
       load_tile(q[t3], wt[t3]);
       multiply_staged(av[a2], av_tok[a2], av_cols[a2]);
       if (!q[(s6 + 1) % 3].valid) { more = false; break; }

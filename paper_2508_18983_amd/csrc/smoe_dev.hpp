@@ -97,6 +97,7 @@ struct FfnArgs {
   int32_t grouped;                         // batch > 1: tasks are the record's expert groups (+ shared)
   int32_t maxg;                            // grouped: upper bound of groups = min(E, B*k)
   int32_t mfma_down;                       // grouped, bf16: down projection on the matrix cores
+  int32_t mfma_contig;                     // its waves take contiguous ranges of items
   int32_t mfma_rt;                         // its output rows per block: 8, 12, 14 or 16
   int32_t mfma_up;                         // ... and the up projection too
   int32_t nsegGR, nsegGS, RBG;             // grouped down kernel: segments per routed / shared row, rows per block

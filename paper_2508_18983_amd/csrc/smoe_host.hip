@@ -126,6 +126,7 @@ struct moe_handle {
                                          // overhead than they gain: measured 16 MB -> 64 MB +3-5 %)
   int64_t pf_bytes_submitted = 0, pf_bytes_withdrawn = 0;
   int mfma_rt = 16;                      // output rows per block of the MFMA down kernel
+  int mfma_contig = 1;                   // its waves take contiguous item ranges (SMOE_MFMA_CONTIG=0: every eighth item)
   int fused_gate = 1;                    // batch 1: gate GEMV in the first blocks of the up kernel
   int gate_spin = 8192;                  // reads of the logit words before a block computes them itself
   int uid = 0;                           // 1..255, distinguishes the epochs of handles that share scratch
@@ -665,6 +666,7 @@ void fill_ffn_args(const moe_handle* h, const Scratch& sc, int layer, int B, con
   fa.mfma_down = (fa.grouped && c.dtype == SMOE_DTYPE_BF16 && h->mfma_ok) ? 1 : 0;
   fa.mfma_up = (fa.mfma_down && h->mfma_ok >= 2) ? 1 : 0;
   fa.mfma_rt = h->mfma_rt;
+  fa.mfma_contig = h->mfma_contig;
   fa.nsegGR = h->nsegGR; fa.nsegGS = h->nsegGS; fa.RBG = h->RBG;
   fa.act_shared_off = (int64_t)fa.maxg * SMOE_MAX_BATCH * c.ffn;
   if (fa.grouped && fa.up_upl == 0) {                 // grouped up kernel needs units per lane
@@ -900,6 +902,7 @@ int moe_cache_init(const moe_cfg_t* cfg, const moe_buffers_t* buf, moe_handle_t*
       static std::atomic<int> next_uid{0};
       h->uid = next_uid.fetch_add(1) % 255 + 1;
     }
+    h->mfma_contig = env_int("SMOE_MFMA_CONTIG", 1) != 0 ? 1 : 0;
     h->mfma_ok = env_int("SMOE_MFMA", 2);   // 0: vector ALUs, 1: MFMA down only, 2: MFMA up and down
     void* dp = nullptr;
     HIP_TRY(hipHostGetDevicePointer(&dp, h->rec_host, 0));

@@ -157,7 +157,7 @@ def test_batched_decode_cross_token_substitution_and_staging(batch):
 
 
 @pytest.mark.parametrize("env", [dict(), dict(SMOE_MFMA="1"), dict(SMOE_MFMA="0"), dict(SMOE_MFMA_RT="16"),
-                                 dict(SMOE_MFMA_RT="14"), dict(SMOE_MFMA_RT="12")])
+                                 dict(SMOE_MFMA_RT="14"), dict(SMOE_MFMA_RT="12"), dict(SMOE_MFMA_CONTIG="0")])
 def test_batched_decode_ragged_shapes_matrix_core_and_vector_down_kernels(env, monkeypatch):
     """bf16 batch with rows and columns that do not fill the 16 x 256 MFMA tiles
     (every rows-per-block variant of the MFMA down kernel, with a ragged last
@@ -591,12 +591,17 @@ def test_load_queue_withdraws_mispredicted_prefetches_and_leaves_the_cache_alone
           f"{pb['copied'] / 1e6:.0f} MB copied, {pb['withdrawn'] / 1e6:.0f} MB withdrawn", flush=True)
 
 
-def test_in_flight_prefetches_can_be_taken_over_by_the_host_cores():
+def test_in_flight_prefetches_can_be_taken_over_by_the_host_cores(monkeypatch):
     """CPU-assisted scheduling with prefetch (Section V-A with Section V-B's second
     dependency): a prefetched expert whose copy has not finished when its layer is
     decided joins the list Algorithm 2 splits; with the host cores cheaper than a
     load the min-max variant computes it on the CPU and abandons the copy.  Which
-    experts were in flight is reported by the call and given to the oracle."""
+    experts were in flight is reported by the call and given to the oracle.  The
+    load queue hands the copy stream 1 MB at a time here and only while a call of
+    the library runs, so a 17 MB expert cannot have landed by its layer's step
+    however slowly the test itself runs between the calls."""
+    monkeypatch.setenv("SMOE_PF_CHUNK_MB", "1")
+    monkeypatch.setenv("SMOE_PF_OUTSTANDING", "1")
     ses_kw, orc_kw = _cpu_kw(3.0, 1.0, threads=8, mode=2)
     shp = SHAPES["c4"].with_(seed=45)
     wl = make_workload(shp, n_layers=4, tokens=30, pred_noise=0.3)
