@@ -1060,10 +1060,13 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void ffn_down_mfma_kernel(const Ff
   int next_it = 0;                          // item index at which describe() last stopped
   // Items of a wave: a contiguous range (a.mfma_contig), so that the wave walks along the rows of one
   // task segment after segment, or every eighth item.
+  // (the pass over the freshly loaded experts has work for a few tasks only: every eighth item
+  // spreads those over all waves, a contiguous range would give a task to one or two of them)
+  const bool contig = PASS == 0 && a.mfma_contig;
   const int ipw = (n_items + kMfmaWaves - 1) / kMfmaWaves;
-  const int it_step = a.mfma_contig ? 1 : kMfmaWaves;
-  const int it_first = a.mfma_contig ? wave * ipw : wave;
-  const int it_end = a.mfma_contig ? min(n_items, (wave + 1) * ipw) : n_items;
+  const int it_step = contig ? 1 : kMfmaWaves;
+  const int it_first = contig ? wave * ipw : wave;
+  const int it_end = contig ? min(n_items, (wave + 1) * ipw) : n_items;
 
   // Task table in LDS (built once per block): decoding an item must not cost a
   // round trip to the decision record in the middle of the pipeline.
